@@ -1,0 +1,194 @@
+/*
+ * kvq — decode-time attention mat-vecs against a sub-4-bit non-uniformly quantized KV cache
+ * (KVQuant, arXiv 2401.18079), native for AMD MI355X (gfx950).
+ *
+ * C ABI.  All pointers named d_* or stored in kvq_cache are DEVICE pointers (HIP global memory,
+ * e.g. torch tensors' data_ptr()); pointers named h_* are HOST pointers.  `stream` is a
+ * hipStream_t passed as void* (NULL = the default stream).  Every call is asynchronous on
+ * `stream` unless stated otherwise.  The library allocates and frees no device memory: the
+ * caller owns every buffer, sized with the kvq_*_bytes helpers below.
+ *
+ * Supported shapes: head_dim = 128; bits in {2,3,4}; n_q_heads a multiple of n_kv_heads;
+ * D = n_kv_heads*128 <= 65536; cap_tokens a multiple of 128.
+ *
+ * Storage format (owned by this library, bit-exact and documented so that a reference
+ * implementation can check it):
+ *   Key codes   — per KV head a plane of cap_tokens chunks; the chunk of (token n, head h) is a
+ *                 16*bits-byte little-endian bit stream of 64 fields of 2*bits bits; field i holds
+ *                 the code of channel i (low bits) and of channel i+64 (high bits), the two channels
+ *                 RoPE rotates together.  The chunk is stored as `bits` pieces of 16 bytes, piece j
+ *                 at byte  h*cap*16*bits + (n/64)*64*16*bits + j*1024 + (n%64)*16
+ *                 (tokens interleaved in blocks of 64 so a wavefront reads 1 KiB contiguous).
+ *   Value codes — per (KV head h, channel half g) a plane of cap_tokens/2 chunks; the chunk of
+ *                 (token pair m, h, g) has the same shape; field j holds the code of channel
+ *                 h*128+g*64+j for token 2m (low bits) and 2m+1 (high bits).  Piece r at byte
+ *                 (h*2+g)*(cap/2)*16*bits + (m/64)*64*16*bits + r*1024 + (m%64)*16.
+ *   v_sz        — [cap_tokens][2] fp16: per-token Value scale and zero-point.
+ *   Sparse outliers (Keys and Values): ptr[cap_tokens+1] uint32 with ptr[0]=0; token n owns
+ *                 entries ptr[n]..ptr[n+1]-1 of idx[] (uint16 channel in [0,D), ascending) and
+ *                 val[] (fp16 bits of the residual x - dequant(code)).
+ * All cache buffers must be zero-filled before the first append (ptr[0] must be 0).
+ */
+#ifndef KVQ_H
+#define KVQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KVQ_OK = 0,
+    KVQ_ERR_INVALID_ARG = 1,   /* null / misaligned pointer, bad count, 2*k_side_v >= D, ...           */
+    KVQ_ERR_UNSUPPORTED = 2,   /* bits not in {2,3,4}, head_dim != 128, ...                            */
+    KVQ_ERR_CAPACITY = 3,      /* n_tokens + T > cap_tokens, or workspace too small (host-detected)    */
+    KVQ_ERR_NNZ_OVERFLOW = 4,  /* reported through *d_status by the device when a sparse array is full */
+    KVQ_ERR_NOT_LOADED = 5,    /* kvq_lut_load has not been called on this cache                       */
+    KVQ_ERR_HIP = 6            /* a HIP runtime call failed                                            */
+} kvq_status;
+
+/*
+ * One layer's cache for one sequence.  Plain data, owned by the caller, lives in HOST memory;
+ * the pointers inside are DEVICE pointers, each 16-byte aligned.  A batch of independent
+ * sequences is an array of these (one call per sequence).
+ */
+typedef struct kvq_cache {
+    int32_t bits;           /* 2, 3 or 4                                                        */
+    int32_t head_dim;       /* 128                                                              */
+    int32_t n_kv_heads;     /* H; D = H*head_dim is the vector the method quantizes per token   */
+    int32_t n_q_heads;      /* multiple of n_kv_heads; query head q reads KV head q/(Hq/H)      */
+    int32_t k_side_v;       /* Value outliers kept per side (largest / smallest) of each token  */
+    int32_t loaded;         /* set by kvq_lut_load                                              */
+    int64_t cap_tokens;     /* multiple of 128                                                  */
+    int64_t n_tokens_k;     /* tokens appended so far; advanced by kvq_quantize_append_k        */
+    int64_t n_tokens_v;     /* likewise for kvq_quantize_append_v                               */
+    int64_t cap_nnz_k;      /* entries in k_idx / k_val                                         */
+    int64_t cap_nnz_v;      /* entries in v_idx / v_val                                         */
+    float rope_base;        /* 10000 (LLaMA / Llama-2) or 500000 (Llama-3)                      */
+    float reserved;
+    void *params;           /* kvq_params_bytes() bytes, filled by kvq_lut_load                 */
+    uint8_t *k_codes;       /* kvq_codes_bytes() bytes                                          */
+    uint8_t *v_codes;       /* kvq_codes_bytes() bytes                                          */
+    uint16_t *v_sz;         /* [cap_tokens][2] fp16 (scale, zero-point)                         */
+    uint32_t *k_ptr;        /* [cap_tokens+1]                                                   */
+    uint32_t *v_ptr;        /* [cap_tokens+1]                                                   */
+    uint16_t *k_idx, *k_val;/* [cap_nnz_k]                                                      */
+    uint16_t *v_idx, *v_val;/* [cap_nnz_v]                                                      */
+    int32_t *d_status;      /* one device word: 0, or a sticky kvq_status set by a kernel       */
+    void *workspace;        /* scratch for partial results, >= kvq_workspace_bytes()            */
+    int64_t workspace_bytes;
+} kvq_cache;
+
+/* Buffer sizes in bytes. */
+int64_t kvq_codes_bytes(int32_t bits, int32_t n_kv_heads, int64_t cap_tokens); /* = cap*D*bits/8 */
+int64_t kvq_params_bytes(int32_t n_kv_heads);
+/* Scratch needed by any call on this cache with at most max_append tokens per append call. */
+int64_t kvq_workspace_bytes(const kvq_cache *cache, int32_t max_append);
+
+const char *kvq_status_string(kvq_status s);
+const char *kvq_version(void);
+
+/*
+ * Stage one layer's quantization constants on the device (paper Sec. 3.3: one sorted 2^bits-entry
+ * signpost table per layer for Keys and one for Values, in [-1,1]; Sec. 3.1/3.4/3.6: per-channel
+ * Key scale, zero-point and lower/upper outlier thresholds calibrated offline).
+ *   h_lut_k, h_lut_v : HOST fp32 [2^bits], ascending.  Values are used as fp16 inside the mat-vec
+ *                      kernels (signposts should be fp16-representable; others are rounded there).
+ *   h_s_k, h_z_k, h_lo_k, h_hi_k : HOST fp16 bit patterns [D].
+ * Copies synchronously from the host arrays (they may be freed on return), then runs a small
+ * kernel on `stream`.  Sets cache->loaded.  Errors: INVALID_ARG, UNSUPPORTED, HIP.
+ */
+kvq_status kvq_lut_load(kvq_cache *cache, const float *h_lut_k, const float *h_lut_v,
+                        const uint16_t *h_s_k, const uint16_t *h_z_k,
+                        const uint16_t *h_lo_k, const uint16_t *h_hi_k, void *stream);
+
+/*
+ * Quantize T new pre-RoPE Key vectors and append them (paper Sec. 3.1, 3.2, 3.4, 3.7; the
+ * normalise / de-quantise equations of App. "Derivation for Quantization Error").  Per element:
+ * x_norm = (x - z_c) * (1/s_c) in fp32, code = nearest signpost (ties to the smaller index),
+ * outlier iff x < lo_c or x > hi_c; an outlier's sparse value is fp16(x - fmaf(s_c, lut[code], z_c)).
+ *   d_k_new : DEVICE fp16 [T][D], row t is token n_tokens_k + t.  1 <= T <= 4096.
+ * Writes the packed codes, k_ptr[n+1..n+T], k_idx/k_val; advances cache->n_tokens_k by T.
+ * Outliers that do not fit cap_nnz_k are dropped (highest channels of the overflowing token
+ * first) and *d_status is set to KVQ_ERR_NNZ_OVERFLOW.  Host errors: INVALID_ARG, CAPACITY,
+ * NOT_LOADED, HIP (nothing is launched, n_tokens_k unchanged).
+ */
+kvq_status kvq_quantize_append_k(kvq_cache *cache, const uint16_t *d_k_new, int32_t T, void *stream);
+
+/*
+ * Quantize T new Value vectors per token and append them (paper Sec. 3.1, 3.4, 3.6: outlier
+ * thresholds and scaling found online per token).  Per token: the k_side_v largest elements
+ * (value descending, then index ascending) and the k_side_v smallest of the rest (value
+ * ascending, then index ascending) are outliers; mx/mn of the rest give zero = fp16((mx+mn)/2),
+ * scale = fp16((mx-mn)/2) (0 -> 1); then every element is coded as for Keys with (scale, zero).
+ *   d_v_new : DEVICE fp16 [T][D].  1 <= T <= 4096.
+ * Writes codes, v_sz, v_ptr, v_idx/v_val; advances cache->n_tokens_v.  Errors as for Keys.
+ */
+kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_v_new, int32_t T, void *stream);
+
+/*
+ * Attention scores against the quantized Keys, dense and sparse parts merged in one result
+ * (paper Sec. 3.2 and App. "RoPE Equation": the rotation of position n is applied to the
+ * de-quantised Key; App. "Kernel Implementation Details": LUT mat-vec plus sparse mat-vec):
+ *   scores[q][n] = scale * sum_c q_rot[q][c] * RoPE_n(khat[n][kv(q)])[c],   0 <= n < n_tokens_k,
+ *   khat[n][c] = s_c*lut_k[code] + z_c + (sparse residual at (n,c)); RoPE pairs channel i with i+64,
+ *   theta_i = rope_base^(-2i/128), positions from 0.
+ *   d_q_rot  : DEVICE fp32 [n_q_heads][128], already rotated to the query's own position.
+ *   d_scores : DEVICE fp32 [n_q_heads][ld_scores], ld_scores >= n_tokens_k; entries n >= n_tokens_k
+ *              are not touched.
+ * fp32 accumulation; table entries are held in fp16 (relative 2^-11).  Errors: INVALID_ARG,
+ * NOT_LOADED, CAPACITY (workspace), HIP.
+ */
+kvq_status kvq_qk_matvec(const kvq_cache *cache, const float *d_q_rot, float scale,
+                         float *d_scores, int64_t ld_scores, void *stream);
+
+/*
+ * Attention output against the quantized Values, dense and sparse parts merged (paper App.
+ * "Kernel Implementation Details"):
+ *   out[q][c] = sum_{n < n_tokens_v} probs[q][n] * vhat[n][kv(q)*128 + c],
+ *   vhat[n][c] = s_n*lut_v[code] + z_n + (sparse residual at (n,c)).
+ *   d_probs : DEVICE fp32 [n_q_heads][ld_probs];  d_out : DEVICE fp32 [n_q_heads][128].
+ * fp32 accumulation in a fixed order (results are run-to-run identical).  Uses cache->workspace.
+ */
+kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs, int64_t ld_probs,
+                         float *d_out, void *stream);
+
+/* ---- helpers beyond the five calls above -------------------------------------------------- */
+
+/*
+ * Row-wise softmax in fp32 with max subtraction: probs[q][n] = exp(x[q][n]-max_q)/sum, n < n_cols.
+ * d_workspace: at least kvq_softmax_workspace_bytes(n_rows, n_cols) bytes.  In-place allowed.
+ */
+int64_t kvq_softmax_workspace_bytes(int32_t n_rows, int64_t n_cols);
+kvq_status kvq_softmax_f32(const float *d_x, int64_t ld_x, float *d_probs, int64_t ld_probs,
+                           int32_t n_rows, int64_t n_cols, void *d_workspace, int64_t workspace_bytes,
+                           void *stream);
+
+/*
+ * Same-GPU fp16-cache baselines (what the quantized path is compared against):
+ *   scores[q][n] = scale * sum_c q[q][c] * K16[n][kv(q)*128+c]   (K16 fp16 [L][D], already rotated)
+ *   out[q][c]    = sum_n probs[q][n] * V16[n][kv(q)*128+c]
+ * d_workspace for the PV baseline: kvq_fp16_pv_workspace_bytes(n_q_heads, L) bytes.
+ */
+kvq_status kvq_fp16_qk_matvec(const uint16_t *d_k16, int64_t L, int32_t n_kv_heads, int32_t n_q_heads,
+                              const float *d_q, float scale, float *d_scores, int64_t ld_scores,
+                              void *stream);
+int64_t kvq_fp16_pv_workspace_bytes(int32_t n_q_heads, int64_t L);
+kvq_status kvq_fp16_pv_matvec(const uint16_t *d_v16, int64_t L, int32_t n_kv_heads, int32_t n_q_heads,
+                              const float *d_probs, int64_t ld_probs, float *d_out,
+                              void *d_workspace, int64_t workspace_bytes, void *stream);
+
+/*
+ * Timing aid: runs `fn`-independent HIP events on `stream`.  kvq_event_* wrap hipEvent so that a
+ * Python caller can time work on the stream the kernels are launched on without another binding.
+ */
+kvq_status kvq_event_create(void **event);
+kvq_status kvq_event_record(void *event, void *stream);
+kvq_status kvq_event_elapsed_ms(void *start, void *stop, float *ms); /* synchronizes on stop */
+kvq_status kvq_event_destroy(void *event);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVQ_H */

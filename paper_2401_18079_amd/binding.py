@@ -1,0 +1,270 @@
+"""ctypes binding of libkvq.so: argument marshalling only, same names as the C ABI (include/kvq.h)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libkvq.so")
+_lib = None
+
+
+class KvqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        msg = kvq_status_string(status) if _lib is not None else str(status)
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class _CCache(C.Structure):
+    _fields_ = [
+        ("bits", C.c_int32), ("head_dim", C.c_int32), ("n_kv_heads", C.c_int32), ("n_q_heads", C.c_int32),
+        ("k_side_v", C.c_int32), ("loaded", C.c_int32),
+        ("cap_tokens", C.c_int64), ("n_tokens_k", C.c_int64), ("n_tokens_v", C.c_int64),
+        ("cap_nnz_k", C.c_int64), ("cap_nnz_v", C.c_int64),
+        ("rope_base", C.c_float), ("reserved", C.c_float),
+        ("params", C.c_void_p), ("k_codes", C.c_void_p), ("v_codes", C.c_void_p), ("v_sz", C.c_void_p),
+        ("k_ptr", C.c_void_p), ("v_ptr", C.c_void_p),
+        ("k_idx", C.c_void_p), ("k_val", C.c_void_p), ("v_idx", C.c_void_p), ("v_val", C.c_void_p),
+        ("d_status", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64),
+    ]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libkvq.so.  There is no fallback: without the built HIP library nothing here works."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it first (python -m paper_2401_18079_amd.build)")
+    lib = C.CDLL(_LIB_PATH)
+    P, V, I32, I64, F = C.POINTER(_CCache), C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    sigs = {
+        "kvq_codes_bytes": (I64, [I32, I32, I64]),
+        "kvq_params_bytes": (I64, [I32]),
+        "kvq_workspace_bytes": (I64, [P, I32]),
+        "kvq_status_string": (C.c_char_p, [C.c_int]),
+        "kvq_version": (C.c_char_p, []),
+        "kvq_lut_load": (C.c_int, [P, V, V, V, V, V, V, V]),
+        "kvq_quantize_append_k": (C.c_int, [P, V, I32, V]),
+        "kvq_quantize_append_v": (C.c_int, [P, V, I32, V]),
+        "kvq_qk_matvec": (C.c_int, [P, V, F, V, I64, V]),
+        "kvq_pv_matvec": (C.c_int, [P, V, I64, V, V]),
+        "kvq_softmax_workspace_bytes": (I64, [I32, I64]),
+        "kvq_softmax_f32": (C.c_int, [V, I64, V, I64, I32, I64, V, I64, V]),
+        "kvq_fp16_qk_matvec": (C.c_int, [V, I64, I32, I32, V, F, V, I64, V]),
+        "kvq_fp16_pv_workspace_bytes": (I64, [I32, I64]),
+        "kvq_fp16_pv_matvec": (C.c_int, [V, I64, I32, I32, V, I64, V, V, I64, V]),
+        "kvq_event_create": (C.c_int, [C.POINTER(V)]),
+        "kvq_event_record": (C.c_int, [V, V]),
+        "kvq_event_elapsed_ms": (C.c_int, [V, V, C.POINTER(F)]),
+        "kvq_event_destroy": (C.c_int, [V]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+EXPORTED_SYMBOLS = [
+    "kvq_codes_bytes", "kvq_params_bytes", "kvq_workspace_bytes", "kvq_status_string", "kvq_version",
+    "kvq_lut_load", "kvq_quantize_append_k", "kvq_quantize_append_v", "kvq_qk_matvec", "kvq_pv_matvec",
+    "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
+    "kvq_fp16_pv_matvec", "kvq_event_create", "kvq_event_record", "kvq_event_elapsed_ms", "kvq_event_destroy",
+]
+
+
+def _stream_ptr(stream=None):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise KvqError(status, where)
+
+
+def kvq_status_string(status: int) -> str:
+    return load_library().kvq_status_string(int(status)).decode()
+
+
+def kvq_version() -> str:
+    return load_library().kvq_version().decode()
+
+
+def kvq_codes_bytes(bits: int, n_kv_heads: int, cap_tokens: int) -> int:
+    return int(load_library().kvq_codes_bytes(bits, n_kv_heads, cap_tokens))
+
+
+def kvq_params_bytes(n_kv_heads: int) -> int:
+    return int(load_library().kvq_params_bytes(n_kv_heads))
+
+
+def kvq_workspace_bytes(cache: "KvqCache", max_append: int) -> int:
+    return int(load_library().kvq_workspace_bytes(C.byref(cache.c), max_append))
+
+
+class KvqCache:
+    """Device buffers of one layer's cache for one sequence (torch tensors) plus the C descriptor."""
+
+    def __init__(self, bits, n_kv_heads, n_q_heads, cap_tokens, k_side_v, rope_base, cap_nnz_k, cap_nnz_v=None,
+                 max_append=4096, device="cuda:0"):
+        load_library()
+        dev = torch.device(device)
+        D = n_kv_heads * 128
+        if cap_nnz_v is None:
+            cap_nnz_v = max(8, cap_tokens * 2 * k_side_v)
+        cap_nnz_k = max(8, int(cap_nnz_k))
+        z = lambda n, dt: torch.zeros(int(n), dtype=dt, device=dev)
+        self.params = z(kvq_params_bytes(n_kv_heads), torch.uint8)
+        nbytes = kvq_codes_bytes(bits, n_kv_heads, cap_tokens)
+        self.k_codes, self.v_codes = z(nbytes, torch.uint8), z(nbytes, torch.uint8)
+        self.v_sz = z(cap_tokens * 2, torch.int16)
+        self.k_ptr, self.v_ptr = z(cap_tokens + 1, torch.int32), z(cap_tokens + 1, torch.int32)
+        self.k_idx, self.k_val = z(cap_nnz_k, torch.int16), z(cap_nnz_k, torch.int16)
+        self.v_idx, self.v_val = z(cap_nnz_v, torch.int16), z(cap_nnz_v, torch.int16)
+        self.d_status = z(4, torch.int32)
+        c = _CCache()
+        c.bits, c.head_dim, c.n_kv_heads, c.n_q_heads = bits, 128, n_kv_heads, n_q_heads
+        c.k_side_v, c.loaded = k_side_v, 0
+        c.cap_tokens, c.n_tokens_k, c.n_tokens_v = cap_tokens, 0, 0
+        c.cap_nnz_k, c.cap_nnz_v = cap_nnz_k, int(cap_nnz_v)
+        c.rope_base = float(rope_base)
+        for name in ("params", "k_codes", "v_codes", "v_sz", "k_ptr", "v_ptr", "k_idx", "k_val", "v_idx", "v_val",
+                     "d_status"):
+            setattr(c, name, getattr(self, name).data_ptr())
+        self.c = c
+        self.D, self.device = D, dev
+        self.workspace = z(int(load_library().kvq_workspace_bytes(C.byref(c), max_append)), torch.uint8)
+        c.workspace, c.workspace_bytes = self.workspace.data_ptr(), self.workspace.numel()
+
+    @property
+    def n_tokens_k(self):
+        return int(self.c.n_tokens_k)
+
+    @property
+    def n_tokens_v(self):
+        return int(self.c.n_tokens_v)
+
+    def status(self) -> int:
+        return int(self.d_status[0].item())
+
+
+def _host_u16(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    assert a.dtype == np.uint16
+    return a
+
+
+def kvq_lut_load(cache: KvqCache, lut_k, lut_v, s_k, z_k, lo_k, hi_k, stream=None):
+    lk = np.ascontiguousarray(lut_k, dtype=np.float32)
+    lv = np.ascontiguousarray(lut_v, dtype=np.float32)
+    arrs = [_host_u16(a) for a in (s_k, z_k, lo_k, hi_k)]
+    assert lk.size == 1 << cache.c.bits and lv.size == lk.size and all(a.size == cache.D for a in arrs)
+    st = load_library().kvq_lut_load(C.byref(cache.c), lk.ctypes.data, lv.ctypes.data,
+                                     *[a.ctypes.data for a in arrs], _stream_ptr(stream))
+    _check(st, "kvq_lut_load")
+
+
+def _fp16_rows(cache: KvqCache, x: torch.Tensor):
+    assert x.is_cuda and x.dtype == torch.float16 and x.dim() == 2 and x.shape[1] == cache.D and x.is_contiguous()
+    return x
+
+
+def kvq_quantize_append_k(cache: KvqCache, k_new: torch.Tensor, stream=None):
+    x = _fp16_rows(cache, k_new)
+    _check(load_library().kvq_quantize_append_k(C.byref(cache.c), x.data_ptr(), x.shape[0], _stream_ptr(stream)),
+           "kvq_quantize_append_k")
+
+
+def kvq_quantize_append_v(cache: KvqCache, v_new: torch.Tensor, stream=None):
+    x = _fp16_rows(cache, v_new)
+    _check(load_library().kvq_quantize_append_v(C.byref(cache.c), x.data_ptr(), x.shape[0], _stream_ptr(stream)),
+           "kvq_quantize_append_v")
+
+
+def kvq_qk_matvec(cache: KvqCache, q_rot: torch.Tensor, scale: float, scores: torch.Tensor, stream=None):
+    assert q_rot.is_cuda and q_rot.dtype == torch.float32 and q_rot.is_contiguous()
+    assert q_rot.shape == (cache.c.n_q_heads, 128)
+    assert scores.is_cuda and scores.dtype == torch.float32 and scores.dim() == 2 and scores.stride(1) == 1
+    assert scores.shape[0] == cache.c.n_q_heads
+    _check(load_library().kvq_qk_matvec(C.byref(cache.c), q_rot.data_ptr(), float(scale), scores.data_ptr(),
+                                        scores.stride(0), _stream_ptr(stream)), "kvq_qk_matvec")
+
+
+def kvq_pv_matvec(cache: KvqCache, probs: torch.Tensor, out: torch.Tensor, stream=None):
+    assert probs.is_cuda and probs.dtype == torch.float32 and probs.dim() == 2 and probs.stride(1) == 1
+    assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.shape == (cache.c.n_q_heads, 128)
+    _check(load_library().kvq_pv_matvec(C.byref(cache.c), probs.data_ptr(), probs.stride(0), out.data_ptr(),
+                                        _stream_ptr(stream)), "kvq_pv_matvec")
+
+
+def kvq_softmax_f32(x: torch.Tensor, probs: torch.Tensor, n_cols: int, workspace: torch.Tensor, stream=None):
+    assert x.is_cuda and x.dtype == torch.float32 and x.stride(1) == 1 and probs.stride(1) == 1
+    _check(load_library().kvq_softmax_f32(x.data_ptr(), x.stride(0), probs.data_ptr(), probs.stride(0), x.shape[0],
+                                          int(n_cols), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                          _stream_ptr(stream)), "kvq_softmax_f32")
+
+
+def kvq_softmax_workspace_bytes(n_rows: int, n_cols: int) -> int:
+    return int(load_library().kvq_softmax_workspace_bytes(n_rows, n_cols))
+
+
+def kvq_fp16_qk_matvec(k16: torch.Tensor, n_kv_heads: int, n_q_heads: int, q: torch.Tensor, scale: float,
+                       scores: torch.Tensor, stream=None):
+    assert k16.dtype == torch.float16 and k16.is_contiguous() and k16.shape[1] == n_kv_heads * 128
+    _check(load_library().kvq_fp16_qk_matvec(k16.data_ptr(), k16.shape[0], n_kv_heads, n_q_heads, q.data_ptr(),
+                                             float(scale), scores.data_ptr(), scores.stride(0), _stream_ptr(stream)),
+           "kvq_fp16_qk_matvec")
+
+
+def kvq_fp16_pv_workspace_bytes(n_q_heads: int, L: int) -> int:
+    return int(load_library().kvq_fp16_pv_workspace_bytes(n_q_heads, L))
+
+
+def kvq_fp16_pv_matvec(v16: torch.Tensor, n_kv_heads: int, n_q_heads: int, probs: torch.Tensor, out: torch.Tensor,
+                       workspace: torch.Tensor, stream=None):
+    assert v16.dtype == torch.float16 and v16.is_contiguous() and v16.shape[1] == n_kv_heads * 128
+    _check(load_library().kvq_fp16_pv_matvec(v16.data_ptr(), v16.shape[0], n_kv_heads, n_q_heads, probs.data_ptr(),
+                                             probs.stride(0), out.data_ptr(), workspace.data_ptr(),
+                                             workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+           "kvq_fp16_pv_matvec")
+
+
+class HipEventTimer:
+    """HIP events recorded on the stream the kernels are launched on (kvq_event_* of the C ABI)."""
+
+    def __init__(self):
+        lib = load_library()
+        self._a, self._b = C.c_void_p(), C.c_void_p()
+        _check(lib.kvq_event_create(C.byref(self._a)), "kvq_event_create")
+        _check(lib.kvq_event_create(C.byref(self._b)), "kvq_event_create")
+
+    def start(self, stream=None):
+        _check(load_library().kvq_event_record(self._a, _stream_ptr(stream)), "kvq_event_record")
+
+    def stop(self, stream=None):
+        _check(load_library().kvq_event_record(self._b, _stream_ptr(stream)), "kvq_event_record")
+
+    def elapsed_ms(self) -> float:
+        ms = C.c_float()
+        _check(load_library().kvq_event_elapsed_ms(self._a, self._b, C.byref(ms)), "kvq_event_elapsed_ms")
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            lib = load_library()
+            lib.kvq_event_destroy(self._a)
+            lib.kvq_event_destroy(self._b)
+        except Exception:
+            pass

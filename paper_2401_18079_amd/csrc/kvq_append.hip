@@ -1,0 +1,401 @@
+// Online quantize-and-append of new Key / Value vectors (paper Sec. 3.1, 3.4, 3.6, 3.7).
+//
+// One workgroup per new token.  Every fp32 step is a single explicitly rounded operation
+// (this file is compiled with floating-point contraction off) so that codes, outlier indices
+// and fp16 residuals are reproducible bit for bit.
+#include "kvq_common.hpp"
+
+namespace {
+
+constexpr int NT = 256;            // threads per workgroup
+constexpr int NW = NT / 64;        // wavefronts per workgroup
+
+// Exclusive rank of this thread's flag among all flags of the workgroup, in thread order, plus
+// the workgroup total.  `wave_tot` is a shared array of NW words.  Contains two barriers.
+__device__ inline uint32_t block_rank(bool flag, uint32_t *wave_tot, uint32_t &total)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    unsigned long long b = __ballot(flag);
+    uint32_t prefix = __popcll(b & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_tot[w] = __popcll(b);
+    __syncthreads();
+    uint32_t before = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        uint32_t t = wave_tot[i];
+        if (i < w) before += t;
+        tot += t;
+    }
+    __syncthreads();
+    total = tot;
+    return before + prefix;
+}
+
+// Number of Key outliers of each new token (threshold test only).
+__global__ __launch_bounds__(NT) void kvq_k_count(const void *params, int D, const uint16_t *k_new, uint32_t *cnt)
+{
+    __shared__ uint32_t red[NW];
+    KvqParamsView pv = kvq_params_view(params, D);
+    const int t = blockIdx.x;
+    uint32_t mine = 0;
+    for (int c = threadIdx.x; c < D; c += NT) {
+        float x = kvq_h2f(k_new[(int64_t)t * D + c]);
+        mine += (x < pv.lo[c] || x > pv.hi[c]) ? 1u : 0u;
+    }
+    for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t s = 0;
+        for (int i = 0; i < NW; ++i) s += red[i];
+        cnt[t] = s;
+    }
+}
+
+// ptr[n0+1+t] = min(ptr[n0] + cnt[0] + ... + cnt[t], cap_nnz); one workgroup, T <= 4096.
+__global__ __launch_bounds__(1024) void kvq_ptr_scan(uint32_t *ptr, int64_t n0, int T, const uint32_t *cnt,
+                                                     int64_t cap_nnz, int32_t *d_status)
+{
+    __shared__ uint32_t part[1024];
+    const int tid = threadIdx.x;
+    uint32_t v[4], s = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int t = tid * 4 + j;
+        v[j] = (t < T) ? cnt[t] : 0u;
+        s += v[j];
+    }
+    part[tid] = s;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        uint32_t add = (tid >= o) ? part[tid - o] : 0u;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    uint64_t run = (uint64_t)ptr[n0] + (part[tid] - s);
+    bool over = false;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int t = tid * 4 + j;
+        run += v[j];
+        if (t < T) {
+            uint64_t p = run;
+            if (p > (uint64_t)cap_nnz) { p = (uint64_t)cap_nnz; over = true; }
+            ptr[n0 + 1 + t] = (uint32_t)p;
+        }
+    }
+    if (over) atomicExch(d_status, (int32_t)KVQ_ERR_NNZ_OVERFLOW);
+}
+
+// OR one field of `width` bits into a little-endian bit stream held as dwords in shared memory.
+__device__ inline void stream_or(uint32_t *words, int bit, uint32_t value, int width)
+{
+    int w = bit >> 5, sh = bit & 31;
+    atomicOr(&words[w], value << sh);
+    if (sh + width > 32) atomicOr(&words[w + 1], value >> (32 - sh));
+}
+
+// Quantize, pack and append the Keys of one new token per workgroup.
+// If `single` the token's outlier count is written to ptr[n+1] here; otherwise ptr[] was already
+// filled by kvq_ptr_scan and is only read.
+template <int BITS>
+__global__ __launch_bounds__(NT) void kvq_k_quant(const void *params, int D, int64_t cap, int64_t n0,
+                                                  const uint16_t *k_new, uint8_t *k_codes, uint32_t *k_ptr,
+                                                  uint16_t *k_idx, uint16_t *k_val, int64_t cap_nnz,
+                                                  int single, int32_t *d_status)
+{
+    constexpr int NE = 1 << BITS;
+    constexpr int CW = 4 * BITS;                 // dwords per chunk
+    __shared__ uint8_t codes_s[NT];
+    __shared__ uint32_t chunk_s[2][CW + 1];
+    __shared__ uint32_t wave_tot[NW];
+    KvqParamsView pv = kvq_params_view(params, D);
+    float lut[NE];
+#pragma unroll
+    for (int j = 0; j < NE; ++j) lut[j] = pv.hdr->lut_k[j];
+
+    const int t = blockIdx.x, tid = threadIdx.x;
+    const int64_t n = n0 + t;
+    const uint32_t base = k_ptr[n];
+    uint32_t running = 0;
+    bool overflow = false;
+    for (int c0 = 0; c0 < D; c0 += NT) {
+        const int c = c0 + tid;
+        bool is_out = false;
+        uint16_t resid = 0;
+        if (c < D) {
+            float x = kvq_h2f(k_new[(int64_t)t * D + c]);
+            float z = pv.z[c], s = pv.s[c];
+            float diff = x - z;
+            float xn = diff * pv.rinv[c];
+            float sp;
+            int code = kvq_nearest<NE>(lut, xn, sp);
+            float deq = __builtin_fmaf(s, sp, z);
+            is_out = (x < pv.lo[c]) || (x > pv.hi[c]);
+            resid = kvq_f2h_rn(x - deq);
+            codes_s[tid] = (uint8_t)code;
+        }
+        if (tid < 2 * (CW + 1)) (&chunk_s[0][0])[tid] = 0;
+        uint32_t tot;
+        uint32_t rank = running + block_rank(is_out, wave_tot, tot);   // barriers inside
+        running += tot;
+        if (is_out) {
+            uint64_t pos = (uint64_t)base + rank;
+            if (pos < (uint64_t)cap_nnz) { k_idx[pos] = (uint16_t)c; k_val[pos] = resid; }
+            else overflow = true;
+        }
+        // pack the (up to) two heads covered by this block of 256 channels
+        const int heads_here = (D - c0 >= NT) ? 2 : (D - c0) / KVQ_HEAD_DIM;
+        if (tid < 64 * heads_here) {
+            int hh = tid >> 6, i = tid & 63;
+            uint32_t field = (uint32_t)codes_s[hh * 128 + i] | ((uint32_t)codes_s[hh * 128 + i + 64] << BITS);
+            stream_or(chunk_s[hh], i * 2 * BITS, field, 2 * BITS);
+        }
+        __syncthreads();
+        if (tid < CW * heads_here) {
+            int hh = tid / CW, wd = tid % CW;
+            int64_t off = kvq_k_piece0(BITS, cap, n, c0 / KVQ_HEAD_DIM + hh) + (wd >> 2) * 1024 + (wd & 3) * 4;
+            *(uint32_t *)(k_codes + off) = chunk_s[hh][wd];
+        }
+        __syncthreads();
+    }
+    if (single && tid == 0) {
+        uint64_t p = (uint64_t)base + running;
+        k_ptr[n + 1] = (uint32_t)(p > (uint64_t)cap_nnz ? (uint64_t)cap_nnz : p);
+    }
+    if (overflow || (single && tid == 0 && (uint64_t)base + running > (uint64_t)cap_nnz))
+        atomicExch(d_status, (int32_t)KVQ_ERR_NNZ_OVERFLOW);
+}
+
+// ---- Values -------------------------------------------------------------------------------
+
+// Order-preserving 16-bit key of an fp16 bit pattern (-0 is treated as +0).
+__device__ inline uint32_t order_key(uint16_t h)
+{
+    if (h == 0x8000u) h = 0;
+    return (h & 0x8000u) ? (uint32_t)(uint16_t)~h : (uint32_t)(h | 0x8000u);
+}
+
+// Workgroup-wide selection of the `k` largest keys among elements with state[c]==0, where the key
+// of element c is keys[c] ^ flip (flip = 0xFFFF turns it into a selection of the k smallest).
+// Marks the selected elements with `mark`; equal keys are taken in ascending index order.
+__device__ void select_top(const uint16_t *keys, uint8_t *state, int D, int k, uint32_t flip, uint8_t mark,
+                           uint32_t *hist, uint32_t *sh, uint32_t *wave_tot)
+{
+    const int tid = threadIdx.x;
+    // level 1: high byte
+    hist[tid] = 0;
+    __syncthreads();
+    for (int c = tid; c < D; c += NT)
+        if (state[c] == 0) atomicAdd(&hist[((keys[c] ^ flip) & 0xFFFFu) >> 8], 1u);
+    __syncthreads();
+    {
+        uint32_t above = 0;                       // elements in bins strictly above bin `tid`
+        for (int b = tid + 1; b < 256; ++b) above += hist[b];
+        if (above < (uint32_t)k && above + hist[tid] >= (uint32_t)k) { sh[0] = tid; sh[1] = above; }
+    }
+    __syncthreads();
+    const uint32_t bin_hi = sh[0], above_hi = sh[1];
+    __syncthreads();
+    // level 2: low byte inside the selected high bin
+    hist[tid] = 0;
+    __syncthreads();
+    for (int c = tid; c < D; c += NT) {
+        uint32_t key = (keys[c] ^ flip) & 0xFFFFu;
+        if (state[c] == 0 && (key >> 8) == bin_hi) atomicAdd(&hist[key & 255u], 1u);
+    }
+    __syncthreads();
+    {
+        uint32_t above = above_hi;
+        for (int b = tid + 1; b < 256; ++b) above += hist[b];
+        if (above < (uint32_t)k && above + hist[tid] >= (uint32_t)k) { sh[0] = (bin_hi << 8) | tid; sh[1] = above; }
+    }
+    __syncthreads();
+    const uint32_t tau = sh[0];
+    const uint32_t need_eq = (uint32_t)k - sh[1];  // how many elements equal to tau are taken
+    __syncthreads();
+    uint32_t running = 0;
+    for (int c0 = 0; c0 < D; c0 += NT) {
+        const int c = c0 + tid;
+        bool cand = false, eq = false, gt = false;
+        if (c < D && state[c] == 0) {
+            uint32_t key = (keys[c] ^ flip) & 0xFFFFu;
+            gt = key > tau;
+            eq = key == tau;
+            cand = true;
+        }
+        uint32_t tot;
+        uint32_t rank = running + block_rank(eq, wave_tot, tot);
+        running += tot;
+        if (cand && (gt || (eq && rank < need_eq))) state[c] = mark;
+    }
+    __syncthreads();
+}
+
+template <int BITS>
+__global__ __launch_bounds__(NT) void kvq_v_quant(const void *params, int D, int64_t cap, int64_t n0, int k_side,
+                                                  const uint16_t *v_new, uint8_t *v_codes, uint16_t *v_sz,
+                                                  uint32_t *v_ptr, uint16_t *v_idx, uint16_t *v_val,
+                                                  int64_t cap_nnz, int32_t *d_status)
+{
+    constexpr int NE = 1 << BITS;
+    constexpr int CW = 4 * BITS;
+    extern __shared__ uint8_t dyn[];              // keys: 2*D bytes, state: D bytes
+    uint16_t *keys = (uint16_t *)dyn;
+    uint8_t *state = dyn + 2 * (size_t)D;
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sh[2];
+    __shared__ uint32_t wave_tot[NW];
+    __shared__ float redmx[NW], redmn[NW];
+    __shared__ uint8_t codes_s[NT];
+    __shared__ uint32_t bits_s[4][CW + 1], mask_s[4][CW + 1];
+
+    KvqParamsView pv = kvq_params_view(params, D);
+    float lut[NE];
+#pragma unroll
+    for (int j = 0; j < NE; ++j) lut[j] = pv.hdr->lut_v[j];
+    const int t = blockIdx.x, tid = threadIdx.x;
+    const int64_t n = n0 + t;
+    const uint16_t *x16 = v_new + (int64_t)t * D;
+
+    for (int c = tid; c < D; c += NT) { keys[c] = (uint16_t)order_key(x16[c]); state[c] = 0; }
+    __syncthreads();
+    if (k_side > 0) {
+        select_top(keys, state, D, k_side, 0u, 1, hist, sh, wave_tot);        // k largest
+        select_top(keys, state, D, k_side, 0xFFFFu, 2, hist, sh, wave_tot);   // k smallest of the rest
+    }
+    // range of the remaining elements
+    float mx = -INFINITY, mn = INFINITY;
+    for (int c = tid; c < D; c += NT)
+        if (state[c] == 0) { float x = kvq_h2f(x16[c]); mx = fmaxf(mx, x); mn = fminf(mn, x); }
+    for (int o = 32; o > 0; o >>= 1) { mx = fmaxf(mx, __shfl_xor(mx, o)); mn = fminf(mn, __shfl_xor(mn, o)); }
+    if ((tid & 63) == 0) { redmx[tid >> 6] = mx; redmn[tid >> 6] = mn; }
+    __syncthreads();
+    mx = redmx[0]; mn = redmn[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) { mx = fmaxf(mx, redmx[i]); mn = fminf(mn, redmn[i]); }
+    const float sum = mx + mn, dif = mx - mn;
+    uint16_t zb = kvq_f2h_rn(sum * 0.5f), sb = kvq_f2h_rn(dif * 0.5f);
+    float zf = kvq_h2f(zb), sf = kvq_h2f(sb);
+    if (sf == 0.0f) { sf = 1.0f; sb = 0x3c00u; }
+    const float rinv = __fdiv_rn(1.0f, sf);
+    if (tid == 0) { v_sz[n * 2 + 0] = sb; v_sz[n * 2 + 1] = zb; }
+
+    const uint32_t base = v_ptr[n0] + (uint32_t)t * 2u * (uint32_t)k_side;
+    const int parity = (int)(n & 1);
+    uint32_t running = 0;
+    bool overflow = false;
+    for (int c0 = 0; c0 < D; c0 += NT) {
+        const int c = c0 + tid;
+        bool is_out = false;
+        uint16_t resid = 0;
+        if (c < D) {
+            float x = kvq_h2f(x16[c]);
+            float diff = x - zf;
+            float xn = diff * rinv;
+            float sp;
+            int code = kvq_nearest<NE>(lut, xn, sp);
+            float deq = __builtin_fmaf(sf, sp, zf);
+            is_out = state[c] != 0;
+            resid = kvq_f2h_rn(x - deq);
+            codes_s[tid] = (uint8_t)code;
+        }
+        if (tid < 4 * (CW + 1)) { (&bits_s[0][0])[tid] = 0; (&mask_s[0][0])[tid] = 0; }
+        uint32_t tot;
+        uint32_t rank = running + block_rank(is_out, wave_tot, tot);
+        running += tot;
+        if (is_out) {
+            uint64_t pos = (uint64_t)base + rank;
+            if (pos < (uint64_t)cap_nnz) { v_idx[pos] = (uint16_t)c; v_val[pos] = resid; }
+            else overflow = true;
+        }
+        // this block of 256 channels covers up to four (head, half) chunks of 64 fields each
+        const int chunks_here = (D - c0 >= NT) ? 4 : (D - c0) / 64;
+        if (tid < 64 * chunks_here) {
+            int q = tid >> 6, j = tid & 63;
+            stream_or(bits_s[q], j * 2 * BITS + parity * BITS, (uint32_t)codes_s[tid], BITS);
+            stream_or(mask_s[q], j * 2 * BITS + parity * BITS, (uint32_t)(NE - 1), BITS);
+        }
+        __syncthreads();
+        if (tid < CW * chunks_here) {
+            int q = tid / CW, wd = tid % CW;
+            int ch0 = c0 + q * 64;
+            int64_t off = kvq_v_piece0(BITS, cap, n >> 1, ch0 / KVQ_HEAD_DIM, (ch0 >> 6) & 1) + (wd >> 2) * 1024 + (wd & 3) * 4;
+            uint32_t *p = (uint32_t *)(v_codes + off);
+            const uint32_t m = mask_s[q][wd], b = bits_s[q][wd];
+            uint32_t old = *p, assumed;
+            do {                                   // the partner token of the pair may be written concurrently
+                assumed = old;
+                old = atomicCAS(p, assumed, (assumed & ~m) | b);
+            } while (old != assumed);
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        uint64_t p = (uint64_t)base + 2u * (uint32_t)k_side;
+        if (p > (uint64_t)cap_nnz) { p = (uint64_t)cap_nnz; overflow = true; }
+        v_ptr[n + 1] = (uint32_t)p;
+    }
+    if (overflow) atomicExch(d_status, (int32_t)KVQ_ERR_NNZ_OVERFLOW);
+}
+
+}  // namespace
+
+static kvq_status append_checks(const kvq_cache *cache, const void *src, int32_t T, int64_t n_now)
+{
+    kvq_status st = kvq_check_cache(cache);
+    if (st != KVQ_OK) return st;
+    if (!cache->loaded) return KVQ_ERR_NOT_LOADED;
+    if (!src || ((uintptr_t)src & 1) || T < 1 || T > KVQ_MAX_APPEND) return KVQ_ERR_INVALID_ARG;
+    if (n_now + T > cache->cap_tokens) return KVQ_ERR_CAPACITY;
+    return KVQ_OK;
+}
+
+extern "C" kvq_status kvq_quantize_append_k(kvq_cache *cache, const uint16_t *d_k_new, int32_t T, void *stream)
+{
+    kvq_status st = append_checks(cache, d_k_new, T, cache ? cache->n_tokens_k : 0);
+    if (st != KVQ_OK) return st;
+    const int D = cache->n_kv_heads * KVQ_HEAD_DIM;
+    hipStream_t s = (hipStream_t)stream;
+    const int single = (T == 1);
+    if (!single) {
+        if (!cache->workspace || cache->workspace_bytes < (int64_t)T * 4) return KVQ_ERR_CAPACITY;
+        uint32_t *cnt = (uint32_t *)cache->workspace;
+        kvq_k_count<<<T, NT, 0, s>>>(cache->params, D, d_k_new, cnt);
+        kvq_ptr_scan<<<1, 1024, 0, s>>>(cache->k_ptr, cache->n_tokens_k, T, cnt, cache->cap_nnz_k, cache->d_status);
+    }
+#define LAUNCH_K(B)                                                                                            \
+    kvq_k_quant<B><<<T, NT, 0, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_k, d_k_new,             \
+                                    cache->k_codes, cache->k_ptr, cache->k_idx, cache->k_val, cache->cap_nnz_k, \
+                                    single, cache->d_status)
+    if (cache->bits == 2) LAUNCH_K(2);
+    else if (cache->bits == 3) LAUNCH_K(3);
+    else LAUNCH_K(4);
+#undef LAUNCH_K
+    KVQ_HIP_CHECK(hipGetLastError());
+    cache->n_tokens_k += T;
+    return KVQ_OK;
+}
+
+extern "C" kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_v_new, int32_t T, void *stream)
+{
+    kvq_status st = append_checks(cache, d_v_new, T, cache ? cache->n_tokens_v : 0);
+    if (st != KVQ_OK) return st;
+    const int D = cache->n_kv_heads * KVQ_HEAD_DIM;
+    if (cache->k_side_v < 0 || 2 * (int64_t)cache->k_side_v >= D) return KVQ_ERR_INVALID_ARG;
+    if (D > 16384) return KVQ_ERR_UNSUPPORTED;       // the per-token selection keeps the vector in LDS
+    hipStream_t s = (hipStream_t)stream;
+    const size_t dyn = 3 * (size_t)D;
+#define LAUNCH_V(B)                                                                                           \
+    kvq_v_quant<B><<<T, NT, dyn, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v, cache->k_side_v, \
+                                      d_v_new, cache->v_codes, cache->v_sz, cache->v_ptr, cache->v_idx,        \
+                                      cache->v_val, cache->cap_nnz_v, cache->d_status)
+    if (cache->bits == 2) LAUNCH_V(2);
+    else if (cache->bits == 3) LAUNCH_V(3);
+    else LAUNCH_V(4);
+#undef LAUNCH_V
+    KVQ_HIP_CHECK(hipGetLastError());
+    cache->n_tokens_v += T;
+    return KVQ_OK;
+}

@@ -1,0 +1,108 @@
+// Shared declarations of the kvq HIP library (gfx950 only): parameter-block layout, storage-format
+// addressing, small device helpers.  Nothing in this file is shared with the CPU oracle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/kvq.h"
+
+#define KVQ_HEAD_DIM 128
+#define KVQ_MAX_APPEND 4096
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+// ---- device parameter block written by kvq_lut_load --------------------------------------
+// Fixed header followed by per-channel arrays of D entries each.
+struct KvqParamsHeader {
+    float lut_k[16];      // sorted signposts, Keys
+    float lut_v[16];      // sorted signposts, Values
+    float rope_vh[64];    // theta_i / (2 pi), fp32 head of a two-term split
+    float rope_vl[64];    // fp32 tail: (theta_i / (2 pi)) - rope_vh[i]
+    int32_t D;
+    int32_t bits;
+    int32_t pad[30];
+};
+static_assert(sizeof(KvqParamsHeader) == 768, "header layout");
+
+struct KvqParamsView {          // device pointers into the block
+    const KvqParamsHeader *hdr;
+    const uint16_t *s16, *z16, *lo16, *hi16;   // raw fp16 inputs [D]
+    const float *s, *z, *rinv, *lo, *hi;       // fp32 expansions [D]; rinv = 1.0f / s (IEEE)
+};
+
+__host__ __device__ inline int64_t kvq_params_bytes_D(int D) { return 768 + (int64_t)D * (4 * 2 + 5 * 4); }
+
+__host__ __device__ inline KvqParamsView kvq_params_view(const void *block, int D)
+{
+    KvqParamsView v;
+    const char *p = (const char *)block;
+    v.hdr = (const KvqParamsHeader *)p;
+    p += 768;
+    v.s16 = (const uint16_t *)p; p += 2 * (int64_t)D;
+    v.z16 = (const uint16_t *)p; p += 2 * (int64_t)D;
+    v.lo16 = (const uint16_t *)p; p += 2 * (int64_t)D;
+    v.hi16 = (const uint16_t *)p; p += 2 * (int64_t)D;
+    v.s = (const float *)p; p += 4 * (int64_t)D;
+    v.z = (const float *)p; p += 4 * (int64_t)D;
+    v.rinv = (const float *)p; p += 4 * (int64_t)D;
+    v.lo = (const float *)p; p += 4 * (int64_t)D;
+    v.hi = (const float *)p;
+    return v;
+}
+
+// ---- storage format addressing (bytes) -----------------------------------------------------
+// Key chunk of (token n, KV head h): `bits` pieces of 16 bytes, piece j at k_piece0 + j*1024.
+__host__ __device__ inline int64_t kvq_k_piece0(int bits, int64_t cap, int64_t n, int h)
+{
+    return (int64_t)h * cap * 16 * bits + (n >> 6) * (64 * 16 * bits) + (n & 63) * 16;
+}
+// Value chunk of (token pair m, KV head h, channel half g).
+__host__ __device__ inline int64_t kvq_v_piece0(int bits, int64_t cap, int64_t m, int h, int g)
+{
+    return (int64_t)(h * 2 + g) * (cap >> 1) * 16 * bits + (m >> 6) * (64 * 16 * bits) + (m & 63) * 16;
+}
+
+// ---- small device helpers -------------------------------------------------------------------
+__device__ inline float kvq_h2f(uint16_t b) { return (float)__builtin_bit_cast(half_t, b); }
+__device__ inline uint16_t kvq_f2h_rn(float f) { return __builtin_bit_cast(uint16_t, (half_t)f); }
+
+// Nearest signpost by exhaustive search in fp32, ties to the smaller index.  Also returns the
+// signpost itself so callers need no dynamically indexed register array.
+template <int NE>
+__device__ inline int kvq_nearest(const float *lut, float xn, float &signpost)
+{
+    int best = 0;
+    float bestd = __builtin_fabsf(xn - lut[0]);
+    float bestv = lut[0];
+#pragma unroll
+    for (int j = 1; j < NE; ++j) {
+        float dj = __builtin_fabsf(xn - lut[j]);
+        if (dj < bestd) { bestd = dj; best = j; bestv = lut[j]; }
+    }
+    signpost = bestv;
+    return best;
+}
+
+#define KVQ_HIP_CHECK(expr)                         \
+    do {                                            \
+        hipError_t _e = (expr);                     \
+        if (_e != hipSuccess) return KVQ_ERR_HIP;   \
+    } while (0)
+
+static inline kvq_status kvq_check_cache(const kvq_cache *c)
+{
+    if (!c) return KVQ_ERR_INVALID_ARG;
+    if (c->bits < 2 || c->bits > 4 || c->head_dim != KVQ_HEAD_DIM) return KVQ_ERR_UNSUPPORTED;
+    if (c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads) return KVQ_ERR_INVALID_ARG;
+    if ((int64_t)c->n_kv_heads * KVQ_HEAD_DIM > 65536) return KVQ_ERR_UNSUPPORTED;
+    if (c->cap_tokens <= 0 || (c->cap_tokens & 127) || c->cap_tokens >= ((int64_t)1 << 24)) return KVQ_ERR_INVALID_ARG;
+    if (c->n_tokens_k < 0 || c->n_tokens_k > c->cap_tokens || c->n_tokens_v < 0 || c->n_tokens_v > c->cap_tokens)
+        return KVQ_ERR_INVALID_ARG;
+    const void *ptrs[] = {c->params, c->k_codes, c->v_codes, c->v_sz, c->k_ptr, c->v_ptr,
+                          c->k_idx, c->k_val, c->v_idx, c->v_val, c->d_status};
+    for (const void *p : ptrs)
+        if (!p || ((uintptr_t)p & 15)) return KVQ_ERR_INVALID_ARG;
+    if (c->workspace && ((uintptr_t)c->workspace & 15)) return KVQ_ERR_INVALID_ARG;
+    return KVQ_OK;
+}

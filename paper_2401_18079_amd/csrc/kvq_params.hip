@@ -1,0 +1,115 @@
+// Host-side helpers of the C ABI and kvq_lut_load (stages one layer's quantization constants).
+#include <math.h>
+#include <string.h>
+#include "kvq_common.hpp"
+
+extern "C" {
+
+int64_t kvq_codes_bytes(int32_t bits, int32_t n_kv_heads, int64_t cap_tokens)
+{
+    return (int64_t)n_kv_heads * cap_tokens * 16 * bits;
+}
+
+int64_t kvq_params_bytes(int32_t n_kv_heads)
+{
+    int64_t b = kvq_params_bytes_D(n_kv_heads * KVQ_HEAD_DIM);
+    return (b + 255) & ~(int64_t)255;
+}
+
+const char *kvq_status_string(kvq_status s)
+{
+    switch (s) {
+    case KVQ_OK: return "ok";
+    case KVQ_ERR_INVALID_ARG: return "invalid argument";
+    case KVQ_ERR_UNSUPPORTED: return "unsupported shape or bit width";
+    case KVQ_ERR_CAPACITY: return "capacity exceeded";
+    case KVQ_ERR_NNZ_OVERFLOW: return "sparse outlier array full";
+    case KVQ_ERR_NOT_LOADED: return "kvq_lut_load not called";
+    case KVQ_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown";
+}
+
+const char *kvq_version(void) { return "kvq 0.1 (gfx950)"; }
+
+kvq_status kvq_event_create(void **event)
+{
+    if (!event) return KVQ_ERR_INVALID_ARG;
+    hipEvent_t e;
+    KVQ_HIP_CHECK(hipEventCreate(&e));
+    *event = (void *)e;
+    return KVQ_OK;
+}
+kvq_status kvq_event_record(void *event, void *stream)
+{
+    KVQ_HIP_CHECK(hipEventRecord((hipEvent_t)event, (hipStream_t)stream));
+    return KVQ_OK;
+}
+kvq_status kvq_event_elapsed_ms(void *start, void *stop, float *ms)
+{
+    if (!ms) return KVQ_ERR_INVALID_ARG;
+    KVQ_HIP_CHECK(hipEventSynchronize((hipEvent_t)stop));
+    KVQ_HIP_CHECK(hipEventElapsedTime(ms, (hipEvent_t)start, (hipEvent_t)stop));
+    return KVQ_OK;
+}
+kvq_status kvq_event_destroy(void *event)
+{
+    KVQ_HIP_CHECK(hipEventDestroy((hipEvent_t)event));
+    return KVQ_OK;
+}
+
+}  // extern "C"
+
+// Expand the fp16 per-channel constants to fp32 and form the reciprocal scale with one IEEE division,
+// so every later kernel normalises with exactly (x - z) * (1/s).
+__global__ void kvq_params_expand(void *block, int D)
+{
+    KvqParamsView v = kvq_params_view(block, D);
+    int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= D) return;
+    float s = kvq_h2f(v.s16[c]);
+    ((float *)v.s)[c] = s;
+    ((float *)v.z)[c] = kvq_h2f(v.z16[c]);
+    ((float *)v.rinv)[c] = __fdiv_rn(1.0f, s);
+    ((float *)v.lo)[c] = kvq_h2f(v.lo16[c]);
+    ((float *)v.hi)[c] = kvq_h2f(v.hi16[c]);
+}
+
+extern "C" kvq_status kvq_lut_load(kvq_cache *cache, const float *h_lut_k, const float *h_lut_v,
+                                   const uint16_t *h_s_k, const uint16_t *h_z_k,
+                                   const uint16_t *h_lo_k, const uint16_t *h_hi_k, void *stream)
+{
+    kvq_status st = kvq_check_cache(cache);
+    if (st != KVQ_OK) return st;
+    if (!h_lut_k || !h_lut_v || !h_s_k || !h_z_k || !h_lo_k || !h_hi_k) return KVQ_ERR_INVALID_ARG;
+    if (!(cache->rope_base > 1.0f)) return KVQ_ERR_INVALID_ARG;
+    const int D = cache->n_kv_heads * KVQ_HEAD_DIM;
+    const int ne = 1 << cache->bits;
+    for (int j = 1; j < ne; ++j)
+        if (!(h_lut_k[j] >= h_lut_k[j - 1]) || !(h_lut_v[j] >= h_lut_v[j - 1])) return KVQ_ERR_INVALID_ARG;
+
+    KvqParamsHeader hdr;
+    memset(&hdr, 0, sizeof(hdr));
+    for (int j = 0; j < ne; ++j) { hdr.lut_k[j] = h_lut_k[j]; hdr.lut_v[j] = h_lut_v[j]; }
+    for (int i = 0; i < 64; ++i) {
+        // rotation frequency of channel pair (i, i+64) in revolutions per position, split in two floats
+        double rev = pow((double)cache->rope_base, -2.0 * (double)i / (double)KVQ_HEAD_DIM) / (2.0 * M_PI);
+        float hi = (float)rev;
+        hdr.rope_vh[i] = hi;
+        hdr.rope_vl[i] = (float)(rev - (double)hi);
+    }
+    hdr.D = D;
+    hdr.bits = cache->bits;
+    hipStream_t s = (hipStream_t)stream;
+    KVQ_HIP_CHECK(hipStreamSynchronize(s));
+    char *blk = (char *)cache->params;
+    KVQ_HIP_CHECK(hipMemcpy(blk, &hdr, sizeof(hdr), hipMemcpyHostToDevice));
+    KVQ_HIP_CHECK(hipMemcpy(blk + 768, h_s_k, 2 * (size_t)D, hipMemcpyHostToDevice));
+    KVQ_HIP_CHECK(hipMemcpy(blk + 768 + 2 * (size_t)D, h_z_k, 2 * (size_t)D, hipMemcpyHostToDevice));
+    KVQ_HIP_CHECK(hipMemcpy(blk + 768 + 4 * (size_t)D, h_lo_k, 2 * (size_t)D, hipMemcpyHostToDevice));
+    KVQ_HIP_CHECK(hipMemcpy(blk + 768 + 6 * (size_t)D, h_hi_k, 2 * (size_t)D, hipMemcpyHostToDevice));
+    kvq_params_expand<<<(D + 255) / 256, 256, 0, s>>>(cache->params, D);
+    KVQ_HIP_CHECK(hipGetLastError());
+    cache->loaded = 1;
+    return KVQ_OK;
+}

@@ -1,0 +1,278 @@
+// Attention output against the quantized Value cache (paper Sec. 3.1 per-token Values, App. "Kernel
+// Implementation Details"): dense look-up-table mat-vec plus the sparse outlier mat-vec, merged into
+// one result.
+//
+// Design (gfx950).  out[q][c] = sum_n p[q][n] (s_n lut[code_{n,c}] + z_n) + sparse.  The storage format
+// keeps the codes of two consecutive tokens of one channel side by side in a 2b-bit field, so the hot
+// loop per field is: extract, one LDS gather of the fp16 pair (lut[a], lut[b]) from a layer-wide table,
+// two mixed-precision FMAs with the fp32 weights w = p*s of the two tokens.  The table is replicated
+// 32 times across LDS banks so gathers never conflict.  Lanes are token pairs, a wavefront owns one
+// (query head, 64-channel half) and keeps 64 fp32 accumulators per lane; lanes are summed once at the
+// end of the wavefront's token slab.  The zero-point term sum_n p z_n is a per-head scalar.  Sparse
+// outliers are handled by separate workgroups (lanes = tokens, LDS fp32 accumulators); all partial
+// results are summed in a fixed order by a final small kernel.
+#include <utility>
+#include "kvq_common.hpp"
+
+namespace {
+
+constexpr int PV_NT = 256;                 // 4 wavefronts = 4 (query head, half) combinations
+constexpr int PV_WAVES = PV_NT / 64;
+constexpr int PV_FIELD_GROUP = 8;
+
+struct PvPlan {
+    int slabs;              // token slabs of the dense kernel
+    int tiles_per_slab;     // tiles of 128 tokens per slab
+    int sslabs;             // token slabs of the sparse kernel
+    int64_t tokens_per_sslab;
+};
+
+inline PvPlan pv_plan(int64_t L, int n_q_heads)
+{
+    PvPlan p;
+    const int64_t tiles = (L + 127) / 128;
+    // aim at ~16 wavefronts per compute unit: 256 CUs * 16 / (2 * Hq) slabs
+    int64_t want = (256 * 16) / (2 * (int64_t)n_q_heads);
+    if (want < 1) want = 1;
+    if (want > 512) want = 512;
+    int64_t tps = (tiles + want - 1) / want;
+    if (tps < 1) tps = 1;
+    p.tiles_per_slab = (int)tps;
+    p.slabs = (int)((tiles + tps - 1) / tps);
+    int64_t ss = (L + 2047) / 2048;            // at least 2048 tokens per sparse workgroup
+    if (ss > 512) ss = 512;
+    if (ss < 1) ss = 1;
+    p.sslabs = (int)ss;
+    p.tokens_per_sslab = (L + ss - 1) / ss;
+    return p;
+}
+
+template <int FBITS>
+__device__ inline uint32_t pv_field_off(const uint32_t *W, int i, uint32_t lane_off)
+{
+    // (field value * 128) | lane_off : entry e of the replicated table sits at dword e*32 + (lane & 31)
+    const int bit = i * FBITS, wi = bit >> 5, sh = bit & 31;
+    constexpr uint32_t M = ((1u << FBITS) - 1u) << 7;
+    uint32_t x;
+    if (sh + FBITS <= 32) {
+        if (sh >= 7) x = W[wi] >> (sh - 7);
+        else x = W[wi] << (7 - sh);
+    } else {
+        x = __builtin_amdgcn_alignbit(W[wi + 1], W[wi], sh - 7);   // straddling fields start at bit >= 26
+    }
+    return (x & M) | lane_off;
+}
+
+template <int BITS, int G0>
+__device__ __forceinline__ void pv_group(const uint32_t (&W)[4 * BITS], float (&acc)[64], const half2_t *ptab,
+                                         uint32_t lane_off, float w0, float w1)
+{
+    half2_t t[PV_FIELD_GROUP];
+#pragma unroll
+    for (int k = 0; k < PV_FIELD_GROUP; ++k) {
+        const uint32_t off = pv_field_off<2 * BITS>(W, G0 * PV_FIELD_GROUP + k, lane_off);
+        t[k] = *(const half2_t *)((const uint8_t *)ptab + off);
+    }
+#pragma unroll
+    for (int k = 0; k < PV_FIELD_GROUP; ++k) {
+        float a = acc[G0 * PV_FIELD_GROUP + k];
+        a = __builtin_fmaf((float)t[k].x, w0, a);
+        a = __builtin_fmaf((float)t[k].y, w1, a);
+        acc[G0 * PV_FIELD_GROUP + k] = a;
+    }
+    // an empty asm that "modifies" the group's accumulators and clobbers memory keeps the groups in
+    // order (otherwise every gather of the tile is issued first and register pressure explodes)
+#pragma unroll
+    for (int k = 0; k < PV_FIELD_GROUP; ++k) asm volatile("" : "+v"(acc[G0 * PV_FIELD_GROUP + k]) : : "memory");
+}
+
+template <int BITS, int... G>
+__device__ __forceinline__ void pv_all_fields(std::integer_sequence<int, G...>, const uint32_t (&W)[4 * BITS],
+                                              float (&acc)[64], const half2_t *ptab, uint32_t lane_off, float w0,
+                                              float w1)
+{
+    (pv_group<BITS, G>(W, acc, ptab, lane_off, w0, w1), ...);
+}
+
+// Dense part.  grid = (slabs, 2*Hq / 4); wavefront w of a workgroup owns combination blockIdx.y*4 + w
+// = query head * 2 + channel half.  Writes partial[slab][q][128] and zpart[slab][q].
+template <int BITS>
+__global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ params, int D, int n_kv_heads,
+                                                      int n_q_heads, int64_t cap, int64_t L,
+                                                      const uint8_t *__restrict__ v_codes,
+                                                      const uint16_t *__restrict__ v_sz,
+                                                      const float *__restrict__ probs, int64_t ld,
+                                                      float *__restrict__ partial, float *__restrict__ zpart,
+                                                      int tiles_per_slab)
+{
+    constexpr int NE2 = 1 << (2 * BITS);
+    constexpr int CW = 4 * BITS;
+    __shared__ __attribute__((aligned(16))) half2_t ptab[NE2 * 32];      // replicated pair table
+    __shared__ float red[PV_WAVES][64][17];
+    const KvqParamsView pv = kvq_params_view(params, D);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int e = tid; e < NE2 * 32; e += PV_NT) {
+        const int f = e >> 5;
+        ptab[e] = half2_t{(half_t)pv.hdr->lut_v[f & ((1 << BITS) - 1)], (half_t)pv.hdr->lut_v[f >> BITS]};
+    }
+    __syncthreads();
+
+    const int combo = blockIdx.y * PV_WAVES + wave;
+    const bool active = combo < 2 * n_q_heads;
+    const int qh = active ? (combo >> 1) : 0, half = combo & 1;
+    const int kvh = qh / (n_q_heads / n_kv_heads);
+    const uint32_t lane_off = (uint32_t)(lane & 31) << 2;
+    const float *prow = probs + (int64_t)qh * ld;
+
+    float acc[64];
+#pragma unroll
+    for (int j = 0; j < 64; ++j) acc[j] = 0.f;
+    float zacc = 0.f;
+
+    const int64_t tile0 = (int64_t)blockIdx.x * tiles_per_slab;
+    if (active) {
+        for (int t = 0; t < tiles_per_slab; ++t) {
+            const int64_t m = (tile0 + t) * 64 + lane;      // token pair
+            const int64_t n0 = 2 * m;
+            if (n0 >= L) continue;
+            uint32_t W[CW];
+            const uint8_t *p = v_codes + kvq_v_piece0(BITS, cap, m, kvh, half);
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) {
+                const uint4 v = *(const uint4 *)(p + j * 1024);
+                W[4 * j + 0] = v.x; W[4 * j + 1] = v.y; W[4 * j + 2] = v.z; W[4 * j + 3] = v.w;
+            }
+            const uint2 sz = *(const uint2 *)(v_sz + n0 * 2);            // (s0, z0, s1, z1) fp16
+            const float p0 = prow[n0];
+            const float p1 = (n0 + 1 < L) ? prow[n0 + 1] : 0.f;          // odd tail: second token absent
+            const float w0 = p0 * kvq_h2f((uint16_t)(sz.x & 0xFFFFu));
+            const float w1 = p1 * kvq_h2f((uint16_t)(sz.y & 0xFFFFu));
+            zacc = __builtin_fmaf(p0, kvq_h2f((uint16_t)(sz.x >> 16)), zacc);
+            zacc = __builtin_fmaf(p1, kvq_h2f((uint16_t)(sz.y >> 16)), zacc);
+            pv_all_fields<BITS>(std::make_integer_sequence<int, 64 / PV_FIELD_GROUP>{}, W, acc, ptab, lane_off, w0, w1);
+        }
+    }
+    // sum the 64 lanes: four rounds of 16 accumulators through LDS
+    float outv = 0.f;      // lane l (< 64) ends up with channel l of this half
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) red[wave][lane][k] = acc[r * 16 + k];
+        __syncthreads();
+        const int col = lane & 15, quarter = lane >> 4;
+        float s = 0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s += red[wave][quarter * 16 + j][col];
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        if ((lane >> 4) == r) outv = s;          // lanes 16r..16r+15 keep channels 16r..16r+15
+        __syncthreads();
+    }
+    for (int o = 32; o > 0; o >>= 1) zacc += __shfl_xor(zacc, o);
+    if (active) {
+        partial[((int64_t)blockIdx.x * n_q_heads + qh) * 128 + half * 64 + lane] = outv;
+        if (half == 0 && lane == 0) zpart[(int64_t)blockIdx.x * n_q_heads + qh] = zacc;
+    }
+}
+
+// Sparse part.  grid = sslabs; lanes are tokens; out[q][c] += p[q][n] * val accumulated in LDS.
+__global__ __launch_bounds__(256) void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L,
+                                                     const uint32_t *__restrict__ v_ptr,
+                                                     const uint16_t *__restrict__ v_idx,
+                                                     const uint16_t *__restrict__ v_val,
+                                                     const float *__restrict__ probs, int64_t ld,
+                                                     float *__restrict__ spartial, int64_t tokens_per_slab)
+{
+    extern __shared__ float sacc[];             // [n_q_heads][128]
+    const int tid = threadIdx.x;
+    const int r = n_q_heads / n_kv_heads;
+    for (int j = tid; j < n_q_heads * 128; j += 256) sacc[j] = 0.f;
+    __syncthreads();
+    const int64_t nb = (int64_t)blockIdx.x * tokens_per_slab;
+    int64_t ne = nb + tokens_per_slab;
+    if (ne > L) ne = L;
+    for (int64_t n = nb + tid; n < ne; n += 256) {
+        const uint32_t e1 = v_ptr[n + 1];
+        for (uint32_t e = v_ptr[n]; e < e1; ++e) {
+            const uint32_t ch = v_idx[e];
+            const float v = kvq_h2f(v_val[e]);
+            const int kvh = ch >> 7, c = ch & 127;
+            for (int j = 0; j < r; ++j) {
+                const int qh = kvh * r + j;
+                atomicAdd(&sacc[qh * 128 + c], probs[(int64_t)qh * ld + n] * v);
+            }
+        }
+    }
+    __syncthreads();
+    for (int j = tid; j < n_q_heads * 128; j += 256) spartial[(int64_t)blockIdx.x * n_q_heads * 128 + j] = sacc[j];
+}
+
+// out[q][c] = sum_slabs partial + sum_slabs zpart + sum_sslabs spartial, in a fixed order.
+__global__ __launch_bounds__(128) void kvq_pv_reduce(int n_q_heads, int slabs, int sslabs,
+                                                     const float *__restrict__ partial,
+                                                     const float *__restrict__ zpart,
+                                                     const float *__restrict__ spartial, float *__restrict__ out)
+{
+    const int qh = blockIdx.x, c = threadIdx.x;
+    float s = 0.f, z = 0.f, sp = 0.f;
+    for (int k = 0; k < slabs; ++k) {
+        s += partial[((int64_t)k * n_q_heads + qh) * 128 + c];
+        z += zpart[(int64_t)k * n_q_heads + qh];
+    }
+    for (int k = 0; k < sslabs; ++k) sp += spartial[((int64_t)k * n_q_heads + qh) * 128 + c];
+    out[qh * 128 + c] = (s + z) + sp;
+}
+
+int64_t pv_workspace_bytes(int64_t cap, int n_q_heads)
+{
+    const PvPlan p = pv_plan(cap, n_q_heads);
+    // the plan for any L <= cap never needs more slabs than 512 dense + 512 sparse
+    (void)p;
+    return ((int64_t)512 * n_q_heads * 128 + (int64_t)512 * n_q_heads + (int64_t)512 * n_q_heads * 128) * 4;
+}
+
+}  // namespace
+
+extern "C" int64_t kvq_workspace_bytes(const kvq_cache *cache, int32_t max_append)
+{
+    if (!cache) return 0;
+    int64_t a = (int64_t)(max_append > 0 ? max_append : 1) * 4;
+    int64_t b = pv_workspace_bytes(cache->cap_tokens, cache->n_q_heads);
+    int64_t w = a > b ? a : b;
+    return (w + 255) & ~(int64_t)255;
+}
+
+extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs, int64_t ld_probs, float *d_out,
+                                    void *stream)
+{
+    kvq_status st = kvq_check_cache(cache);
+    if (st != KVQ_OK) return st;
+    if (!cache->loaded) return KVQ_ERR_NOT_LOADED;
+    if (!d_probs || !d_out || ((uintptr_t)d_probs & 3) || ((uintptr_t)d_out & 3)) return KVQ_ERR_INVALID_ARG;
+    const int64_t L = cache->n_tokens_v;
+    if (ld_probs < L) return KVQ_ERR_INVALID_ARG;
+    const int Hq = cache->n_q_heads, D = cache->n_kv_heads * KVQ_HEAD_DIM;
+    hipStream_t s = (hipStream_t)stream;
+    if (!cache->workspace || cache->workspace_bytes < pv_workspace_bytes(cache->cap_tokens, Hq)) return KVQ_ERR_CAPACITY;
+    const PvPlan plan = (L > 0) ? pv_plan(L, Hq) : PvPlan{0, 0, 0, 0};
+    float *partial = (float *)cache->workspace;
+    float *zpart = partial + (int64_t)512 * Hq * 128;
+    float *spartial = zpart + (int64_t)512 * Hq;
+    if (L > 0) {
+        dim3 grid((unsigned)plan.slabs, (unsigned)((2 * Hq + PV_WAVES - 1) / PV_WAVES));
+#define LAUNCH_PV(B)                                                                                          \
+    kvq_pv_dense<B><<<grid, PV_NT, 0, s>>>(cache->params, D, cache->n_kv_heads, Hq, cache->cap_tokens, L,      \
+                                           cache->v_codes, cache->v_sz, d_probs, ld_probs, partial, zpart,    \
+                                           plan.tiles_per_slab)
+        if (cache->bits == 2) LAUNCH_PV(2);
+        else if (cache->bits == 3) LAUNCH_PV(3);
+        else LAUNCH_PV(4);
+#undef LAUNCH_PV
+        kvq_pv_sparse<<<plan.sslabs, 256, (size_t)Hq * 128 * 4, s>>>(cache->n_kv_heads, Hq, L, cache->v_ptr,
+                                                                     cache->v_idx, cache->v_val, d_probs, ld_probs,
+                                                                     spartial, plan.tokens_per_sslab);
+    }
+    kvq_pv_reduce<<<Hq, 128, 0, s>>>(Hq, plan.slabs, plan.sslabs, partial, zpart, spartial, d_out);
+    KVQ_HIP_CHECK(hipGetLastError());
+    return KVQ_OK;
+}

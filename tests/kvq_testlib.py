@@ -1,0 +1,101 @@
+"""Shared helpers of the GPU parity tests: build the same synthetic cache through the CPU oracle and
+through the HIP library (each with its own code), and the tolerance used for mat-vec results."""
+import numpy as np
+
+import kvq_synth as S
+from oracle import kvq_oracle as O
+
+REL_TOL = 1e-3      # spec tolerance: 1e-3 relative, fp32 accumulation
+
+
+def matvec_close(got, ref, rel=REL_TOL):
+    """|got - ref| <= rel*|ref| + rel*rms(ref) per row (scores cancel to ~0, so a purely relative
+    test is ill-posed; the absolute floor is rel times the row's RMS)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True))
+    err = np.abs(got - ref)
+    bound = rel * np.abs(ref) + rel * rms
+    worst = float(np.max(err / np.maximum(bound, 1e-300)))
+    return bool(np.all(err <= bound)), worst
+
+
+class Setup:
+    """Synthetic layer: look-up tables, Key calibration constants, outlier counts."""
+
+    def __init__(self, wl: S.Workload, layer=0):
+        self.wl = wl
+        self.bits = wl.bits
+        self.lut_k = S.make_lut(wl.bits, wl.seed, layer, 0)
+        self.lut_v = S.make_lut(wl.bits, wl.seed, layer, 1)
+        self.kprof = S.key_channel_profile(wl, layer)
+        self.vprof = S.value_channel_profile(wl, layer)
+        self.s, self.z, self.lo, self.hi = S.calibrate_k(wl, layer, profile=self.kprof)
+        self.k_side = S.k_side_from_fraction(wl.outlier_fraction, wl.D)
+        self.layer = layer
+
+    def cap_nnz_k(self, cap):
+        return int(max(1024, 2.0 * max(self.wl.outlier_fraction, 1e-4) * self.wl.D * cap))
+
+    def k(self, t0, T, seq=0):
+        return S.gen_k(self.wl, self.layer, seq, t0, T, profile=self.kprof)
+
+    def v(self, t0, T, seq=0):
+        return S.gen_v(self.wl, self.layer, seq, t0, T, profile=self.vprof)
+
+    def oracle_cache(self, cap):
+        wl = self.wl
+        return O.OracleCache(wl.bits, wl.n_kv_heads, wl.n_q_heads, cap, self.k_side, wl.rope_base, self.lut_k,
+                             self.lut_v, self.s, self.z, self.lo, self.hi, cap_nnz_k=self.cap_nnz_k(cap))
+
+    def gpu_cache(self, cap, max_append=4096):
+        import paper_2401_18079_amd as K
+        wl = self.wl
+        c = K.KvqCache(wl.bits, wl.n_kv_heads, wl.n_q_heads, cap, self.k_side, wl.rope_base, self.cap_nnz_k(cap),
+                       max_append=max_append)
+        K.kvq_lut_load(c, self.lut_k, self.lut_v, self.s, self.z, self.lo, self.hi)
+        return c
+
+
+def fill_both(setup: Setup, oc, gc, L, chunks, seq=0):
+    """Append tokens [0, L) to both caches in the given chunk sizes (cycled)."""
+    import torch
+    import paper_2401_18079_amd as K
+    t0, i = 0, 0
+    while t0 < L:
+        T = min(chunks[i % len(chunks)], L - t0)
+        k, v = setup.k(t0, T, seq), setup.v(t0, T, seq)
+        if oc is not None:
+            oc.append_k(k)
+            oc.append_v(v)
+        if gc is not None:
+            K.kvq_quantize_append_k(gc, torch.from_numpy(k).cuda())
+            K.kvq_quantize_append_v(gc, torch.from_numpy(v).cuda())
+        t0 += T
+        i += 1
+
+
+def compare_caches(oc, gc):
+    """Bit-exact comparison of every stored array.  Returns a list of mismatch descriptions."""
+    bad = []
+    L = oc.n_k
+
+    def chk(name, a, b):
+        a = np.asarray(a); b = np.asarray(b)
+        if a.shape != b.shape or not np.array_equal(a, b):
+            n = int(np.sum(a != b)) if a.shape == b.shape else -1
+            first = int(np.nonzero(a != b)[0][0]) if n > 0 else -1
+            bad.append(f"{name}: {n} mismatches, first at {first}")
+
+    g = lambda t: t.cpu().numpy()
+    chk("k_codes", oc.k_codes, g(gc.k_codes))
+    chk("v_codes", oc.v_codes, g(gc.v_codes))
+    chk("v_sz", oc.v_sz.reshape(-1)[:2 * L], g(gc.v_sz).view(np.uint16)[:2 * L])
+    chk("k_ptr", oc.k_ptr[:L + 1], g(gc.k_ptr).view(np.uint32)[:L + 1])
+    chk("v_ptr", oc.v_ptr[:L + 1], g(gc.v_ptr).view(np.uint32)[:L + 1])
+    nk, nv = int(oc.k_ptr[L]), int(oc.v_ptr[L])
+    chk("k_idx", oc.k_idx[:nk], g(gc.k_idx).view(np.uint16)[:nk])
+    chk("k_val", oc.k_val[:nk], g(gc.k_val).view(np.uint16)[:nk])
+    chk("v_idx", oc.v_idx[:nv], g(gc.v_idx).view(np.uint16)[:nv])
+    chk("v_val", oc.v_val[:nv], g(gc.v_val).view(np.uint16)[:nv])
+    return bad
