@@ -1,0 +1,244 @@
+"""Benchmark of the quantized-KV decode hot path on one MI355X.
+
+A step is one pass of the whole path over the cached context: quantize-append the new token's Key
+and Value, q.K^T against the quantized Keys (RoPE after de-quantisation, sparse outliers merged),
+softmax, p.V against the quantized Values.  Workload: LLaMA-7B attention layer shape (32 heads x 128),
+context 131072, batch 1, 3-bit NUQ with 1 % outliers, seeded synthetic activations.
+Prints one JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def build_cache(st, L, cap, K, torch, keep_fp16=False):
+    """Fill a GPU cache with L synthetic tokens generated on the device, in chunks of 4096."""
+    from kvq_synth.device import DeviceGen
+    dg = DeviceGen(st.wl, st.layer, st.kprof, st.vprof)
+    gc = st.gpu_cache(cap)
+    k16 = torch.empty((L, st.wl.D), dtype=torch.float16, device="cuda") if keep_fp16 else None
+    v16 = torch.empty((L, st.wl.D), dtype=torch.float16, device="cuda") if keep_fp16 else None
+    t0 = 0
+    while t0 < L:
+        T = min(4096, L - t0)
+        k = dg.k(t0, T, out=k16[t0:t0 + T] if keep_fp16 else None)
+        v = dg.v(t0, T, out=v16[t0:t0 + T] if keep_fp16 else None)
+        K.kvq_quantize_append_k(gc, k)
+        K.kvq_quantize_append_v(gc, v)
+        t0 += T
+    torch.cuda.synchronize()
+    return gc, dg, k16, v16
+
+
+def algorithmic_bytes(wl, L, nnz_k, nnz_v):
+    """Bytes the method must move per launch (compressed cache + outputs), not the fp16 bytes it avoids."""
+    D, Hq, b = wl.D, wl.n_q_heads, wl.bits
+    qk = L * (D * b // 8) + 4 * nnz_k + 4 * (L + 1) + 4 * Hq * L
+    pv = L * (D * b // 8) + 4 * L + 4 * nnz_v + 4 * (L + 1) + 4 * Hq * L
+    return qk, pv
+
+
+def cpu_baseline(st, sample_tokens):
+    """Time the CPU oracle (as it stands) on a bounded sample of the same workload."""
+    import kvq_synth as S
+    from oracle import kvq_oracle as O
+    wl = st.wl
+    cap = ((sample_tokens + 127) // 128) * 128
+    oc = st.oracle_cache(cap)
+    t0 = 0
+    tq = 0.0
+    while t0 < sample_tokens:                       # cache construction is not timed, except one token
+        T = min(1024, sample_tokens - t0)
+        k, v = st.k(t0, T), st.v(t0, T)
+        if t0 + T == sample_tokens:
+            oc.append_k(k[:-1]); oc.append_v(v[:-1])
+            a = time.perf_counter()
+            oc.append_k(k[-1:]); oc.append_v(v[-1:])
+            tq = time.perf_counter() - a
+        else:
+            oc.append_k(k); oc.append_v(v)
+        t0 += T
+    q = S.gen_q(wl, 0, 0)
+    times = []
+    for _ in range(5):
+        a = time.perf_counter()
+        scores = oc.qk(q, 1.0 / np.sqrt(128.0))
+        probs = O.softmax(scores)
+        out = oc.pv(probs)
+        times.append(time.perf_counter() - a)
+    return tq, float(np.median(times)), O.max_threads(), float(out[0, 0])
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--context", type=int, default=0, help="override the context length")
+    ap.add_argument("--cpu-sample", type=int, default=4096, help="tokens of context for the CPU-oracle timing (0 = skip)")
+    ap.add_argument("--no-fp16", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import kvq_synth as S
+    import paper_2401_18079_amd as K
+    from kvq_testlib import Setup
+
+    wl = S.workload(args.workload)
+    if args.context:
+        wl = S.workload(args.workload, context=args.context)
+    st = Setup(wl)
+    L = wl.context
+    steps, warmup = args.steps, args.warmup
+    cap = ((L + steps + warmup + 8 + 127) // 128) * 128
+    Hq, D = wl.n_q_heads, wl.D
+    scale = 1.0 / np.sqrt(128.0)
+
+    gc, dg, k16, v16 = build_cache(st, L, cap, K, torch, keep_fp16=not args.no_fp16)
+    assert gc.status() == 0
+    new_k = dg.k(L, steps + warmup)
+    new_v = dg.v(L, steps + warmup)
+    qs = torch.from_numpy(np.stack([S.gen_q(wl, 0, 0, step=i) for i in range(steps + warmup)])).cuda()
+    scores = torch.zeros((Hq, cap), device="cuda")
+    probs = torch.zeros((Hq, cap), device="cuda")
+    out = torch.zeros((Hq, 128), device="cuda")
+    sm_ws = torch.zeros(K.binding.kvq_softmax_workspace_bytes(Hq, cap), dtype=torch.uint8, device="cuda")
+
+    def step(i, ev=None):
+        K.kvq_quantize_append_k(gc, new_k[i:i + 1])
+        if ev: ev[1].start()  # noqa: E701
+        K.kvq_quantize_append_v(gc, new_v[i:i + 1])
+        if ev: ev[2].start()  # noqa: E701
+        K.kvq_qk_matvec(gc, qs[i], scale, scores)
+        if ev: ev[3].start()  # noqa: E701
+        K.kvq_softmax_f32(scores, probs, gc.n_tokens_k, sm_ws)
+        if ev: ev[4].start()  # noqa: E701
+        K.kvq_pv_matvec(gc, probs, out)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    # events on the launch stream between the calls of every timed step (start() records one event)
+    evs = [[K.HipEventTimer() for _ in range(6)] for _ in range(steps)]
+    t_begin = time.perf_counter()
+    for i in range(steps):
+        ev = evs[i]
+        ev[0].start()
+        step(warmup + i, ev)
+        ev[5].start()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_begin
+    ms_per_step = wall * 1e3 / steps
+
+    import ctypes
+    lib = K.load_library()
+
+    def gap_ms(a, b):
+        ms = ctypes.c_float()
+        lib.kvq_event_elapsed_ms(a._a, b._a, ctypes.byref(ms))
+        return ms.value
+
+    names = ["append_k", "append_v", "qk_matvec", "softmax", "pv_matvec"]
+    per = {n: [] for n in names}
+    for ev in evs:
+        for j, n in enumerate(names):
+            per[n].append(gap_ms(ev[j], ev[j + 1]) * 1e3)
+    breakdown = {n: float(np.mean(v)) for n, v in per.items()}
+    breakdown_min = {n: float(np.min(v)) for n, v in per.items()}
+
+    Lend = gc.n_tokens_k
+    nnz_k = int(gc.k_ptr[Lend].item()) & 0xFFFFFFFF
+    nnz_v = int(gc.v_ptr[Lend].item()) & 0xFFFFFFFF
+    qk_bytes, pv_bytes = algorithmic_bytes(wl, Lend, nnz_k, nnz_v)
+    qk_gbps = qk_bytes / (breakdown["qk_matvec"] * 1e-6) / 1e9
+    pv_gbps = pv_bytes / (breakdown["pv_matvec"] * 1e-6) / 1e9
+
+    fp16 = None
+    if not args.no_fp16:
+        fws = torch.zeros(K.binding.kvq_fp16_pv_workspace_bytes(Hq, L), dtype=torch.uint8, device="cuda")
+        p16 = probs[:, :L].contiguous()
+        s16 = torch.zeros((Hq, L), device="cuda")
+        tm = K.HipEventTimer()
+        res = {}
+        for name, fn in (("qk", lambda: K.kvq_fp16_qk_matvec(k16, wl.n_kv_heads, Hq, qs[0], scale, s16)),
+                         ("pv", lambda: K.kvq_fp16_pv_matvec(v16, wl.n_kv_heads, Hq, p16, out, fws))):
+            for _ in range(5):
+                fn()
+            tm.start()
+            for _ in range(20):
+                fn()
+            tm.stop()
+            res[name] = tm.elapsed_ms() * 1e3 / 20
+        # library cross-check of the same fp16 mat-vecs
+        kk = k16.view(L, wl.n_kv_heads, 128)
+        qv = qs[0].view(wl.n_kv_heads, Hq // wl.n_kv_heads, 128)
+        for _ in range(3):
+            torch.einsum("lhc,hrc->hrl", kk.float() if False else kk, qv.half())
+        tm.start()
+        for _ in range(10):
+            torch.einsum("lhc,hrc->hrl", kk, qv.half())
+        tm.stop()
+        res["qk_torch"] = tm.elapsed_ms() * 1e3 / 10
+        fp16 = {"qk_us": res["qk"], "pv_us": res["pv"], "qk_torch_einsum_us": res["qk_torch"],
+                "qk_gbps": L * D * 2 / (res["qk"] * 1e-6) / 1e9, "pv_gbps": L * D * 2 / (res["pv"] * 1e-6) / 1e9}
+        del k16, v16
+
+    cpu = None
+    if args.cpu_sample > 0:
+        tq, tmv, cores, _ = cpu_baseline(st, args.cpu_sample)
+        # the oracle's cost is linear in the context: scale the sample to the benchmark's context
+        est_us = (tq + tmv * (L / args.cpu_sample)) * 1e6
+        cpu = {"value": est_us, "unit": "us per decode step (append + qk + softmax + pv)", "cores": cores,
+               "kind": "oracle",
+               "sample": f"oracle timed on the first {args.cpu_sample} tokens of the same workload "
+                         f"(append of one token {tq * 1e3:.2f} ms, qk+softmax+pv {tmv * 1e3:.1f} ms, median of 5), "
+                         f"mat-vec time scaled linearly to context {L}"}
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            tj = json.load(open(tpath))
+            traffic = tj.get(f"{wl.name}_L{L}", {}).get("qk_matvec_bytes")
+        except Exception:
+            traffic = None
+
+    line = {
+        "metric": "quantized-KV decode step latency (append K/V + QK^T + softmax + PV), one attention layer",
+        "value": ms_per_step * 1e3, "unit": "us", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.n_q_heads} q-heads x {wl.n_kv_heads} kv-heads x 128, context {L}, "
+                               f"batch 1, nuq{wl.bits} with {wl.outlier_fraction * 100:g}% outliers, "
+                               f"rope base {wl.rope_base:g}",
+                   "bits": wl.bits, "context": L, "outlier_fraction": wl.outlier_fraction},
+        "breakdown_us": breakdown, "breakdown_min_us": breakdown_min,
+        "qk_pv_us": breakdown["qk_matvec"] + breakdown["pv_matvec"],
+        "hbm_gbps": {"qk_matvec": qk_gbps, "pv_matvec": pv_gbps},
+        "fp16_cache_baseline": fp16,
+        "speedup_vs_fp16": ({"qk": fp16["qk_us"] / breakdown["qk_matvec"], "pv": fp16["pv_us"] / breakdown["pv_matvec"]}
+                            if fp16 else None),
+        "roofline": {"bound": "hbm", "kernel": "kvq_qk_matvec", "achieved": qk_gbps, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": qk_gbps / HBM_PEAK_GBPS, "traffic": traffic,
+                     "algorithmic_bytes": qk_bytes, "avg_launch_us": breakdown["qk_matvec"]},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

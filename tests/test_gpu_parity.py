@@ -203,3 +203,15 @@ def test_fp16_baselines_match_torch():
         vv = v16.float().view(L, Hkv, 128).repeat_interleave(r, dim=1)
         ref_o = torch.einsum("hl,lhc->hc", p, vv)
         assert torch.allclose(out, ref_o, rtol=1e-4, atol=1e-5)
+
+
+def test_device_generator_equals_host_generator():
+    import torch
+    from kvq_synth.device import DeviceGen
+    for name, ov in (("c2", dict(n_kv_heads=4, n_q_heads=4)), ("c1", dict())):
+        wl = S.workload(name, **ov)
+        st = Setup(wl)
+        dg = DeviceGen(wl, 0, st.kprof, st.vprof)
+        for t0, T in ((0, 64), (100000, 33)):
+            assert np.array_equal(dg.k(t0, T).cpu().numpy().view(np.uint16), st.k(t0, T).view(np.uint16))
+            assert np.array_equal(dg.v(t0, T).cpu().numpy().view(np.uint16), st.v(t0, T).view(np.uint16))
