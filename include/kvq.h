@@ -59,7 +59,7 @@ typedef struct kvq_cache {
     int32_t n_kv_heads;     /* H; D = H*head_dim is the vector the method quantizes per token   */
     int32_t n_q_heads;      /* multiple of n_kv_heads; query head q reads KV head q/(Hq/H)      */
     int32_t k_side_v;       /* Value outliers kept per side (largest / smallest) of each token  */
-    int32_t loaded;         /* set by kvq_lut_load                                              */
+    int32_t loaded;         /* set by kvq_lut_load (0 = not loaded)                             */
     int64_t cap_tokens;     /* multiple of 128                                                  */
     int64_t n_tokens_k;     /* tokens appended so far; advanced by kvq_quantize_append_k        */
     int64_t n_tokens_v;     /* likewise for kvq_quantize_append_v                               */

@@ -84,6 +84,16 @@ __device__ inline int kvq_nearest(const float *lut, float xn, float &signpost)
     return best;
 }
 
+// Scatter-add of floats into LDS without floating-point atomics (ds_add_f32 processes lanes one at a
+// time on gfx950, roughly 30x slower than integer LDS atomics): the value is converted to 64-bit
+// fixed point and added with an integer atomic.  Integer addition is associative, so the result does
+// not depend on the order in which lanes arrive.
+__device__ inline void kvq_lds_add_fixed(long long *cell, float x, double scale)
+{
+    const long long q = (long long)((double)x * scale);
+    atomicAdd((unsigned long long *)cell, (unsigned long long)q);
+}
+
 #define KVQ_HIP_CHECK(expr)                         \
     do {                                            \
         hipError_t _e = (expr);                     \

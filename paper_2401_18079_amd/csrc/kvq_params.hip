@@ -110,6 +110,11 @@ extern "C" kvq_status kvq_lut_load(kvq_cache *cache, const float *h_lut_k, const
     KVQ_HIP_CHECK(hipMemcpy(blk + 768 + 6 * (size_t)D, h_hi_k, 2 * (size_t)D, hipMemcpyHostToDevice));
     kvq_params_expand<<<(D + 255) / 256, 256, 0, s>>>(cache->params, D);
     KVQ_HIP_CHECK(hipGetLastError());
-    cache->loaded = 1;
+    // bit 0: loaded; bit 1: the thresholds admit no Key outlier at all (every finite fp16 passes), so
+    // the score kernel can skip the sparse part
+    bool no_outliers = true;
+    for (int c = 0; c < D && no_outliers; ++c)
+        no_outliers = (h_lo_k[c] == 0xFBFFu) && (h_hi_k[c] == 0x7BFFu);   // -65504 / +65504
+    cache->loaded = no_outliers ? 3 : 1;
     return KVQ_OK;
 }

@@ -9,8 +9,8 @@
 // 32 times across LDS banks so gathers never conflict.  Lanes are token pairs, a wavefront owns one
 // (query head, 64-channel half) and keeps 64 fp32 accumulators per lane; lanes are summed once at the
 // end of the wavefront's token slab.  The zero-point term sum_n p z_n is a per-head scalar.  Sparse
-// outliers are handled by separate workgroups (lanes = tokens, LDS fp32 accumulators); all partial
-// results are summed in a fixed order by a final small kernel.
+// outliers are handled by a balanced kernel (lanes = outlier entries, LDS fp32 accumulators); all
+// partial results are summed in a fixed order by a final small kernel.
 #include <utility>
 #include "kvq_common.hpp"
 
@@ -39,8 +39,8 @@ inline PvPlan pv_plan(int64_t L, int n_q_heads)
     if (tps < 1) tps = 1;
     p.tiles_per_slab = (int)tps;
     p.slabs = (int)((tiles + tps - 1) / tps);
-    int64_t ss = (L + 2047) / 2048;            // at least 2048 tokens per sparse workgroup
-    if (ss > 512) ss = 512;
+    int64_t ss = (L + 511) / 512;              // at least 512 tokens per sparse workgroup
+    if (ss > 256) ss = 256;
     if (ss < 1) ss = 1;
     p.sslabs = (int)ss;
     p.tokens_per_sslab = (L + ss - 1) / ss;
@@ -175,52 +175,126 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
     }
 }
 
-// Sparse part.  grid = sslabs; lanes are tokens; out[q][c] += p[q][n] * val accumulated in LDS.
-__global__ __launch_bounds__(256) void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L,
-                                                     const uint32_t *__restrict__ v_ptr,
-                                                     const uint16_t *__restrict__ v_idx,
-                                                     const uint16_t *__restrict__ v_val,
-                                                     const float *__restrict__ probs, int64_t ld,
-                                                     float *__restrict__ spartial, int64_t tokens_per_slab)
+// Sparse part, balanced (paper App. "Kernel Implementation Details": equal non-zeros per thread):
+// lanes are outlier entries, so every lane does the same amount of work whatever the sparsity
+// pattern.  grid = sslabs; a workgroup owns tokens [nb, ne), walks them in chunks of PVS_TC tokens
+// whose pointers and probabilities it stages in LDS, finds each entry's token by a guess plus a
+// short walk and accumulates p[q][n] * val into fixed-point LDS accumulators (integer atomics).
+constexpr int PVS_TC = 128;
+constexpr int PVS_NT = 1024;
+constexpr int PVS_U = 8;                  // entries in flight per lane
+
+__global__ __launch_bounds__(PVS_NT) void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L,
+                                                        const uint32_t *__restrict__ v_ptr,
+                                                        const uint16_t *__restrict__ v_idx,
+                                                        const uint16_t *__restrict__ v_val,
+                                                        const float *__restrict__ probs, int64_t ld,
+                                                        float *__restrict__ spartial, int64_t tokens_per_slab)
 {
-    extern __shared__ float sacc[];             // [n_q_heads][128]
-    const int tid = threadIdx.x;
+    extern __shared__ __attribute__((aligned(16))) float dyn[];
+    // accumulators are 2^40-scaled fixed point (see kvq_lds_add_fixed)
+    constexpr double FIX = 1099511627776.0;
+    long long *sacc = (long long *)dyn;                  // [n_q_heads][128]
+    // rows padded by one float so that one token's column does not sit in a single LDS bank
+    constexpr int PROW = PVS_TC + 1;
+    float *ps = dyn + (size_t)n_q_heads * 128 * 2;       // [n_q_heads][PVS_TC + 1] probabilities of the chunk
+    __shared__ uint32_t ptr_s[PVS_TC + 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = n_q_heads / n_kv_heads;
-    for (int j = tid; j < n_q_heads * 128; j += 256) sacc[j] = 0.f;
-    __syncthreads();
+    for (int j = tid; j < n_q_heads * 128; j += PVS_NT) sacc[j] = 0;
     const int64_t nb = (int64_t)blockIdx.x * tokens_per_slab;
     int64_t ne = nb + tokens_per_slab;
     if (ne > L) ne = L;
-    for (int64_t n = nb + tid; n < ne; n += 256) {
-        const uint32_t e1 = v_ptr[n + 1];
-        for (uint32_t e = v_ptr[n]; e < e1; ++e) {
-            const uint32_t ch = v_idx[e];
-            const float v = kvq_h2f(v_val[e]);
-            const int kvh = ch >> 7, c = ch & 127;
-            for (int j = 0; j < r; ++j) {
-                const int qh = kvh * r + j;
-                atomicAdd(&sacc[qh * 128 + c], probs[(int64_t)qh * ld + n] * v);
+    for (int64_t nc = nb; nc < ne; nc += PVS_TC) {
+        const int tc = (int)((ne - nc < PVS_TC) ? (ne - nc) : PVS_TC);
+        __syncthreads();
+        for (int j = tid; j <= tc; j += PVS_NT) ptr_s[j] = v_ptr[nc + j];
+        for (int qh = wave; qh < n_q_heads; qh += PVS_NT / 64) {
+#pragma unroll
+            for (int k = 0; k < PVS_TC / 64; ++k) {
+                const int t = lane + 64 * k;
+                ps[qh * PROW + t] = (t < tc) ? probs[(int64_t)qh * ld + nc + t] : 0.f;
+            }
+        }
+        __syncthreads();
+        const uint32_t e_begin = ptr_s[0], e_end = ptr_s[tc];
+        // every token normally owns the same number of entries: guess the token, then walk
+        const uint32_t per = (e_end - e_begin) / (uint32_t)tc;
+        for (uint32_t e0 = e_begin + tid; e0 < e_end; e0 += PVS_NT * PVS_U) {
+            uint32_t chv[PVS_U];
+            uint16_t vb[PVS_U];
+#pragma unroll
+            for (int u = 0; u < PVS_U; ++u) {
+                const uint32_t e = e0 + (uint32_t)PVS_NT * u;
+                const uint32_t ec = (e < e_end) ? e : e_end - 1;   // clamped: straight-line loads, all in flight
+                chv[u] = (uint32_t)v_idx[ec];
+                vb[u] = v_val[ec];
+            }
+#pragma unroll
+            for (int u = 0; u < PVS_U; ++u) {
+                const uint32_t e = e0 + (uint32_t)PVS_NT * u;
+                if (e >= e_end) break;
+                int t = per ? (int)((e - e_begin) / per) : 0;
+                if (t >= tc) t = tc - 1;
+                while (ptr_s[t] > e) --t;             // ptr_s[0] <= e, so this stops at t >= 0
+                while (ptr_s[t + 1] <= e) ++t;        // ptr_s[tc] > e, so this stops at t < tc
+                const float v = kvq_h2f(vb[u]);
+                const int kvh = chv[u] >> 7, c = chv[u] & 127;
+                for (int j = 0; j < r; ++j) {
+                    const int qh = kvh * r + j;
+                    kvq_lds_add_fixed(&sacc[qh * 128 + c], ps[qh * PROW + t] * v, FIX);
+                }
             }
         }
     }
     __syncthreads();
-    for (int j = tid; j < n_q_heads * 128; j += 256) spartial[(int64_t)blockIdx.x * n_q_heads * 128 + j] = sacc[j];
+    for (int j = tid; j < n_q_heads * 128; j += PVS_NT) spartial[(int64_t)blockIdx.x * n_q_heads * 128 + j] = (float)((double)sacc[j] * (1.0 / FIX));
 }
 
-// out[q][c] = sum_slabs partial + sum_slabs zpart + sum_sslabs spartial, in a fixed order.
-__global__ __launch_bounds__(128) void kvq_pv_reduce(int n_q_heads, int slabs, int sslabs,
-                                                     const float *__restrict__ partial,
-                                                     const float *__restrict__ zpart,
-                                                     const float *__restrict__ spartial, float *__restrict__ out)
+// out[q][c] = sum_slabs partial + sum_slabs zpart + sum_sslabs spartial.  One workgroup per query
+// head, 128 channels x 8 slab groups; every sum is taken in a fixed order.
+__global__ __launch_bounds__(1024) void kvq_pv_reduce(int n_q_heads, int slabs, int sslabs,
+                                                      const float *__restrict__ partial,
+                                                      const float *__restrict__ zpart,
+                                                      const float *__restrict__ spartial, float *__restrict__ out)
 {
-    const int qh = blockIdx.x, c = threadIdx.x;
-    float s = 0.f, z = 0.f, sp = 0.f;
-    for (int k = 0; k < slabs; ++k) {
-        s += partial[((int64_t)k * n_q_heads + qh) * 128 + c];
-        z += zpart[(int64_t)k * n_q_heads + qh];
+    __shared__ float red[8][128];
+    __shared__ float zred[8];
+    const int qh = blockIdx.x, c = threadIdx.x & 127, j = threadIdx.x >> 7;
+    float s = 0.f;
+    for (int k0 = j; k0 < slabs; k0 += 64) {           // eight loads in flight per thread
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + 8 * u;
+            v[u] = (k < slabs) ? partial[((int64_t)k * n_q_heads + qh) * 128 + c] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
     }
-    for (int k = 0; k < sslabs; ++k) sp += spartial[((int64_t)k * n_q_heads + qh) * 128 + c];
-    out[qh * 128 + c] = (s + z) + sp;
+    for (int k0 = j; k0 < sslabs; k0 += 64) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + 8 * u;
+            v[u] = (k < sslabs) ? spartial[((int64_t)k * n_q_heads + qh) * 128 + c] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    red[j][c] = s;
+    if (c == 0) {
+        float z = 0.f;
+        for (int k = j; k < slabs; k += 8) z += zpart[(int64_t)k * n_q_heads + qh];
+        zred[j] = z;
+    }
+    __syncthreads();
+    if (j == 0) {
+        float t = 0.f, z = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { t += red[i][c]; z += zred[i]; }
+        out[qh * 128 + c] = t + z;
+    }
 }
 
 int64_t pv_workspace_bytes(int64_t cap, int n_q_heads)
@@ -268,11 +342,11 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
         else if (cache->bits == 3) LAUNCH_PV(3);
         else LAUNCH_PV(4);
 #undef LAUNCH_PV
-        kvq_pv_sparse<<<plan.sslabs, 256, (size_t)Hq * 128 * 4, s>>>(cache->n_kv_heads, Hq, L, cache->v_ptr,
+        kvq_pv_sparse<<<plan.sslabs, PVS_NT, (size_t)Hq * (256 + PVS_TC + 1) * 4, s>>>(cache->n_kv_heads, Hq, L, cache->v_ptr,
                                                                      cache->v_idx, cache->v_val, d_probs, ld_probs,
                                                                      spartial, plan.tokens_per_sslab);
     }
-    kvq_pv_reduce<<<Hq, 128, 0, s>>>(Hq, plan.slabs, plan.sslabs, partial, zpart, spartial, d_out);
+    kvq_pv_reduce<<<Hq, 1024, 0, s>>>(Hq, plan.slabs, plan.sslabs, partial, zpart, spartial, d_out);
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }

@@ -11,8 +11,13 @@
 // the hot loop per (token, head, pair) is: extract a field, one LDS gather, two mixed-precision FMAs
 // with the fp32 cos/sin of the token's angle.  cos/sin are computed once per (token, pair) and
 // shared by all query heads the workgroup handles.  Lanes are tokens; a wavefront reads 1 KiB of
-// contiguous codes per load instruction.  For 4-bit codes the joint table would be 256 entries, so
+// contiguous codes per load instruction, and the 16-byte pieces of the next token tile are requested
+// as soon as the current tile no longer needs the registers they land in, so HBM latency hides
+// behind the table look-ups.  The sparse outliers are handled by a second, balanced kernel (lanes =
+// outlier entries) launched right behind the dense one in the same call; it adds its per-(head,
+// token) sums to the dense scores, so one call yields one merged result.  For 4-bit codes the joint table would be 256 entries, so
 // A and B are split into a part indexed by each code (two 16-entry gathers).
+#include <stdlib.h>
 #include <utility>
 #include "kvq_common.hpp"
 
@@ -59,8 +64,9 @@ __device__ inline float rope_rev(float nf, float vh, float vl)
 constexpr int PAIR_GROUP = 2;
 
 template <int BITS, int QH, int R, int G0>
-__device__ __forceinline__ void qk_group(const uint32_t (&W)[QH / R][QkCfg<BITS>::CW], float (&acc)[QH],
-                                         const half2_t *tab, float nf, const KvqParamsHeader *hdr)
+__device__ __forceinline__ void qk_group(uint32_t (&W)[QH / R][QkCfg<BITS>::CW], float (&acc)[QH],
+                                         const half2_t *tab, float nf, const KvqParamsHeader *hdr,
+                                         const uint8_t *next_chunk, int64_t plane, bool next_valid)
 {
     using C = QkCfg<BITS>;
     constexpr int KVH = QH / R;
@@ -108,22 +114,35 @@ __device__ __forceinline__ void qk_group(const uint32_t (&W)[QH / R][QkCfg<BITS>
     // group's arithmetic below later gathers.
 #pragma unroll
     for (int qh = 0; qh < QH; ++qh) asm volatile("" : "+v"(acc[qh]) : : "memory");
+    // Software pipelining: a 16-byte piece of the chunk is dead once the last field that touches it
+    // has been consumed; request the same piece of the NEXT token tile into those registers now.
+    constexpr int FB = 2 * BITS;
+    constexpr int first_field = G0 * PAIR_GROUP, last_field = first_field + PAIR_GROUP - 1;
+#pragma unroll
+    for (int j = 0; j < BITS; ++j) {
+        const int last_user = (128 * (j + 1) - 1) / FB;      // last field with a bit in piece j
+        if (last_user >= first_field && last_user <= last_field && next_valid) {
+#pragma unroll
+            for (int g = 0; g < KVH; ++g) {
+                const uint4 v = *(const uint4 *)(next_chunk + g * plane + j * 1024);
+                W[g][4 * j + 0] = v.x; W[g][4 * j + 1] = v.y; W[g][4 * j + 2] = v.z; W[g][4 * j + 3] = v.w;
+            }
+        }
+    }
 }
 
 template <int BITS, int QH, int R, int... G>
 __device__ __forceinline__ void qk_all_pairs(std::integer_sequence<int, G...>,
-                                             const uint32_t (&W)[QH / R][QkCfg<BITS>::CW], float (&acc)[QH],
-                                             const half2_t *tab, float nf, const KvqParamsHeader *hdr)
+                                             uint32_t (&W)[QH / R][QkCfg<BITS>::CW], float (&acc)[QH],
+                                             const half2_t *tab, float nf, const KvqParamsHeader *hdr,
+                                             const uint8_t *next_chunk, int64_t plane, bool next_valid)
 {
-    (qk_group<BITS, QH, R, G>(W, acc, tab, nf, hdr), ...);
+    (qk_group<BITS, QH, R, G>(W, acc, tab, nf, hdr, next_chunk, plane, next_valid), ...);
 }
 
 template <int BITS, int QH, int R, int NT>
 __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ params, int D, int n_kv_heads,
                                                     int64_t cap, int64_t L, const uint8_t *__restrict__ k_codes,
-                                                    const uint32_t *__restrict__ k_ptr,
-                                                    const uint16_t *__restrict__ k_idx,
-                                                    const uint16_t *__restrict__ k_val,
                                                     const float *__restrict__ q_rot, float scale,
                                                     float *__restrict__ scores, int64_t ld, int tiles_per_wg)
 {
@@ -135,128 +154,224 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
     // address the table offsets fold into the gathers' immediate offsets.
     __shared__ __attribute__((aligned(16))) half2_t tab[QH * 64 * ENT];   // [QH][64][ENT]
     __shared__ float qs[QH * 128];                                        // query * scale
-    __shared__ float2_t rope[64];                                         // (vh, vl)
+    __shared__ float2_t szs[(QH / R) * 128];                              // per-channel (scale, zero-point)
     __shared__ float hmax[QH];                                            // table magnitude per head
+    __shared__ float down_s[QH];
     const KvqParamsView pv = kvq_params_view(params, D);
     const int tid = threadIdx.x;
     const int q0 = blockIdx.y * QH;
     const int kv0 = q0 / R;
 
-    // ---- stage query, rope constants ------------------------------------------------------
+    // ---- stage query, rope constants, per-channel (scale, zero-point) -------------------------
     for (int j = tid; j < QH * 128; j += NT) qs[j] = q_rot[(int64_t)q0 * 128 + j] * scale;
-    if (tid < 64) rope[tid] = float2_t{pv.hdr->rope_vh[tid], pv.hdr->rope_vl[tid]};
+    for (int j = tid; j < KVH * 128; j += NT) szs[j] = float2_t{pv.s[kv0 * 128 + j], pv.z[kv0 * 128 + j]};
     if (tid < QH) hmax[tid] = 0.0f;
     __syncthreads();
 
     // ---- build the (A,B) tables -----------------------------------------------------------
-    // pass 0 finds the largest magnitude per query head, pass 1 stores entries scaled by a power
+    // A table (one query head, one channel pair) has ENT entries; ENT lanes of a wavefront fill it,
+    // one entry each, so a lane's signposts are loop constants and LDS writes are conflict-free.
+    // Pass 0 finds the largest magnitude per query head, pass 1 stores the entries scaled by a power
     // of two so that fp16 neither overflows nor loses small heads to subnormals.
-    float lut[NE];
+    {
+        constexpr int TW = 64 / ENT;                     // tables per wavefront step
+        constexpr int NWAVES = NT / 64;
+        constexpr int STEP = NWAVES * TW;                // tables per workgroup step (divides 64)
+        const int lane = tid & 63, wave = tid >> 6;
+        const int f = lane % ENT, sub = lane / ENT;
+        float lut_a = 0.f, lut_b = 0.f;                  // joint: signposts of the two codes; split: lut_a only
 #pragma unroll
-    for (int j = 0; j < NE; ++j) lut[j] = pv.hdr->lut_k[j];
-    for (int pass = 0; pass < 2; ++pass) {
-        for (int e = tid; e < QH * 64 * ENT; e += NT) {
-            const int qh = e / (64 * ENT), i = (e / ENT) & 63, f = e % ENT;
-            const int ch = (kv0 + qh / R) * 128 + i;
-            const float qa = qs[qh * 128 + i], qb = qs[qh * 128 + i + 64];
-            float a, b;
-            if (C::JOINT) {
-                float klo = 0.f, khi = 0.f;
-#pragma unroll
-                for (int j = 0; j < NE; ++j) {
-                    if ((f & (NE - 1)) == j) klo = __builtin_fmaf(pv.s[ch], lut[j], pv.z[ch]);
-                    if ((f >> BITS) == j) khi = __builtin_fmaf(pv.s[ch + 64], lut[j], pv.z[ch + 64]);
-                }
-                a = qa * klo + qb * khi;
-                b = qb * klo - qa * khi;
-            } else {
-                const int code = f & (NE - 1), upper = f >> BITS;   // [0,NE): lower channel, [NE,2NE): upper
-                float k = 0.f;
-#pragma unroll
-                for (int j = 0; j < NE; ++j)
-                    if (code == j) k = __builtin_fmaf(pv.s[ch + 64 * upper], lut[j], pv.z[ch + 64 * upper]);
-                a = upper ? qb * k : qa * k;
-                b = upper ? -qa * k : qb * k;
-            }
-            if (pass == 0) {
-                float m = fmaxf(__builtin_fabsf(a), __builtin_fabsf(b));
-                atomicMax((unsigned int *)&hmax[qh], __float_as_uint(m));   // non-negative floats order as uints
-            } else {
-                // scale so the largest entry of the head lands in [2^12, 2^13)
-                int ex;
-                (void)__builtin_frexpf(hmax[qh], &ex);
-                const float up = __builtin_ldexpf(1.0f, 13 - ex);
-                tab[e] = half2_t{(half_t)(a * up), (half_t)(b * up)};
-            }
+        for (int j = 0; j < NE; ++j) {
+            const float v = pv.hdr->lut_k[j];
+            if ((f & (NE - 1)) == j) lut_a = v;
+            if (C::JOINT && (f >> BITS) == j) lut_b = v;
         }
-        __syncthreads();
-    }
-    float down[QH];
+        const bool upper = !C::JOINT && f >= NE;         // split tables: second half belongs to channel i+64
+        for (int pass = 0; pass < 2; ++pass) {
+            for (int qh = 0; qh < QH; ++qh) {
+                float m = 0.f, up = 0.f;
+                if (pass == 1) {
+                    int ex;
+                    (void)__builtin_frexpf(hmax[qh], &ex);
+                    up = __builtin_ldexpf(1.0f, 13 - ex);   // largest entry of the head lands in [2^12, 2^13)
+                }
 #pragma unroll
-    for (int qh = 0; qh < QH; ++qh) {
+                for (int it = 0; it < 64 / STEP; ++it) {
+                    const int i = wave * TW + sub + it * STEP;
+                    const float2_t lo = szs[(qh / R) * 128 + i], hi = szs[(qh / R) * 128 + i + 64];
+                    const float qa = qs[qh * 128 + i], qb = qs[qh * 128 + i + 64];
+                    float a, b;
+                    if (C::JOINT) {
+                        const float klo = __builtin_fmaf(lo.x, lut_a, lo.y), khi = __builtin_fmaf(hi.x, lut_b, hi.y);
+                        a = qa * klo + qb * khi;
+                        b = qb * klo - qa * khi;
+                    } else {
+                        const float k = upper ? __builtin_fmaf(hi.x, lut_a, hi.y) : __builtin_fmaf(lo.x, lut_a, lo.y);
+                        a = upper ? qb * k : qa * k;
+                        b = upper ? -qa * k : qb * k;
+                    }
+                    if (pass == 0) m = fmaxf(m, fmaxf(__builtin_fabsf(a), __builtin_fabsf(b)));
+                    else tab[(qh * 64 + i) * ENT + f] = half2_t{(half_t)(a * up), (half_t)(b * up)};
+                }
+                if (pass == 0) {
+                    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+                    if (lane == 0) atomicMax((unsigned int *)&hmax[qh], __float_as_uint(m));   // non-negative floats order as uints
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (tid < QH) {                                       // per-head factor that undoes the table scaling
         int ex;
-        (void)__builtin_frexpf(hmax[qh], &ex);
-        down[qh] = (hmax[qh] > 0.f) ? __builtin_ldexpf(1.0f, ex - 13) : 0.f;
+        (void)__builtin_frexpf(hmax[tid], &ex);
+        down_s[tid] = (hmax[tid] > 0.f) ? __builtin_ldexpf(1.0f, ex - 13) : 0.f;
     }
+    __syncthreads();
 
-    // ---- token tiles ------------------------------------------------------------------------
-    const int64_t tile0 = (int64_t)blockIdx.x * tiles_per_wg;
-    for (int tile = 0; tile < tiles_per_wg; ++tile) {
-        const int64_t n = (tile0 + tile) * NT + tid;
-        if (n >= L) continue;                          // no barriers below: lanes may drop out
-        uint32_t W[KVH][C::CW];
+    // ---- token tiles (software-pipelined over the workgroup's tiles) -------------------------
+    const int64_t plane = cap * 16 * BITS;                 // bytes between consecutive KV heads
+    int64_t n = (int64_t)blockIdx.x * tiles_per_wg * NT + tid;
+    bool valid = n < L;
+    uint32_t W[KVH][C::CW];
+    if (valid) {
+        const uint8_t *p = k_codes + kvq_k_piece0(BITS, cap, n, kv0);
 #pragma unroll
-        for (int g = 0; g < KVH; ++g) {
-            const uint8_t *p = k_codes + kvq_k_piece0(BITS, cap, n, kv0 + g);
+        for (int g = 0; g < KVH; ++g)
 #pragma unroll
             for (int j = 0; j < BITS; ++j) {
-                const uint4 v = *(const uint4 *)(p + j * 1024);
+                const uint4 v = *(const uint4 *)(p + g * plane + j * 1024);
                 W[g][4 * j + 0] = v.x; W[g][4 * j + 1] = v.y; W[g][4 * j + 2] = v.z; W[g][4 * j + 3] = v.w;
             }
-        }
+    }
+    for (int tile = 0; tile < tiles_per_wg; ++tile) {
+        const int64_t nn = n + NT;
+        const bool next_valid = (tile + 1 < tiles_per_wg) && (nn < L);
+        const uint8_t *next_chunk = k_codes + kvq_k_piece0(BITS, cap, next_valid ? nn : n, kv0);
         const float nf = (float)n;
         float acc[QH];
 #pragma unroll
         for (int qh = 0; qh < QH; ++qh) acc[qh] = 0.f;
+        // lanes past the end run the arithmetic on whatever their registers hold (table offsets are
+        // masked, so every gather stays inside the table) and simply skip loads and stores
+        qk_all_pairs<BITS, QH, R>(std::make_integer_sequence<int, 64 / PAIR_GROUP>{}, W, acc, tab, nf, pv.hdr,
+                                  next_chunk, plane, next_valid);
+        if (valid) {
+#pragma unroll
+            for (int qh = 0; qh < QH; ++qh)
+                scores[(int64_t)(q0 + qh) * ld + n] = acc[qh] * down_s[qh];
+        }
+        n = nn;
+        valid = next_valid;
+    }
+}
 
-        // dense part
-        qk_all_pairs<BITS, QH, R>(std::make_integer_sequence<int, 64 / PAIR_GROUP>{}, W, acc, tab, nf, pv.hdr);
+// Sparse Key outliers, balanced (paper App. "Kernel Implementation Details": equal non-zeros per
+// thread): lanes are outlier entries.  A workgroup owns a chunk of `tc` consecutive tokens, stages
+// their pointers in LDS, finds each entry's token by a guess plus a short walk, rotates the
+// query instead of the Key (by linearity  <q, R_n (v e_c)> = v (R_n^T q)_c ) and accumulates
+// scale * v * (R_n^T q)_c into an LDS tile [query head][token] (fixed-point integer atomics: LDS
+// floating-point atomics are an order of magnitude slower here), which it then adds to the dense
+// scores already in the score buffer.  Entries are fetched several at a time so that their global
+// loads overlap.
+template <int R>
+__global__ __launch_bounds__(1024) void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads,
+                                                      int64_t L, const uint32_t *__restrict__ k_ptr,
+                                                      const uint16_t *__restrict__ k_idx,
+                                                      const uint16_t *__restrict__ k_val,
+                                                      const float *__restrict__ q_rot, float scale,
+                                                      float *__restrict__ scores, int64_t ld, int tc_max)
+{
+    extern __shared__ __attribute__((aligned(16))) float dyn[];
+    // S holds 2^32-scaled fixed-point sums (see kvq_lds_add_fixed).  Rows are padded by one cell: the
+    // outliers of one token hit the same column of many rows, and an unpadded row length would put
+    // them all in one LDS bank.
+    constexpr double FIX = 4294967296.0;
+    const int srow = tc_max + 1;
+    long long *S = (long long *)dyn;                  // [n_q_heads][tc_max + 1]
+    float *qs = dyn + (size_t)n_q_heads * srow * 2;    // [n_q_heads][128]
+    uint32_t *ptr_s = (uint32_t *)(qs + (size_t)n_q_heads * 128);   // [tc_max + 1]
+    __shared__ float2_t rope[64];
+    const KvqParamsView pv = kvq_params_view(params, D);
+    const int tid = threadIdx.x;
+    const int64_t nc = (int64_t)blockIdx.x * tc_max;
+    const int tc = (int)((L - nc < tc_max) ? (L - nc) : tc_max);
+    for (int j = tid; j < n_q_heads * srow; j += 1024) S[j] = 0;
+    for (int j = tid; j < n_q_heads * 128; j += 1024) qs[j] = q_rot[j] * scale;
+    for (int j = tid; j <= tc; j += 1024) ptr_s[j] = k_ptr[nc + j];
+    if (tid < 64) rope[tid] = float2_t{pv.hdr->rope_vh[tid], pv.hdr->rope_vl[tid]};
+    __syncthreads();
+    const uint32_t e_begin = ptr_s[0], e_end = ptr_s[tc];
+    const uint32_t per = (e_end - e_begin) / (uint32_t)tc;
+    constexpr int U = 8;                              // entries in flight per lane
+    for (uint32_t e0 = e_begin + tid; e0 < e_end; e0 += 1024 * U) {
+        uint32_t chv[U];
+        uint16_t vb[U];
 #pragma unroll
-        for (int qh = 0; qh < QH; ++qh) acc[qh] *= down[qh];
-
-        // sparse part: this token's outliers whose channel lies in the workgroup's KV heads.
-        // Entries are sorted by channel; outliers are spread evenly over channels (per-channel
-        // thresholds), so the start is found by interpolation and a short walk.
-        {
-            const uint32_t e0 = k_ptr[n], e1 = k_ptr[n + 1];
-            const uint32_t target = (uint32_t)kv0 * 128u;
-            uint32_t e = e0 + (uint32_t)(((uint64_t)(e1 - e0) * (uint32_t)kv0) / (uint32_t)n_kv_heads);
-            while (e > e0 && k_idx[e - 1] >= target) --e;
-            while (e < e1 && k_idx[e] < target) ++e;
-#pragma unroll
-            for (int g = 0; g < KVH; ++g) {
-                while (e < e1) {
-                    const uint32_t ch = k_idx[e];
-                    if ((ch >> 7) != (uint32_t)(kv0 + g)) break;
-                    const float v = kvq_h2f(k_val[e]);
-                    const int i = ch & 63, upper = (ch >> 6) & 1;
-                    const float2_t vv = rope[i];
-                    const float rev = rope_rev(nf, vv.x, vv.y);
-                    const float cs = __builtin_amdgcn_cosf(rev), sn = __builtin_amdgcn_sinf(rev);
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        const int qh = g * R + r;
-                        const float qa = qs[qh * 128 + i], qb = qs[qh * 128 + i + 64];
-                        const float qp = upper ? (qb * cs - qa * sn) : (qa * cs + qb * sn);
-                        acc[qh] = __builtin_fmaf(v, qp, acc[qh]);
-                    }
-                    ++e;
-                }
-            }
+        for (int u = 0; u < U; ++u) {
+            const uint32_t e = e0 + 1024u * u;
+            const uint32_t ec = (e < e_end) ? e : e_end - 1;   // clamped: straight-line loads, all in flight
+            chv[u] = (uint32_t)k_idx[ec];
+            vb[u] = k_val[ec];
         }
 #pragma unroll
-        for (int qh = 0; qh < QH; ++qh) scores[(int64_t)(q0 + qh) * ld + n] = acc[qh];
+        for (int u = 0; u < U; ++u) {
+            const uint32_t e = e0 + 1024u * u;
+            if (e >= e_end) break;
+            const uint32_t ch = chv[u];
+            const float v = kvq_h2f(vb[u]);
+            int t = per ? (int)((e - e_begin) / per) : 0;
+            if (t >= tc) t = tc - 1;
+            while (ptr_s[t] > e) --t;                 // ptr_s[0] <= e, so this stops at t >= 0
+            while (ptr_s[t + 1] <= e) ++t;            // ptr_s[tc] > e, so this stops at t < tc
+            const int kvh = ch >> 7, i = ch & 63, upper = (ch >> 6) & 1;
+            const float2_t vv = rope[i];
+            const float rev = rope_rev((float)(nc + t), vv.x, vv.y);
+            const float cs = __builtin_amdgcn_cosf(rev), sn = __builtin_amdgcn_sinf(rev);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int qh = kvh * R + r;
+                const float qa = qs[qh * 128 + i], qb = qs[qh * 128 + i + 64];
+                const float qp = upper ? (qb * cs - qa * sn) : (qa * cs + qb * sn);
+                kvq_lds_add_fixed(&S[qh * srow + t], v * qp, FIX);
+            }
+        }
     }
+    __syncthreads();
+    // add the tile to the dense scores: one wavefront per query-head row, all of a row's loads in flight
+    {
+        const int lane = tid & 63, wave = tid >> 6;
+        for (int qh = wave; qh < n_q_heads; qh += 16) {
+            float *row = scores + (int64_t)qh * ld + nc;
+            float v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int t = lane + 64 * k;
+                v[k] = (t < tc) ? row[t] : 0.f;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int t = lane + 64 * k;
+                if (t < tc) row[t] = v[k] + (float)((double)S[qh * srow + t] * (1.0 / FIX));
+            }
+        }
+    }
+}
+
+template <int R>
+kvq_status launch_qk_sparse(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
+{
+    const int Hq = c->n_q_heads;
+    const int64_t L = c->n_tokens_k;
+    // LDS: Hq*tc floats + Hq*128 floats + (tc+1) words, kept under 60 KiB
+    int tc = (int)((61440 - 4 - (int64_t)Hq * 520) / ((int64_t)Hq * 8 + 4));
+    tc = (tc >= 256) ? 256 : (tc / 64) * 64;
+    if (tc < 64) return KVQ_ERR_UNSUPPORTED;
+    const size_t lds = (size_t)Hq * (tc + 1) * 8 + (size_t)Hq * 128 * 4 + (size_t)(tc + 1) * 4;
+    const unsigned grid = (unsigned)((L + tc - 1) / tc);
+    kvq_qk_sparse<R><<<grid, 1024, lds, s>>>(c->params, c->n_kv_heads * KVQ_HEAD_DIM, Hq, L, c->k_ptr, c->k_idx,
+                                             c->k_val, q, scale, scores, ld, tc);
+    KVQ_HIP_CHECK(hipGetLastError());
+    return KVQ_OK;
 }
 
 template <int BITS, int QH, int R, int NT>
@@ -272,9 +387,14 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     int64_t tpw = (tiles * groups + 511) / 512;
     if (tpw < 1) tpw = 1;
     if (tpw > 16) tpw = 16;
+    if (const char *e = getenv("KVQ_QK_TPW")) tpw = atoi(e);   // TEMPORARY tuning knob
     dim3 grid((unsigned)((tiles + tpw - 1) / tpw), (unsigned)groups);
-    kern<<<grid, NT, 0, s>>>(c->params, D, c->n_kv_heads, c->cap_tokens, L, c->k_codes, c->k_ptr, c->k_idx,
-                               c->k_val, q, scale, scores, ld, (int)tpw);
+    kern<<<grid, NT, 0, s>>>(c->params, D, c->n_kv_heads, c->cap_tokens, L, c->k_codes, q, scale, scores, ld,
+                               (int)tpw);
+    if (!(c->loaded & 2)) {                              // bit 1: thresholds admit no Key outliers
+        kvq_status st = launch_qk_sparse<R>(c, q, scale, scores, ld, s);
+        if (st != KVQ_OK) return st;
+    }
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }
@@ -285,7 +405,11 @@ kvq_status dispatch_qk(const kvq_cache *c, const float *q, float scale, float *s
 {
     constexpr int QHMAX = (BITS == 3) ? 8 : 8;
     constexpr int QH = (R > QHMAX) ? R : QHMAX;
-    if (c->n_q_heads % QH == 0) return launch_qk<BITS, QH, R, 512>(c, q, scale, scores, ld, s);
+    if (c->n_q_heads % QH == 0) {
+        if (const char *e = getenv("KVQ_QK_NT"))   // TEMPORARY tuning knob
+            if (atoi(e) == 1024) return launch_qk<BITS, QH, R, 1024>(c, q, scale, scores, ld, s);
+        return launch_qk<BITS, QH, R, 512>(c, q, scale, scores, ld, s);
+    }
     // small models (fewer query heads than the preferred group): one KV head's query heads per workgroup
     return launch_qk<BITS, R, R, 512>(c, q, scale, scores, ld, s);
 }
