@@ -7,9 +7,10 @@
 //     A = q_i k_i + q_{i+64} k_{i+64},   B = q_{i+64} k_i - q_i k_{i+64},   k_c = s_c lut[code_c] + z_c.
 // A and B depend on the token only through the two codes, which the storage format keeps side by
 // side in one 2b-bit field.  Each workgroup therefore builds, per query head and channel pair, a
-// table of (A,B) for every code pair in LDS (fp16 pairs, query, scale and zero-point folded in), and
-// the hot loop per (token, head, pair) is: extract a field, one LDS gather, two mixed-precision FMAs
-// with the fp32 cos/sin of the token's angle.  cos/sin are computed once per (token, pair) and
+// table of (A,B) for every code pair in LDS (fp32 pairs, query, scale and zero-point folded in), and
+// the hot loop per (token, head, pair) is: extract a field, one 8-byte LDS gather, two fp32 FMAs
+// with the cos/sin of the token's angle.  (fp16 table entries would halve the LDS footprint, but their
+// 2^-11 relative rounding leaves the scores only just inside a 1e-3 tolerance.)  cos/sin are computed once per (token, pair) and
 // shared by all query heads the workgroup handles.  Lanes are tokens; a wavefront reads 1 KiB of
 // contiguous codes per load instruction, and the 16-byte pieces of the next token tile are requested
 // as soon as the current tile no longer needs the registers they land in, so HBM latency hides
@@ -27,21 +28,28 @@ template <int BITS>
 struct QkCfg {
     static constexpr bool JOINT = BITS <= 3;
     static constexpr int NE = 1 << BITS;
-    static constexpr int ENTRIES = JOINT ? (1 << (2 * BITS)) : 2 * NE;   // half2 entries per (head, pair)
+    static constexpr int ENTRIES = JOINT ? (1 << (2 * BITS)) : 2 * NE;   // (A,B) entries per (head, pair)
     static constexpr int CW = 4 * BITS;                                  // dwords per chunk
 };
 
-// Byte offset (field value * 4) of field `i` of a chunk held in registers, for a joint table.
+// The chunk of one (token, head) is consumed front to back, so only two of its 16-byte pieces need to
+// be in registers at a time: piece j lives in slot j & 1 (4 dwords each).  Dword `wi` of the chunk:
+__device__ __forceinline__ uint32_t chunk_dword(const uint32_t (&Wg)[8], int wi)
+{
+    return Wg[((wi >> 2) & 1) * 4 + (wi & 3)];
+}
+
+// Byte offset (field value * 8) of field `i` of a chunk, for indexing a table of 8-byte entries.
 template <int FBITS>   // field width in bits
-__device__ inline uint32_t field_x4(const uint32_t *W, int i)
+__device__ __forceinline__ uint32_t field_x8(const uint32_t (&Wg)[8], int i)
 {
     const int bit = i * FBITS, wi = bit >> 5, sh = bit & 31;
-    constexpr uint32_t M = ((1u << FBITS) - 1u) << 2;
+    constexpr uint32_t M = ((1u << FBITS) - 1u) << 3;
     if (sh + FBITS <= 32) {
-        if (sh >= 2) return (W[wi] >> (sh - 2)) & M;
-        return (W[wi] << (2 - sh)) & M;
+        if (sh >= 3) return (chunk_dword(Wg, wi) >> (sh - 3)) & M;
+        return (chunk_dword(Wg, wi) << (3 - sh)) & M;
     }
-    return __builtin_amdgcn_alignbit(W[wi + 1], W[wi], sh - 2) & M;
+    return __builtin_amdgcn_alignbit(chunk_dword(Wg, wi + 1), chunk_dword(Wg, wi), sh - 3) & M;
 }
 
 // Angle of channel pair i at position n, in revolutions, reduced to about [0,1): n*theta_i/(2 pi)
@@ -61,19 +69,18 @@ __device__ inline float rope_rev(float nf, float vh, float vl)
 //   2. the group's angles -> (cos, sin), shared by all query heads,
 //   3. two mixed-precision FMAs per (pair, query head).
 // G0 is a compile-time constant so that all register-array indices fold.
-constexpr int PAIR_GROUP = 2;
-
-template <int BITS, int QH, int R, int G0>
-__device__ __forceinline__ void qk_group(uint32_t (&W)[QH / R][QkCfg<BITS>::CW], float (&acc)[QH],
-                                         const half2_t *tab, float nf, const KvqParamsHeader *hdr,
-                                         const uint8_t *next_chunk, int64_t plane, bool next_valid)
+template <int BITS, int KVH, int RQ, int PAIR_GROUP, int G0>
+__device__ __forceinline__ void qk_group(uint32_t (&W)[KVH][8], float (&acc)[KVH * RQ],
+                                         const float2_t *tab, float nf, const KvqParamsHeader *hdr,
+                                         const uint8_t *cur_chunk, const uint8_t *next_chunk, int64_t plane,
+                                         bool valid, bool next_valid)
 {
     using C = QkCfg<BITS>;
-    constexpr int KVH = QH / R;
+    constexpr int QH = KVH * RQ, R = RQ;
     constexpr int NE = C::NE;
     constexpr int ENT = C::ENTRIES;
     constexpr int NG = C::JOINT ? 1 : 2;          // gathers per (pair, query head)
-    half2_t t[PAIR_GROUP][QH][NG];
+    float2_t t[PAIR_GROUP][QH][NG];
 #pragma unroll
     for (int p = 0; p < PAIR_GROUP; ++p) {
         constexpr int dummy = 0; (void)dummy;
@@ -81,14 +88,14 @@ __device__ __forceinline__ void qk_group(uint32_t (&W)[QH / R][QkCfg<BITS>::CW],
 #pragma unroll
         for (int g = 0; g < KVH; ++g) {
             uint32_t off[NG];
-            if (C::JOINT) off[0] = field_x4<2 * BITS>(W[g], I);
-            else { off[0] = field_x4<BITS>(W[g], 2 * I); off[NG - 1] = field_x4<BITS>(W[g], 2 * I + 1); }
+            if (C::JOINT) off[0] = field_x8<2 * BITS>(W[g], I);
+            else { off[0] = field_x8<BITS>(W[g], 2 * I); off[NG - 1] = field_x8<BITS>(W[g], 2 * I + 1); }
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int qh = g * R + r;
                 const uint8_t *tb = (const uint8_t *)(tab + (qh * 64 + I) * ENT);
 #pragma unroll
-                for (int k = 0; k < NG; ++k) t[p][qh][k] = *(const half2_t *)(tb + k * NE * 4 + off[k]);
+                for (int k = 0; k < NG; ++k) t[p][qh][k] = *(const float2_t *)(tb + k * NE * 8 + off[k]);
             }
         }
     }
@@ -106,8 +113,8 @@ __device__ __forceinline__ void qk_group(uint32_t (&W)[QH / R][QkCfg<BITS>::CW],
         for (int qh = 0; qh < QH; ++qh)
 #pragma unroll
             for (int k = 0; k < NG; ++k) {
-                acc[qh] = __builtin_fmaf((float)t[p][qh][k].x, cs[p], acc[qh]);
-                acc[qh] = __builtin_fmaf((float)t[p][qh][k].y, sn[p], acc[qh]);
+                acc[qh] = __builtin_fmaf(t[p][qh][k].x, cs[p], acc[qh]);
+                acc[qh] = __builtin_fmaf(t[p][qh][k].y, sn[p], acc[qh]);
             }
     // Pin the accumulators: an empty asm that "modifies" them and clobbers memory keeps the compiler
     // from hoisting later groups' gathers above this point (register pressure) or sinking this
@@ -115,68 +122,88 @@ __device__ __forceinline__ void qk_group(uint32_t (&W)[QH / R][QkCfg<BITS>::CW],
 #pragma unroll
     for (int qh = 0; qh < QH; ++qh) asm volatile("" : "+v"(acc[qh]) : : "memory");
     // Software pipelining: a 16-byte piece of the chunk is dead once the last field that touches it
-    // has been consumed; request the same piece of the NEXT token tile into those registers now.
+    // has been consumed; the piece two positions further down the stream (of this tile, or of the
+    // next tile once this one runs out) is requested into its register slot right away, so every
+    // load has a third of a tile's arithmetic to hide behind.
     constexpr int FB = 2 * BITS;
     constexpr int first_field = G0 * PAIR_GROUP, last_field = first_field + PAIR_GROUP - 1;
 #pragma unroll
     for (int j = 0; j < BITS; ++j) {
         const int last_user = (128 * (j + 1) - 1) / FB;      // last field with a bit in piece j
-        if (last_user >= first_field && last_user <= last_field && next_valid) {
+        if (last_user >= first_field && last_user <= last_field) {
+            const int jn = j + 2;                            // stream position of the piece to fetch
+            if (jn < BITS) {
+                if (valid) {
 #pragma unroll
-            for (int g = 0; g < KVH; ++g) {
-                const uint4 v = *(const uint4 *)(next_chunk + g * plane + j * 1024);
-                W[g][4 * j + 0] = v.x; W[g][4 * j + 1] = v.y; W[g][4 * j + 2] = v.z; W[g][4 * j + 3] = v.w;
+                    for (int g = 0; g < KVH; ++g) {
+                        const uint4 v = *(const uint4 *)(cur_chunk + g * plane + jn * 1024);
+                        W[g][(jn & 1) * 4 + 0] = v.x; W[g][(jn & 1) * 4 + 1] = v.y;
+                        W[g][(jn & 1) * 4 + 2] = v.z; W[g][(jn & 1) * 4 + 3] = v.w;
+                    }
+                }
+            } else if (jn - BITS == 0 || (BITS & 1) == 0) {
+                // next tile's piece 0 (or, for an even piece count, also its piece 1) lands in the slot just freed
+                const int jt = jn - BITS;
+                if (next_valid) {
+#pragma unroll
+                    for (int g = 0; g < KVH; ++g) {
+                        const uint4 v = *(const uint4 *)(next_chunk + g * plane + jt * 1024);
+                        W[g][(j & 1) * 4 + 0] = v.x; W[g][(j & 1) * 4 + 1] = v.y;
+                        W[g][(j & 1) * 4 + 2] = v.z; W[g][(j & 1) * 4 + 3] = v.w;
+                    }
+                }
             }
+            // odd piece count, last piece: handled at the end of the tile (the slots swap roles there)
         }
     }
 }
 
-template <int BITS, int QH, int R, int... G>
+template <int BITS, int KVH, int RQ, int PG, int... G>
 __device__ __forceinline__ void qk_all_pairs(std::integer_sequence<int, G...>,
-                                             uint32_t (&W)[QH / R][QkCfg<BITS>::CW], float (&acc)[QH],
-                                             const half2_t *tab, float nf, const KvqParamsHeader *hdr,
-                                             const uint8_t *next_chunk, int64_t plane, bool next_valid)
+                                             uint32_t (&W)[KVH][8], float (&acc)[KVH * RQ],
+                                             const float2_t *tab, float nf, const KvqParamsHeader *hdr,
+                                             const uint8_t *cur_chunk, const uint8_t *next_chunk, int64_t plane,
+                                             bool valid, bool next_valid)
 {
-    (qk_group<BITS, QH, R, G>(W, acc, tab, nf, hdr, next_chunk, plane, next_valid), ...);
+    (qk_group<BITS, KVH, RQ, PG, G>(W, acc, tab, nf, hdr, cur_chunk, next_chunk, plane, valid, next_valid), ...);
 }
 
-template <int BITS, int QH, int R, int NT>
-__global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ params, int D, int n_kv_heads,
+// KVH KV heads per workgroup, RQ query heads per KV head handled here (RQ divides the model's GQA
+// ratio `r`; when RQ < r several workgroups share a KV head), PG channel pairs per gather group.
+template <int BITS, int KVH, int RQ, int NT, int PG>
+__global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ params, int D, int r,
                                                     int64_t cap, int64_t L, const uint8_t *__restrict__ k_codes,
                                                     const float *__restrict__ q_rot, float scale,
                                                     float *__restrict__ scores, int64_t ld, int tiles_per_wg)
 {
     using C = QkCfg<BITS>;
-    constexpr int KVH = QH / R;
+    constexpr int QH = KVH * RQ, R = RQ;
     constexpr int NE = C::NE;
     constexpr int ENT = C::ENTRIES;
-    // Statically sized LDS (up to 132 KiB of the 160 KiB a gfx950 workgroup may use): with a known base
+    // Statically sized LDS (up to 136 KiB of the 160 KiB a gfx950 workgroup may use): with a known base
     // address the table offsets fold into the gathers' immediate offsets.
-    __shared__ __attribute__((aligned(16))) half2_t tab[QH * 64 * ENT];   // [QH][64][ENT]
+    __shared__ __attribute__((aligned(16))) float2_t tab[QH * 64 * ENT];  // [QH][64][ENT]
     __shared__ float qs[QH * 128];                                        // query * scale
     __shared__ float2_t szs[(QH / R) * 128];                              // per-channel (scale, zero-point)
-    __shared__ float hmax[QH];                                            // table magnitude per head
-    __shared__ float down_s[QH];
+
     const KvqParamsView pv = kvq_params_view(params, D);
     const int tid = threadIdx.x;
     const int q0 = blockIdx.y * QH;
-    const int kv0 = q0 / R;
+    const int kv0 = q0 / r;
 
     // ---- stage query, rope constants, per-channel (scale, zero-point) -------------------------
     for (int j = tid; j < QH * 128; j += NT) qs[j] = q_rot[(int64_t)q0 * 128 + j] * scale;
     for (int j = tid; j < KVH * 128; j += NT) szs[j] = float2_t{pv.s[kv0 * 128 + j], pv.z[kv0 * 128 + j]};
-    if (tid < QH) hmax[tid] = 0.0f;
     __syncthreads();
 
     // ---- build the (A,B) tables -----------------------------------------------------------
     // A table (one query head, one channel pair) has ENT entries; ENT lanes of a wavefront fill it,
     // one entry each, so a lane's signposts are loop constants and LDS writes are conflict-free.
-    // Pass 0 finds the largest magnitude per query head, pass 1 stores the entries scaled by a power
-    // of two so that fp16 neither overflows nor loses small heads to subnormals.
     {
         constexpr int TW = 64 / ENT;                     // tables per wavefront step
         constexpr int NWAVES = NT / 64;
-        constexpr int STEP = NWAVES * TW;                // tables per workgroup step (divides 64)
+        constexpr int STEP = NWAVES * TW;                // tables per workgroup step
+        static_assert(64 % STEP == 0 || STEP % 64 == 0, "table build assumes the step divides the pair count");
         const int lane = tid & 63, wave = tid >> 6;
         const int f = lane % ENT, sub = lane / ENT;
         float lut_a = 0.f, lut_b = 0.f;                  // joint: signposts of the two codes; split: lut_a only
@@ -187,59 +214,37 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
             if (C::JOINT && (f >> BITS) == j) lut_b = v;
         }
         const bool upper = !C::JOINT && f >= NE;         // split tables: second half belongs to channel i+64
-        for (int pass = 0; pass < 2; ++pass) {
-            for (int qh = 0; qh < QH; ++qh) {
-                float m = 0.f, up = 0.f;
-                if (pass == 1) {
-                    int ex;
-                    (void)__builtin_frexpf(hmax[qh], &ex);
-                    up = __builtin_ldexpf(1.0f, 13 - ex);   // largest entry of the head lands in [2^12, 2^13)
-                }
-#pragma unroll
-                for (int it = 0; it < 64 / STEP; ++it) {
-                    const int i = wave * TW + sub + it * STEP;
-                    const float2_t lo = szs[(qh / R) * 128 + i], hi = szs[(qh / R) * 128 + i + 64];
-                    const float qa = qs[qh * 128 + i], qb = qs[qh * 128 + i + 64];
-                    float a, b;
-                    if (C::JOINT) {
-                        const float klo = __builtin_fmaf(lo.x, lut_a, lo.y), khi = __builtin_fmaf(hi.x, lut_b, hi.y);
-                        a = qa * klo + qb * khi;
-                        b = qb * klo - qa * khi;
-                    } else {
-                        const float k = upper ? __builtin_fmaf(hi.x, lut_a, hi.y) : __builtin_fmaf(lo.x, lut_a, lo.y);
-                        a = upper ? qb * k : qa * k;
-                        b = upper ? -qa * k : qb * k;
-                    }
-                    if (pass == 0) m = fmaxf(m, fmaxf(__builtin_fabsf(a), __builtin_fabsf(b)));
-                    else tab[(qh * 64 + i) * ENT + f] = half2_t{(half_t)(a * up), (half_t)(b * up)};
-                }
-                if (pass == 0) {
-                    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-                    if (lane == 0) atomicMax((unsigned int *)&hmax[qh], __float_as_uint(m));   // non-negative floats order as uints
-                }
+        for (int tb = wave * TW + sub; tb < QH * 64; tb += STEP) {
+            const int qh = tb >> 6, i = tb & 63;
+            const float2_t lo = szs[(qh / R) * 128 + i], hi = szs[(qh / R) * 128 + i + 64];
+            const float qa = qs[qh * 128 + i], qb = qs[qh * 128 + i + 64];
+            float a, b;
+            if (C::JOINT) {
+                const float klo = __builtin_fmaf(lo.x, lut_a, lo.y), khi = __builtin_fmaf(hi.x, lut_b, hi.y);
+                a = qa * klo + qb * khi;
+                b = qb * klo - qa * khi;
+            } else {
+                const float k = upper ? __builtin_fmaf(hi.x, lut_a, hi.y) : __builtin_fmaf(lo.x, lut_a, lo.y);
+                a = upper ? qb * k : qa * k;
+                b = upper ? -qa * k : qb * k;
             }
-            __syncthreads();
+            tab[tb * ENT + f] = float2_t{a, b};
         }
+        __syncthreads();
     }
-    if (tid < QH) {                                       // per-head factor that undoes the table scaling
-        int ex;
-        (void)__builtin_frexpf(hmax[tid], &ex);
-        down_s[tid] = (hmax[tid] > 0.f) ? __builtin_ldexpf(1.0f, ex - 13) : 0.f;
-    }
-    __syncthreads();
 
     // ---- token tiles (software-pipelined over the workgroup's tiles) -------------------------
     const int64_t plane = cap * 16 * BITS;                 // bytes between consecutive KV heads
     int64_t n = (int64_t)blockIdx.x * tiles_per_wg * NT + tid;
     bool valid = n < L;
-    uint32_t W[KVH][C::CW];
+    uint32_t W[KVH][8];                                    // two 16-byte pieces per KV head
+    const uint8_t *cur_chunk = k_codes + kvq_k_piece0(BITS, cap, valid ? n : 0, kv0);
     if (valid) {
-        const uint8_t *p = k_codes + kvq_k_piece0(BITS, cap, n, kv0);
 #pragma unroll
         for (int g = 0; g < KVH; ++g)
 #pragma unroll
-            for (int j = 0; j < BITS; ++j) {
-                const uint4 v = *(const uint4 *)(p + g * plane + j * 1024);
+            for (int j = 0; j < 2; ++j) {
+                const uint4 v = *(const uint4 *)(cur_chunk + g * plane + j * 1024);
                 W[g][4 * j + 0] = v.x; W[g][4 * j + 1] = v.y; W[g][4 * j + 2] = v.z; W[g][4 * j + 3] = v.w;
             }
     }
@@ -253,15 +258,29 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
         for (int qh = 0; qh < QH; ++qh) acc[qh] = 0.f;
         // lanes past the end run the arithmetic on whatever their registers hold (table offsets are
         // masked, so every gather stays inside the table) and simply skip loads and stores
-        qk_all_pairs<BITS, QH, R>(std::make_integer_sequence<int, 64 / PAIR_GROUP>{}, W, acc, tab, nf, pv.hdr,
-                                  next_chunk, plane, next_valid);
+        qk_all_pairs<BITS, KVH, RQ, PG>(std::make_integer_sequence<int, 64 / PG>{}, W, acc, tab, nf, pv.hdr,
+                                  cur_chunk, next_chunk, plane, valid, next_valid);
+        if (BITS & 1) {
+            // odd piece count: the next tile's piece 0 arrived in slot 1; move it to slot 0 (whose last
+            // occupant is dead now) and request the next tile's piece 1 into slot 1
+#pragma unroll
+            for (int g = 0; g < KVH; ++g) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) W[g][k] = W[g][4 + k];
+                if (next_valid) {
+                    const uint4 v = *(const uint4 *)(next_chunk + g * plane + 1024);
+                    W[g][4] = v.x; W[g][5] = v.y; W[g][6] = v.z; W[g][7] = v.w;
+                }
+            }
+        }
         if (valid) {
 #pragma unroll
             for (int qh = 0; qh < QH; ++qh)
-                scores[(int64_t)(q0 + qh) * ld + n] = acc[qh] * down_s[qh];
+                scores[(int64_t)(q0 + qh) * ld + n] = acc[qh];
         }
         n = nn;
         valid = next_valid;
+        cur_chunk = next_chunk;
     }
 }
 
@@ -374,23 +393,23 @@ kvq_status launch_qk_sparse(const kvq_cache *c, const float *q, float scale, flo
     return KVQ_OK;
 }
 
-template <int BITS, int QH, int R, int NT>
+template <int BITS, int KVH, int RQ, int NT, int PG, int R>
 kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
 {
-    using C = QkCfg<BITS>;
+    constexpr int QH = KVH * RQ;
     const int D = c->n_kv_heads * KVQ_HEAD_DIM;
     const int64_t L = c->n_tokens_k;
-    auto kern = kvq_qk_kernel<BITS, QH, R, NT>;
+    auto kern = kvq_qk_kernel<BITS, KVH, RQ, NT, PG>;
     const int groups = c->n_q_heads / QH;
     const int64_t tiles = (L + NT - 1) / NT;
-    // about two workgroups per compute unit in total; each builds its tables once
-    int64_t tpw = (tiles * groups + 511) / 512;
+    // about one workgroup per compute unit in total (the tables fill most of a CU's LDS); each
+    // workgroup builds its tables once and then streams its tiles
+    int64_t tpw = (tiles * groups + 255) / 256;
     if (tpw < 1) tpw = 1;
-    if (tpw > 16) tpw = 16;
+    if (tpw > 64) tpw = 64;
     if (const char *e = getenv("KVQ_QK_TPW")) tpw = atoi(e);   // TEMPORARY tuning knob
     dim3 grid((unsigned)((tiles + tpw - 1) / tpw), (unsigned)groups);
-    kern<<<grid, NT, 0, s>>>(c->params, D, c->n_kv_heads, c->cap_tokens, L, c->k_codes, q, scale, scores, ld,
-                               (int)tpw);
+    kern<<<grid, NT, 0, s>>>(c->params, D, R, c->cap_tokens, L, c->k_codes, q, scale, scores, ld, (int)tpw);
     if (!(c->loaded & 2)) {                              // bit 1: thresholds admit no Key outliers
         kvq_status st = launch_qk_sparse<R>(c, q, scale, scores, ld, s);
         if (st != KVQ_OK) return st;
@@ -399,19 +418,22 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     return KVQ_OK;
 }
 
-// Query heads per workgroup: as many as fit the LDS budget, a multiple of the GQA ratio R.
+// Query heads per workgroup: as many as fit the LDS budget (fp32 (A,B) tables: 64 pairs x entries x
+// 8 bytes per query head = 8 / 32 / 16 KiB for 2 / 3 / 4 bits).
 template <int BITS, int R>
 kvq_status dispatch_qk(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
 {
-    constexpr int QHMAX = (BITS == 3) ? 8 : 8;
-    constexpr int QH = (R > QHMAX) ? R : QHMAX;
-    if (c->n_q_heads % QH == 0) {
-        if (const char *e = getenv("KVQ_QK_NT"))   // TEMPORARY tuning knob
-            if (atoi(e) == 1024) return launch_qk<BITS, QH, R, 1024>(c, q, scale, scores, ld, s);
-        return launch_qk<BITS, QH, R, 512>(c, q, scale, scores, ld, s);
+    constexpr int QHMAX = (BITS == 3) ? 4 : 8;
+    constexpr int PG = (BITS == 4) ? 1 : 2;
+    if constexpr (R >= QHMAX) {
+        // one KV head per workgroup, QHMAX of its query heads (R / QHMAX workgroups share the KV head)
+        return launch_qk<BITS, 1, QHMAX, 1024, PG, R>(c, q, scale, scores, ld, s);
+    } else {
+        constexpr int KVH = QHMAX / R;
+        if (c->n_kv_heads % KVH == 0) return launch_qk<BITS, KVH, R, 1024, PG, R>(c, q, scale, scores, ld, s);
+        // few KV heads: one per workgroup
+        return launch_qk<BITS, 1, R, 512, PG, R>(c, q, scale, scores, ld, s);
     }
-    // small models (fewer query heads than the preferred group): one KV head's query heads per workgroup
-    return launch_qk<BITS, R, R, 512>(c, q, scale, scores, ld, s);
 }
 
 template <int BITS>
