@@ -7,13 +7,15 @@
 
 namespace {
 
-constexpr int NT = 256;            // threads per workgroup
-constexpr int NW = NT / 64;        // wavefronts per workgroup
+// Workgroups have NT threads: 256 for narrow models, 1024 once a token vector has >= 2048 channels
+// (fewer passes over the vector, hence fewer barriers, for the single-token decode append).
 
 // Exclusive rank of this thread's flag among all flags of the workgroup, in thread order, plus
-// the workgroup total.  `wave_tot` is a shared array of NW words.  Contains two barriers.
+// the workgroup total.  `wave_tot` is a shared array of NT/64 words.  Contains two barriers.
+template <int NT>
 __device__ inline uint32_t block_rank(bool flag, uint32_t *wave_tot, uint32_t &total)
 {
+    constexpr int NW = NT / 64;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     unsigned long long b = __ballot(flag);
     uint32_t prefix = __popcll(b & ((1ull << lane) - 1ull));
@@ -32,8 +34,10 @@ __device__ inline uint32_t block_rank(bool flag, uint32_t *wave_tot, uint32_t &t
 }
 
 // Number of Key outliers of each new token (threshold test only).
+template <int NT>
 __global__ __launch_bounds__(NT) void kvq_k_count(const void *params, int D, const uint16_t *k_new, uint32_t *cnt)
 {
+    constexpr int NW = NT / 64;
     __shared__ uint32_t red[NW];
     KvqParamsView pv = kvq_params_view(params, D);
     const int t = blockIdx.x;
@@ -99,7 +103,7 @@ __device__ inline void stream_or(uint32_t *words, int bit, uint32_t value, int w
 // Quantize, pack and append the Keys of one new token per workgroup.
 // If `single` the token's outlier count is written to ptr[n+1] here; otherwise ptr[] was already
 // filled by kvq_ptr_scan and is only read.
-template <int BITS>
+template <int BITS, int NT>
 __global__ __launch_bounds__(NT) void kvq_k_quant(const void *params, int D, int64_t cap, int64_t n0,
                                                   const uint16_t *k_new, uint8_t *k_codes, uint32_t *k_ptr,
                                                   uint16_t *k_idx, uint16_t *k_val, int64_t cap_nnz,
@@ -107,8 +111,10 @@ __global__ __launch_bounds__(NT) void kvq_k_quant(const void *params, int D, int
 {
     constexpr int NE = 1 << BITS;
     constexpr int CW = 4 * BITS;                 // dwords per chunk
+    constexpr int NW = NT / 64;
+    constexpr int HB = NT / KVQ_HEAD_DIM;        // heads covered by one block of NT channels
     __shared__ uint8_t codes_s[NT];
-    __shared__ uint32_t chunk_s[2][CW + 1];
+    __shared__ uint32_t chunk_s[HB][CW + 1];
     __shared__ uint32_t wave_tot[NW];
     KvqParamsView pv = kvq_params_view(params, D);
     float lut[NE];
@@ -136,17 +142,17 @@ __global__ __launch_bounds__(NT) void kvq_k_quant(const void *params, int D, int
             resid = kvq_f2h_rn(x - deq);
             codes_s[tid] = (uint8_t)code;
         }
-        if (tid < 2 * (CW + 1)) (&chunk_s[0][0])[tid] = 0;
+        if (tid < HB * (CW + 1)) (&chunk_s[0][0])[tid] = 0;
         uint32_t tot;
-        uint32_t rank = running + block_rank(is_out, wave_tot, tot);   // barriers inside
+        uint32_t rank = running + block_rank<NT>(is_out, wave_tot, tot);   // barriers inside
         running += tot;
         if (is_out) {
             uint64_t pos = (uint64_t)base + rank;
             if (pos < (uint64_t)cap_nnz) { k_idx[pos] = (uint16_t)c; k_val[pos] = resid; }
             else overflow = true;
         }
-        // pack the (up to) two heads covered by this block of 256 channels
-        const int heads_here = (D - c0 >= NT) ? 2 : (D - c0) / KVQ_HEAD_DIM;
+        // pack the heads covered by this block of NT channels
+        const int heads_here = (D - c0 >= NT) ? HB : (D - c0) / KVQ_HEAD_DIM;
         if (tid < 64 * heads_here) {
             int hh = tid >> 6, i = tid & 63;
             uint32_t field = (uint32_t)codes_s[hh * 128 + i] | ((uint32_t)codes_s[hh * 128 + i + 64] << BITS);
@@ -177,29 +183,50 @@ __device__ inline uint32_t order_key(uint16_t h)
     return (h & 0x8000u) ? (uint32_t)(uint16_t)~h : (uint32_t)(h | 0x8000u);
 }
 
+// For the 256 histogram bins held one per thread (threads >= 256 pass 0): the number of elements in
+// bins strictly above this thread's bin.  Suffix scan inside each wavefront plus the totals of the
+// (up to four) wavefronts that hold bins.  `wsum` is a shared array of 4 words.  One barrier.
+__device__ inline uint32_t bins_above(uint32_t mine, uint32_t *wsum)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t s = mine;                            // becomes the sum over lanes lane..63
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_down(s, o);
+        if (lane + o < 64) s += t;
+    }
+    if (lane == 0 && w < 4) wsum[w] = s;
+    __syncthreads();
+    uint32_t above = s - mine;
+    for (int i = w + 1; i < 4; ++i) above += wsum[i];
+    return above;
+}
+
 // Workgroup-wide selection of the `k` largest keys among elements with state[c]==0, where the key
 // of element c is keys[c] ^ flip (flip = 0xFFFF turns it into a selection of the k smallest).
 // Marks the selected elements with `mark`; equal keys are taken in ascending index order.
+// Two-level radix select on the 16-bit keys; the index-ordered pass over the elements equal to the
+// threshold is only needed when some but not all of them are taken.
+template <int NT>
 __device__ void select_top(const uint16_t *keys, uint8_t *state, int D, int k, uint32_t flip, uint8_t mark,
                            uint32_t *hist, uint32_t *sh, uint32_t *wave_tot)
 {
     const int tid = threadIdx.x;
     // level 1: high byte
-    hist[tid] = 0;
+    if (tid < 256) hist[tid] = 0;
     __syncthreads();
     for (int c = tid; c < D; c += NT)
         if (state[c] == 0) atomicAdd(&hist[((keys[c] ^ flip) & 0xFFFFu) >> 8], 1u);
     __syncthreads();
     {
-        uint32_t above = 0;                       // elements in bins strictly above bin `tid`
-        for (int b = tid + 1; b < 256; ++b) above += hist[b];
-        if (above < (uint32_t)k && above + hist[tid] >= (uint32_t)k) { sh[0] = tid; sh[1] = above; }
+        const uint32_t mine = (tid < 256) ? hist[tid] : 0u;
+        const uint32_t above = bins_above(mine, sh + 4);      // elements in bins strictly above bin `tid`
+        if (tid < 256 && above < (uint32_t)k && above + mine >= (uint32_t)k) { sh[0] = tid; sh[1] = above; }
     }
     __syncthreads();
     const uint32_t bin_hi = sh[0], above_hi = sh[1];
     __syncthreads();
     // level 2: low byte inside the selected high bin
-    hist[tid] = 0;
+    if (tid < 256) hist[tid] = 0;
     __syncthreads();
     for (int c = tid; c < D; c += NT) {
         uint32_t key = (keys[c] ^ flip) & 0xFFFFu;
@@ -207,33 +234,41 @@ __device__ void select_top(const uint16_t *keys, uint8_t *state, int D, int k, u
     }
     __syncthreads();
     {
-        uint32_t above = above_hi;
-        for (int b = tid + 1; b < 256; ++b) above += hist[b];
-        if (above < (uint32_t)k && above + hist[tid] >= (uint32_t)k) { sh[0] = (bin_hi << 8) | tid; sh[1] = above; }
+        const uint32_t mine = (tid < 256) ? hist[tid] : 0u;
+        const uint32_t above = above_hi + bins_above(mine, sh + 4);
+        if (tid < 256 && above < (uint32_t)k && above + mine >= (uint32_t)k) {
+            sh[0] = (bin_hi << 8) | tid; sh[1] = above; sh[2] = mine;
+        }
     }
     __syncthreads();
     const uint32_t tau = sh[0];
     const uint32_t need_eq = (uint32_t)k - sh[1];  // how many elements equal to tau are taken
+    const bool all_eq = need_eq == sh[2];          // ... all of them: no index order needed
     __syncthreads();
-    uint32_t running = 0;
-    for (int c0 = 0; c0 < D; c0 += NT) {
-        const int c = c0 + tid;
-        bool cand = false, eq = false, gt = false;
-        if (c < D && state[c] == 0) {
-            uint32_t key = (keys[c] ^ flip) & 0xFFFFu;
-            gt = key > tau;
-            eq = key == tau;
-            cand = true;
+    if (all_eq) {
+        for (int c = tid; c < D; c += NT)
+            if (state[c] == 0 && ((keys[c] ^ flip) & 0xFFFFu) >= tau) state[c] = mark;
+    } else {
+        uint32_t running = 0;
+        for (int c0 = 0; c0 < D; c0 += NT) {
+            const int c = c0 + tid;
+            bool cand = false, eq = false, gt = false;
+            if (c < D && state[c] == 0) {
+                uint32_t key = (keys[c] ^ flip) & 0xFFFFu;
+                gt = key > tau;
+                eq = key == tau;
+                cand = true;
+            }
+            uint32_t tot;
+            uint32_t rank = running + block_rank<NT>(eq, wave_tot, tot);
+            running += tot;
+            if (cand && (gt || (eq && rank < need_eq))) state[c] = mark;
         }
-        uint32_t tot;
-        uint32_t rank = running + block_rank(eq, wave_tot, tot);
-        running += tot;
-        if (cand && (gt || (eq && rank < need_eq))) state[c] = mark;
     }
     __syncthreads();
 }
 
-template <int BITS>
+template <int BITS, int NT>
 __global__ __launch_bounds__(NT) void kvq_v_quant(const void *params, int D, int64_t cap, int64_t n0, int k_side,
                                                   const uint16_t *v_new, uint8_t *v_codes, uint16_t *v_sz,
                                                   uint32_t *v_ptr, uint16_t *v_idx, uint16_t *v_val,
@@ -244,12 +279,14 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *params, int D, int
     extern __shared__ uint8_t dyn[];              // keys: 2*D bytes, state: D bytes
     uint16_t *keys = (uint16_t *)dyn;
     uint8_t *state = dyn + 2 * (size_t)D;
+    constexpr int NW = NT / 64;
+    constexpr int CB = NT / 64;                   // (head, half) chunks covered by one block of NT channels
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t sh[2];
+    __shared__ uint32_t sh[8];
     __shared__ uint32_t wave_tot[NW];
     __shared__ float redmx[NW], redmn[NW];
     __shared__ uint8_t codes_s[NT];
-    __shared__ uint32_t bits_s[4][CW + 1], mask_s[4][CW + 1];
+    __shared__ uint32_t bits_s[CB][CW + 1], mask_s[CB][CW + 1];
 
     KvqParamsView pv = kvq_params_view(params, D);
     float lut[NE];
@@ -262,8 +299,8 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *params, int D, int
     for (int c = tid; c < D; c += NT) { keys[c] = (uint16_t)order_key(x16[c]); state[c] = 0; }
     __syncthreads();
     if (k_side > 0) {
-        select_top(keys, state, D, k_side, 0u, 1, hist, sh, wave_tot);        // k largest
-        select_top(keys, state, D, k_side, 0xFFFFu, 2, hist, sh, wave_tot);   // k smallest of the rest
+        select_top<NT>(keys, state, D, k_side, 0u, 1, hist, sh, wave_tot);        // k largest
+        select_top<NT>(keys, state, D, k_side, 0xFFFFu, 2, hist, sh, wave_tot);   // k smallest of the rest
     }
     // range of the remaining elements
     float mx = -INFINITY, mn = INFINITY;
@@ -301,17 +338,17 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *params, int D, int
             resid = kvq_f2h_rn(x - deq);
             codes_s[tid] = (uint8_t)code;
         }
-        if (tid < 4 * (CW + 1)) { (&bits_s[0][0])[tid] = 0; (&mask_s[0][0])[tid] = 0; }
+        if (tid < CB * (CW + 1)) { (&bits_s[0][0])[tid] = 0; (&mask_s[0][0])[tid] = 0; }
         uint32_t tot;
-        uint32_t rank = running + block_rank(is_out, wave_tot, tot);
+        uint32_t rank = running + block_rank<NT>(is_out, wave_tot, tot);
         running += tot;
         if (is_out) {
             uint64_t pos = (uint64_t)base + rank;
             if (pos < (uint64_t)cap_nnz) { v_idx[pos] = (uint16_t)c; v_val[pos] = resid; }
             else overflow = true;
         }
-        // this block of 256 channels covers up to four (head, half) chunks of 64 fields each
-        const int chunks_here = (D - c0 >= NT) ? 4 : (D - c0) / 64;
+        // this block of NT channels covers up to CB (head, half) chunks of 64 fields each
+        const int chunks_here = (D - c0 >= NT) ? CB : (D - c0) / 64;
         if (tid < 64 * chunks_here) {
             int q = tid >> 6, j = tid & 63;
             stream_or(bits_s[q], j * 2 * BITS + parity * BITS, (uint32_t)codes_s[tid], BITS);
@@ -362,13 +399,21 @@ extern "C" kvq_status kvq_quantize_append_k(kvq_cache *cache, const uint16_t *d_
     if (!single) {
         if (!cache->workspace || cache->workspace_bytes < (int64_t)T * 4) return KVQ_ERR_CAPACITY;
         uint32_t *cnt = (uint32_t *)cache->workspace;
-        kvq_k_count<<<T, NT, 0, s>>>(cache->params, D, d_k_new, cnt);
+        if (D >= 2048) kvq_k_count<1024><<<T, 1024, 0, s>>>(cache->params, D, d_k_new, cnt);
+        else kvq_k_count<256><<<T, 256, 0, s>>>(cache->params, D, d_k_new, cnt);
         kvq_ptr_scan<<<1, 1024, 0, s>>>(cache->k_ptr, cache->n_tokens_k, T, cnt, cache->cap_nnz_k, cache->d_status);
     }
-#define LAUNCH_K(B)                                                                                            \
-    kvq_k_quant<B><<<T, NT, 0, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_k, d_k_new,             \
-                                    cache->k_codes, cache->k_ptr, cache->k_idx, cache->k_val, cache->cap_nnz_k, \
-                                    single, cache->d_status)
+#define LAUNCH_K(B)                                                                                             \
+    do {                                                                                                        \
+        if (D >= 2048)                                                                                          \
+            kvq_k_quant<B, 1024><<<T, 1024, 0, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_k,      \
+                                                    d_k_new, cache->k_codes, cache->k_ptr, cache->k_idx,         \
+                                                    cache->k_val, cache->cap_nnz_k, single, cache->d_status);    \
+        else                                                                                                    \
+            kvq_k_quant<B, 256><<<T, 256, 0, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_k,        \
+                                                  d_k_new, cache->k_codes, cache->k_ptr, cache->k_idx,           \
+                                                  cache->k_val, cache->cap_nnz_k, single, cache->d_status);      \
+    } while (0)
     if (cache->bits == 2) LAUNCH_K(2);
     else if (cache->bits == 3) LAUNCH_K(3);
     else LAUNCH_K(4);
@@ -387,10 +432,19 @@ extern "C" kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_
     if (D > 16384) return KVQ_ERR_UNSUPPORTED;       // the per-token selection keeps the vector in LDS
     hipStream_t s = (hipStream_t)stream;
     const size_t dyn = 3 * (size_t)D;
-#define LAUNCH_V(B)                                                                                           \
-    kvq_v_quant<B><<<T, NT, dyn, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v, cache->k_side_v, \
-                                      d_v_new, cache->v_codes, cache->v_sz, cache->v_ptr, cache->v_idx,        \
-                                      cache->v_val, cache->cap_nnz_v, cache->d_status)
+#define LAUNCH_V(B)                                                                                             \
+    do {                                                                                                        \
+        if (D >= 2048)                                                                                          \
+            kvq_v_quant<B, 1024><<<T, 1024, dyn, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v,    \
+                                                      cache->k_side_v, d_v_new, cache->v_codes, cache->v_sz,     \
+                                                      cache->v_ptr, cache->v_idx, cache->v_val,                  \
+                                                      cache->cap_nnz_v, cache->d_status);                        \
+        else                                                                                                    \
+            kvq_v_quant<B, 256><<<T, 256, dyn, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v,      \
+                                                    cache->k_side_v, d_v_new, cache->v_codes, cache->v_sz,       \
+                                                    cache->v_ptr, cache->v_idx, cache->v_val, cache->cap_nnz_v,  \
+                                                    cache->d_status);                                            \
+    } while (0)
     if (cache->bits == 2) LAUNCH_V(2);
     else if (cache->bits == 3) LAUNCH_V(3);
     else LAUNCH_V(4);

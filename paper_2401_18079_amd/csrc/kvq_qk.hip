@@ -424,7 +424,11 @@ template <int BITS, int R>
 kvq_status dispatch_qk(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
 {
     constexpr int QHMAX = (BITS == 3) ? 4 : 8;
-    constexpr int PG = (BITS == 4) ? 1 : 2;
+    constexpr int PGD = (BITS == 4) ? 1 : (BITS == 3 ? 4 : 2);
+    const int PGE = getenv("KVQ_QK_PG") ? atoi(getenv("KVQ_QK_PG")) : 0;   // TEMPORARY tuning knob
+    if (BITS == 3 && R == 1 && PGE == 2) return launch_qk<BITS, 4, 1, 1024, 2, R>(c, q, scale, scores, ld, s);
+    if (BITS == 3 && R == 1 && PGE == 1) return launch_qk<BITS, 4, 1, 1024, 1, R>(c, q, scale, scores, ld, s);
+    constexpr int PG = PGD;
     if constexpr (R >= QHMAX) {
         // one KV head per workgroup, QHMAX of its query heads (R / QHMAX workgroups share the KV head)
         return launch_qk<BITS, 1, QHMAX, 1024, PG, R>(c, q, scale, scores, ld, s);
