@@ -72,17 +72,29 @@ __global__ __launch_bounds__(256) void fp16_pv(const uint16_t *__restrict__ v16,
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[r][j] = 0.f;
-        for (int64_t n = nb; n < ne; ++n) {
-            const uint4 raw = *(const uint4 *)(v16 + n * D + (int64_t)v * 8);
-            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+        constexpr int U = 8;                       // token rows in flight per thread
+        for (int64_t n0 = nb; n0 < ne; n0 += U) {
+            uint4 raw[U];
+            float pr[U][R];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const float p = probs[(int64_t)(kvh * R + r) * ld + n];
+            for (int u = 0; u < U; ++u) {
+                const int64_t n = (n0 + u < ne) ? n0 + u : ne - 1;   // clamped: straight-line loads
+                raw[u] = *(const uint4 *)(v16 + n * D + (int64_t)v * 8);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const half2_t h = __builtin_bit_cast(half2_t, w[j]);
-                    acc[r][2 * j] = __builtin_fmaf((float)h.x, p, acc[r][2 * j]);
-                    acc[r][2 * j + 1] = __builtin_fmaf((float)h.y, p, acc[r][2 * j + 1]);
+                for (int r = 0; r < R; ++r)
+                    pr[u][r] = (n0 + u < ne) ? probs[(int64_t)(kvh * R + r) * ld + n] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t w[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const half2_t h = __builtin_bit_cast(half2_t, w[j]);
+                        acc[r][2 * j] = __builtin_fmaf((float)h.x, pr[u][r], acc[r][2 * j]);
+                        acc[r][2 * j + 1] = __builtin_fmaf((float)h.y, pr[u][r], acc[r][2 * j + 1]);
+                    }
                 }
             }
         }
@@ -94,16 +106,33 @@ __global__ __launch_bounds__(256) void fp16_pv(const uint16_t *__restrict__ v16,
     }
 }
 
-__global__ __launch_bounds__(128) void fp16_pv_reduce(int n_q_heads, int slabs, const float *__restrict__ partial,
-                                                      float *__restrict__ out)
+__global__ __launch_bounds__(1024) void fp16_pv_reduce(int n_q_heads, int slabs, const float *__restrict__ partial,
+                                                       float *__restrict__ out)
 {
-    const int qh = blockIdx.x, c = threadIdx.x;
+    __shared__ float red[8][128];
+    const int qh = blockIdx.x, c = threadIdx.x & 127, j = threadIdx.x >> 7;
     float s = 0.f;
-    for (int k = 0; k < slabs; ++k) s += partial[((int64_t)k * n_q_heads + qh) * 128 + c];
-    out[qh * 128 + c] = s;
+    for (int k0 = j; k0 < slabs; k0 += 64) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + 8 * u;
+            v[u] = (k < slabs) ? partial[((int64_t)k * n_q_heads + qh) * 128 + c] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    red[j][c] = s;
+    __syncthreads();
+    if (j == 0) {
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t += red[i][c];
+        out[qh * 128 + c] = t;
+    }
 }
 
-constexpr int FP16_PV_SLABS = 2048;
+constexpr int FP16_PV_SLABS = 1024;
 
 }  // namespace
 
@@ -152,7 +181,7 @@ extern "C" kvq_status kvq_fp16_pv_matvec(const uint16_t *d_v16, int64_t L, int32
     case 4: fp16_pv<4><<<slabs, 256, 0, s>>>(d_v16, L, n_kv_heads, d_probs, ld_probs, partial, tps); break;
     default: return KVQ_ERR_UNSUPPORTED;
     }
-    fp16_pv_reduce<<<n_q_heads, 128, 0, s>>>(n_q_heads, slabs, partial, d_out);
+    fp16_pv_reduce<<<n_q_heads, 1024, 0, s>>>(n_q_heads, slabs, partial, d_out);
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }

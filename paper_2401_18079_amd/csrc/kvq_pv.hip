@@ -21,8 +21,8 @@ constexpr int PV_WAVES = PV_NT / 64;
 constexpr int PV_FIELD_GROUP = 8;
 
 struct PvPlan {
-    int slabs;              // token slabs of the dense kernel
-    int tiles_per_slab;     // tiles of 128 tokens per slab
+    int slabs;              // token slabs of the dense kernel (tiles are split evenly among them)
+    int tiles;              // tiles of 128 tokens
     int sslabs;             // token slabs of the sparse kernel
     int64_t tokens_per_sslab;
 };
@@ -35,10 +35,9 @@ inline PvPlan pv_plan(int64_t L, int n_q_heads)
     int64_t want = (256 * 16) / (2 * (int64_t)n_q_heads);
     if (want < 1) want = 1;
     if (want > 512) want = 512;
-    int64_t tps = (tiles + want - 1) / want;
-    if (tps < 1) tps = 1;
-    p.tiles_per_slab = (int)tps;
-    p.slabs = (int)((tiles + tps - 1) / tps);
+    if (want > tiles) want = tiles;
+    p.tiles = (int)tiles;
+    p.slabs = (int)want;
     int64_t ss = (L + 511) / 512;              // at least 512 tokens per sparse workgroup
     if (ss > 256) ss = 256;
     if (ss < 1) ss = 1;
@@ -103,7 +102,7 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
                                                       const uint16_t *__restrict__ v_sz,
                                                       const float *__restrict__ probs, int64_t ld,
                                                       float *__restrict__ partial, float *__restrict__ zpart,
-                                                      int tiles_per_slab)
+                                                      int n_tiles)
 {
     constexpr int NE2 = 1 << (2 * BITS);
     constexpr int CW = 4 * BITS;
@@ -129,10 +128,11 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
     for (int j = 0; j < 64; ++j) acc[j] = 0.f;
     float zacc = 0.f;
 
-    const int64_t tile0 = (int64_t)blockIdx.x * tiles_per_slab;
+    const int64_t tile0 = ((int64_t)blockIdx.x * n_tiles) / gridDim.x;
+    const int64_t tile1 = ((int64_t)(blockIdx.x + 1) * n_tiles) / gridDim.x;
     if (active) {
-        for (int t = 0; t < tiles_per_slab; ++t) {
-            const int64_t m = (tile0 + t) * 64 + lane;      // token pair
+        for (int64_t t = tile0; t < tile1; ++t) {
+            const int64_t m = t * 64 + lane;                // token pair
             const int64_t n0 = 2 * m;
             if (n0 >= L) continue;
             uint32_t W[CW];
@@ -337,7 +337,7 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
 #define LAUNCH_PV(B)                                                                                          \
     kvq_pv_dense<B><<<grid, PV_NT, 0, s>>>(cache->params, D, cache->n_kv_heads, Hq, cache->cap_tokens, L,      \
                                            cache->v_codes, cache->v_sz, d_probs, ld_probs, partial, zpart,    \
-                                           plan.tiles_per_slab)
+                                           plan.tiles)
         if (cache->bits == 2) LAUNCH_PV(2);
         else if (cache->bits == 3) LAUNCH_PV(3);
         else LAUNCH_PV(4);

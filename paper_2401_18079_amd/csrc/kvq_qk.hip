@@ -174,7 +174,7 @@ template <int BITS, int KVH, int RQ, int NT, int PG>
 __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ params, int D, int r,
                                                     int64_t cap, int64_t L, const uint8_t *__restrict__ k_codes,
                                                     const float *__restrict__ q_rot, float scale,
-                                                    float *__restrict__ scores, int64_t ld, int tiles_per_wg)
+                                                    float *__restrict__ scores, int64_t ld, int n_tiles)
 {
     using C = QkCfg<BITS>;
     constexpr int QH = KVH * RQ, R = RQ;
@@ -235,7 +235,11 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
 
     // ---- token tiles (software-pipelined over the workgroup's tiles) -------------------------
     const int64_t plane = cap * 16 * BITS;                 // bytes between consecutive KV heads
-    int64_t n = (int64_t)blockIdx.x * tiles_per_wg * NT + tid;
+    // the workgroups of a head group split the tiles as evenly as possible
+    const int tile_begin = (int)(((int64_t)blockIdx.x * n_tiles) / gridDim.x);
+    const int tile_end = (int)(((int64_t)(blockIdx.x + 1) * n_tiles) / gridDim.x);
+    const int tiles_per_wg = tile_end - tile_begin;
+    int64_t n = (int64_t)tile_begin * NT + tid;
     bool valid = n < L;
     uint32_t W[KVH][8];                                    // two 16-byte pieces per KV head
     const uint8_t *cur_chunk = k_codes + kvq_k_piece0(BITS, cap, valid ? n : 0, kv0);
@@ -258,8 +262,10 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
         for (int qh = 0; qh < QH; ++qh) acc[qh] = 0.f;
         // lanes past the end run the arithmetic on whatever their registers hold (table offsets are
         // masked, so every gather stays inside the table) and simply skip loads and stores
-        qk_all_pairs<BITS, KVH, RQ, PG>(std::make_integer_sequence<int, 64 / PG>{}, W, acc, tab, nf, pv.hdr,
-                                  cur_chunk, next_chunk, plane, valid, next_valid);
+        // a wavefront whose 64 tokens all lie past the end (ragged last tile) skips the arithmetic
+        if (__ballot(valid) != 0ull)
+            qk_all_pairs<BITS, KVH, RQ, PG>(std::make_integer_sequence<int, 64 / PG>{}, W, acc, tab, nf, pv.hdr,
+                                      cur_chunk, next_chunk, plane, valid, next_valid);
         if (BITS & 1) {
             // odd piece count: the next tile's piece 0 arrived in slot 1; move it to slot 0 (whose last
             // occupant is dead now) and request the next tile's piece 1 into slot 1
@@ -403,13 +409,13 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     const int groups = c->n_q_heads / QH;
     const int64_t tiles = (L + NT - 1) / NT;
     // about one workgroup per compute unit in total (the tables fill most of a CU's LDS); each
-    // workgroup builds its tables once and then streams its tiles
-    int64_t tpw = (tiles * groups + 255) / 256;
-    if (tpw < 1) tpw = 1;
-    if (tpw > 64) tpw = 64;
-    if (const char *e = getenv("KVQ_QK_TPW")) tpw = atoi(e);   // TEMPORARY tuning knob
-    dim3 grid((unsigned)((tiles + tpw - 1) / tpw), (unsigned)groups);
-    kern<<<grid, NT, 0, s>>>(c->params, D, R, c->cap_tokens, L, c->k_codes, q, scale, scores, ld, (int)tpw);
+    // workgroup builds its tables once and then streams its share of the tiles
+    int64_t gx = 256 / groups;
+    if (gx < 1) gx = 1;
+    if (gx > tiles) gx = tiles;
+    if (const char *e = getenv("KVQ_QK_TPW")) gx = (tiles + atoi(e) - 1) / atoi(e);   // TEMPORARY tuning knob
+    dim3 grid((unsigned)gx, (unsigned)groups);
+    kern<<<grid, NT, 0, s>>>(c->params, D, R, c->cap_tokens, L, c->k_codes, q, scale, scores, ld, (int)tiles);
     if (!(c->loaded & 2)) {                              // bit 1: thresholds admit no Key outliers
         kvq_status st = launch_qk_sparse<R>(c, q, scale, scores, ld, s);
         if (st != KVQ_OK) return st;

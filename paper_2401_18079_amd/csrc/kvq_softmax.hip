@@ -6,7 +6,7 @@
 namespace {
 
 constexpr int SM_NT = 256;
-constexpr int SM_CHUNK = 8192;     // elements per workgroup
+constexpr int SM_CHUNK = 4096;     // elements per workgroup
 
 __device__ inline void block_max_sum(float &m, float &s, float *sh_m, float *sh_s)
 {
@@ -36,12 +36,21 @@ __global__ __launch_bounds__(SM_NT) void kvq_softmax_partial(const float *__rest
     const int row = blockIdx.y, chunk = blockIdx.x;
     const float *xr = x + (int64_t)row * ld;
     const int64_t b = (int64_t)chunk * SM_CHUNK;
+    constexpr int PER = SM_CHUNK / SM_NT;          // elements per thread, read once and kept in registers
+    float v[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int64_t i = b + threadIdx.x + (int64_t)k * SM_NT;
+        v[k] = (i < n) ? xr[i] : -INFINITY;
+    }
     float m = -INFINITY;
-    for (int64_t i = b + threadIdx.x; i < b + SM_CHUNK && i < n; i += SM_NT) m = fmaxf(m, xr[i]);
+#pragma unroll
+    for (int k = 0; k < PER; ++k) m = fmaxf(m, v[k]);
     float s = 0.f;
-    for (int64_t i = b + threadIdx.x; i < b + SM_CHUNK && i < n; i += SM_NT) s += __expf(xr[i] - m);
     // threads without elements: a finite floor instead of -inf keeps exp(m - m') free of inf - inf
-    if (m == -INFINITY) { s = 0.f; m = -3.0e38f; }
+    if (m == -INFINITY) m = -3.0e38f;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) s += __expf(v[k] - m);        // exp(-inf) = 0 for the padding
     block_max_sum(m, s, sh_m, sh_s);
     if (threadIdx.x == 0) ws[(int64_t)row * chunks + chunk] = float2_t{m, s};
 }
@@ -67,7 +76,18 @@ __global__ __launch_bounds__(SM_NT) void kvq_softmax_finish(const float *__restr
     const float *xr = x + (int64_t)row * ld_x;
     float *yr = y + (int64_t)row * ld_y;
     const int64_t b = (int64_t)chunk * SM_CHUNK;
-    for (int64_t i = b + threadIdx.x; i < b + SM_CHUNK && i < n; i += SM_NT) yr[i] = __expf(xr[i] - m) * inv;
+    constexpr int PER = SM_CHUNK / SM_NT;
+    float v[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int64_t i = b + threadIdx.x + (int64_t)k * SM_NT;
+        v[k] = (i < n) ? xr[i] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int64_t i = b + threadIdx.x + (int64_t)k * SM_NT;
+        if (i < n) yr[i] = __expf(v[k] - m) * inv;
+    }
 }
 
 }  // namespace
