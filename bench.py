@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--context", type=int, default=0, help="override the context length")
     ap.add_argument("--cpu-sample", type=int, default=4096, help="tokens of context for the CPU-oracle timing (0 = skip)")
     ap.add_argument("--no-fp16", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 1 GiB device copy (known traffic) so profiler byte counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -167,6 +169,21 @@ def main():
     qk_gbps = qk_bytes / (breakdown["qk_matvec"] * 1e-6) / 1e9
     pv_gbps = pv_bytes / (breakdown["pv_matvec"] * 1e-6) / 1e9
 
+    # the dominant kernel on its own: the dense Key kernel inside kvq_qk_matvec, bracketed by HIP events
+    # on the launch stream (same workload, same launch configuration as the timed steps)
+    K.kvq_profile_enable(True)
+    dense_qk, dense_pv = [], []
+    for i in range(min(steps, 50)):
+        K.kvq_qk_matvec(gc, qs[warmup + i], scale, scores)
+        K.kvq_pv_matvec(gc, probs, out)
+        dense_qk.append(K.kvq_profile_last_ms(0) * 1e3)
+        dense_pv.append(K.kvq_profile_last_ms(1) * 1e3)
+    K.kvq_profile_enable(False)
+    dense_qk_us, dense_pv_us = float(np.mean(dense_qk)), float(np.mean(dense_pv))
+    # dense kernel: packed codes in, fp32 scores out (the sparse kernel's bytes are counted with the call)
+    dense_qk_bytes = Lend * (D * wl.bits // 8) + 4 * Hq * Lend
+    dense_qk_gbps = dense_qk_bytes / (dense_qk_us * 1e-6) / 1e9
+
     fp16 = None
     if not args.no_fp16:
         fws = torch.zeros(K.binding.kvq_fp16_pv_workspace_bytes(Hq, L), dtype=torch.uint8, device="cuda")
@@ -197,6 +214,14 @@ def main():
                 "qk_gbps": L * D * 2 / (res["qk"] * 1e-6) / 1e9, "pv_gbps": L * D * 2 / (res["pv"] * 1e-6) / 1e9}
         del k16, v16
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     cpu = None
     if args.cpu_sample > 0:
         tq, tmv, cores, _ = cpu_baseline(st, args.cpu_sample)
@@ -208,14 +233,14 @@ def main():
                          f"(append of one token {tq * 1e3:.2f} ms, qk+softmax+pv {tmv * 1e3:.1f} ms, median of 5), "
                          f"mat-vec time scaled linearly to context {L}"}
 
+    # HBM bytes per launch of the dense Key kernel from rocprofv3 counter runs of this command
+    # (FETCH_SIZE / WRITE_SIZE scaled by a known-size copy), kept as a text summary under profiles/
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            tj = json.load(open(tpath))
-            traffic = tj.get(f"{wl.name}_L{L}", {}).get("qk_matvec_bytes")
-        except Exception:
-            traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"kvq_qk_kernel_{wl.name}_hbm_traffic.txt")
+    if os.path.exists(tpath) and not args.context:
+        for ln in open(tpath):
+            if ln.startswith("dense_kernel_traffic_bytes_per_launch:"):
+                traffic = float(ln.split(":")[1])
 
     line = {
         "metric": "quantized-KV decode step latency (append K/V + QK^T + softmax + PV), one attention layer",
@@ -232,9 +257,13 @@ def main():
         "fp16_cache_baseline": fp16,
         "speedup_vs_fp16": ({"qk": fp16["qk_us"] / breakdown["qk_matvec"], "pv": fp16["pv_us"] / breakdown["pv_matvec"]}
                             if fp16 else None),
-        "roofline": {"bound": "hbm", "kernel": "kvq_qk_matvec", "achieved": qk_gbps, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": qk_gbps / HBM_PEAK_GBPS, "traffic": traffic,
-                     "algorithmic_bytes": qk_bytes, "avg_launch_us": breakdown["qk_matvec"]},
+        "dense_kernel_us": {"qk": dense_qk_us, "pv": dense_pv_us},
+        "roofline": {"bound": "hbm", "kernel": "kvq_qk_kernel (dense Key kernel of kvq_qk_matvec)",
+                     "achieved": dense_qk_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": dense_qk_gbps / HBM_PEAK_GBPS, "traffic": traffic,
+                     "algorithmic_bytes": dense_qk_bytes, "avg_launch_us": dense_qk_us,
+                     "whole_call": {"algorithmic_bytes": qk_bytes, "avg_us": breakdown["qk_matvec"],
+                                    "achieved": qk_gbps, "frac": qk_gbps / HBM_PEAK_GBPS}},
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))

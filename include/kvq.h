@@ -188,6 +188,15 @@ kvq_status kvq_event_record(void *event, void *stream);
 kvq_status kvq_event_elapsed_ms(void *start, void *stop, float *ms); /* synchronizes on stop */
 kvq_status kvq_event_destroy(void *event);
 
+/*
+ * Per-kernel timing aid for benchmarks.  While enabled, kvq_qk_matvec and kvq_pv_matvec bracket
+ * their dense kernel with HIP events on the launch stream; kvq_profile_last_ms synchronizes on the
+ * events of the most recent call and returns the dense kernel's duration (`which`: 0 = QK dense
+ * kernel, 1 = PV dense kernel).  Not thread-safe; leave disabled in production.
+ */
+kvq_status kvq_profile_enable(int32_t on);
+kvq_status kvq_profile_last_ms(int32_t which, float *ms);
+
 #ifdef __cplusplus
 }
 #endif

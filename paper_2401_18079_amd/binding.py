@@ -66,6 +66,8 @@ def load_library():
         "kvq_event_record": (C.c_int, [V, V]),
         "kvq_event_elapsed_ms": (C.c_int, [V, V, C.POINTER(F)]),
         "kvq_event_destroy": (C.c_int, [V]),
+        "kvq_profile_enable": (C.c_int, [I32]),
+        "kvq_profile_last_ms": (C.c_int, [I32, C.POINTER(F)]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -79,7 +81,18 @@ EXPORTED_SYMBOLS = [
     "kvq_lut_load", "kvq_quantize_append_k", "kvq_quantize_append_v", "kvq_qk_matvec", "kvq_pv_matvec",
     "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
     "kvq_fp16_pv_matvec", "kvq_event_create", "kvq_event_record", "kvq_event_elapsed_ms", "kvq_event_destroy",
+    "kvq_profile_enable", "kvq_profile_last_ms",
 ]
+
+
+def kvq_profile_enable(on: bool):
+    _check(load_library().kvq_profile_enable(1 if on else 0), "kvq_profile_enable")
+
+
+def kvq_profile_last_ms(which: int) -> float:
+    ms = C.c_float()
+    _check(load_library().kvq_profile_last_ms(which, C.byref(ms)), "kvq_profile_last_ms")
+    return float(ms.value)
 
 
 def _stream_ptr(stream=None):

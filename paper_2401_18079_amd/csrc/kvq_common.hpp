@@ -94,6 +94,14 @@ __device__ inline void kvq_lds_add_fixed(long long *cell, float x, double scale)
     atomicAdd((unsigned long long *)cell, (unsigned long long)q);
 }
 
+// Optional per-kernel timing (kvq_profile_enable): events bracketing the dense kernels.
+struct KvqProfile {
+    int enabled;
+    hipEvent_t ev[2][2];     // [QK, PV][start, stop]
+    int have[2];
+};
+KvqProfile &kvq_profile_state();
+
 #define KVQ_HIP_CHECK(expr)                         \
     do {                                            \
         hipError_t _e = (expr);                     \

@@ -58,7 +58,34 @@ kvq_status kvq_event_destroy(void *event)
     return KVQ_OK;
 }
 
+kvq_status kvq_profile_enable(int32_t on)
+{
+    KvqProfile &p = kvq_profile_state();
+    if (on && !p.ev[0][0]) {
+        for (int k = 0; k < 2; ++k)
+            for (int j = 0; j < 2; ++j) KVQ_HIP_CHECK(hipEventCreate(&p.ev[k][j]));
+    }
+    p.enabled = on ? 1 : 0;
+    p.have[0] = p.have[1] = 0;
+    return KVQ_OK;
+}
+
+kvq_status kvq_profile_last_ms(int32_t which, float *ms)
+{
+    KvqProfile &p = kvq_profile_state();
+    if (which < 0 || which > 1 || !ms || !p.have[which]) return KVQ_ERR_INVALID_ARG;
+    KVQ_HIP_CHECK(hipEventSynchronize(p.ev[which][1]));
+    KVQ_HIP_CHECK(hipEventElapsedTime(ms, p.ev[which][0], p.ev[which][1]));
+    return KVQ_OK;
+}
+
 }  // extern "C"
+
+KvqProfile &kvq_profile_state()
+{
+    static KvqProfile p = {};
+    return p;
+}
 
 // Expand the fp16 per-channel constants to fp32 and form the reciprocal scale with one IEEE division,
 // so every later kernel normalises with exactly (x - z) * (1/s).

@@ -338,10 +338,13 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
     kvq_pv_dense<B><<<grid, PV_NT, 0, s>>>(cache->params, D, cache->n_kv_heads, Hq, cache->cap_tokens, L,      \
                                            cache->v_codes, cache->v_sz, d_probs, ld_probs, partial, zpart,    \
                                            plan.tiles)
+        KvqProfile &prof = kvq_profile_state();
+        if (prof.enabled) KVQ_HIP_CHECK(hipEventRecord(prof.ev[1][0], s));
         if (cache->bits == 2) LAUNCH_PV(2);
         else if (cache->bits == 3) LAUNCH_PV(3);
         else LAUNCH_PV(4);
 #undef LAUNCH_PV
+        if (prof.enabled) { KVQ_HIP_CHECK(hipEventRecord(prof.ev[1][1], s)); prof.have[1] = 1; }
         kvq_pv_sparse<<<plan.sslabs, PVS_NT, (size_t)Hq * (256 + PVS_TC + 1) * 4, s>>>(cache->n_kv_heads, Hq, L, cache->v_ptr,
                                                                      cache->v_idx, cache->v_val, d_probs, ld_probs,
                                                                      spartial, plan.tokens_per_sslab);

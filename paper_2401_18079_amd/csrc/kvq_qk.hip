@@ -415,7 +415,10 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     if (gx > tiles) gx = tiles;
     if (const char *e = getenv("KVQ_QK_TPW")) gx = (tiles + atoi(e) - 1) / atoi(e);   // TEMPORARY tuning knob
     dim3 grid((unsigned)gx, (unsigned)groups);
+    KvqProfile &prof = kvq_profile_state();
+    if (prof.enabled) KVQ_HIP_CHECK(hipEventRecord(prof.ev[0][0], s));
     kern<<<grid, NT, 0, s>>>(c->params, D, R, c->cap_tokens, L, c->k_codes, q, scale, scores, ld, (int)tiles);
+    if (prof.enabled) { KVQ_HIP_CHECK(hipEventRecord(prof.ev[0][1], s)); prof.have[0] = 1; }
     if (!(c->loaded & 2)) {                              // bit 1: thresholds admit no Key outliers
         kvq_status st = launch_qk_sparse<R>(c, q, scale, scores, ld, s);
         if (st != KVQ_OK) return st;
