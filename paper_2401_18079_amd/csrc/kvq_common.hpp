@@ -84,6 +84,15 @@ __device__ inline int kvq_nearest(const float *lut, float xn, float &signpost)
     return best;
 }
 
+// (x & mask) | bits in one instruction (the compiler emits an AND and an OR/ADD for this pattern).
+// The mask travels in a scalar register: VOP3 instructions take no 32-bit literals on gfx9.
+__device__ __forceinline__ uint32_t kvq_and_or(uint32_t x, uint32_t mask, uint32_t bits)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(mask), "v"(bits));
+    return r;
+}
+
 // Scatter-add of floats into LDS without floating-point atomics (ds_add_f32 processes lanes one at a
 // time on gfx950, roughly 30x slower than integer LDS atomics): the value is converted to 64-bit
 // fixed point and added with an integer atomic.  Integer addition is associative, so the result does

@@ -25,6 +25,8 @@ struct PvPlan {
     int tiles;              // tiles of 128 tokens
     int sslabs;             // token slabs of the sparse kernel
     int64_t tokens_per_sslab;
+    int stc;                // tokens per LDS chunk of the sparse kernel
+    size_t slds;            // its dynamic LDS bytes
 };
 
 inline PvPlan pv_plan(int64_t L, int n_q_heads)
@@ -38,11 +40,18 @@ inline PvPlan pv_plan(int64_t L, int n_q_heads)
     if (want > tiles) want = tiles;
     p.tiles = (int)tiles;
     p.slabs = (int)want;
-    int64_t ss = (L + 511) / 512;              // at least 512 tokens per sparse workgroup
+    // sparse kernel: LDS holds Hq*128 64-bit accumulators plus the chunk's probabilities and pointers;
+    // chunks of up to 512 tokens, fewer if many query heads (stay under ~144 KiB)
+    int64_t tc = (147456 - (int64_t)n_q_heads * 1024 - 8) / ((int64_t)n_q_heads * 4 + 4) - 1;
+    tc = (tc >= 512) ? 512 : (tc / 64) * 64;
+    if (tc < 64) tc = 64;
+    p.stc = (int)tc;
+    p.slds = (size_t)n_q_heads * 1024 + ((size_t)n_q_heads * (tc + 1) + (tc + 1)) * 4;
+    int64_t ss = (L + tc - 1) / tc;            // one chunk per workgroup up to 256 workgroups
     if (ss > 256) ss = 256;
     if (ss < 1) ss = 1;
     p.sslabs = (int)ss;
-    p.tokens_per_sslab = (L + ss - 1) / ss;
+    p.tokens_per_sslab = ((L + ss - 1) / ss + tc - 1) / tc * tc;
     return p;
 }
 
@@ -59,7 +68,7 @@ __device__ inline uint32_t pv_field_off(const uint32_t *W, int i, uint32_t lane_
     } else {
         x = __builtin_amdgcn_alignbit(W[wi + 1], W[wi], sh - 7);   // straddling fields start at bit >= 26
     }
-    return (x & M) | lane_off;
+    return kvq_and_or(x, M, lane_off);
 }
 
 template <int BITS, int G0>
@@ -180,7 +189,6 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
 // pattern.  grid = sslabs; a workgroup owns tokens [nb, ne), walks them in chunks of PVS_TC tokens
 // whose pointers and probabilities it stages in LDS, finds each entry's token by a guess plus a
 // short walk and accumulates p[q][n] * val into fixed-point LDS accumulators (integer atomics).
-constexpr int PVS_TC = 128;
 constexpr int PVS_NT = 1024;
 constexpr int PVS_U = 8;                  // entries in flight per lane
 
@@ -189,37 +197,36 @@ __global__ __launch_bounds__(PVS_NT) void kvq_pv_sparse(int n_kv_heads, int n_q_
                                                         const uint16_t *__restrict__ v_idx,
                                                         const uint16_t *__restrict__ v_val,
                                                         const float *__restrict__ probs, int64_t ld,
-                                                        float *__restrict__ spartial, int64_t tokens_per_slab)
+                                                        float *__restrict__ spartial, int64_t tokens_per_slab,
+                                                        int tc_max)
 {
     extern __shared__ __attribute__((aligned(16))) float dyn[];
     // accumulators are 2^40-scaled fixed point (see kvq_lds_add_fixed)
     constexpr double FIX = 1099511627776.0;
     long long *sacc = (long long *)dyn;                  // [n_q_heads][128]
     // rows padded by one float so that one token's column does not sit in a single LDS bank
-    constexpr int PROW = PVS_TC + 1;
-    float *ps = dyn + (size_t)n_q_heads * 128 * 2;       // [n_q_heads][PVS_TC + 1] probabilities of the chunk
-    __shared__ uint32_t ptr_s[PVS_TC + 1];
+    const int prow = tc_max + 1;
+    float *ps = dyn + (size_t)n_q_heads * 128 * 2;       // [n_q_heads][tc_max + 1] probabilities of the chunk
+    uint32_t *ptr_s = (uint32_t *)(ps + (size_t)n_q_heads * prow);   // [tc_max + 1]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = n_q_heads / n_kv_heads;
     for (int j = tid; j < n_q_heads * 128; j += PVS_NT) sacc[j] = 0;
     const int64_t nb = (int64_t)blockIdx.x * tokens_per_slab;
     int64_t ne = nb + tokens_per_slab;
     if (ne > L) ne = L;
-    for (int64_t nc = nb; nc < ne; nc += PVS_TC) {
-        const int tc = (int)((ne - nc < PVS_TC) ? (ne - nc) : PVS_TC);
+    for (int64_t nc = nb; nc < ne; nc += tc_max) {
+        const int tc = (int)((ne - nc < tc_max) ? (ne - nc) : tc_max);
         __syncthreads();
         for (int j = tid; j <= tc; j += PVS_NT) ptr_s[j] = v_ptr[nc + j];
         for (int qh = wave; qh < n_q_heads; qh += PVS_NT / 64) {
-#pragma unroll
-            for (int k = 0; k < PVS_TC / 64; ++k) {
-                const int t = lane + 64 * k;
-                ps[qh * PROW + t] = (t < tc) ? probs[(int64_t)qh * ld + nc + t] : 0.f;
-            }
+            const float *prow_g = probs + (int64_t)qh * ld + nc;
+#pragma unroll 8
+            for (int t = lane; t < tc_max; t += 64) ps[qh * prow + t] = (t < tc) ? prow_g[t] : 0.f;
         }
         __syncthreads();
         const uint32_t e_begin = ptr_s[0], e_end = ptr_s[tc];
         // every token normally owns the same number of entries: guess the token, then walk
-        const uint32_t per = (e_end - e_begin) / (uint32_t)tc;
+        const float inv_per = (e_end > e_begin) ? (float)tc / (float)(e_end - e_begin) : 0.f;
         for (uint32_t e0 = e_begin + tid; e0 < e_end; e0 += PVS_NT * PVS_U) {
             uint32_t chv[PVS_U];
             uint16_t vb[PVS_U];
@@ -234,7 +241,7 @@ __global__ __launch_bounds__(PVS_NT) void kvq_pv_sparse(int n_kv_heads, int n_q_
             for (int u = 0; u < PVS_U; ++u) {
                 const uint32_t e = e0 + (uint32_t)PVS_NT * u;
                 if (e >= e_end) break;
-                int t = per ? (int)((e - e_begin) / per) : 0;
+                int t = (int)((float)(e - e_begin) * inv_per);
                 if (t >= tc) t = tc - 1;
                 while (ptr_s[t] > e) --t;             // ptr_s[0] <= e, so this stops at t >= 0
                 while (ptr_s[t + 1] <= e) ++t;        // ptr_s[tc] > e, so this stops at t < tc
@@ -242,7 +249,7 @@ __global__ __launch_bounds__(PVS_NT) void kvq_pv_sparse(int n_kv_heads, int n_q_
                 const int kvh = chv[u] >> 7, c = chv[u] & 127;
                 for (int j = 0; j < r; ++j) {
                     const int qh = kvh * r + j;
-                    kvq_lds_add_fixed(&sacc[qh * 128 + c], ps[qh * PROW + t] * v, FIX);
+                    kvq_lds_add_fixed(&sacc[qh * 128 + c], ps[qh * prow + t] * v, FIX);
                 }
             }
         }
@@ -328,11 +335,23 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
     const int Hq = cache->n_q_heads, D = cache->n_kv_heads * KVQ_HEAD_DIM;
     hipStream_t s = (hipStream_t)stream;
     if (!cache->workspace || cache->workspace_bytes < pv_workspace_bytes(cache->cap_tokens, Hq)) return KVQ_ERR_CAPACITY;
-    const PvPlan plan = (L > 0) ? pv_plan(L, Hq) : PvPlan{0, 0, 0, 0};
+    const PvPlan plan = (L > 0) ? pv_plan(L, Hq) : PvPlan{0, 0, 0, 0, 0, 0};
     float *partial = (float *)cache->workspace;
     float *zpart = partial + (int64_t)512 * Hq * 128;
     float *spartial = zpart + (int64_t)512 * Hq;
     if (L > 0) {
+        static size_t lds_attr = 0;
+        if (plan.slds > lds_attr) {
+            KVQ_HIP_CHECK(hipFuncSetAttribute((const void *)kvq_pv_sparse, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                              (int)plan.slds));
+            lds_attr = plan.slds;
+        }
+        // (Running this latency-bound kernel on a second stream beside the dense one was tried: its
+        // 100 KiB of LDS per workgroup evicts dense workgroups from the CUs and the pair gets slower.)
+        kvq_pv_sparse<<<plan.sslabs, PVS_NT, plan.slds, s>>>(cache->n_kv_heads, Hq, L, cache->v_ptr, cache->v_idx,
+                                                             cache->v_val, d_probs, ld_probs, spartial,
+                                                             plan.tokens_per_sslab, plan.stc);
+
         dim3 grid((unsigned)plan.slabs, (unsigned)((2 * Hq + PV_WAVES - 1) / PV_WAVES));
 #define LAUNCH_PV(B)                                                                                          \
     kvq_pv_dense<B><<<grid, PV_NT, 0, s>>>(cache->params, D, cache->n_kv_heads, Hq, cache->cap_tokens, L,      \
@@ -345,9 +364,6 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
         else LAUNCH_PV(4);
 #undef LAUNCH_PV
         if (prof.enabled) { KVQ_HIP_CHECK(hipEventRecord(prof.ev[1][1], s)); prof.have[1] = 1; }
-        kvq_pv_sparse<<<plan.sslabs, PVS_NT, (size_t)Hq * (256 + PVS_TC + 1) * 4, s>>>(cache->n_kv_heads, Hq, L, cache->v_ptr,
-                                                                     cache->v_idx, cache->v_val, d_probs, ld_probs,
-                                                                     spartial, plan.tokens_per_sslab);
     }
     kvq_pv_reduce<<<Hq, 1024, 0, s>>>(Hq, plan.slabs, plan.sslabs, partial, zpart, spartial, d_out);
     KVQ_HIP_CHECK(hipGetLastError());

@@ -41,15 +41,15 @@ __device__ __forceinline__ uint32_t chunk_dword(const uint32_t (&Wg)[8], int wi)
 
 // Byte offset (field value * 8) of field `i` of a chunk, for indexing a table of 8-byte entries.
 template <int FBITS>   // field width in bits
-__device__ __forceinline__ uint32_t field_x8(const uint32_t (&Wg)[8], int i)
+__device__ __forceinline__ uint32_t field_shifted(const uint32_t (&Wg)[8], int i)
 {
+    // the field, moved to bit 3 (so that, masked, it is a byte offset into 8-byte entries)
     const int bit = i * FBITS, wi = bit >> 5, sh = bit & 31;
-    constexpr uint32_t M = ((1u << FBITS) - 1u) << 3;
     if (sh + FBITS <= 32) {
-        if (sh >= 3) return (chunk_dword(Wg, wi) >> (sh - 3)) & M;
-        return (chunk_dword(Wg, wi) << (3 - sh)) & M;
+        if (sh >= 3) return chunk_dword(Wg, wi) >> (sh - 3);
+        return chunk_dword(Wg, wi) << (3 - sh);
     }
-    return __builtin_amdgcn_alignbit(chunk_dword(Wg, wi + 1), chunk_dword(Wg, wi), sh - 3) & M;
+    return __builtin_amdgcn_alignbit(chunk_dword(Wg, wi + 1), chunk_dword(Wg, wi), sh - 3);
 }
 
 // Angle of channel pair i at position n, in revolutions, reduced to about [0,1): n*theta_i/(2 pi)
@@ -87,15 +87,35 @@ __device__ __forceinline__ void qk_group(uint32_t (&W)[KVH][8], float (&acc)[KVH
         const int I = G0 * PAIR_GROUP + p;
 #pragma unroll
         for (int g = 0; g < KVH; ++g) {
-            uint32_t off[NG];
-            if (C::JOINT) off[0] = field_x8<2 * BITS>(W[g], I);
-            else { off[0] = field_x8<BITS>(W[g], 2 * I); off[NG - 1] = field_x8<BITS>(W[g], 2 * I + 1); }
+            uint32_t sh[NG];
+            constexpr uint32_t M = ((C::JOINT ? (1u << (2 * BITS)) : (1u << BITS)) - 1u) << 3;
+            if (C::JOINT) sh[0] = field_shifted<2 * BITS>(W[g], I);
+            else { sh[0] = field_shifted<BITS>(W[g], 2 * I); sh[NG - 1] = field_shifted<BITS>(W[g], 2 * I + 1); }
+            uint32_t off_lo[NG];
+            bool have_lo = false;
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int qh = g * R + r;
-                const uint8_t *tb = (const uint8_t *)(tab + (qh * 64 + I) * ENT);
+                // LDS instructions reach 64 KiB past their address register; tables further up get the
+                // excess folded into the masking instruction instead of an extra add
+                const uint32_t base = (uint32_t)((qh * 64 + I) * ENT) * 8u;
+                const uint32_t hi = base & ~0xFFFFu;
+                const uint8_t *tb = (const uint8_t *)tab + (base - hi);
+                if (hi == 0) {
+                    if (!have_lo) {
 #pragma unroll
-                for (int k = 0; k < NG; ++k) t[p][qh][k] = *(const float2_t *)(tb + k * NE * 8 + off[k]);
+                        for (int k = 0; k < NG; ++k) off_lo[k] = sh[k] & M;
+                        have_lo = true;
+                    }
+#pragma unroll
+                    for (int k = 0; k < NG; ++k) t[p][qh][k] = *(const float2_t *)(tb + k * NE * 8 + off_lo[k]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < NG; ++k) {
+                        const uint32_t off = kvq_and_or(sh[k], M, hi);
+                        t[p][qh][k] = *(const float2_t *)(tb + k * NE * 8 + off);
+                    }
+                }
             }
         }
     }
@@ -324,9 +344,19 @@ __global__ __launch_bounds__(1024) void kvq_qk_sparse(const void *__restrict__ p
     for (int j = tid; j < n_q_heads * 128; j += 1024) qs[j] = q_rot[j] * scale;
     for (int j = tid; j <= tc; j += 1024) ptr_s[j] = k_ptr[nc + j];
     if (tid < 64) rope[tid] = float2_t{pv.hdr->rope_vh[tid], pv.hdr->rope_vl[tid]};
+    // the dense scores this workgroup will add to: requested now, consumed after the entry loop
+    const int lane = tid & 63, wave = tid >> 6;
+    float dense[2][4];
+#pragma unroll
+    for (int it = 0; it < 2; ++it)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int qh = wave + 16 * it, t = lane + 64 * k;
+            dense[it][k] = (qh < n_q_heads && t < tc) ? scores[(int64_t)qh * ld + nc + t] : 0.f;
+        }
     __syncthreads();
     const uint32_t e_begin = ptr_s[0], e_end = ptr_s[tc];
-    const uint32_t per = (e_end - e_begin) / (uint32_t)tc;
+    const float inv_per = (e_end > e_begin) ? (float)tc / (float)(e_end - e_begin) : 0.f;
     constexpr int U = 8;                              // entries in flight per lane
     for (uint32_t e0 = e_begin + tid; e0 < e_end; e0 += 1024 * U) {
         uint32_t chv[U];
@@ -344,7 +374,7 @@ __global__ __launch_bounds__(1024) void kvq_qk_sparse(const void *__restrict__ p
             if (e >= e_end) break;
             const uint32_t ch = chv[u];
             const float v = kvq_h2f(vb[u]);
-            int t = per ? (int)((e - e_begin) / per) : 0;
+            int t = (int)((float)(e - e_begin) * inv_per);
             if (t >= tc) t = tc - 1;
             while (ptr_s[t] > e) --t;                 // ptr_s[0] <= e, so this stops at t >= 0
             while (ptr_s[t + 1] <= e) ++t;            // ptr_s[tc] > e, so this stops at t < tc
@@ -362,24 +392,19 @@ __global__ __launch_bounds__(1024) void kvq_qk_sparse(const void *__restrict__ p
         }
     }
     __syncthreads();
-    // add the tile to the dense scores: one wavefront per query-head row, all of a row's loads in flight
-    {
-        const int lane = tid & 63, wave = tid >> 6;
-        for (int qh = wave; qh < n_q_heads; qh += 16) {
-            float *row = scores + (int64_t)qh * ld + nc;
-            float v[4];
+    // add the tile to the dense scores (rows prefetched above: wavefront w owns rows w and w+16;
+    // models with more than 32 query heads take the remaining rows the slow way)
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int t = lane + 64 * k;
-                v[k] = (t < tc) ? row[t] : 0.f;
-            }
+    for (int it = 0; it < 2; ++it)
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int t = lane + 64 * k;
-                if (t < tc) row[t] = v[k] + (float)((double)S[qh * srow + t] * (1.0 / FIX));
-            }
+        for (int k = 0; k < 4; ++k) {
+            const int qh = wave + 16 * it, t = lane + 64 * k;
+            if (qh < n_q_heads && t < tc)
+                scores[(int64_t)qh * ld + nc + t] = dense[it][k] + (float)((double)S[qh * srow + t] * (1.0 / FIX));
         }
-    }
+    for (int qh = wave + 32; qh < n_q_heads; qh += 16)
+        for (int t = lane; t < tc; t += 64)
+            scores[(int64_t)qh * ld + nc + t] += (float)((double)S[qh * srow + t] * (1.0 / FIX));
 }
 
 template <int R>
