@@ -183,8 +183,8 @@ def make_lut(bits: int, seed: int, layer: int, which: int):
     n = 1 << bits
     salt = 0
     while True:
-        h = splitmix64(np.arange(n, dtype=_U64) ^ (_U64(seed) << _U64(8)) ^ _U64(layer * 4 + which)
-                       ^ (_U64(salt) << _U64(40)))
+        h = splitmix64(np.arange(n, dtype=_U64) ^ (_U64(seed & 0xFFFFFF) << _U64(8)) ^ (_U64(layer * 4 + which) << _U64(32))
+                       ^ (_U64(salt) << _U64(48)))
         u = ((h >> _U64(11)).astype(np.float64) / float(1 << 53)) * 2.0 - 1.0
         u = np.sort(u)
         u[0], u[-1] = -1.0, 1.0

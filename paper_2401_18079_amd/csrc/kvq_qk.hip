@@ -412,11 +412,17 @@ kvq_status launch_qk_sparse(const kvq_cache *c, const float *q, float scale, flo
 {
     const int Hq = c->n_q_heads;
     const int64_t L = c->n_tokens_k;
-    // LDS: Hq*tc floats + Hq*128 floats + (tc+1) words, kept under 60 KiB
-    int tc = (int)((61440 - 4 - (int64_t)Hq * 520) / ((int64_t)Hq * 8 + 4));
+    // LDS: Hq*(tc+1) 64-bit sums + Hq*128 floats + (tc+1) words, kept under 144 KiB; at most 256 tokens
+    int tc = (int)((147456 - 4 - (int64_t)Hq * 520) / ((int64_t)Hq * 8 + 4));
     tc = (tc >= 256) ? 256 : (tc / 64) * 64;
     if (tc < 64) return KVQ_ERR_UNSUPPORTED;
     const size_t lds = (size_t)Hq * (tc + 1) * 8 + (size_t)Hq * 128 * 4 + (size_t)(tc + 1) * 4;
+    static size_t lds_attr = 0;      // per instantiation
+    if (lds > lds_attr) {
+        KVQ_HIP_CHECK(hipFuncSetAttribute((const void *)kvq_qk_sparse<R>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)lds));
+        lds_attr = lds;
+    }
     const unsigned grid = (unsigned)((L + tc - 1) / tc);
     kvq_qk_sparse<R><<<grid, 1024, lds, s>>>(c->params, c->n_kv_heads * KVQ_HEAD_DIM, Hq, L, c->k_ptr, c->k_idx,
                                              c->k_val, q, scale, scores, ld, tc);
