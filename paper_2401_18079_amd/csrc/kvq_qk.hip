@@ -71,10 +71,12 @@ __device__ inline float rope_rev(float nf, float vh, float vl)
 // G0 is a compile-time constant so that all register-array indices fold.
 template <int BITS, int KVH, int RQ, int PAIR_GROUP, int G0>
 __device__ __forceinline__ void qk_group(uint32_t (&W)[KVH][8], float (&acc)[KVH * RQ],
-                                         const float2_t *tab, float nf, const KvqParamsHeader *hdr,
+                                         const float2_t *tab, float nf, float wave_base, const KvqParamsHeader *hdr,
                                          const uint8_t *cur_chunk, const uint8_t *next_chunk, int64_t plane,
                                          bool valid, bool next_valid)
 {
+    // nf: this lane's index inside its wavefront (as float); wave_base: lane i holds the reduced angle
+    // (in revolutions) of channel pair i at the wavefront's first token
     using C = QkCfg<BITS>;
     constexpr int QH = KVH * RQ, R = RQ;
     constexpr int NE = C::NE;
@@ -123,7 +125,10 @@ __device__ __forceinline__ void qk_group(uint32_t (&W)[KVH][8], float (&acc)[KVH
 #pragma unroll
     for (int p = 0; p < PAIR_GROUP; ++p) {
         const int I = G0 * PAIR_GROUP + p;
-        const float rev = rope_rev(nf, hdr->rope_vh[I], hdr->rope_vl[I]);
+        // angle of pair I at this lane's token = (angle at the wavefront's first token, held by lane I)
+        //                                        + lane * theta_I / (2 pi)
+        const float base = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wave_base), I));
+        const float rev = __builtin_fmaf(nf, hdr->rope_vh[I], base);
         cs[p] = __builtin_amdgcn_cosf(rev);
         sn[p] = __builtin_amdgcn_sinf(rev);
     }
@@ -181,11 +186,11 @@ __device__ __forceinline__ void qk_group(uint32_t (&W)[KVH][8], float (&acc)[KVH
 template <int BITS, int KVH, int RQ, int PG, int... G>
 __device__ __forceinline__ void qk_all_pairs(std::integer_sequence<int, G...>,
                                              uint32_t (&W)[KVH][8], float (&acc)[KVH * RQ],
-                                             const float2_t *tab, float nf, const KvqParamsHeader *hdr,
-                                             const uint8_t *cur_chunk, const uint8_t *next_chunk, int64_t plane,
-                                             bool valid, bool next_valid)
+                                             const float2_t *tab, float nf, float wave_base,
+                                             const KvqParamsHeader *hdr, const uint8_t *cur_chunk,
+                                             const uint8_t *next_chunk, int64_t plane, bool valid, bool next_valid)
 {
-    (qk_group<BITS, KVH, RQ, PG, G>(W, acc, tab, nf, hdr, cur_chunk, next_chunk, plane, valid, next_valid), ...);
+    (qk_group<BITS, KVH, RQ, PG, G>(W, acc, tab, nf, wave_base, hdr, cur_chunk, next_chunk, plane, valid, next_valid), ...);
 }
 
 // KVH KV heads per workgroup, RQ query heads per KV head handled here (RQ divides the model's GQA
@@ -261,6 +266,7 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
     const int tiles_per_wg = tile_end - tile_begin;
     int64_t n = (int64_t)tile_begin * NT + tid;
     bool valid = n < L;
+    const float my_vh = pv.hdr->rope_vh[tid & 63], my_vl = pv.hdr->rope_vl[tid & 63];   // this lane's pair
     uint32_t W[KVH][8];                                    // two 16-byte pieces per KV head
     const uint8_t *cur_chunk = k_codes + kvq_k_piece0(BITS, cap, valid ? n : 0, kv0);
     if (valid) {
@@ -276,7 +282,11 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
         const int64_t nn = n + NT;
         const bool next_valid = (tile + 1 < tiles_per_wg) && (nn < L);
         const uint8_t *next_chunk = k_codes + kvq_k_piece0(BITS, cap, next_valid ? nn : n, kv0);
-        const float nf = (float)n;
+        // lane i reduces the angle of channel pair i at the wavefront's first token (n - lane, a multiple
+        // of 64); every lane then needs one FMA per pair instead of its own reduction
+        const int lane_id = tid & 63;
+        const float nf = (float)lane_id;
+        const float wave_base = rope_rev((float)(n - lane_id), my_vh, my_vl);
         float acc[QH];
 #pragma unroll
         for (int qh = 0; qh < QH; ++qh) acc[qh] = 0.f;
@@ -284,8 +294,8 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
         // masked, so every gather stays inside the table) and simply skip loads and stores
         // a wavefront whose 64 tokens all lie past the end (ragged last tile) skips the arithmetic
         if (__ballot(valid) != 0ull)
-            qk_all_pairs<BITS, KVH, RQ, PG>(std::make_integer_sequence<int, 64 / PG>{}, W, acc, tab, nf, pv.hdr,
-                                      cur_chunk, next_chunk, plane, valid, next_valid);
+            qk_all_pairs<BITS, KVH, RQ, PG>(std::make_integer_sequence<int, 64 / PG>{}, W, acc, tab, nf, wave_base,
+                                            pv.hdr, cur_chunk, next_chunk, plane, valid, next_valid);
         if (BITS & 1) {
             // odd piece count: the next tile's piece 0 arrived in slot 1; move it to slot 0 (whose last
             // occupant is dead now) and request the next tile's piece 1 into slot 1
