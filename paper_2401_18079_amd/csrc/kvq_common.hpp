@@ -97,10 +97,39 @@ __device__ __forceinline__ uint32_t kvq_and_or(uint32_t x, uint32_t mask, uint32
 // time on gfx950, roughly 30x slower than integer LDS atomics): the value is converted to 64-bit
 // fixed point and added with an integer atomic.  Integer addition is associative, so the result does
 // not depend on the order in which lanes arrive.
-__device__ inline void kvq_lds_add_fixed(long long *cell, float x, double scale)
+//
+// kvq_to_fixed<SH>(x) = x * 2^(32+SH) as a two's-complement 64-bit integer, for |x| < 2^(31-SH):
+// integer part (floor) in the high word, fraction in the low word.  Non-negative values are exact
+// down to 2^-(32+SH); the fraction of a negative value (1 - frac|y|) is rounded to fp32, an absolute
+// error of at most 2^-(24+SH) per value.
+template <int SH>
+__device__ __forceinline__ unsigned long long kvq_to_fixed(float x)
 {
-    const long long q = (long long)((double)x * scale);
-    atomicAdd((unsigned long long *)cell, (unsigned long long)q);
+    const float y = x * (float)(1 << SH);
+    const int hi = (int)__builtin_floorf(y);
+    const uint32_t lo = (uint32_t)(__builtin_amdgcn_fractf(y) * 4294967296.0f);
+    return ((unsigned long long)(uint32_t)hi << 32) | lo;
+}
+template <int SH>
+__device__ __forceinline__ float kvq_from_fixed(unsigned long long v)
+{
+    const long long sv = (long long)v;
+    const unsigned long long m = (unsigned long long)(sv < 0 ? -sv : sv);    // magnitude: no cancellation below
+    const float r = ((float)(uint32_t)(m >> 32) + (float)(uint32_t)m * (1.0f / 4294967296.0f)) * (1.0f / (float)(1 << SH));
+    return sv < 0 ? -r : r;
+}
+// Same conversion in three instructions; the low word is rounded to fp32 before the (possibly
+// cancelling) addition, an absolute error of at most 2^-(25+SH).
+template <int SH>
+__device__ __forceinline__ float kvq_from_fixed_fast(unsigned long long v)
+{
+    const float hi = (float)(int)(uint32_t)(v >> 32), lo = (float)(uint32_t)v;
+    return __builtin_fmaf(lo, 1.0f / 4294967296.0f, hi) * (1.0f / (float)(1 << SH));
+}
+template <int SH>
+__device__ __forceinline__ void kvq_lds_add_fixed(unsigned long long *cell, float x)
+{
+    atomicAdd(cell, kvq_to_fixed<SH>(x));
 }
 
 // Optional per-kernel timing (kvq_profile_enable): events bracketing the dense kernels.

@@ -23,11 +23,23 @@ constexpr int PV_FIELD_GROUP = 8;
 struct PvPlan {
     int slabs;              // token slabs of the dense kernel (tiles are split evenly among them)
     int tiles;              // tiles of 128 tokens
-    int sslabs;             // token slabs of the sparse kernel
-    int64_t tokens_per_sslab;
-    int stc;                // tokens per LDS chunk of the sparse kernel
+    int sslabs;             // workgroups of the sparse kernel
+    int swaves;             // its wavefronts per workgroup
+    int64_t tokens_per_swave;
     size_t slds;            // its dynamic LDS bytes
 };
+
+constexpr int PVS_TW = 16;                // tokens per sub-range of a sparse-kernel wavefront
+// row length of the staged probabilities: one token's outliers read the same column of many rows,
+// and an odd row length spreads that column over all LDS banks
+constexpr int PVS_ROW = PVS_TW + 1;
+constexpr int PVS_U = 8;                  // 64-entry batches in flight per wavefront
+constexpr int PVS_MAX_SLABS = 512;
+
+__host__ __device__ constexpr int pvs_wave_lds_floats(int n_q_heads)
+{
+    return n_q_heads * PVS_ROW;                          // the sub-range's probabilities
+}
 
 inline PvPlan pv_plan(int64_t L, int n_q_heads)
 {
@@ -40,18 +52,28 @@ inline PvPlan pv_plan(int64_t L, int n_q_heads)
     if (want > tiles) want = tiles;
     p.tiles = (int)tiles;
     p.slabs = (int)want;
-    // sparse kernel: LDS holds Hq*128 64-bit accumulators plus the chunk's probabilities and pointers;
-    // chunks of up to 512 tokens, fewer if many query heads (stay under ~144 KiB)
-    int64_t tc = (147456 - (int64_t)n_q_heads * 1024 - 8) / ((int64_t)n_q_heads * 4 + 4) - 1;
-    tc = (tc >= 512) ? 512 : (tc / 64) * 64;
-    if (tc < 64) tc = 64;
-    p.stc = (int)tc;
-    p.slds = (size_t)n_q_heads * 1024 + ((size_t)n_q_heads * (tc + 1) + (tc + 1)) * 4;
-    int64_t ss = (L + tc - 1) / tc;            // one chunk per workgroup up to 256 workgroups
-    if (ss > 256) ss = 256;
-    if (ss < 1) ss = 1;
-    p.sslabs = (int)ss;
-    p.tokens_per_sslab = ((L + ss - 1) / ss + tc - 1) / tc * tc;
+    // sparse kernel: LDS holds Hq*128 64-bit accumulators shared by the workgroup plus a private slice
+    // per wavefront (two workgroups of 12 wavefronts per CU when they fit in 77 KiB each); the launch
+    // fills the chip once (256 CUs, 160 KiB of LDS and 24 wavefronts each, at most PVS_MAX_SLABS workgroups) and every wavefront gets the same number
+    // of tokens (a multiple of 8)
+    int waves = 12;
+    const size_t per_wave = (size_t)pvs_wave_lds_floats(n_q_heads) * 4;
+    while (waves > 1 && (size_t)n_q_heads * 1024 + waves * per_wave > 78848) waves -= (waves > 4) ? 4 : waves / 2;
+    p.swaves = waves;
+    p.slds = (size_t)n_q_heads * 1024 + waves * per_wave;
+    int wgs_per_cu = (int)(163840 / p.slds);
+    if (wgs_per_cu * waves > 24) wgs_per_cu = 24 / waves;      // six wavefronts per SIMD (register budget)
+    if (wgs_per_cu < 1) wgs_per_cu = 1;
+    int64_t max_wgs = (int64_t)256 * wgs_per_cu;
+    if (max_wgs > PVS_MAX_SLABS) max_wgs = PVS_MAX_SLABS;
+    const int64_t resident = max_wgs * waves;
+    int64_t tpw = (L + resident - 1) / resident;
+    tpw = (tpw + 7) & ~(int64_t)7;
+    if (tpw < 8) tpw = 8;
+    const int64_t n_waves = (L + tpw - 1) / tpw;
+    p.tokens_per_swave = tpw;
+    p.sslabs = (int)((n_waves + waves - 1) / waves);
+    if (p.sslabs < 1) p.sslabs = 1;
     return p;
 }
 
@@ -186,76 +208,154 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
 
 // Sparse part, balanced (paper App. "Kernel Implementation Details": equal non-zeros per thread):
 // lanes are outlier entries, so every lane does the same amount of work whatever the sparsity
-// pattern.  grid = sslabs; a workgroup owns tokens [nb, ne), walks them in chunks of PVS_TC tokens
-// whose pointers and probabilities it stages in LDS, finds each entry's token by a guess plus a
-// short walk and accumulates p[q][n] * val into fixed-point LDS accumulators (integer atomics).
-constexpr int PVS_NT = 1024;
-constexpr int PVS_U = 8;                  // entries in flight per lane
+// pattern.  A wavefront owns a run of consecutive tokens and walks it PVS_TW tokens at a time on its
+// own (no workgroup barrier inside the loop): it stages the sub-range's pointers and probabilities in
+// its private LDS slice, finds each entry's token by a binary search over the pointers and adds
+// p[q][n] * val to the workgroup's fixed-point LDS accumulators (integer atomics).  The workgroup's
+// sums go to the workspace; the reduce kernel adds them up.
+// One batch of index/value loads.  CLAMP = false: the whole batch lies inside the arrays (possibly
+// past the sub-range's end, where the loaded values are ignored), one address per lane plus
+// immediate offsets; CLAMP = true: lanes past the end re-read the last entry.
+template <bool CLAMP>
+__device__ __forceinline__ void sparse_load_batch(const uint16_t *__restrict__ idx, const uint16_t *__restrict__ val,
+                                                  uint32_t eb, uint32_t e_end, int lane, uint32_t (&chv)[PVS_U],
+                                                  uint32_t (&vb)[PVS_U])
+{
+    const char *ib = (const char *)idx, *vbp = (const char *)val;
+    if (!CLAMP) {
+        const uint32_t off0 = (eb + (uint32_t)lane) * 2u;
+#pragma unroll
+        for (int u = 0; u < PVS_U; ++u) {
+            if (eb + 64u * u >= e_end) break;            // uniform: the rest of the batch is past the end
+            chv[u] = *(const uint16_t *)(ib + (size_t)off0 + 128 * u);
+            vb[u] = *(const uint16_t *)(vbp + (size_t)off0 + 128 * u);
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < PVS_U; ++u) {
+            if (eb + 64u * u >= e_end) break;
+            uint32_t e = eb + (uint32_t)lane + 64u * u;
+            e = (e < e_end) ? e : e_end - 1;
+            chv[u] = *(const uint16_t *)(ib + (size_t)(e * 2u));
+            vb[u] = *(const uint16_t *)(vbp + (size_t)(e * 2u));
+        }
+    }
+}
 
-__global__ __launch_bounds__(PVS_NT) void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L,
-                                                        const uint32_t *__restrict__ v_ptr,
-                                                        const uint16_t *__restrict__ v_idx,
-                                                        const uint16_t *__restrict__ v_val,
-                                                        const float *__restrict__ probs, int64_t ld,
-                                                        float *__restrict__ spartial, int64_t tokens_per_slab,
-                                                        int tc_max)
+// Token (relative to the sub-range) of entry `first + lane`.  `pw` holds the sub-range's pointers
+// (lane j: first entry of token j; lanes >= tc: the end), `tcur` is the wavefront's cursor: the token
+// that entry `first` belongs to once advanced.  Everything but the final compare-and-add is scalar.
+__device__ __forceinline__ int sparse_token(uint32_t pw, int tc, int &tcur, uint32_t first, uint32_t e)
+{
+    while (tcur + 1 < tc && (uint32_t)__builtin_amdgcn_readlane((int)pw, tcur + 1) <= first) ++tcur;
+    int t = tcur;
+    int j = tcur + 1;
+    while (j < tc) {
+        const uint32_t pj = (uint32_t)__builtin_amdgcn_readlane((int)pw, j);
+        if (pj > first + 63u) break;
+        t += (e >= pj) ? 1 : 0;
+        j = __builtin_amdgcn_readfirstlane(j + 1);
+    }
+    return t;
+}
+
+// R = query heads per KV head (0: any ratio, looked up at run time)
+template <int R>
+__global__ __launch_bounds__(768) __attribute__((amdgpu_waves_per_eu(6, 6)))
+void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__restrict__ v_ptr,
+                   const uint16_t *__restrict__ v_idx, const uint16_t *__restrict__ v_val, uint32_t nnz_cap,
+                   const float *__restrict__ probs, int64_t ld, float *__restrict__ spartial, int64_t tokens_per_wave)
 {
     extern __shared__ __attribute__((aligned(16))) float dyn[];
-    // accumulators are 2^40-scaled fixed point (see kvq_lds_add_fixed)
-    constexpr double FIX = 1099511627776.0;
-    long long *sacc = (long long *)dyn;                  // [n_q_heads][128]
-    // rows padded by one float so that one token's column does not sit in a single LDS bank
-    const int prow = tc_max + 1;
-    float *ps = dyn + (size_t)n_q_heads * 128 * 2;       // [n_q_heads][tc_max + 1] probabilities of the chunk
-    uint32_t *ptr_s = (uint32_t *)(ps + (size_t)n_q_heads * prow);   // [tc_max + 1]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = n_q_heads / n_kv_heads;
-    for (int j = tid; j < n_q_heads * 128; j += PVS_NT) sacc[j] = 0;
-    const int64_t nb = (int64_t)blockIdx.x * tokens_per_slab;
-    int64_t ne = nb + tokens_per_slab;
+    unsigned long long *sacc = (unsigned long long *)dyn;     // [n_q_heads][128] 2^40-scaled sums
+    const int tid = threadIdx.x, lane = tid & 63, n_waves = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);           // scalar: loop bounds below are uniform
+    float *ps = (float *)(sacc + n_q_heads * 128) + (size_t)wave * pvs_wave_lds_floats(n_q_heads);   // [n_q_heads][PVS_ROW]
+    const int r = R ? R : n_q_heads / n_kv_heads;
+    for (int j = tid; j < n_q_heads * 128; j += blockDim.x) sacc[j] = 0ull;
+    bool cleared = false;      // the barrier after the clearing comes once the first loads are requested
+    const int64_t nb = ((int64_t)blockIdx.x * n_waves + wave) * tokens_per_wave;
+    int64_t ne = nb + tokens_per_wave;
     if (ne > L) ne = L;
-    for (int64_t nc = nb; nc < ne; nc += tc_max) {
-        const int tc = (int)((ne - nc < tc_max) ? (ne - nc) : tc_max);
-        __syncthreads();
-        for (int j = tid; j <= tc; j += PVS_NT) ptr_s[j] = v_ptr[nc + j];
-        for (int qh = wave; qh < n_q_heads; qh += PVS_NT / 64) {
-            const float *prow_g = probs + (int64_t)qh * ld + nc;
-#pragma unroll 8
-            for (int t = lane; t < tc_max; t += 64) ps[qh * prow + t] = (t < tc) ? prow_g[t] : 0.f;
-        }
-        __syncthreads();
-        const uint32_t e_begin = ptr_s[0], e_end = ptr_s[tc];
-        // every token normally owns the same number of entries: guess the token, then walk
-        const float inv_per = (e_end > e_begin) ? (float)tc / (float)(e_end - e_begin) : 0.f;
-        for (uint32_t e0 = e_begin + tid; e0 < e_end; e0 += PVS_NT * PVS_U) {
-            uint32_t chv[PVS_U];
-            uint16_t vb[PVS_U];
+    const int n_cells = n_q_heads * PVS_TW;
+    // the run is cut into equal sub-ranges of at most PVS_TW tokens; the pointers of the next one are
+    // requested while the current one is processed
+    const int run = (nb < ne) ? (int)(ne - nb) : 0, n_sub = (run + PVS_TW - 1) / PVS_TW;
+    const int sub_len = n_sub ? (run + n_sub - 1) / n_sub : 0;
+    int64_t nc = nb;
+    int tc = sub_len;
+    uint32_t pw = 0;
+    if (tc > 0) pw = v_ptr[nc + (lane < tc ? lane : tc)];
+    while (tc > 0) {
+        const int64_t nc_next = nc + tc;
+        const int tc_next = (int)((ne - nc_next < sub_len) ? (ne - nc_next) : sub_len);
+        // probabilities: cell j = (query head j / 16, token j % 16); loads are straight-line (cells
+        // outside the sub-range re-read its first probability and store zero)
+        float pr[8];
 #pragma unroll
-            for (int u = 0; u < PVS_U; ++u) {
-                const uint32_t e = e0 + (uint32_t)PVS_NT * u;
-                const uint32_t ec = (e < e_end) ? e : e_end - 1;   // clamped: straight-line loads, all in flight
-                chv[u] = (uint32_t)v_idx[ec];
-                vb[u] = v_val[ec];
+        for (int k = 0; k < 8; ++k) {
+            const int j = lane + 64 * k, qh = j / PVS_TW, t = j % PVS_TW;
+            const bool ok = j < n_cells && t < tc;
+            const float x = probs[ok ? (int64_t)qh * ld + nc + t : nc];
+            pr[k] = ok ? x : 0.f;
+        }
+        const uint32_t e_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)pw);
+        const uint32_t e_end = (uint32_t)__builtin_amdgcn_readlane((int)pw, 63);
+        uint32_t chv[PVS_U], vb[PVS_U];
+        if (e_begin < e_end) {
+            if (e_begin + 64u * PVS_U <= nnz_cap) sparse_load_batch<false>(v_idx, v_val, e_begin, e_end, lane, chv, vb);
+            else sparse_load_batch<true>(v_idx, v_val, e_begin, e_end, lane, chv, vb);
+        }
+        uint32_t pw_next = 0;
+        if (tc_next > 0) pw_next = v_ptr[nc_next + (lane < tc_next ? lane : tc_next)];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int j = lane + 64 * k;
+            if (j < n_cells) ps[(j / PVS_TW) * PVS_ROW + j % PVS_TW] = pr[k];
+        }
+        for (int j0 = 64 * 8; j0 < n_cells; j0 += 64) {      // models with more than 32 query heads
+            const int j = j0 + lane, qh = j / PVS_TW, t = j % PVS_TW;
+            if (j < n_cells) ps[qh * PVS_ROW + t] = (t < tc) ? probs[(int64_t)qh * ld + nc + t] : 0.f;
+        }
+        if (!cleared) {
+            __syncthreads();
+            cleared = true;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        int tcur = 0;
+        for (uint32_t eb = e_begin; eb < e_end; eb += 64 * PVS_U) {
+            if (eb != e_begin) {                         // (the first batch was requested above)
+                if (eb + 64u * PVS_U <= nnz_cap) sparse_load_batch<false>(v_idx, v_val, eb, e_end, lane, chv, vb);
+                else sparse_load_batch<true>(v_idx, v_val, eb, e_end, lane, chv, vb);
             }
 #pragma unroll
             for (int u = 0; u < PVS_U; ++u) {
-                const uint32_t e = e0 + (uint32_t)PVS_NT * u;
-                if (e >= e_end) break;
-                int t = (int)((float)(e - e_begin) * inv_per);
-                if (t >= tc) t = tc - 1;
-                while (ptr_s[t] > e) --t;             // ptr_s[0] <= e, so this stops at t >= 0
-                while (ptr_s[t + 1] <= e) ++t;        // ptr_s[tc] > e, so this stops at t < tc
-                const float v = kvq_h2f(vb[u]);
-                const int kvh = chv[u] >> 7, c = chv[u] & 127;
-                for (int j = 0; j < r; ++j) {
-                    const int qh = kvh * r + j;
-                    kvq_lds_add_fixed(&sacc[qh * 128 + c], ps[qh * prow + t] * v, FIX);
+                const uint32_t first = eb + 64u * u, e = first + (uint32_t)lane;
+                if (first >= e_end) break;
+                const int t = sparse_token(pw, tc, tcur, first, e);
+                if (e < e_end) {
+                    const uint32_t ch = chv[u];
+                    const float v = kvq_h2f((uint16_t)vb[u]);
+                    const uint32_t kvh = ch >> 7, c = ch & 127u;
+                    for (int j = 0; j < r; ++j) {
+                        const uint32_t qh = kvh * r + j;
+                        kvq_lds_add_fixed<8>(&sacc[(R == 1) ? ch : qh * 128u + c], ps[qh * PVS_ROW + t] * v);
+                    }
                 }
             }
         }
+        // the next sub-range overwrites ps: order those stores after this sub-range's reads
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        nc = nc_next;
+        tc = tc_next;
+        pw = pw_next;
     }
+    if (!cleared) __syncthreads();       // a wavefront without tokens still meets the workgroup's barrier
     __syncthreads();
-    for (int j = tid; j < n_q_heads * 128; j += PVS_NT) spartial[(int64_t)blockIdx.x * n_q_heads * 128 + j] = (float)((double)sacc[j] * (1.0 / FIX));
+    for (int j = tid; j < n_q_heads * 128; j += blockDim.x)
+        spartial[(int64_t)blockIdx.x * n_q_heads * 128 + j] = kvq_from_fixed<8>(sacc[j]);
 }
 
 // out[q][c] = sum_slabs partial + sum_slabs zpart + sum_sslabs spartial.  One workgroup per query
@@ -340,17 +440,23 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
     float *zpart = partial + (int64_t)512 * Hq * 128;
     float *spartial = zpart + (int64_t)512 * Hq;
     if (L > 0) {
-        static size_t lds_attr = 0;
-        if (plan.slds > lds_attr) {
-            KVQ_HIP_CHECK(hipFuncSetAttribute((const void *)kvq_pv_sparse, hipFuncAttributeMaxDynamicSharedMemorySize,
+        const int r = Hq / cache->n_kv_heads;
+        auto sparse = (r == 1) ? kvq_pv_sparse<1> : (r == 2) ? kvq_pv_sparse<2> : (r == 4) ? kvq_pv_sparse<4>
+                    : (r == 8) ? kvq_pv_sparse<8> : kvq_pv_sparse<0>;
+        // one dynamic-LDS limit per instantiation, raised on demand
+        static size_t lds_attr[5] = {0, 0, 0, 0, 0};
+        size_t &attr = lds_attr[(r == 1) ? 1 : (r == 2) ? 2 : (r == 4) ? 3 : (r == 8) ? 4 : 0];
+        if (plan.slds > attr) {
+            KVQ_HIP_CHECK(hipFuncSetAttribute((const void *)sparse, hipFuncAttributeMaxDynamicSharedMemorySize,
                                               (int)plan.slds));
-            lds_attr = plan.slds;
+            attr = plan.slds;
         }
-        // (Running this latency-bound kernel on a second stream beside the dense one was tried: its
-        // 100 KiB of LDS per workgroup evicts dense workgroups from the CUs and the pair gets slower.)
-        kvq_pv_sparse<<<plan.sslabs, PVS_NT, plan.slds, s>>>(cache->n_kv_heads, Hq, L, cache->v_ptr, cache->v_idx,
-                                                             cache->v_val, d_probs, ld_probs, spartial,
-                                                             plan.tokens_per_sslab, plan.stc);
+        // (Running this kernel on a second stream beside the dense one was tried: its LDS footprint
+        // evicts dense workgroups from the CUs and the pair gets slower.)
+        if (cache->cap_nnz_v >= ((int64_t)1 << 31)) return KVQ_ERR_UNSUPPORTED;      // byte offsets are 32-bit
+        sparse<<<plan.sslabs, 64 * plan.swaves, plan.slds, s>>>(cache->n_kv_heads, Hq, L, cache->v_ptr, cache->v_idx,
+                                                                cache->v_val, (uint32_t)cache->cap_nnz_v, d_probs,
+                                                                ld_probs, spartial, plan.tokens_per_swave);
 
         dim3 grid((unsigned)plan.slabs, (unsigned)((2 * Hq + PV_WAVES - 1) / PV_WAVES));
 #define LAUNCH_PV(B)                                                                                          \

@@ -199,8 +199,10 @@ template <int BITS, int KVH, int RQ, int NT, int PG>
 __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ params, int D, int r,
                                                     int64_t cap, int64_t L, const uint8_t *__restrict__ k_codes,
                                                     const float *__restrict__ q_rot, float scale,
-                                                    float *__restrict__ scores, int64_t ld, int n_tiles)
+                                                    float *__restrict__ scores, int64_t ld, int n_tiles,
+                                                    int add_prev)
 {
+    // add_prev != 0: the score buffer already holds the sparse part; add to it instead of overwriting
     using C = QkCfg<BITS>;
     constexpr int QH = KVH * RQ, R = RQ;
     constexpr int NE = C::NE;
@@ -287,9 +289,13 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
         const int lane_id = tid & 63;
         const float nf = (float)lane_id;
         const float wave_base = rope_rev((float)(n - lane_id), my_vh, my_vl);
-        float acc[QH];
+        float acc[QH], prev[QH];
 #pragma unroll
-        for (int qh = 0; qh < QH; ++qh) acc[qh] = 0.f;
+        for (int qh = 0; qh < QH; ++qh) {
+            acc[qh] = 0.f;
+            // requested now, consumed after the tile's arithmetic
+            prev[qh] = (add_prev && valid) ? scores[(int64_t)(q0 + qh) * ld + n] : 0.f;
+        }
         // lanes past the end run the arithmetic on whatever their registers hold (table offsets are
         // masked, so every gather stays inside the table) and simply skip loads and stores
         // a wavefront whose 64 tokens all lie past the end (ragged last tile) skips the arithmetic
@@ -312,7 +318,7 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
         if (valid) {
 #pragma unroll
             for (int qh = 0; qh < QH; ++qh)
-                scores[(int64_t)(q0 + qh) * ld + n] = acc[qh];
+                scores[(int64_t)(q0 + qh) * ld + n] = acc[qh] + prev[qh];
         }
         n = nn;
         valid = next_valid;
@@ -321,100 +327,170 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
 }
 
 // Sparse Key outliers, balanced (paper App. "Kernel Implementation Details": equal non-zeros per
-// thread): lanes are outlier entries.  A workgroup owns a chunk of `tc` consecutive tokens, stages
-// their pointers in LDS, finds each entry's token by a guess plus a short walk, rotates the
-// query instead of the Key (by linearity  <q, R_n (v e_c)> = v (R_n^T q)_c ) and accumulates
-// scale * v * (R_n^T q)_c into an LDS tile [query head][token] (fixed-point integer atomics: LDS
-// floating-point atomics are an order of magnitude slower here), which it then adds to the dense
-// scores already in the score buffer.  Entries are fetched several at a time so that their global
-// loads overlap.
-template <int R>
-__global__ __launch_bounds__(1024) void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads,
-                                                      int64_t L, const uint32_t *__restrict__ k_ptr,
-                                                      const uint16_t *__restrict__ k_idx,
-                                                      const uint16_t *__restrict__ k_val,
-                                                      const float *__restrict__ q_rot, float scale,
-                                                      float *__restrict__ scores, int64_t ld, int tc_max)
+// thread): lanes are outlier entries.  Every wavefront works on its own: it owns a run of consecutive
+// tokens and walks it QS_TW tokens at a time.  A sub-range's pointers sit in one register (lane j:
+// token j), so the token of an entry is a wavefront-uniform cursor plus the number of token starts
+// among the 64 entries of the batch, found with scalar reads of that register.  The query is
+// rotated instead of the Key (by linearity  <q, R_n (v e_c)> = v (R_n^T q)_c ) and
+// scale * v * (R_n^T q)_c is accumulated into the wavefront's private LDS tile [query head][token]
+// (fixed-point integer atomics: LDS floating-point atomics are an order of magnitude slower here),
+// which is then written to the score buffer; the dense kernel, launched afterwards, adds its part.
+// The only workgroup-wide barrier follows the staging of the scaled query.
+constexpr int QS_TW = 8;              // tokens per sub-range
+// row length of the LDS tile: one token's outliers hit the same column of many rows, and an odd row
+// length spreads that column over all LDS banks
+constexpr int QS_ROW = QS_TW + 1;
+constexpr int QS_U = 6;               // 64-entry batches in flight per wavefront
+
+__host__ __device__ constexpr int qs_wave_lds_bytes(int n_q_heads)
 {
-    extern __shared__ __attribute__((aligned(16))) float dyn[];
-    // S holds 2^32-scaled fixed-point sums (see kvq_lds_add_fixed).  Rows are padded by one cell: the
-    // outliers of one token hit the same column of many rows, and an unpadded row length would put
-    // them all in one LDS bank.
-    constexpr double FIX = 4294967296.0;
-    const int srow = tc_max + 1;
-    long long *S = (long long *)dyn;                  // [n_q_heads][tc_max + 1]
-    float *qs = dyn + (size_t)n_q_heads * srow * 2;    // [n_q_heads][128]
-    uint32_t *ptr_s = (uint32_t *)(qs + (size_t)n_q_heads * 128);   // [tc_max + 1]
-    __shared__ float2_t rope[64];
-    const KvqParamsView pv = kvq_params_view(params, D);
-    const int tid = threadIdx.x;
-    const int64_t nc = (int64_t)blockIdx.x * tc_max;
-    const int tc = (int)((L - nc < tc_max) ? (L - nc) : tc_max);
-    for (int j = tid; j < n_q_heads * srow; j += 1024) S[j] = 0;
-    for (int j = tid; j < n_q_heads * 128; j += 1024) qs[j] = q_rot[j] * scale;
-    for (int j = tid; j <= tc; j += 1024) ptr_s[j] = k_ptr[nc + j];
-    if (tid < 64) rope[tid] = float2_t{pv.hdr->rope_vh[tid], pv.hdr->rope_vl[tid]};
-    // the dense scores this workgroup will add to: requested now, consumed after the entry loop
-    const int lane = tid & 63, wave = tid >> 6;
-    float dense[2][4];
+    return ((n_q_heads * QS_ROW * 8 + 15) & ~15) + 64 * 8;       // sums, per-pair angles
+}
+
+// One batch of index/value loads.  CLAMP = false: the whole batch lies inside the arrays (possibly
+// past the sub-range's end, where the loaded values are ignored), one address per lane plus
+// immediate offsets; CLAMP = true: lanes past the end re-read the last entry.
+template <bool CLAMP>
+__device__ __forceinline__ void sparse_load_batch(const uint16_t *__restrict__ idx, const uint16_t *__restrict__ val,
+                                                  uint32_t eb, uint32_t e_end, int lane, uint32_t (&chv)[QS_U],
+                                                  uint32_t (&vb)[QS_U])
+{
+    const char *ib = (const char *)idx, *vbp = (const char *)val;
+    if (!CLAMP) {
+        const uint32_t off0 = (eb + (uint32_t)lane) * 2u;
 #pragma unroll
-    for (int it = 0; it < 2; ++it)
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int qh = wave + 16 * it, t = lane + 64 * k;
-            dense[it][k] = (qh < n_q_heads && t < tc) ? scores[(int64_t)qh * ld + nc + t] : 0.f;
+        for (int u = 0; u < QS_U; ++u) {
+            if (eb + 64u * u >= e_end) break;            // uniform: the rest of the batch is past the end
+            chv[u] = *(const uint16_t *)(ib + (size_t)off0 + 128 * u);
+            vb[u] = *(const uint16_t *)(vbp + (size_t)off0 + 128 * u);
         }
-    __syncthreads();
-    const uint32_t e_begin = ptr_s[0], e_end = ptr_s[tc];
-    const float inv_per = (e_end > e_begin) ? (float)tc / (float)(e_end - e_begin) : 0.f;
-    constexpr int U = 8;                              // entries in flight per lane
-    for (uint32_t e0 = e_begin + tid; e0 < e_end; e0 += 1024 * U) {
-        uint32_t chv[U];
-        uint16_t vb[U];
+    } else {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t e = e0 + 1024u * u;
-            const uint32_t ec = (e < e_end) ? e : e_end - 1;   // clamped: straight-line loads, all in flight
-            chv[u] = (uint32_t)k_idx[ec];
-            vb[u] = k_val[ec];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t e = e0 + 1024u * u;
-            if (e >= e_end) break;
-            const uint32_t ch = chv[u];
-            const float v = kvq_h2f(vb[u]);
-            int t = (int)((float)(e - e_begin) * inv_per);
-            if (t >= tc) t = tc - 1;
-            while (ptr_s[t] > e) --t;                 // ptr_s[0] <= e, so this stops at t >= 0
-            while (ptr_s[t + 1] <= e) ++t;            // ptr_s[tc] > e, so this stops at t < tc
-            const int kvh = ch >> 7, i = ch & 63, upper = (ch >> 6) & 1;
-            const float2_t vv = rope[i];
-            const float rev = rope_rev((float)(nc + t), vv.x, vv.y);
-            const float cs = __builtin_amdgcn_cosf(rev), sn = __builtin_amdgcn_sinf(rev);
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int qh = kvh * R + r;
-                const float qa = qs[qh * 128 + i], qb = qs[qh * 128 + i + 64];
-                const float qp = upper ? (qb * cs - qa * sn) : (qa * cs + qb * sn);
-                kvq_lds_add_fixed(&S[qh * srow + t], v * qp, FIX);
-            }
+        for (int u = 0; u < QS_U; ++u) {
+            if (eb + 64u * u >= e_end) break;
+            uint32_t e = eb + (uint32_t)lane + 64u * u;
+            e = (e < e_end) ? e : e_end - 1;
+            chv[u] = *(const uint16_t *)(ib + (size_t)(e * 2u));
+            vb[u] = *(const uint16_t *)(vbp + (size_t)(e * 2u));
         }
     }
-    __syncthreads();
-    // add the tile to the dense scores (rows prefetched above: wavefront w owns rows w and w+16;
-    // models with more than 32 query heads take the remaining rows the slow way)
-#pragma unroll
-    for (int it = 0; it < 2; ++it)
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int qh = wave + 16 * it, t = lane + 64 * k;
-            if (qh < n_q_heads && t < tc)
-                scores[(int64_t)qh * ld + nc + t] = dense[it][k] + (float)((double)S[qh * srow + t] * (1.0 / FIX));
+}
+
+// Token (relative to the sub-range) of entry `first + lane`.  `pw` holds the sub-range's pointers
+// (lane j: first entry of token j; lanes >= tc: the end), `tcur` is the wavefront's cursor: the token
+// that entry `first` belongs to once advanced.  Everything but the final compare-and-add is scalar.
+__device__ __forceinline__ int sparse_token(uint32_t pw, int tc, int &tcur, uint32_t first, uint32_t e)
+{
+    while (tcur + 1 < tc && (uint32_t)__builtin_amdgcn_readlane((int)pw, tcur + 1) <= first) ++tcur;
+    int t = tcur;
+    int j = tcur + 1;
+    while (j < tc) {
+        const uint32_t pj = (uint32_t)__builtin_amdgcn_readlane((int)pw, j);
+        if (pj > first + 63u) break;
+        t += (e >= pj) ? 1 : 0;
+        j = __builtin_amdgcn_readfirstlane(j + 1);
+    }
+    return t;
+}
+
+template <int R>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_t L,
+                   const uint32_t *__restrict__ k_ptr, const uint16_t *__restrict__ k_idx,
+                   const uint16_t *__restrict__ k_val, uint32_t nnz_cap, const float *__restrict__ q_rot,
+                   float scale, float *__restrict__ scores, int64_t ld, int64_t tokens_per_wave)
+{
+    extern __shared__ __attribute__((aligned(16))) float dyn[];
+    const KvqParamsView pv = kvq_params_view(params, D);
+    const int tid = threadIdx.x, lane = tid & 63, n_waves = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // scalar: loop bounds below are uniform
+    float *qs = dyn;                                                     // [n_q_heads][128], scaled query
+    char *mine = (char *)(dyn + n_q_heads * 128) + (size_t)wave * qs_wave_lds_bytes(n_q_heads);
+    unsigned long long *S = (unsigned long long *)mine;                  // [n_q_heads][QS_ROW] 2^32-scaled sums
+    float2_t *ang = (float2_t *)(mine + ((n_q_heads * QS_ROW * 8 + 15) & ~15));   // [64] (angle at the sub-range start, theta/2pi)
+    const int64_t nb = ((int64_t)blockIdx.x * n_waves + wave) * tokens_per_wave;
+    int64_t ne = nb + tokens_per_wave;
+    if (ne > L) ne = L;
+    const int n_cells = n_q_heads * QS_TW;
+    // the run is cut into equal sub-ranges of at most QS_TW tokens; the pointers of the next one are
+    // requested while the current one is processed
+    const int run = (nb < ne) ? (int)(ne - nb) : 0, n_sub = (run + QS_TW - 1) / QS_TW;
+    const int sub_len = n_sub ? (run + n_sub - 1) / n_sub : 0;
+    int64_t nc = nb;
+    int tc = sub_len;
+    uint32_t pw = 0;
+    if (tc > 0) pw = k_ptr[nc + (lane < tc ? lane : tc)];
+    // staging of the scaled query: its barrier comes after the first sub-range's loads are requested
+    for (int j = tid; j < n_q_heads * 128; j += blockDim.x) qs[j] = q_rot[j] * scale;
+    for (int j = lane; j < n_q_heads * QS_ROW; j += 64) S[j] = 0ull;
+    const float my_vh = pv.hdr->rope_vh[lane], my_vl = pv.hdr->rope_vl[lane];
+    bool staged = false;
+    while (tc > 0) {
+        const int64_t nc_next = nc + tc;
+        const int tc_next = (int)((ne - nc_next < sub_len) ? (ne - nc_next) : sub_len);
+        const uint32_t e_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)pw);
+        const uint32_t e_end = (uint32_t)__builtin_amdgcn_readlane((int)pw, 63);
+        uint32_t chv[QS_U], vb[QS_U];
+        if (e_begin < e_end) {
+            if (e_begin + 64u * QS_U <= nnz_cap) sparse_load_batch<false>(k_idx, k_val, e_begin, e_end, lane, chv, vb);
+            else sparse_load_batch<true>(k_idx, k_val, e_begin, e_end, lane, chv, vb);
         }
-    for (int qh = wave + 32; qh < n_q_heads; qh += 16)
-        for (int t = lane; t < tc; t += 64)
-            scores[(int64_t)qh * ld + nc + t] += (float)((double)S[qh * srow + t] * (1.0 / FIX));
+        uint32_t pw_next = 0;
+        if (tc_next > 0) pw_next = k_ptr[nc_next + (lane < tc_next ? lane : tc_next)];
+        ang[lane] = float2_t{rope_rev((float)nc, my_vh, my_vl), my_vh};
+        if (!staged) {
+            __syncthreads();
+            staged = true;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        int tcur = 0;
+        for (uint32_t eb = e_begin; eb < e_end; eb += 64 * QS_U) {
+            if (eb != e_begin) {                         // (the first batch was requested above)
+                if (eb + 64u * QS_U <= nnz_cap) sparse_load_batch<false>(k_idx, k_val, eb, e_end, lane, chv, vb);
+                else sparse_load_batch<true>(k_idx, k_val, eb, e_end, lane, chv, vb);
+            }
+#pragma unroll
+            for (int u = 0; u < QS_U; ++u) {
+                const uint32_t first = eb + 64u * u, e = first + (uint32_t)lane;
+                if (first >= e_end) break;
+                const int t = sparse_token(pw, tc, tcur, first, e);
+                if (e < e_end) {
+                    const uint32_t ch = chv[u];
+                    const float v = kvq_h2f((uint16_t)vb[u]);
+                    const float2_t a = ang[ch & 63];
+                    const float rev = __builtin_fmaf((float)t, a.y, a.x);
+                    const float cs = __builtin_amdgcn_cosf(rev);
+                    // (R_n^T q)_c = q_c cos + s q_{c^64} sin with s = +1 for the lower channel of the
+                    // pair and -1 for the upper: fold s into the sine
+                    const float sn = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, __builtin_amdgcn_sinf(rev)) ^ ((ch & 64u) << 25));
+                    const uint32_t cl = ch & 127u, kvh = ch >> 7;
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const uint32_t qh = kvh * R + r;
+                        const uint32_t qi = (R == 1) ? ch : qh * 128u + cl;
+                        const float qp = qs[qi] * cs + qs[qi ^ 64u] * sn;
+                        kvq_lds_add_fixed<0>(&S[qh * QS_ROW + t], v * qp);
+                    }
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        // write the tile to the score buffer and clear it for the next sub-range
+        for (int j = lane; j < n_cells; j += 64) {
+            const int qh = j / QS_TW, t = j % QS_TW;
+            const unsigned long long x = S[qh * QS_ROW + t];
+            S[qh * QS_ROW + t] = 0ull;
+            if (t < tc) scores[(int64_t)qh * ld + nc + t] = kvq_from_fixed_fast<0>(x);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        nc = nc_next;
+        tc = tc_next;
+        pw = pw_next;
+    }
+    if (!staged) __syncthreads();        // a wavefront without tokens still meets the workgroup's barrier
 }
 
 template <int R>
@@ -422,20 +498,31 @@ kvq_status launch_qk_sparse(const kvq_cache *c, const float *q, float scale, flo
 {
     const int Hq = c->n_q_heads;
     const int64_t L = c->n_tokens_k;
-    // LDS: Hq*(tc+1) 64-bit sums + Hq*128 floats + (tc+1) words, kept under 144 KiB; at most 256 tokens
-    int tc = (int)((147456 - 4 - (int64_t)Hq * 520) / ((int64_t)Hq * 8 + 4));
-    tc = (tc >= 256) ? 256 : (tc / 64) * 64;
-    if (tc < 64) return KVQ_ERR_UNSUPPORTED;
-    const size_t lds = (size_t)Hq * (tc + 1) * 8 + (size_t)Hq * 128 * 4 + (size_t)(tc + 1) * 4;
+    if (c->cap_nnz_k >= ((int64_t)1 << 31)) return KVQ_ERR_UNSUPPORTED;      // byte offsets are 32-bit
+    // LDS: the scaled query plus one private slice per wavefront; two workgroups of 12 wavefronts per
+    // CU when they fit in 77 KiB each, fewer wavefronts otherwise
+    const int per_wave = qs_wave_lds_bytes(Hq);
+    int waves = 16;
+    while (waves > 1 && (size_t)Hq * 512 + (size_t)waves * per_wave > 78848) waves -= (waves > 4) ? 4 : waves / 2;
+    if ((size_t)Hq * 512 + (size_t)waves * per_wave > 147456) return KVQ_ERR_UNSUPPORTED;
+    const size_t lds = (size_t)Hq * 512 + (size_t)waves * per_wave;
     static size_t lds_attr = 0;      // per instantiation
     if (lds > lds_attr) {
         KVQ_HIP_CHECK(hipFuncSetAttribute((const void *)kvq_qk_sparse<R>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                           (int)lds));
         lds_attr = lds;
     }
-    const unsigned grid = (unsigned)((L + tc - 1) / tc);
-    kvq_qk_sparse<R><<<grid, 1024, lds, s>>>(c->params, c->n_kv_heads * KVQ_HEAD_DIM, Hq, L, c->k_ptr, c->k_idx,
-                                             c->k_val, q, scale, scores, ld, tc);
+    // as many wavefronts as the chip holds at once (256 CUs, 160 KiB of LDS and 24 wavefronts each),
+    // every one with the same number of tokens (a multiple of 8)
+    int wgs_per_cu = (int)(163840 / lds);
+    if (wgs_per_cu * waves > 32) wgs_per_cu = 32 / waves;
+    if (wgs_per_cu < 1) wgs_per_cu = 1;
+    const int64_t resident = (int64_t)256 * wgs_per_cu * waves;
+    int64_t tpw = (L + resident - 1) / resident;
+    const int64_t n_waves = (L + tpw - 1) / tpw;
+    const unsigned grid = (unsigned)((n_waves + waves - 1) / waves);
+    kvq_qk_sparse<R><<<grid, 64 * waves, lds, s>>>(c->params, c->n_kv_heads * KVQ_HEAD_DIM, Hq, L, c->k_ptr, c->k_idx,
+                                                   c->k_val, (uint32_t)c->cap_nnz_k, q, scale, scores, ld, tpw);
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }
@@ -454,16 +541,18 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     int64_t gx = 256 / groups;
     if (gx < 1) gx = 1;
     if (gx > tiles) gx = tiles;
-    if (const char *e = getenv("KVQ_QK_TPW")) gx = (tiles + atoi(e) - 1) / atoi(e);   // TEMPORARY tuning knob
     dim3 grid((unsigned)gx, (unsigned)groups);
-    KvqProfile &prof = kvq_profile_state();
-    if (prof.enabled) KVQ_HIP_CHECK(hipEventRecord(prof.ev[0][0], s));
-    kern<<<grid, NT, 0, s>>>(c->params, D, R, c->cap_tokens, L, c->k_codes, q, scale, scores, ld, (int)tiles);
-    if (prof.enabled) { KVQ_HIP_CHECK(hipEventRecord(prof.ev[0][1], s)); prof.have[0] = 1; }
-    if (!(c->loaded & 2)) {                              // bit 1: thresholds admit no Key outliers
+    // the sparse kernel goes first and writes its part of every score; the dense kernel adds its own
+    const int sparse_first = !(c->loaded & 2);           // bit 1: thresholds admit no Key outliers
+    if (sparse_first) {
         kvq_status st = launch_qk_sparse<R>(c, q, scale, scores, ld, s);
         if (st != KVQ_OK) return st;
     }
+    KvqProfile &prof = kvq_profile_state();
+    if (prof.enabled) KVQ_HIP_CHECK(hipEventRecord(prof.ev[0][0], s));
+    kern<<<grid, NT, 0, s>>>(c->params, D, R, c->cap_tokens, L, c->k_codes, q, scale, scores, ld, (int)tiles,
+                             sparse_first);
+    if (prof.enabled) { KVQ_HIP_CHECK(hipEventRecord(prof.ev[0][1], s)); prof.have[0] = 1; }
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }
@@ -475,9 +564,6 @@ kvq_status dispatch_qk(const kvq_cache *c, const float *q, float scale, float *s
 {
     constexpr int QHMAX = (BITS == 3) ? 4 : 8;
     constexpr int PGD = (BITS == 4) ? 1 : (BITS == 3 ? 4 : 2);
-    const int PGE = getenv("KVQ_QK_PG") ? atoi(getenv("KVQ_QK_PG")) : 0;   // TEMPORARY tuning knob
-    if (BITS == 3 && R == 1 && PGE == 2) return launch_qk<BITS, 4, 1, 1024, 2, R>(c, q, scale, scores, ld, s);
-    if (BITS == 3 && R == 1 && PGE == 1) return launch_qk<BITS, 4, 1, 1024, 1, R>(c, q, scale, scores, ld, s);
     constexpr int PG = PGD;
     if constexpr (R >= QHMAX) {
         // one KV head per workgroup, QHMAX of its query heads (R / QHMAX workgroups share the KV head)
