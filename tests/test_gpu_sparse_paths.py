@@ -1,0 +1,134 @@
+"""GPU parity for the sparse (outlier) kernels on inputs chosen to reach every branch of them:
+tokens without any Key outlier, a token whose channels are all outliers, outlier counts large enough
+that a sub-range of tokens needs several batches of entries, and sparse arrays with no slack after
+the last entry (loads near the end must not run past the arrays)."""
+import numpy as np
+import pytest
+
+import kvq_synth as S
+from oracle import kvq_oracle as O
+from kvq_testlib import Setup, compare_caches, matvec_close
+
+pytestmark = pytest.mark.gpu
+
+SCALE = 1.0 / np.sqrt(128.0)
+
+
+def _crafted_keys(st, L, rng):
+    """Synthetic keys with planted rows: empty rows sit at the channels' mid-points (inside every
+    threshold), full rows far outside them."""
+    k = st.k(0, L).copy()
+    z, hi, lo = (np.asarray(a, dtype=np.float16).astype(np.float32) for a in (st.z, st.hi, st.lo))
+    empty = rng.choice(L, size=L // 5, replace=False)
+    k[empty] = z.astype(np.float16)
+    # runs of consecutive empty tokens, including the very first and the very last token
+    k[0:3] = z.astype(np.float16)
+    k[L - 2:L] = z.astype(np.float16)
+    k[40:59] = z.astype(np.float16)
+    full = [7, 64, L // 2]
+    sign = np.where(rng.random(st.wl.D) < 0.5, -1.0, 1.0).astype(np.float32)
+    far = np.where(sign > 0, hi + 4.0 * (hi - lo) + 1.0, lo - 4.0 * (hi - lo) - 1.0)
+    k[full] = far.astype(np.float16)
+    return k, empty, full
+
+
+def _run(st, k, v, L, cap, cap_nnz_k=None, cap_nnz_v=None, chunks=(1, 5, 64, 130)):
+    import torch
+    import paper_2401_18079_amd as K
+    wl = st.wl
+    oc = O.OracleCache(wl.bits, wl.n_kv_heads, wl.n_q_heads, cap, st.k_side, wl.rope_base, st.lut_k, st.lut_v,
+                       st.s, st.z, st.lo, st.hi, cap_nnz_k=cap_nnz_k or wl.D * cap,
+                       cap_nnz_v=cap_nnz_v or max(1, 2 * st.k_side * cap))
+    gc = K.KvqCache(wl.bits, wl.n_kv_heads, wl.n_q_heads, cap, st.k_side, wl.rope_base,
+                    cap_nnz_k or wl.D * cap, cap_nnz_v=cap_nnz_v or max(1, 2 * st.k_side * cap))
+    K.kvq_lut_load(gc, st.lut_k, st.lut_v, st.s, st.z, st.lo, st.hi)
+    t0, i = 0, 0
+    while t0 < L:
+        T = min(chunks[i % len(chunks)], L - t0)
+        oc.append_k(k[t0:t0 + T]); oc.append_v(v[t0:t0 + T])
+        K.kvq_quantize_append_k(gc, torch.from_numpy(k[t0:t0 + T]).cuda())
+        K.kvq_quantize_append_v(gc, torch.from_numpy(v[t0:t0 + T]).cuda())
+        t0 += T
+        i += 1
+    torch.cuda.synchronize()
+    return oc, gc
+
+
+def _check_matvecs(st, oc, gc, L):
+    import torch
+    import paper_2401_18079_amd as K
+    wl = st.wl
+    for step in range(2):
+        q = S.gen_q(wl, 0, 0, step=step)
+        ref = oc.qk(q, SCALE)
+        scores = torch.full((wl.n_q_heads, L + 3), -7.0, device="cuda")
+        K.kvq_qk_matvec(gc, torch.from_numpy(q).cuda(), SCALE, scores)
+        got = scores.cpu().numpy()
+        assert np.all(got[:, L:] == -7.0)
+        ok, worst = matvec_close(got[:, :L], ref)
+        assert ok, f"qk worst error / bound = {worst:.3f}"
+        p = O.softmax(ref)
+        out = torch.empty((wl.n_q_heads, 128), device="cuda")
+        K.kvq_pv_matvec(gc, torch.from_numpy(p).cuda(), out)
+        ok, worst = matvec_close(out.cpu().numpy(), oc.pv(p))
+        assert ok, f"pv worst error / bound = {worst:.3f}"
+
+
+@pytest.mark.parametrize("bits,L", [(3, 333), (4, 200)])
+def test_empty_and_full_tokens(bits, L):
+    wl = S.workload("c2", n_kv_heads=4, n_q_heads=4, bits=bits)
+    st = Setup(wl)
+    rng = np.random.default_rng(7)
+    k, empty, full = _crafted_keys(st, L, rng)
+    v = st.v(0, L)
+    cap = 512
+    oc, gc = _run(st, k, v, L, cap)
+    assert gc.status() == 0
+    assert not compare_caches(oc, gc)
+    cnt = np.diff(oc.k_ptr[:L + 1].astype(np.int64))
+    assert np.all(cnt[empty] == 0) and np.all(cnt[:3] == 0) and np.all(cnt[L - 2:] == 0)   # the plant took
+    assert np.all(cnt[full] == wl.D)
+    _check_matvecs(st, oc, gc, L)
+
+
+def test_many_outliers_per_token_need_several_batches():
+    # 8 % outliers on D = 1024: 82 entries per token, so eight tokens exceed one batch of either kernel
+    wl = S.workload("c2", n_kv_heads=8, n_q_heads=8, outlier_fraction=0.08)
+    st = Setup(wl)
+    L = 700
+    oc, gc = _run(st, st.k(0, L), st.v(0, L), L, 768)
+    assert gc.status() == 0
+    assert not compare_caches(oc, gc)
+    cnt_k = np.diff(oc.k_ptr[:L + 1].astype(np.int64))
+    cnt_v = np.diff(oc.v_ptr[:L + 1].astype(np.int64))
+    assert cnt_k.mean() > 60 and np.all(cnt_v == 2 * st.k_side) and 2 * st.k_side > 64
+    _check_matvecs(st, oc, gc, L)
+
+
+def test_sparse_arrays_without_slack():
+    """The sparse arrays end exactly at the last entry: batched loads near the end must stay inside."""
+    wl = S.workload("c2", n_kv_heads=8, n_q_heads=8)
+    st = Setup(wl)
+    L = 391
+    k, v = st.k(0, L), st.v(0, L)
+    # first pass through the oracle alone tells how many entries there will be
+    probe = O.OracleCache(wl.bits, wl.n_kv_heads, wl.n_q_heads, 512, st.k_side, wl.rope_base, st.lut_k, st.lut_v,
+                          st.s, st.z, st.lo, st.hi)
+    probe.append_k(k); probe.append_v(v)
+    nnz_k, nnz_v = int(probe.k_ptr[L]), int(probe.v_ptr[L])
+    oc, gc = _run(st, k, v, L, 512, cap_nnz_k=nnz_k, cap_nnz_v=nnz_v)
+    assert gc.status() == 0                     # exactly full is not an overflow
+    assert not compare_caches(oc, gc)
+    _check_matvecs(st, oc, gc, L)
+
+
+def test_gqa_with_crafted_tokens():
+    wl = S.workload("c4", n_kv_heads=2, n_q_heads=8)
+    st = Setup(wl)
+    L = 150
+    rng = np.random.default_rng(11)
+    k, empty, full = _crafted_keys(st, L, rng)
+    oc, gc = _run(st, k, st.v(0, L), L, 256)
+    assert gc.status() == 0
+    assert not compare_caches(oc, gc)
+    _check_matvecs(st, oc, gc, L)
