@@ -100,22 +100,60 @@ __device__ inline void stream_or(uint32_t *words, int bit, uint32_t value, int w
     if (sh + width > 32) atomicOr(&words[w + 1], value >> (32 - sh));
 }
 
+// Exclusive ranks, in channel order, of IT flags per thread (flag j belongs to channel block j, a
+// block being NT consecutive channels, one per thread): rank[j] counts the set flags of all earlier
+// blocks plus those of lower threads in block j.  `wave_tot` is a shared array of IT*NT/64 words.
+// Returns the total.  Contains two barriers, whatever IT.
+template <int NT, int IT>
+__device__ inline uint32_t block_rank_multi(const bool (&flag)[IT], uint32_t (&rank)[IT], uint32_t *wave_tot)
+{
+    constexpr int NW = NT / 64;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t prefix[IT];
+#pragma unroll
+    for (int j = 0; j < IT; ++j) {
+        const unsigned long long b = __ballot(flag[j]);
+        prefix[j] = __popcll(b & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_tot[j * NW + w] = __popcll(b);
+    }
+    __syncthreads();
+    uint32_t run = 0;
+#pragma unroll
+    for (int j = 0; j < IT; ++j) {
+        uint32_t before = 0, tot = 0;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const uint32_t t = wave_tot[j * NW + i];
+            if (i < w) before += t;
+            tot += t;
+        }
+        rank[j] = run + before + prefix[j];
+        run += tot;
+    }
+    __syncthreads();
+    return run;
+}
+
 // Quantize, pack and append the Keys of one new token per workgroup.
 // If `single` the token's outlier count is written to ptr[n+1] here; otherwise ptr[] was already
 // filled by kvq_ptr_scan and is only read.
+// A pass handles IT blocks of NT channels: all its loads are issued up front, and ranks, packing and
+// stores of the IT blocks share one set of barriers (a single-token decode append is pure latency).
 template <int BITS, int NT>
-__global__ __launch_bounds__(NT) void kvq_k_quant(const void *params, int D, int64_t cap, int64_t n0,
-                                                  const uint16_t *k_new, uint8_t *k_codes, uint32_t *k_ptr,
-                                                  uint16_t *k_idx, uint16_t *k_val, int64_t cap_nnz,
-                                                  int single, int32_t *d_status)
+__global__ __launch_bounds__(NT) void kvq_k_quant(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
+                                                  const uint16_t *__restrict__ k_new, uint8_t *__restrict__ k_codes,
+                                                  uint32_t *__restrict__ k_ptr, uint16_t *__restrict__ k_idx,
+                                                  uint16_t *__restrict__ k_val, int64_t cap_nnz, int single,
+                                                  int32_t *d_status)
 {
     constexpr int NE = 1 << BITS;
     constexpr int CW = 4 * BITS;                 // dwords per chunk
     constexpr int NW = NT / 64;
     constexpr int HB = NT / KVQ_HEAD_DIM;        // heads covered by one block of NT channels
-    __shared__ uint8_t codes_s[NT];
-    __shared__ uint32_t chunk_s[HB][CW + 1];
-    __shared__ uint32_t wave_tot[NW];
+    constexpr int IT = 4;                        // blocks per pass
+    __shared__ uint8_t codes_s[IT][NT];
+    __shared__ uint32_t chunk_s[IT][HB][CW + 1];
+    __shared__ uint32_t wave_tot[IT * NW];
     KvqParamsView pv = kvq_params_view(params, D);
     float lut[NE];
 #pragma unroll
@@ -126,45 +164,59 @@ __global__ __launch_bounds__(NT) void kvq_k_quant(const void *params, int D, int
     const uint32_t base = k_ptr[n];
     uint32_t running = 0;
     bool overflow = false;
-    for (int c0 = 0; c0 < D; c0 += NT) {
-        const int c = c0 + tid;
-        bool is_out = false;
-        uint16_t resid = 0;
-        if (c < D) {
-            float x = kvq_h2f(k_new[(int64_t)t * D + c]);
-            float z = pv.z[c], s = pv.s[c];
-            float diff = x - z;
-            float xn = diff * pv.rinv[c];
+    for (int cb = 0; cb < D; cb += NT * IT) {
+        bool is_out[IT];
+        uint16_t resid[IT];
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int c = cb + j * NT + tid;
+            const int cc = (c < D) ? c : D - 1;                      // clamped: straight-line loads
+            const float x = kvq_h2f(k_new[(int64_t)t * D + cc]);
+            const float z = pv.z[cc], sc = pv.s[cc];
+            const float diff = x - z;
+            const float xn = diff * pv.rinv[cc];
             float sp;
-            int code = kvq_nearest<NE>(lut, xn, sp);
-            float deq = __builtin_fmaf(s, sp, z);
-            is_out = (x < pv.lo[c]) || (x > pv.hi[c]);
-            resid = kvq_f2h_rn(x - deq);
-            codes_s[tid] = (uint8_t)code;
+            const int code = kvq_nearest<NE>(lut, xn, sp);
+            const float deq = __builtin_fmaf(sc, sp, z);
+            is_out[j] = (c < D) && ((x < pv.lo[cc]) || (x > pv.hi[cc]));
+            resid[j] = kvq_f2h_rn(x - deq);
+            codes_s[j][tid] = (uint8_t)code;
         }
-        if (tid < HB * (CW + 1)) (&chunk_s[0][0])[tid] = 0;
-        uint32_t tot;
-        uint32_t rank = running + block_rank<NT>(is_out, wave_tot, tot);   // barriers inside
+        for (int i = tid; i < IT * HB * (CW + 1); i += NT) (&chunk_s[0][0][0])[i] = 0;
+        uint32_t rank[IT];
+        const uint32_t tot = block_rank_multi<NT, IT>(is_out, rank, wave_tot);   // barriers inside
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            if (is_out[j]) {
+                const uint64_t pos = (uint64_t)base + running + rank[j];
+                if (pos < (uint64_t)cap_nnz) { k_idx[pos] = (uint16_t)(cb + j * NT + tid); k_val[pos] = resid[j]; }
+                else overflow = true;
+            }
+        }
         running += tot;
-        if (is_out) {
-            uint64_t pos = (uint64_t)base + rank;
-            if (pos < (uint64_t)cap_nnz) { k_idx[pos] = (uint16_t)c; k_val[pos] = resid; }
-            else overflow = true;
-        }
-        // pack the heads covered by this block of NT channels
-        const int heads_here = (D - c0 >= NT) ? HB : (D - c0) / KVQ_HEAD_DIM;
-        if (tid < 64 * heads_here) {
-            int hh = tid >> 6, i = tid & 63;
-            uint32_t field = (uint32_t)codes_s[hh * 128 + i] | ((uint32_t)codes_s[hh * 128 + i + 64] << BITS);
-            stream_or(chunk_s[hh], i * 2 * BITS, field, 2 * BITS);
-        }
-        __syncthreads();
-        if (tid < CW * heads_here) {
-            int hh = tid / CW, wd = tid % CW;
-            int64_t off = kvq_k_piece0(BITS, cap, n, c0 / KVQ_HEAD_DIM + hh) + (wd >> 2) * 1024 + (wd & 3) * 4;
-            *(uint32_t *)(k_codes + off) = chunk_s[hh][wd];
+        // pack the heads covered by each block of NT channels
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int c0 = cb + j * NT;
+            const int heads_here = (c0 >= D) ? 0 : ((D - c0 >= NT) ? HB : (D - c0) / KVQ_HEAD_DIM);
+            if (tid < 64 * heads_here) {
+                const int hh = tid >> 6, i = tid & 63;
+                const uint32_t field = (uint32_t)codes_s[j][hh * 128 + i] | ((uint32_t)codes_s[j][hh * 128 + i + 64] << BITS);
+                stream_or(chunk_s[j][hh], i * 2 * BITS, field, 2 * BITS);
+            }
         }
         __syncthreads();
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int c0 = cb + j * NT;
+            const int heads_here = (c0 >= D) ? 0 : ((D - c0 >= NT) ? HB : (D - c0) / KVQ_HEAD_DIM);
+            if (tid < CW * heads_here) {
+                const int hh = tid / CW, wd = tid % CW;
+                const int64_t off = kvq_k_piece0(BITS, cap, n, c0 / KVQ_HEAD_DIM + hh) + (wd >> 2) * 1024 + (wd & 3) * 4;
+                *(uint32_t *)(k_codes + off) = chunk_s[j][hh][wd];
+            }
+        }
+        if (cb + NT * IT < D) __syncthreads();       // the next pass reuses the shared arrays
     }
     if (single && tid == 0) {
         uint64_t p = (uint64_t)base + running;
@@ -268,25 +320,123 @@ __device__ void select_top(const uint16_t *keys, uint8_t *state, int D, int k, u
     __syncthreads();
 }
 
+// Two bin sets at once (same scan as bins_above, one barrier for both).  `wsum` holds 8 words.
+__device__ inline void bins_above2(uint32_t mine_a, uint32_t mine_b, uint32_t *wsum, uint32_t &above_a,
+                                   uint32_t &above_b)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t sa = mine_a, sb = mine_b;
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t ta = __shfl_down(sa, o), tb = __shfl_down(sb, o);
+        if (lane + o < 64) { sa += ta; sb += tb; }
+    }
+    if (lane == 0 && w < 4) { wsum[w] = sa; wsum[4 + w] = sb; }
+    __syncthreads();
+    above_a = sa - mine_a;
+    above_b = sb - mine_b;
+    for (int i = w + 1; i < 4; ++i) { above_a += wsum[i]; above_b += wsum[4 + i]; }
+}
+
+// The k largest keys (marked 1) and, among the rest, the k smallest (marked 2) in one go; state[] is
+// all zero on entry and 2k < D.  Equal keys are taken in ascending index order on both sides.  Both
+// thresholds come out of the same two histogram passes (high byte, then low byte inside the two
+// selected bins).  Because 2k < D the k-th largest key is >= the k-th smallest; when they differ the
+// two selections cannot interact and this routine is exact; when they coincide (heavy ties) it
+// leaves state[] untouched and returns false, and the caller runs the two selections one after the
+// other.  hist: 512 words, sh: 24 words, wave_tot: 2*NT/64 words.
+template <int NT>
+__device__ bool select_both(const uint16_t *keys, uint8_t *state, int D, int k, uint32_t *hist, uint32_t *sh,
+                            uint32_t *wave_tot)
+{
+    const int tid = threadIdx.x;
+    const uint32_t K = (uint32_t)k;
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int c = tid; c < D; c += NT) atomicAdd(&hist[keys[c] >> 8], 1u);
+    __syncthreads();
+    {
+        const uint32_t mine = (tid < 256) ? hist[tid] : 0u;
+        const uint32_t above = bins_above(mine, sh + 16);
+        const uint32_t below = (uint32_t)D - above - mine;
+        if (tid < 256 && above < K && above + mine >= K) { sh[0] = tid; sh[1] = above; }
+        if (tid < 256 && below < K && below + mine >= K) { sh[2] = tid; sh[3] = below; sh[4] = mine; }
+    }
+    __syncthreads();
+    const uint32_t bin_top = sh[0], above_top = sh[1], bin_bot = sh[2], below_bot = sh[3], in_bot = sh[4];
+    if (tid < 256) { hist[tid] = 0; hist[256 + tid] = 0; }
+    __syncthreads();
+    for (int c = tid; c < D; c += NT) {
+        const uint32_t key = keys[c];
+        if ((key >> 8) == bin_top) atomicAdd(&hist[key & 255u], 1u);
+        if ((key >> 8) == bin_bot) atomicAdd(&hist[256 + (key & 255u)], 1u);
+    }
+    __syncthreads();
+    {
+        const uint32_t mt = (tid < 256) ? hist[tid] : 0u, mb = (tid < 256) ? hist[256 + tid] : 0u;
+        uint32_t at, ab;
+        bins_above2(mt, mb, sh + 16, at, ab);
+        const uint32_t above = above_top + at;                   // keys strictly greater than this one
+        const uint32_t below = below_bot + (in_bot - ab - mb);   // keys strictly smaller than this one
+        if (tid < 256 && above < K && above + mt >= K) { sh[5] = (bin_top << 8) | tid; sh[6] = above; sh[7] = mt; }
+        if (tid < 256 && below < K && below + mb >= K) { sh[8] = (bin_bot << 8) | tid; sh[9] = below; sh[10] = mb; }
+    }
+    __syncthreads();
+    const uint32_t tau_top = sh[5], tau_bot = sh[8];
+    const uint32_t need_top = K - sh[6], need_bot = K - sh[9];
+    const bool all_top = need_top == sh[7], all_bot = need_bot == sh[10];
+    if (tau_top == tau_bot) return false;
+    if (all_top && all_bot) {
+        for (int c = tid; c < D; c += NT) {
+            const uint32_t key = keys[c];
+            if (key >= tau_top) state[c] = 1;
+            else if (key <= tau_bot) state[c] = 2;
+        }
+    } else {
+        // ties straddle a threshold: equal keys are taken in index order
+        uint32_t run_top = 0, run_bot = 0;
+        for (int c0 = 0; c0 < D; c0 += NT) {
+            const int c = c0 + tid;
+            const uint32_t key = (c < D) ? keys[c] : 0u;
+            const bool flag[2] = {c < D && key == tau_top, c < D && key == tau_bot};
+            uint32_t rank[2];
+            // ranks of flag[1] continue after all of flag[0]: take the per-flag counts apart again
+            const uint32_t both = block_rank_multi<NT, 2>(flag, rank, wave_tot);
+            const uint32_t n_top = __syncthreads_count(flag[0]);
+            const uint32_t rt = run_top + rank[0], rb = run_bot + (rank[1] - n_top);
+            if (c < D) {
+                if (key > tau_top || (flag[0] && rt < need_top)) state[c] = 1;
+                else if (key < tau_bot || (flag[1] && rb < need_bot)) state[c] = 2;
+            }
+            run_top += n_top;
+            run_bot += both - n_top;
+        }
+    }
+    __syncthreads();
+    return true;
+}
+
+// A pass of the main loop handles IT blocks of NT channels (see kvq_k_quant).
 template <int BITS, int NT>
-__global__ __launch_bounds__(NT) void kvq_v_quant(const void *params, int D, int64_t cap, int64_t n0, int k_side,
-                                                  const uint16_t *v_new, uint8_t *v_codes, uint16_t *v_sz,
-                                                  uint32_t *v_ptr, uint16_t *v_idx, uint16_t *v_val,
-                                                  int64_t cap_nnz, int32_t *d_status)
+__global__ __launch_bounds__(NT) void kvq_v_quant(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
+                                                  int k_side, const uint16_t *__restrict__ v_new,
+                                                  uint8_t *__restrict__ v_codes, uint16_t *__restrict__ v_sz,
+                                                  uint32_t *__restrict__ v_ptr, uint16_t *__restrict__ v_idx,
+                                                  uint16_t *__restrict__ v_val, int64_t cap_nnz, int32_t *d_status)
 {
     constexpr int NE = 1 << BITS;
     constexpr int CW = 4 * BITS;
+    constexpr int IT = 4;                         // blocks per pass
     extern __shared__ uint8_t dyn[];              // keys: 2*D bytes, state: D bytes
     uint16_t *keys = (uint16_t *)dyn;
     uint8_t *state = dyn + 2 * (size_t)D;
     constexpr int NW = NT / 64;
     constexpr int CB = NT / 64;                   // (head, half) chunks covered by one block of NT channels
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t sh[8];
-    __shared__ uint32_t wave_tot[NW];
+    __shared__ uint32_t hist[512];
+    __shared__ uint32_t sh[24];
+    __shared__ uint32_t wave_tot[IT * NW];
     __shared__ float redmx[NW], redmn[NW];
-    __shared__ uint8_t codes_s[NT];
-    __shared__ uint32_t bits_s[CB][CW + 1], mask_s[CB][CW + 1];
+    __shared__ uint8_t codes_s[IT][NT];
+    __shared__ uint32_t bits_s[IT][CB][CW + 1], mask_s[IT][CB][CW + 1];
 
     KvqParamsView pv = kvq_params_view(params, D);
     float lut[NE];
@@ -295,12 +445,15 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *params, int D, int
     const int t = blockIdx.x, tid = threadIdx.x;
     const int64_t n = n0 + t;
     const uint16_t *x16 = v_new + (int64_t)t * D;
+    const uint32_t base = v_ptr[n0] + (uint32_t)t * 2u * (uint32_t)k_side;
 
     for (int c = tid; c < D; c += NT) { keys[c] = (uint16_t)order_key(x16[c]); state[c] = 0; }
     __syncthreads();
     if (k_side > 0) {
-        select_top<NT>(keys, state, D, k_side, 0u, 1, hist, sh, wave_tot);        // k largest
-        select_top<NT>(keys, state, D, k_side, 0xFFFFu, 2, hist, sh, wave_tot);   // k smallest of the rest
+        if (!select_both<NT>(keys, state, D, k_side, hist, sh, wave_tot)) {
+            select_top<NT>(keys, state, D, k_side, 0u, 1, hist, sh, wave_tot);        // k largest
+            select_top<NT>(keys, state, D, k_side, 0xFFFFu, 2, hist, sh, wave_tot);   // k smallest of the rest
+        }
     }
     // range of the remaining elements
     float mx = -INFINITY, mn = INFINITY;
@@ -319,55 +472,68 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *params, int D, int
     const float rinv = __fdiv_rn(1.0f, sf);
     if (tid == 0) { v_sz[n * 2 + 0] = sb; v_sz[n * 2 + 1] = zb; }
 
-    const uint32_t base = v_ptr[n0] + (uint32_t)t * 2u * (uint32_t)k_side;
     const int parity = (int)(n & 1);
     uint32_t running = 0;
     bool overflow = false;
-    for (int c0 = 0; c0 < D; c0 += NT) {
-        const int c = c0 + tid;
-        bool is_out = false;
-        uint16_t resid = 0;
-        if (c < D) {
-            float x = kvq_h2f(x16[c]);
-            float diff = x - zf;
-            float xn = diff * rinv;
+    for (int cb = 0; cb < D; cb += NT * IT) {
+        bool is_out[IT];
+        uint16_t resid[IT];
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int c = cb + j * NT + tid;
+            const int cc = (c < D) ? c : D - 1;
+            const float x = kvq_h2f(x16[cc]);
+            const float diff = x - zf;
+            const float xn = diff * rinv;
             float sp;
-            int code = kvq_nearest<NE>(lut, xn, sp);
-            float deq = __builtin_fmaf(sf, sp, zf);
-            is_out = state[c] != 0;
-            resid = kvq_f2h_rn(x - deq);
-            codes_s[tid] = (uint8_t)code;
+            const int code = kvq_nearest<NE>(lut, xn, sp);
+            const float deq = __builtin_fmaf(sf, sp, zf);
+            is_out[j] = (c < D) && state[cc] != 0;
+            resid[j] = kvq_f2h_rn(x - deq);
+            codes_s[j][tid] = (uint8_t)code;
         }
-        if (tid < CB * (CW + 1)) { (&bits_s[0][0])[tid] = 0; (&mask_s[0][0])[tid] = 0; }
-        uint32_t tot;
-        uint32_t rank = running + block_rank<NT>(is_out, wave_tot, tot);
+        for (int i = tid; i < IT * CB * (CW + 1); i += NT) { (&bits_s[0][0][0])[i] = 0; (&mask_s[0][0][0])[i] = 0; }
+        uint32_t rank[IT];
+        const uint32_t tot = block_rank_multi<NT, IT>(is_out, rank, wave_tot);   // barriers inside
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            if (is_out[j]) {
+                const uint64_t pos = (uint64_t)base + running + rank[j];
+                if (pos < (uint64_t)cap_nnz) { v_idx[pos] = (uint16_t)(cb + j * NT + tid); v_val[pos] = resid[j]; }
+                else overflow = true;
+            }
+        }
         running += tot;
-        if (is_out) {
-            uint64_t pos = (uint64_t)base + rank;
-            if (pos < (uint64_t)cap_nnz) { v_idx[pos] = (uint16_t)c; v_val[pos] = resid; }
-            else overflow = true;
-        }
-        // this block of NT channels covers up to CB (head, half) chunks of 64 fields each
-        const int chunks_here = (D - c0 >= NT) ? CB : (D - c0) / 64;
-        if (tid < 64 * chunks_here) {
-            int q = tid >> 6, j = tid & 63;
-            stream_or(bits_s[q], j * 2 * BITS + parity * BITS, (uint32_t)codes_s[tid], BITS);
-            stream_or(mask_s[q], j * 2 * BITS + parity * BITS, (uint32_t)(NE - 1), BITS);
-        }
-        __syncthreads();
-        if (tid < CW * chunks_here) {
-            int q = tid / CW, wd = tid % CW;
-            int ch0 = c0 + q * 64;
-            int64_t off = kvq_v_piece0(BITS, cap, n >> 1, ch0 / KVQ_HEAD_DIM, (ch0 >> 6) & 1) + (wd >> 2) * 1024 + (wd & 3) * 4;
-            uint32_t *p = (uint32_t *)(v_codes + off);
-            const uint32_t m = mask_s[q][wd], b = bits_s[q][wd];
-            uint32_t old = *p, assumed;
-            do {                                   // the partner token of the pair may be written concurrently
-                assumed = old;
-                old = atomicCAS(p, assumed, (assumed & ~m) | b);
-            } while (old != assumed);
+        // a block of NT channels covers up to CB (head, half) chunks of 64 fields each
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int c0 = cb + j * NT;
+            const int chunks_here = (c0 >= D) ? 0 : ((D - c0 >= NT) ? CB : (D - c0) / 64);
+            if (tid < 64 * chunks_here) {
+                const int q = tid >> 6, i = tid & 63;
+                stream_or(bits_s[j][q], i * 2 * BITS + parity * BITS, (uint32_t)codes_s[j][tid], BITS);
+                stream_or(mask_s[j][q], i * 2 * BITS + parity * BITS, (uint32_t)(NE - 1), BITS);
+            }
         }
         __syncthreads();
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int c0 = cb + j * NT;
+            const int chunks_here = (c0 >= D) ? 0 : ((D - c0 >= NT) ? CB : (D - c0) / 64);
+            if (tid < CW * chunks_here) {
+                const int q = tid / CW, wd = tid % CW;
+                const int ch0 = c0 + q * 64;
+                const int64_t off = kvq_v_piece0(BITS, cap, n >> 1, ch0 / KVQ_HEAD_DIM, (ch0 >> 6) & 1) + (wd >> 2) * 1024 + (wd & 3) * 4;
+                uint32_t *p = (uint32_t *)(v_codes + off);
+                const uint32_t m = mask_s[j][q][wd], b = bits_s[j][q][wd];
+                uint32_t old = *p, assumed;
+                do {                               // the partner token of the pair may be written concurrently
+                    assumed = old;
+                    old = atomicCAS(p, assumed, (assumed & ~m) | b);
+                } while (old != assumed);
+            }
+        }
+        if (cb + NT * IT < D) __syncthreads();     // the next pass reuses the shared arrays
     }
     if (tid == 0) {
         uint64_t p = (uint64_t)base + 2u * (uint32_t)k_side;
