@@ -63,7 +63,9 @@ kvq_status kvq_profile_enable(int32_t on)
     KvqProfile &p = kvq_profile_state();
     if (on && !p.ev[0][0]) {
         for (int k = 0; k < 2; ++k)
-            for (int j = 0; j < 2; ++j) KVQ_HIP_CHECK(hipEventCreate(&p.ev[k][j]));
+            for (int j = 0; j < 2; ++j)
+                // no system-scope fence at the record: the bracket should disturb the kernels as little as possible
+                KVQ_HIP_CHECK(hipEventCreateWithFlags(&p.ev[k][j], hipEventDisableSystemFence));
     }
     p.enabled = on ? 1 : 0;
     p.have[0] = p.have[1] = 0;

@@ -358,48 +358,48 @@ void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__r
         spartial[(int64_t)blockIdx.x * n_q_heads * 128 + j] = kvq_from_fixed<8>(sacc[j]);
 }
 
-// out[q][c] = sum_slabs partial + sum_slabs zpart + sum_sslabs spartial.  One workgroup per query
-// head, 128 channels x 8 slab groups; every sum is taken in a fixed order.
+// out[q][c] = sum_slabs partial + sum_slabs zpart + sum_sslabs spartial.  Four workgroups per query
+// head, each 32 channels x 32 slab groups; every sum is taken in a fixed order.
 __global__ __launch_bounds__(1024) void kvq_pv_reduce(int n_q_heads, int slabs, int sslabs,
                                                       const float *__restrict__ partial,
                                                       const float *__restrict__ zpart,
                                                       const float *__restrict__ spartial, float *__restrict__ out)
 {
-    __shared__ float red[8][128];
-    __shared__ float zred[8];
-    const int qh = blockIdx.x, c = threadIdx.x & 127, j = threadIdx.x >> 7;
+    __shared__ float red[32][33];
+    __shared__ float zred[32];
+    const int qh = blockIdx.x >> 2, c = (blockIdx.x & 3) * 32 + (threadIdx.x & 31), j = threadIdx.x >> 5;
     float s = 0.f;
-    for (int k0 = j; k0 < slabs; k0 += 64) {           // eight loads in flight per thread
+    for (int k0 = j; k0 < slabs; k0 += 256) {          // eight loads in flight per thread
         float v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int k = k0 + 8 * u;
+            const int k = k0 + 32 * u;
             v[u] = (k < slabs) ? partial[((int64_t)k * n_q_heads + qh) * 128 + c] : 0.f;
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) s += v[u];
     }
-    for (int k0 = j; k0 < sslabs; k0 += 64) {
+    for (int k0 = j; k0 < sslabs; k0 += 256) {
         float v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int k = k0 + 8 * u;
+            const int k = k0 + 32 * u;
             v[u] = (k < sslabs) ? spartial[((int64_t)k * n_q_heads + qh) * 128 + c] : 0.f;
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) s += v[u];
     }
-    red[j][c] = s;
-    if (c == 0) {
+    red[j][threadIdx.x & 31] = s;
+    if ((threadIdx.x & 31) == 0) {
         float z = 0.f;
-        for (int k = j; k < slabs; k += 8) z += zpart[(int64_t)k * n_q_heads + qh];
+        for (int k = j; k < slabs; k += 32) z += zpart[(int64_t)k * n_q_heads + qh];
         zred[j] = z;
     }
     __syncthreads();
     if (j == 0) {
         float t = 0.f, z = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { t += red[i][c]; z += zred[i]; }
+        for (int i = 0; i < 32; ++i) { t += red[i][threadIdx.x & 31]; z += zred[i]; }
         out[qh * 128 + c] = t + z;
     }
 }
@@ -471,7 +471,7 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
 #undef LAUNCH_PV
         if (prof.enabled) { KVQ_HIP_CHECK(hipEventRecord(prof.ev[1][1], s)); prof.have[1] = 1; }
     }
-    kvq_pv_reduce<<<Hq, 1024, 0, s>>>(Hq, plan.slabs, plan.sslabs, partial, zpart, spartial, d_out);
+    kvq_pv_reduce<<<4 * Hq, 1024, 0, s>>>(Hq, plan.slabs, plan.sslabs, partial, zpart, spartial, d_out);
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }
