@@ -251,6 +251,21 @@ def main():
             if ln.startswith("dense_kernel_traffic_bytes_per_launch:"):
                 traffic = float(ln.split(":")[1])
 
+    # instruction-issue side of the same kernel (it is bound by VALU issue): issue slots per
+    # launch from the rocprofv3 SQ_INSTS_VALU run of this command, kept under profiles/
+    valu = None
+    vpath = os.path.join(ROOT, "profiles", f"bench_{wl.name}_valu_issue.txt")
+    if os.path.exists(vpath) and not args.context:
+        kv = {}
+        for ln in open(vpath):
+            if ":" in ln and ln.split(":")[0] in ("qk_valu_issue_slots_per_launch", "valu_issue_peak_slots_per_s"):
+                kv[ln.split(":")[0]] = float(ln.split(":")[1])
+        if len(kv) == 2:
+            ach = kv["qk_valu_issue_slots_per_launch"] / (dense_qk_us * 1e-6)
+            valu = {"slots_per_launch": kv["qk_valu_issue_slots_per_launch"], "achieved": ach,
+                    "peak": kv["valu_issue_peak_slots_per_s"], "unit": "wavefront VALU issue slots/s",
+                    "frac": ach / kv["valu_issue_peak_slots_per_s"]}
+
     line = {
         "metric": "quantized-KV decode step latency (append K/V + QK^T + softmax + PV), one attention layer",
         "value": ms_per_step * 1e3, "unit": "us", "n_gpus": 1, "steps": steps, "warmup": warmup,
@@ -272,7 +287,8 @@ def main():
                      "frac": dense_qk_gbps / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes": dense_qk_bytes, "avg_launch_us": dense_qk_us,
                      "whole_call": {"algorithmic_bytes": qk_bytes, "avg_us": breakdown["qk_matvec"],
-                                    "achieved": qk_gbps, "frac": qk_gbps / HBM_PEAK_GBPS}},
+                                    "achieved": qk_gbps, "frac": qk_gbps / HBM_PEAK_GBPS},
+                     "valu_issue": valu},
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
