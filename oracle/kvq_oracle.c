@@ -413,11 +413,13 @@ void kvqo_rope(const double *x, int d, int64_t n, double base, double *y)
  * scores[h][n] = scale * sum_c q[h][c] * RoPE_n(khat[n][kvhead(h)])[c],  0 <= n < L.
  * q: fp32 [n_q_heads][128], already rotated to its own position by the caller.
  * Query head h reads KV head h / (n_q_heads / n_kv_heads).  Double accumulation, fp32 result.
+ * Attention-sink-aware quantization (paper Sec. 3.5): the first n_sink tokens are kept in fp16;
+ * for them khat[n] is the stored pre-RoPE fp16 Key sink_k[n][D] itself (their codes are ignored).
  */
 void kvqo_qk(const uint8_t *kbuf, int bits, int n_kv_heads, int n_q_heads, int64_t cap, int64_t L,
              const float *lut, const uint16_t *s, const uint16_t *z, const uint32_t *ptr,
              const uint16_t *idx, const uint16_t *val, const float *q, float scale, double rope_base,
-             float *scores, int64_t ld)
+             float *scores, int64_t ld, int64_t n_sink, const uint16_t *sink_k)
 {
     const int d = KVQO_HEAD_DIM;
     int D = n_kv_heads * d;
@@ -428,7 +430,10 @@ void kvqo_qk(const uint8_t *kbuf, int bits, int n_kv_heads, int n_q_heads, int64
         double *krot = (double *)malloc(sizeof(double) * (size_t)d);
 #pragma omp for schedule(static)
         for (int64_t n = 0; n < L; ++n) {
-            kvqo_reconstruct_k(kbuf, bits, n_kv_heads, cap, lut, s, z, ptr, idx, val, n, 1, khat);
+            if (n < n_sink)
+                for (int c = 0; c < D; ++c) khat[c] = (double)kvqo_h2f(sink_k[n * D + c]);
+            else
+                kvqo_reconstruct_k(kbuf, bits, n_kv_heads, cap, lut, s, z, ptr, idx, val, n, 1, khat);
             for (int hk = 0; hk < n_kv_heads; ++hk) {
                 kvqo_rope(khat + hk * d, d, n, rope_base, krot);
                 for (int j = 0; j < group; ++j) {
@@ -459,10 +464,14 @@ void kvqo_softmax(const float *scores, int n_q_heads, int64_t L, int64_t ld_in, 
     }
 }
 
-/* out[h][c] = sum_n probs[h][n] * vhat[n][kvhead(h)*128 + c], double accumulation, fp32 result. */
+/*
+ * out[h][c] = sum_n probs[h][n] * vhat[n][kvhead(h)*128 + c], double accumulation, fp32 result.
+ * The first n_sink tokens are kept in fp16 (paper Sec. 3.5): vhat[n] = sink_v[n][D] for them.
+ */
 void kvqo_pv(const uint8_t *vbuf, int bits, int n_kv_heads, int n_q_heads, int64_t cap, int64_t L,
              const float *lut, const uint16_t *sz, const uint32_t *ptr, const uint16_t *idx,
-             const uint16_t *val, const float *probs, int64_t ld, float *out)
+             const uint16_t *val, const float *probs, int64_t ld, float *out, int64_t n_sink,
+             const uint16_t *sink_v)
 {
     const int d = KVQO_HEAD_DIM;
     int D = n_kv_heads * d;
@@ -482,7 +491,10 @@ void kvqo_pv(const uint8_t *vbuf, int bits, int n_kv_heads, int n_q_heads, int64
         double *vhat = (double *)malloc(sizeof(double) * (size_t)D);
 #pragma omp for schedule(static)
         for (int64_t n = 0; n < L; ++n) {
-            kvqo_reconstruct_v(vbuf, bits, n_kv_heads, cap, lut, sz, ptr, idx, val, n, 1, vhat);
+            if (n < n_sink)
+                for (int c = 0; c < D; ++c) vhat[c] = (double)kvqo_h2f(sink_v[n * D + c]);
+            else
+                kvqo_reconstruct_v(vbuf, bits, n_kv_heads, cap, lut, sz, ptr, idx, val, n, 1, vhat);
             for (int h = 0; h < n_q_heads; ++h) {
                 int hk = h / group;
                 double p = (double)probs[h * ld + n];

@@ -48,10 +48,10 @@ _reconstruct_v = _sig("kvqo_reconstruct_v", None, _u8p, _i32, _i32, _i64, _f32p,
                       _u16p, _i64, _i64, _f64p)
 _rope = _sig("kvqo_rope", None, _f64p, _i32, _i64, _f64, _f64p)
 _qk = _sig("kvqo_qk", None, _u8p, _i32, _i32, _i32, _i64, _i64, _f32p, _u16p, _u16p, _u32p, _u16p, _u16p,
-           _f32p, _f32, _f64, _f32p, _i64)
+           _f32p, _f32, _f64, _f32p, _i64, _i64, _u16p)
 _softmax = _sig("kvqo_softmax", None, _f32p, _i32, _i64, _i64, _f32p, _i64)
 _pv = _sig("kvqo_pv", None, _u8p, _i32, _i32, _i32, _i64, _i64, _f32p, _u16p, _u32p, _u16p, _u16p,
-           _f32p, _i64, _f32p)
+           _f32p, _i64, _f32p, _i64, _u16p)
 _set_threads = _sig("kvqo_set_threads", None, _i32)
 _get_max_threads = _sig("kvqo_get_max_threads", _i32)
 
@@ -140,7 +140,7 @@ class OracleCache:
     """One layer's quantized KV cache held in numpy arrays, driven by the C oracle."""
 
     def __init__(self, bits, n_kv_heads, n_q_heads, cap_tokens, k_side_v, rope_base,
-                 lut_k, lut_v, s_k, z_k, lo_k, hi_k, cap_nnz_k=None, cap_nnz_v=None):
+                 lut_k, lut_v, s_k, z_k, lo_k, hi_k, cap_nnz_k=None, cap_nnz_v=None, n_sink=0):
         assert cap_tokens % 128 == 0
         self.bits, self.H, self.Hq, self.cap = bits, n_kv_heads, n_q_heads, cap_tokens
         self.D = n_kv_heads * HEAD_DIM
@@ -163,6 +163,11 @@ class OracleCache:
         self.v_val = np.zeros(self.cap_nnz_v, dtype=np.uint16)
         self.n_k = 0
         self.n_v = 0
+        # attention-sink tokens (paper Sec. 3.5): the first n_sink tokens are also kept in fp16 and the
+        # mat-vecs use those values instead of the quantized ones
+        self.n_sink = int(n_sink)
+        self.sink_k = np.zeros((max(1, self.n_sink), self.D), dtype=np.uint16)
+        self.sink_v = np.zeros((max(1, self.n_sink), self.D), dtype=np.uint16)
 
     def _append_sparse(self, ptr, idxa, vala, n0, cnt, idx, val):
         for t, c in enumerate(cnt):
@@ -177,6 +182,9 @@ class OracleCache:
         codes, cnt, idx, val = quantize_k(x, self.bits, self.lut_k, self.s_k, self.z_k, self.lo_k, self.hi_k)
         _pack_k(self.k_codes, self.bits, self.H, self.cap, self.n_k, T, codes)
         self._append_sparse(self.k_ptr, self.k_idx, self.k_val, self.n_k, cnt, idx, val)
+        for t in range(T):
+            if self.n_k + t < self.n_sink:
+                self.sink_k[self.n_k + t] = _as_bits(x)[t]
         self.n_k += T
         return codes
 
@@ -187,6 +195,9 @@ class OracleCache:
         _pack_v(self.v_codes, self.bits, self.H, self.cap, self.n_v, T, codes)
         self.v_sz[self.n_v:self.n_v + T] = sz
         self._append_sparse(self.v_ptr, self.v_idx, self.v_val, self.n_v, cnt, idx, val)
+        for t in range(T):
+            if self.n_v + t < self.n_sink:
+                self.sink_v[self.n_v + t] = _as_bits(x)[t]
         self.n_v += T
         return codes
 
@@ -217,7 +228,7 @@ class OracleCache:
         q = np.ascontiguousarray(q, dtype=np.float32)
         scores = np.zeros((self.Hq, L), dtype=np.float32)
         _qk(self.k_codes, self.bits, self.H, self.Hq, self.cap, L, self.lut_k, self.s_k, self.z_k, self.k_ptr,
-            self.k_idx, self.k_val, q, float(scale), self.rope_base, scores, L)
+            self.k_idx, self.k_val, q, float(scale), self.rope_base, scores, L, self.n_sink, self.sink_k)
         return scores
 
     def pv(self, probs, L=None):
@@ -225,5 +236,5 @@ class OracleCache:
         probs = np.ascontiguousarray(probs, dtype=np.float32)
         out = np.zeros((self.Hq, HEAD_DIM), dtype=np.float32)
         _pv(self.v_codes, self.bits, self.H, self.Hq, self.cap, L, self.lut_v, self.v_sz, self.v_ptr,
-            self.v_idx, self.v_val, probs, probs.shape[1], out)
+            self.v_idx, self.v_val, probs, probs.shape[1], out, self.n_sink, self.sink_v)
         return out

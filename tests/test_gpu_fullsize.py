@@ -99,7 +99,7 @@ def test_c2_full_context_sampled_parity():
     ref = np.zeros((wl.n_q_heads, L), np.float32)
     O._qk(ok_codes, bits, H, wl.n_q_heads, cap, L, st.lut_k, O._as_bits(st.s), O._as_bits(st.z), okp,
           oki if oki.size else np.zeros(1, np.uint16), okv if okv.size else np.zeros(1, np.uint16),
-          np.ascontiguousarray(q), float(scale), float(wl.rope_base), ref, L)
+          np.ascontiguousarray(q), float(scale), float(wl.rope_base), ref, L, 0, np.zeros(1, np.uint16))
     scores = torch.zeros((wl.n_q_heads, cap), device="cuda")
     K.kvq_qk_matvec(gc, torch.from_numpy(q).cuda(), float(scale), scores)
     got = scores.cpu().numpy()
@@ -110,7 +110,7 @@ def test_c2_full_context_sampled_parity():
     p = np.zeros((wl.n_q_heads, L), np.float32)
     p[:, sampled] = O.softmax(np.ascontiguousarray(ref[:, sampled]))
     ref_out = np.zeros((wl.n_q_heads, 128), np.float32)
-    O._pv(ov_codes, bits, H, wl.n_q_heads, cap, L, st.lut_v, o_sz, ovp, ovi, ovv, p, L, ref_out)
+    O._pv(ov_codes, bits, H, wl.n_q_heads, cap, L, st.lut_v, o_sz, ovp, ovi, ovv, p, L, ref_out, 0, np.zeros(1, np.uint16))
     pfull = torch.zeros((wl.n_q_heads, cap), device="cuda")
     pfull[:, :L] = torch.from_numpy(p).cuda()
     out = torch.zeros((wl.n_q_heads, 128), device="cuda")
