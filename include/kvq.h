@@ -27,6 +27,7 @@
  *   Sparse outliers (Keys and Values): ptr[cap_tokens+1] uint32 with ptr[0]=0; token n owns
  *                 entries ptr[n]..ptr[n+1]-1 of idx[] (uint16 channel in [0,D), ascending) and
  *                 val[] (fp16 bits of the residual x - dequant(code)).
+ *   Sink tokens — sink_k / sink_v [n_sink][D] fp16: the unquantized rows of the first n_sink tokens.
  * All cache buffers must be zero-filled before the first append (ptr[0] must be 0).
  */
 #ifndef KVQ_H
@@ -66,7 +67,7 @@ typedef struct kvq_cache {
     int64_t cap_nnz_k;      /* entries in k_idx / k_val                                         */
     int64_t cap_nnz_v;      /* entries in v_idx / v_val                                         */
     float rope_base;        /* 10000 (LLaMA / Llama-2) or 500000 (Llama-3)                      */
-    float reserved;
+    int32_t n_sink;         /* attention-sink tokens kept in fp16 (paper Sec. 3.5): 0..KVQ_MAX_SINK */
     void *params;           /* kvq_params_bytes() bytes, filled by kvq_lut_load                 */
     uint8_t *k_codes;       /* kvq_codes_bytes() bytes                                          */
     uint8_t *v_codes;       /* kvq_codes_bytes() bytes                                          */
@@ -78,7 +79,17 @@ typedef struct kvq_cache {
     int32_t *d_status;      /* one device word: 0, or a sticky kvq_status set by a kernel       */
     void *workspace;        /* scratch for partial results, >= kvq_workspace_bytes()            */
     int64_t workspace_bytes;
+    uint16_t *sink_k;       /* [n_sink][D] fp16: pre-RoPE Keys of tokens 0..n_sink-1 (NULL if 0) */
+    uint16_t *sink_v;       /* [n_sink][D] fp16: Values of tokens 0..n_sink-1 (NULL if n_sink=0) */
 } kvq_cache;
+
+/*
+ * Attention-sink-aware quantization (paper Sec. 3.5): the first n_sink tokens of the sequence stay
+ * in fp16.  The append calls still quantize them like any other token (so the packed arrays do not
+ * depend on n_sink) and also copy their fp16 rows to sink_k / sink_v; kvq_qk_matvec and
+ * kvq_pv_matvec use the fp16 rows for those tokens and ignore their codes and outliers.
+ */
+#define KVQ_MAX_SINK 4
 
 /* Buffer sizes in bytes. */
 int64_t kvq_codes_bytes(int32_t bits, int32_t n_kv_heads, int64_t cap_tokens); /* = cap*D*bits/8 */

@@ -25,11 +25,12 @@ class _CCache(C.Structure):
         ("k_side_v", C.c_int32), ("loaded", C.c_int32),
         ("cap_tokens", C.c_int64), ("n_tokens_k", C.c_int64), ("n_tokens_v", C.c_int64),
         ("cap_nnz_k", C.c_int64), ("cap_nnz_v", C.c_int64),
-        ("rope_base", C.c_float), ("reserved", C.c_float),
+        ("rope_base", C.c_float), ("n_sink", C.c_int32),
         ("params", C.c_void_p), ("k_codes", C.c_void_p), ("v_codes", C.c_void_p), ("v_sz", C.c_void_p),
         ("k_ptr", C.c_void_p), ("v_ptr", C.c_void_p),
         ("k_idx", C.c_void_p), ("k_val", C.c_void_p), ("v_idx", C.c_void_p), ("v_val", C.c_void_p),
         ("d_status", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64),
+        ("sink_k", C.c_void_p), ("sink_v", C.c_void_p),
     ]
 
 
@@ -129,7 +130,7 @@ class KvqCache:
     """Device buffers of one layer's cache for one sequence (torch tensors) plus the C descriptor."""
 
     def __init__(self, bits, n_kv_heads, n_q_heads, cap_tokens, k_side_v, rope_base, cap_nnz_k, cap_nnz_v=None,
-                 max_append=4096, device="cuda:0"):
+                 max_append=4096, device="cuda:0", n_sink=0):
         load_library()
         dev = torch.device(device)
         D = n_kv_heads * 128
@@ -145,14 +146,17 @@ class KvqCache:
         self.k_idx, self.k_val = z(cap_nnz_k, torch.int16), z(cap_nnz_k, torch.int16)
         self.v_idx, self.v_val = z(cap_nnz_v, torch.int16), z(cap_nnz_v, torch.int16)
         self.d_status = z(4, torch.int32)
+        # attention-sink tokens: the first n_sink tokens are also kept in fp16
+        self.sink_k, self.sink_v = z(max(1, n_sink) * D, torch.int16), z(max(1, n_sink) * D, torch.int16)
         c = _CCache()
         c.bits, c.head_dim, c.n_kv_heads, c.n_q_heads = bits, 128, n_kv_heads, n_q_heads
         c.k_side_v, c.loaded = k_side_v, 0
         c.cap_tokens, c.n_tokens_k, c.n_tokens_v = cap_tokens, 0, 0
         c.cap_nnz_k, c.cap_nnz_v = cap_nnz_k, int(cap_nnz_v)
         c.rope_base = float(rope_base)
+        c.n_sink = int(n_sink)
         for name in ("params", "k_codes", "v_codes", "v_sz", "k_ptr", "v_ptr", "k_idx", "k_val", "v_idx", "v_val",
-                     "d_status"):
+                     "d_status", "sink_k", "sink_v"):
             setattr(c, name, getattr(self, name).data_ptr())
         self.c = c
         self.D, self.device = D, dev

@@ -545,6 +545,17 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *__restrict__ param
 
 }  // namespace
 
+// The first n_sink tokens are also kept as they came (paper Sec. 3.5): copy their rows.
+static kvq_status copy_sink_rows(const kvq_cache *cache, uint16_t *sink, const uint16_t *src, int64_t n0, int32_t T,
+                                 hipStream_t s)
+{
+    if (n0 >= cache->n_sink) return KVQ_OK;
+    const int64_t rows = (cache->n_sink - n0 < T) ? cache->n_sink - n0 : T;
+    const size_t D = (size_t)cache->n_kv_heads * KVQ_HEAD_DIM;
+    KVQ_HIP_CHECK(hipMemcpyAsync(sink + n0 * D, src, (size_t)rows * D * 2, hipMemcpyDeviceToDevice, s));
+    return KVQ_OK;
+}
+
 static kvq_status append_checks(const kvq_cache *cache, const void *src, int32_t T, int64_t n_now)
 {
     kvq_status st = kvq_check_cache(cache);
@@ -585,6 +596,8 @@ extern "C" kvq_status kvq_quantize_append_k(kvq_cache *cache, const uint16_t *d_
     else LAUNCH_K(4);
 #undef LAUNCH_K
     KVQ_HIP_CHECK(hipGetLastError());
+    st = copy_sink_rows(cache, cache->sink_k, d_k_new, cache->n_tokens_k, T, s);
+    if (st != KVQ_OK) return st;
     cache->n_tokens_k += T;
     return KVQ_OK;
 }
@@ -616,6 +629,8 @@ extern "C" kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_
     else LAUNCH_V(4);
 #undef LAUNCH_V
     KVQ_HIP_CHECK(hipGetLastError());
+    st = copy_sink_rows(cache, cache->sink_v, d_v_new, cache->n_tokens_v, T, s);
+    if (st != KVQ_OK) return st;
     cache->n_tokens_v += T;
     return KVQ_OK;
 }

@@ -160,5 +160,8 @@ static inline kvq_status kvq_check_cache(const kvq_cache *c)
     for (const void *p : ptrs)
         if (!p || ((uintptr_t)p & 15)) return KVQ_ERR_INVALID_ARG;
     if (c->workspace && ((uintptr_t)c->workspace & 15)) return KVQ_ERR_INVALID_ARG;
+    if (c->n_sink < 0 || c->n_sink > KVQ_MAX_SINK) return KVQ_ERR_INVALID_ARG;
+    if (c->n_sink > 0 && (!c->sink_k || !c->sink_v || ((uintptr_t)c->sink_k & 15) || ((uintptr_t)c->sink_v & 15)))
+        return KVQ_ERR_INVALID_ARG;
     return KVQ_OK;
 }

@@ -133,8 +133,10 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
                                                       const uint16_t *__restrict__ v_sz,
                                                       const float *__restrict__ probs, int64_t ld,
                                                       float *__restrict__ partial, float *__restrict__ zpart,
-                                                      int n_tiles)
+                                                      int n_tiles, int n_sink)
 {
+    // tokens below n_sink are attention-sink tokens kept in fp16: their quantized form gets weight 0
+    // here and the reduce kernel adds their fp16 rows
     constexpr int NE2 = 1 << (2 * BITS);
     constexpr int CW = 4 * BITS;
     __shared__ __attribute__((aligned(16))) half2_t ptab[NE2 * 32];      // replicated pair table
@@ -174,8 +176,8 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
                 W[4 * j + 0] = v.x; W[4 * j + 1] = v.y; W[4 * j + 2] = v.z; W[4 * j + 3] = v.w;
             }
             const uint2 sz = *(const uint2 *)(v_sz + n0 * 2);            // (s0, z0, s1, z1) fp16
-            const float p0 = prow[n0];
-            const float p1 = (n0 + 1 < L) ? prow[n0 + 1] : 0.f;          // odd tail: second token absent
+            const float p0 = (n0 >= n_sink) ? prow[n0] : 0.f;
+            const float p1 = (n0 + 1 < L && n0 + 1 >= n_sink) ? prow[n0 + 1] : 0.f;   // odd tail: second token absent
             const float w0 = p0 * kvq_h2f((uint16_t)(sz.x & 0xFFFFu));
             const float w1 = p1 * kvq_h2f((uint16_t)(sz.y & 0xFFFFu));
             zacc = __builtin_fmaf(p0, kvq_h2f((uint16_t)(sz.x >> 16)), zacc);
@@ -264,7 +266,8 @@ template <int R>
 __global__ __launch_bounds__(768) __attribute__((amdgpu_waves_per_eu(6, 6)))
 void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__restrict__ v_ptr,
                    const uint16_t *__restrict__ v_idx, const uint16_t *__restrict__ v_val, uint32_t nnz_cap,
-                   const float *__restrict__ probs, int64_t ld, float *__restrict__ spartial, int64_t tokens_per_wave)
+                   const float *__restrict__ probs, int64_t ld, float *__restrict__ spartial, int64_t tokens_per_wave,
+                   int n_sink)
 {
     extern __shared__ __attribute__((aligned(16))) float dyn[];
     unsigned long long *sacc = (unsigned long long *)dyn;     // [n_q_heads][128] 2^40-scaled sums
@@ -297,7 +300,7 @@ void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__r
             const int j = lane + 64 * k, qh = j / PVS_TW, t = j % PVS_TW;
             const bool ok = j < n_cells && t < tc;
             const float x = probs[ok ? (int64_t)qh * ld + nc + t : nc];
-            pr[k] = ok ? x : 0.f;
+            pr[k] = (ok && nc + t >= n_sink) ? x : 0.f;          // sink tokens: weight 0 (kept in fp16)
         }
         const uint32_t e_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)pw);
         const uint32_t e_end = (uint32_t)__builtin_amdgcn_readlane((int)pw, 63);
@@ -315,7 +318,7 @@ void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__r
         }
         for (int j0 = 64 * 8; j0 < n_cells; j0 += 64) {      // models with more than 32 query heads
             const int j = j0 + lane, qh = j / PVS_TW, t = j % PVS_TW;
-            if (j < n_cells) ps[qh * PVS_ROW + t] = (t < tc) ? probs[(int64_t)qh * ld + nc + t] : 0.f;
+            if (j < n_cells) ps[qh * PVS_ROW + t] = (t < tc && nc + t >= n_sink) ? probs[(int64_t)qh * ld + nc + t] : 0.f;
         }
         if (!cleared) {
             __syncthreads();
@@ -363,8 +366,11 @@ void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__r
 __global__ __launch_bounds__(1024) void kvq_pv_reduce(int n_q_heads, int slabs, int sslabs,
                                                       const float *__restrict__ partial,
                                                       const float *__restrict__ zpart,
-                                                      const float *__restrict__ spartial, float *__restrict__ out)
+                                                      const float *__restrict__ spartial, float *__restrict__ out,
+                                                      int n_sink, int n_kv_heads, const uint16_t *__restrict__ sink_v,
+                                                      const float *__restrict__ probs, int64_t ld)
 {
+    // n_sink: attention-sink tokens (already clipped to the tokens present), added from their fp16 rows
     __shared__ float red[32][33];
     __shared__ float zred[32];
     const int qh = blockIdx.x >> 2, c = (blockIdx.x & 3) * 32 + (threadIdx.x & 31), j = threadIdx.x >> 5;
@@ -400,7 +406,11 @@ __global__ __launch_bounds__(1024) void kvq_pv_reduce(int n_q_heads, int slabs, 
         float t = 0.f, z = 0.f;
 #pragma unroll
         for (int i = 0; i < 32; ++i) { t += red[i][threadIdx.x & 31]; z += zred[i]; }
-        out[qh * 128 + c] = t + z;
+        float sink = 0.f;
+        const int kvh = qh / (n_q_heads / n_kv_heads);
+        for (int n = 0; n < n_sink; ++n)
+            sink = __builtin_fmaf(probs[(int64_t)qh * ld + n], kvq_h2f(sink_v[(int64_t)n * n_kv_heads * 128 + kvh * 128 + c]), sink);
+        out[qh * 128 + c] = t + z + sink;
     }
 }
 
@@ -456,13 +466,14 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
         if (cache->cap_nnz_v >= ((int64_t)1 << 31)) return KVQ_ERR_UNSUPPORTED;      // byte offsets are 32-bit
         sparse<<<plan.sslabs, 64 * plan.swaves, plan.slds, s>>>(cache->n_kv_heads, Hq, L, cache->v_ptr, cache->v_idx,
                                                                 cache->v_val, (uint32_t)cache->cap_nnz_v, d_probs,
-                                                                ld_probs, spartial, plan.tokens_per_swave);
+                                                                ld_probs, spartial, plan.tokens_per_swave,
+                                                                cache->n_sink);
 
         dim3 grid((unsigned)plan.slabs, (unsigned)((2 * Hq + PV_WAVES - 1) / PV_WAVES));
 #define LAUNCH_PV(B)                                                                                          \
     kvq_pv_dense<B><<<grid, PV_NT, 0, s>>>(cache->params, D, cache->n_kv_heads, Hq, cache->cap_tokens, L,      \
                                            cache->v_codes, cache->v_sz, d_probs, ld_probs, partial, zpart,    \
-                                           plan.tiles)
+                                           plan.tiles, cache->n_sink)
         KvqProfile &prof = kvq_profile_state();
         if (prof.enabled) KVQ_HIP_CHECK(hipEventRecord(prof.ev[1][0], s));
         if (cache->bits == 2) LAUNCH_PV(2);
@@ -471,7 +482,9 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
 #undef LAUNCH_PV
         if (prof.enabled) { KVQ_HIP_CHECK(hipEventRecord(prof.ev[1][1], s)); prof.have[1] = 1; }
     }
-    kvq_pv_reduce<<<4 * Hq, 1024, 0, s>>>(Hq, plan.slabs, plan.sslabs, partial, zpart, spartial, d_out);
+    const int ns = (int)(cache->n_sink < L ? cache->n_sink : L);
+    kvq_pv_reduce<<<4 * Hq, 1024, 0, s>>>(Hq, plan.slabs, plan.sslabs, partial, zpart, spartial, d_out, ns,
+                                          cache->n_kv_heads, cache->sink_v, d_probs, ld_probs);
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }

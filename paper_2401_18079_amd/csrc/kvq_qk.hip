@@ -538,6 +538,26 @@ kvq_status launch_qk_sparse(const kvq_cache *c, const float *q, float scale, flo
     return KVQ_OK;
 }
 
+// Attention-sink tokens (paper Sec. 3.5): score of query head blockIdx.y against the fp16 Key of token
+// blockIdx.x, overwriting what the quantized kernels wrote there.  One wavefront; lane i owns the
+// channel pair (i, i+64).
+__global__ __launch_bounds__(64) void kvq_qk_sink(const void *__restrict__ params, int D, int r,
+                                                   const uint16_t *__restrict__ sink_k,
+                                                   const float *__restrict__ q_rot, float scale,
+                                                   float *__restrict__ scores, int64_t ld)
+{
+    const KvqParamsView pv = kvq_params_view(params, D);
+    const int n = blockIdx.x, qh = blockIdx.y, i = threadIdx.x, kvh = qh / r;
+    const float k_lo = kvq_h2f(sink_k[(int64_t)n * D + kvh * 128 + i]);
+    const float k_hi = kvq_h2f(sink_k[(int64_t)n * D + kvh * 128 + i + 64]);
+    const float qa = q_rot[qh * 128 + i] * scale, qb = q_rot[qh * 128 + i + 64] * scale;
+    const float rev = rope_rev((float)n, pv.hdr->rope_vh[i], pv.hdr->rope_vl[i]);
+    const float cs = __builtin_amdgcn_cosf(rev), sn = __builtin_amdgcn_sinf(rev);
+    float t = (qa * k_lo + qb * k_hi) * cs + (qb * k_lo - qa * k_hi) * sn;
+    for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o);
+    if (i == 0) scores[(int64_t)qh * ld + n] = t;
+}
+
 template <int BITS, int KVH, int RQ, int NT, int PG, int R>
 kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
 {
@@ -564,6 +584,10 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     kern<<<grid, NT, 0, s>>>(c->params, D, R, c->cap_tokens, L, c->k_codes, q, scale, scores, ld, (int)tiles,
                              sparse_first);
     if (prof.enabled) { KVQ_HIP_CHECK(hipEventRecord(prof.ev[0][1], s)); prof.have[0] = 1; }
+    if (c->n_sink > 0) {
+        const unsigned ns = (unsigned)(c->n_sink < L ? c->n_sink : L);
+        kvq_qk_sink<<<dim3(ns, (unsigned)c->n_q_heads), 64, 0, s>>>(c->params, D, R, c->sink_k, q, scale, scores, ld);
+    }
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }
