@@ -132,6 +132,58 @@ __device__ __forceinline__ void kvq_lds_add_fixed(unsigned long long *cell, floa
     atomicAdd(cell, kvq_to_fixed<SH>(x));
 }
 
+// ---- helpers shared by the two balanced sparse kernels (lanes = outlier entries) ----------------
+
+// One batch of U x 64 index/value loads starting at entry `eb` (lane l takes entries eb + l + 64 u).
+// CLAMP = false: the whole batch lies inside the arrays (possibly past the sub-range's end `e_end`,
+// where the loaded values are ignored), one address per lane plus immediate offsets; CLAMP = true:
+// lanes past the end re-read the last entry.  Groups of 64 entries that lie entirely past `e_end`
+// are skipped (a wavefront-uniform branch).
+template <bool CLAMP, int U>
+__device__ __forceinline__ void kvq_sparse_load_batch(const uint16_t *__restrict__ idx,
+                                                      const uint16_t *__restrict__ val, uint32_t eb,
+                                                      uint32_t e_end, int lane, uint32_t (&chv)[U],
+                                                      uint32_t (&vb)[U])
+{
+    const char *ib = (const char *)idx, *vbp = (const char *)val;
+    if (!CLAMP) {
+        const uint32_t off0 = (eb + (uint32_t)lane) * 2u;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (eb + 64u * u >= e_end) break;            // uniform: the rest of the batch is past the end
+            chv[u] = *(const uint16_t *)(ib + (size_t)off0 + 128 * u);
+            vb[u] = *(const uint16_t *)(vbp + (size_t)off0 + 128 * u);
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (eb + 64u * u >= e_end) break;
+            uint32_t e = eb + (uint32_t)lane + 64u * u;
+            e = (e < e_end) ? e : e_end - 1;
+            chv[u] = *(const uint16_t *)(ib + (size_t)(e * 2u));
+            vb[u] = *(const uint16_t *)(vbp + (size_t)(e * 2u));
+        }
+    }
+}
+
+// Token (relative to the sub-range) of entry `e` = `first` + lane.  `pw` holds the sub-range's
+// pointers (lane j: first entry of token j; lanes >= tc: the end), `tcur` is the wavefront's cursor:
+// the token that entry `first` belongs to once advanced.  Everything but the final compare-and-add
+// is scalar work on values read out of `pw` with v_readlane.
+__device__ __forceinline__ int kvq_sparse_token(uint32_t pw, int tc, int &tcur, uint32_t first, uint32_t e)
+{
+    while (tcur + 1 < tc && (uint32_t)__builtin_amdgcn_readlane((int)pw, tcur + 1) <= first) ++tcur;
+    int t = tcur;
+    int j = tcur + 1;
+    while (j < tc) {
+        const uint32_t pj = (uint32_t)__builtin_amdgcn_readlane((int)pw, j);
+        if (pj > first + 63u) break;
+        t += (e >= pj) ? 1 : 0;
+        j = __builtin_amdgcn_readfirstlane(j + 1);       // keeps the loop counter in a scalar register
+    }
+    return t;
+}
+
 // Optional per-kernel timing (kvq_profile_enable): events bracketing the dense kernels.
 struct KvqProfile {
     int enabled;

@@ -9,8 +9,9 @@
 // 32 times across LDS banks so gathers never conflict.  Lanes are token pairs, a wavefront owns one
 // (query head, 64-channel half) and keeps 64 fp32 accumulators per lane; lanes are summed once at the
 // end of the wavefront's token slab.  The zero-point term sum_n p z_n is a per-head scalar.  Sparse
-// outliers are handled by a balanced kernel (lanes = outlier entries, LDS fp32 accumulators); all
-// partial results are summed in a fixed order by a final small kernel.
+// outliers are handled by a balanced kernel (lanes = outlier entries, fixed-point LDS accumulators);
+// all partial results, and the fp16 rows of attention-sink tokens (paper Sec. 3.5) if any, are
+// summed in a fixed order by a final small kernel.
 #include <utility>
 #include "kvq_common.hpp"
 
@@ -54,8 +55,8 @@ inline PvPlan pv_plan(int64_t L, int n_q_heads)
     p.slabs = (int)want;
     // sparse kernel: LDS holds Hq*128 64-bit accumulators shared by the workgroup plus a private slice
     // per wavefront (two workgroups of 12 wavefronts per CU when they fit in 77 KiB each); the launch
-    // fills the chip once (256 CUs, 160 KiB of LDS and 24 wavefronts each, at most PVS_MAX_SLABS workgroups) and every wavefront gets the same number
-    // of tokens (a multiple of 8)
+    // fills the chip once (256 CUs, 160 KiB of LDS and 24 wavefronts each, at most PVS_MAX_SLABS
+    // workgroups) and every wavefront gets the same number of tokens (a multiple of 8)
     int waves = 12;
     const size_t per_wave = (size_t)pvs_wave_lds_floats(n_q_heads) * 4;
     while (waves > 1 && (size_t)n_q_heads * 1024 + waves * per_wave > 78848) waves -= (waves > 4) ? 4 : waves / 2;
@@ -215,52 +216,6 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
 // its private LDS slice, finds each entry's token by a binary search over the pointers and adds
 // p[q][n] * val to the workgroup's fixed-point LDS accumulators (integer atomics).  The workgroup's
 // sums go to the workspace; the reduce kernel adds them up.
-// One batch of index/value loads.  CLAMP = false: the whole batch lies inside the arrays (possibly
-// past the sub-range's end, where the loaded values are ignored), one address per lane plus
-// immediate offsets; CLAMP = true: lanes past the end re-read the last entry.
-template <bool CLAMP>
-__device__ __forceinline__ void sparse_load_batch(const uint16_t *__restrict__ idx, const uint16_t *__restrict__ val,
-                                                  uint32_t eb, uint32_t e_end, int lane, uint32_t (&chv)[PVS_U],
-                                                  uint32_t (&vb)[PVS_U])
-{
-    const char *ib = (const char *)idx, *vbp = (const char *)val;
-    if (!CLAMP) {
-        const uint32_t off0 = (eb + (uint32_t)lane) * 2u;
-#pragma unroll
-        for (int u = 0; u < PVS_U; ++u) {
-            if (eb + 64u * u >= e_end) break;            // uniform: the rest of the batch is past the end
-            chv[u] = *(const uint16_t *)(ib + (size_t)off0 + 128 * u);
-            vb[u] = *(const uint16_t *)(vbp + (size_t)off0 + 128 * u);
-        }
-    } else {
-#pragma unroll
-        for (int u = 0; u < PVS_U; ++u) {
-            if (eb + 64u * u >= e_end) break;
-            uint32_t e = eb + (uint32_t)lane + 64u * u;
-            e = (e < e_end) ? e : e_end - 1;
-            chv[u] = *(const uint16_t *)(ib + (size_t)(e * 2u));
-            vb[u] = *(const uint16_t *)(vbp + (size_t)(e * 2u));
-        }
-    }
-}
-
-// Token (relative to the sub-range) of entry `first + lane`.  `pw` holds the sub-range's pointers
-// (lane j: first entry of token j; lanes >= tc: the end), `tcur` is the wavefront's cursor: the token
-// that entry `first` belongs to once advanced.  Everything but the final compare-and-add is scalar.
-__device__ __forceinline__ int sparse_token(uint32_t pw, int tc, int &tcur, uint32_t first, uint32_t e)
-{
-    while (tcur + 1 < tc && (uint32_t)__builtin_amdgcn_readlane((int)pw, tcur + 1) <= first) ++tcur;
-    int t = tcur;
-    int j = tcur + 1;
-    while (j < tc) {
-        const uint32_t pj = (uint32_t)__builtin_amdgcn_readlane((int)pw, j);
-        if (pj > first + 63u) break;
-        t += (e >= pj) ? 1 : 0;
-        j = __builtin_amdgcn_readfirstlane(j + 1);
-    }
-    return t;
-}
-
 // R = query heads per KV head (0: any ratio, looked up at run time)
 template <int R>
 __global__ __launch_bounds__(768) __attribute__((amdgpu_waves_per_eu(6, 6)))
@@ -306,8 +261,8 @@ void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__r
         const uint32_t e_end = (uint32_t)__builtin_amdgcn_readlane((int)pw, 63);
         uint32_t chv[PVS_U], vb[PVS_U];
         if (e_begin < e_end) {
-            if (e_begin + 64u * PVS_U <= nnz_cap) sparse_load_batch<false>(v_idx, v_val, e_begin, e_end, lane, chv, vb);
-            else sparse_load_batch<true>(v_idx, v_val, e_begin, e_end, lane, chv, vb);
+            if (e_begin + 64u * PVS_U <= nnz_cap) kvq_sparse_load_batch<false, PVS_U>(v_idx, v_val, e_begin, e_end, lane, chv, vb);
+            else kvq_sparse_load_batch<true, PVS_U>(v_idx, v_val, e_begin, e_end, lane, chv, vb);
         }
         uint32_t pw_next = 0;
         if (tc_next > 0) pw_next = v_ptr[nc_next + (lane < tc_next ? lane : tc_next)];
@@ -329,14 +284,14 @@ void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__r
         int tcur = 0;
         for (uint32_t eb = e_begin; eb < e_end; eb += 64 * PVS_U) {
             if (eb != e_begin) {                         // (the first batch was requested above)
-                if (eb + 64u * PVS_U <= nnz_cap) sparse_load_batch<false>(v_idx, v_val, eb, e_end, lane, chv, vb);
-                else sparse_load_batch<true>(v_idx, v_val, eb, e_end, lane, chv, vb);
+                if (eb + 64u * PVS_U <= nnz_cap) kvq_sparse_load_batch<false, PVS_U>(v_idx, v_val, eb, e_end, lane, chv, vb);
+                else kvq_sparse_load_batch<true, PVS_U>(v_idx, v_val, eb, e_end, lane, chv, vb);
             }
 #pragma unroll
             for (int u = 0; u < PVS_U; ++u) {
                 const uint32_t first = eb + 64u * u, e = first + (uint32_t)lane;
                 if (first >= e_end) break;
-                const int t = sparse_token(pw, tc, tcur, first, e);
+                const int t = kvq_sparse_token(pw, tc, tcur, first, e);
                 if (e < e_end) {
                     const uint32_t ch = chv[u];
                     const float v = kvq_h2f((uint16_t)vb[u]);

@@ -1,6 +1,6 @@
 // Attention scores against the quantized, pre-RoPE Key cache (paper Sec. 3.2, 3.7, App. "RoPE
 // Equation", App. "Kernel Implementation Details"): dense look-up-table mat-vec with the rotary
-// embedding applied after de-quantisation, plus the sparse outlier mat-vec, merged in one kernel.
+// embedding applied after de-quantisation, plus the sparse outlier mat-vec, merged in one call.
 //
 // Design (gfx950).  RoPE rotates channel i with channel i+64, so for one (token n, query head) the
 // contribution of that channel pair is   A cos(n theta_i) + B sin(n theta_i)   with
@@ -9,15 +9,19 @@
 // side in one 2b-bit field.  Each workgroup therefore builds, per query head and channel pair, a
 // table of (A,B) for every code pair in LDS (fp32 pairs, query, scale and zero-point folded in), and
 // the hot loop per (token, head, pair) is: extract a field, one 8-byte LDS gather, two fp32 FMAs
-// with the cos/sin of the token's angle.  (fp16 table entries would halve the LDS footprint, but their
-// 2^-11 relative rounding leaves the scores only just inside a 1e-3 tolerance.)  cos/sin are computed once per (token, pair) and
-// shared by all query heads the workgroup handles.  Lanes are tokens; a wavefront reads 1 KiB of
-// contiguous codes per load instruction, and the 16-byte pieces of the next token tile are requested
-// as soon as the current tile no longer needs the registers they land in, so HBM latency hides
-// behind the table look-ups.  The sparse outliers are handled by a second, balanced kernel (lanes =
-// outlier entries) launched right behind the dense one in the same call; it adds its per-(head,
-// token) sums to the dense scores, so one call yields one merged result.  For 4-bit codes the joint table would be 256 entries, so
-// A and B are split into a part indexed by each code (two 16-entry gathers).
+// with the cos/sin of the token's angle.  (fp16 table entries would halve the LDS footprint, but
+// their 2^-11 relative rounding leaves the scores only just inside a 1e-3 tolerance.)  cos/sin are
+// computed once per (token, pair) and shared by all query heads the workgroup handles.  Lanes are
+// tokens; a wavefront reads 1 KiB of contiguous codes per load instruction, and the 16-byte pieces
+// of the next token tile are requested as soon as the current tile no longer needs the registers
+// they land in, so HBM latency hides behind the table look-ups.  For 4-bit codes the joint table
+// would have 256 entries, so A and B are split into a part indexed by each code (two 16-entry
+// gathers).
+//
+// The sparse outliers are handled by a second, balanced kernel (lanes = outlier entries) launched
+// in front of the dense one in the same call: it writes its per-(head, token) sums to the score
+// buffer and the dense kernel adds its own part, so one call yields one merged result.  Attention-
+// sink tokens (paper Sec. 3.5), if any, are scored last from their fp16 rows.
 #include <stdlib.h>
 #include <utility>
 #include "kvq_common.hpp"
@@ -347,52 +351,6 @@ __host__ __device__ constexpr int qs_wave_lds_bytes(int n_q_heads)
     return ((n_q_heads * QS_ROW * 8 + 15) & ~15) + 64 * 8;       // sums, per-pair angles
 }
 
-// One batch of index/value loads.  CLAMP = false: the whole batch lies inside the arrays (possibly
-// past the sub-range's end, where the loaded values are ignored), one address per lane plus
-// immediate offsets; CLAMP = true: lanes past the end re-read the last entry.
-template <bool CLAMP>
-__device__ __forceinline__ void sparse_load_batch(const uint16_t *__restrict__ idx, const uint16_t *__restrict__ val,
-                                                  uint32_t eb, uint32_t e_end, int lane, uint32_t (&chv)[QS_U],
-                                                  uint32_t (&vb)[QS_U])
-{
-    const char *ib = (const char *)idx, *vbp = (const char *)val;
-    if (!CLAMP) {
-        const uint32_t off0 = (eb + (uint32_t)lane) * 2u;
-#pragma unroll
-        for (int u = 0; u < QS_U; ++u) {
-            if (eb + 64u * u >= e_end) break;            // uniform: the rest of the batch is past the end
-            chv[u] = *(const uint16_t *)(ib + (size_t)off0 + 128 * u);
-            vb[u] = *(const uint16_t *)(vbp + (size_t)off0 + 128 * u);
-        }
-    } else {
-#pragma unroll
-        for (int u = 0; u < QS_U; ++u) {
-            if (eb + 64u * u >= e_end) break;
-            uint32_t e = eb + (uint32_t)lane + 64u * u;
-            e = (e < e_end) ? e : e_end - 1;
-            chv[u] = *(const uint16_t *)(ib + (size_t)(e * 2u));
-            vb[u] = *(const uint16_t *)(vbp + (size_t)(e * 2u));
-        }
-    }
-}
-
-// Token (relative to the sub-range) of entry `first + lane`.  `pw` holds the sub-range's pointers
-// (lane j: first entry of token j; lanes >= tc: the end), `tcur` is the wavefront's cursor: the token
-// that entry `first` belongs to once advanced.  Everything but the final compare-and-add is scalar.
-__device__ __forceinline__ int sparse_token(uint32_t pw, int tc, int &tcur, uint32_t first, uint32_t e)
-{
-    while (tcur + 1 < tc && (uint32_t)__builtin_amdgcn_readlane((int)pw, tcur + 1) <= first) ++tcur;
-    int t = tcur;
-    int j = tcur + 1;
-    while (j < tc) {
-        const uint32_t pj = (uint32_t)__builtin_amdgcn_readlane((int)pw, j);
-        if (pj > first + 63u) break;
-        t += (e >= pj) ? 1 : 0;
-        j = __builtin_amdgcn_readfirstlane(j + 1);
-    }
-    return t;
-}
-
 template <int R>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_t L,
@@ -407,7 +365,8 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
     float *qs = dyn;                                                     // [n_q_heads][128], scaled query
     char *mine = (char *)(dyn + n_q_heads * 128) + (size_t)wave * qs_wave_lds_bytes(n_q_heads);
     unsigned long long *S = (unsigned long long *)mine;                  // [n_q_heads][QS_ROW] 2^32-scaled sums
-    float2_t *ang = (float2_t *)(mine + ((n_q_heads * QS_ROW * 8 + 15) & ~15));   // [64] (angle at the sub-range start, theta/2pi)
+    // [64] (angle of the pair at the sub-range's first token, theta / 2 pi)
+    float2_t *ang = (float2_t *)(mine + ((n_q_heads * QS_ROW * 8 + 15) & ~15));
     const int64_t nb = ((int64_t)blockIdx.x * n_waves + wave) * tokens_per_wave;
     int64_t ne = nb + tokens_per_wave;
     if (ne > L) ne = L;
@@ -424,8 +383,7 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
     for (int j = tid; j < n_q_heads * 128; j += blockDim.x) qs[j] = q_rot[j] * scale;
     for (int j = lane; j < n_q_heads * QS_ROW; j += 64) S[j] = 0ull;
     const float my_vh = pv.hdr->rope_vh[lane], my_vl = pv.hdr->rope_vl[lane];
-    bool staged = false, have_next = false;
-    uint32_t chn[QS_U], vbn[QS_U];
+    bool staged = false;
     while (tc > 0) {
         const int64_t nc_next = nc + tc;
         const int tc_next = (int)((ne - nc_next < sub_len) ? (ne - nc_next) : sub_len);
@@ -433,19 +391,11 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
         const uint32_t e_end = (uint32_t)__builtin_amdgcn_readlane((int)pw, 63);
         uint32_t chv[QS_U], vb[QS_U];
         if (e_begin < e_end) {
-            if (have_next) {                             // requested during the previous sub-range
-#pragma unroll
-                for (int u = 0; u < QS_U; ++u) { chv[u] = chn[u]; vb[u] = vbn[u]; }
-            } else if (e_begin + 64u * QS_U <= nnz_cap) {
-                sparse_load_batch<false>(k_idx, k_val, e_begin, e_end, lane, chv, vb);
-            } else {
-                sparse_load_batch<true>(k_idx, k_val, e_begin, e_end, lane, chv, vb);
-            }
+            if (e_begin + 64u * QS_U <= nnz_cap)
+                kvq_sparse_load_batch<false, QS_U>(k_idx, k_val, e_begin, e_end, lane, chv, vb);
+            else
+                kvq_sparse_load_batch<true, QS_U>(k_idx, k_val, e_begin, e_end, lane, chv, vb);
         }
-        // the next sub-range's entries follow this one's: request its first batch now (its end is not
-        // known yet, so the whole batch is requested, which must then lie inside the arrays)
-        have_next = tc_next > 0 && e_end + 64u * QS_U <= nnz_cap;
-        if (have_next) sparse_load_batch<false>(k_idx, k_val, e_end, 0xFFFFFFFFu, lane, chn, vbn);
         uint32_t pw_next = 0;
         if (tc_next > 0) pw_next = k_ptr[nc_next + (lane < tc_next ? lane : tc_next)];
         ang[lane] = float2_t{rope_rev((float)nc, my_vh, my_vl), my_vh};
@@ -458,14 +408,16 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
         int tcur = 0;
         for (uint32_t eb = e_begin; eb < e_end; eb += 64 * QS_U) {
             if (eb != e_begin) {                         // (the first batch was requested above)
-                if (eb + 64u * QS_U <= nnz_cap) sparse_load_batch<false>(k_idx, k_val, eb, e_end, lane, chv, vb);
-                else sparse_load_batch<true>(k_idx, k_val, eb, e_end, lane, chv, vb);
+                if (eb + 64u * QS_U <= nnz_cap)
+                    kvq_sparse_load_batch<false, QS_U>(k_idx, k_val, eb, e_end, lane, chv, vb);
+                else
+                    kvq_sparse_load_batch<true, QS_U>(k_idx, k_val, eb, e_end, lane, chv, vb);
             }
 #pragma unroll
             for (int u = 0; u < QS_U; ++u) {
                 const uint32_t first = eb + 64u * u, e = first + (uint32_t)lane;
                 if (first >= e_end) break;
-                const int t = sparse_token(pw, tc, tcur, first, e);
+                const int t = kvq_sparse_token(pw, tc, tcur, first, e);
                 if (e < e_end) {
                     const uint32_t ch = chv[u];
                     const float v = kvq_h2f((uint16_t)vb[u]);
@@ -474,7 +426,8 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
                     const float cs = __builtin_amdgcn_cosf(rev);
                     // (R_n^T q)_c = q_c cos + s q_{c^64} sin with s = +1 for the lower channel of the
                     // pair and -1 for the upper: fold s into the sine
-                    const float sn = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, __builtin_amdgcn_sinf(rev)) ^ ((ch & 64u) << 25));
+                    const float sn = __builtin_bit_cast(
+                        float, __builtin_bit_cast(uint32_t, __builtin_amdgcn_sinf(rev)) ^ ((ch & 64u) << 25));
                     const uint32_t cl = ch & 127u, kvh = ch >> 7;
 #pragma unroll
                     for (int r = 0; r < R; ++r) {
