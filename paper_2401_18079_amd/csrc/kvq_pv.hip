@@ -216,8 +216,9 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
 // its private LDS slice, finds each entry's token by a binary search over the pointers and adds
 // p[q][n] * val to the workgroup's fixed-point LDS accumulators (integer atomics).  The workgroup's
 // sums go to the workspace; the reduce kernel adds them up.
-// R = query heads per KV head (0: any ratio, looked up at run time)
-template <int R>
+// R = query heads per KV head (0: any ratio, looked up at run time); SINK: the cache keeps its first
+// n_sink tokens in fp16 (a separate instantiation: the plain one has no register to spare)
+template <int R, bool SINK>
 __global__ __launch_bounds__(768) __attribute__((amdgpu_waves_per_eu(6, 6)))
 void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__restrict__ v_ptr,
                    const uint16_t *__restrict__ v_idx, const uint16_t *__restrict__ v_val, uint32_t nnz_cap,
@@ -249,13 +250,14 @@ void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__r
         const int tc_next = (int)((ne - nc_next < sub_len) ? (ne - nc_next) : sub_len);
         // probabilities: cell j = (query head j / 16, token j % 16); loads are straight-line (cells
         // outside the sub-range re-read its first probability and store zero)
+        const int t_sink = (SINK && nc < n_sink) ? (int)(n_sink - nc) : 0;    // tokens of this sub-range kept in fp16
         float pr[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int j = lane + 64 * k, qh = j / PVS_TW, t = j % PVS_TW;
             const bool ok = j < n_cells && t < tc;
             const float x = probs[ok ? (int64_t)qh * ld + nc + t : nc];
-            pr[k] = (ok && nc + t >= n_sink) ? x : 0.f;          // sink tokens: weight 0 (kept in fp16)
+            pr[k] = (ok && (!SINK || t >= t_sink)) ? x : 0.f;    // sink tokens: weight 0 (kept in fp16)
         }
         const uint32_t e_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)pw);
         const uint32_t e_end = (uint32_t)__builtin_amdgcn_readlane((int)pw, 63);
@@ -273,7 +275,8 @@ void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__r
         }
         for (int j0 = 64 * 8; j0 < n_cells; j0 += 64) {      // models with more than 32 query heads
             const int j = j0 + lane, qh = j / PVS_TW, t = j % PVS_TW;
-            if (j < n_cells) ps[qh * PVS_ROW + t] = (t < tc && nc + t >= n_sink) ? probs[(int64_t)qh * ld + nc + t] : 0.f;
+            if (j < n_cells)
+                ps[qh * PVS_ROW + t] = (t < tc && (!SINK || t >= t_sink)) ? probs[(int64_t)qh * ld + nc + t] : 0.f;
         }
         if (!cleared) {
             __syncthreads();
@@ -406,11 +409,18 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
     float *spartial = zpart + (int64_t)512 * Hq;
     if (L > 0) {
         const int r = Hq / cache->n_kv_heads;
-        auto sparse = (r == 1) ? kvq_pv_sparse<1> : (r == 2) ? kvq_pv_sparse<2> : (r == 4) ? kvq_pv_sparse<4>
-                    : (r == 8) ? kvq_pv_sparse<8> : kvq_pv_sparse<0>;
+        const bool sink = cache->n_sink > 0;
+        const int ri = (r == 1) ? 1 : (r == 2) ? 2 : (r == 4) ? 3 : (r == 8) ? 4 : 0;
+        using SparseKernel = decltype(&kvq_pv_sparse<0, false>);
+        static const SparseKernel kernels[5][2] = {{kvq_pv_sparse<0, false>, kvq_pv_sparse<0, true>},
+                                                   {kvq_pv_sparse<1, false>, kvq_pv_sparse<1, true>},
+                                                   {kvq_pv_sparse<2, false>, kvq_pv_sparse<2, true>},
+                                                   {kvq_pv_sparse<4, false>, kvq_pv_sparse<4, true>},
+                                                   {kvq_pv_sparse<8, false>, kvq_pv_sparse<8, true>}};
+        const SparseKernel sparse = kernels[ri][sink];
         // one dynamic-LDS limit per instantiation, raised on demand
-        static size_t lds_attr[5] = {0, 0, 0, 0, 0};
-        size_t &attr = lds_attr[(r == 1) ? 1 : (r == 2) ? 2 : (r == 4) ? 3 : (r == 8) ? 4 : 0];
+        static size_t lds_attr[5][2] = {};
+        size_t &attr = lds_attr[ri][sink];
         if (plan.slds > attr) {
             KVQ_HIP_CHECK(hipFuncSetAttribute((const void *)sparse, hipFuncAttributeMaxDynamicSharedMemorySize,
                                               (int)plan.slds));

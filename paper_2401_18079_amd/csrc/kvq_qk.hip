@@ -383,7 +383,8 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
     for (int j = tid; j < n_q_heads * 128; j += blockDim.x) qs[j] = q_rot[j] * scale;
     for (int j = lane; j < n_q_heads * QS_ROW; j += 64) S[j] = 0ull;
     const float my_vh = pv.hdr->rope_vh[lane], my_vl = pv.hdr->rope_vl[lane];
-    bool staged = false;
+    bool staged = false, have_next = false;
+    uint32_t chn[QS_U], vbn[QS_U];
     while (tc > 0) {
         const int64_t nc_next = nc + tc;
         const int tc_next = (int)((ne - nc_next < sub_len) ? (ne - nc_next) : sub_len);
@@ -391,11 +392,19 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
         const uint32_t e_end = (uint32_t)__builtin_amdgcn_readlane((int)pw, 63);
         uint32_t chv[QS_U], vb[QS_U];
         if (e_begin < e_end) {
-            if (e_begin + 64u * QS_U <= nnz_cap)
+            if (have_next) {                             // requested during the previous sub-range
+#pragma unroll
+                for (int u = 0; u < QS_U; ++u) { chv[u] = chn[u]; vb[u] = vbn[u]; }
+            } else if (e_begin + 64u * QS_U <= nnz_cap) {
                 kvq_sparse_load_batch<false, QS_U>(k_idx, k_val, e_begin, e_end, lane, chv, vb);
-            else
+            } else {
                 kvq_sparse_load_batch<true, QS_U>(k_idx, k_val, e_begin, e_end, lane, chv, vb);
+            }
         }
+        // the next sub-range's entries follow this one's: request its first batch now (its end is not
+        // known yet, so the whole batch is requested, which must then lie inside the arrays)
+        have_next = tc_next > 0 && e_end + 64u * QS_U <= nnz_cap;
+        if (have_next) kvq_sparse_load_batch<false, QS_U>(k_idx, k_val, e_end, 0xFFFFFFFFu, lane, chn, vbn);
         uint32_t pw_next = 0;
         if (tc_next > 0) pw_next = k_ptr[nc_next + (lane < tc_next ? lane : tc_next)];
         ang[lane] = float2_t{rope_rev((float)nc, my_vh, my_vl), my_vh};
