@@ -43,8 +43,8 @@ __global__ __launch_bounds__(NT) void kvq_k_count(const void *params, int D, con
     const int t = blockIdx.x;
     uint32_t mine = 0;
     for (int c = threadIdx.x; c < D; c += NT) {
-        float x = kvq_h2f(k_new[(int64_t)t * D + c]);
-        mine += (x < pv.lo[c] || x > pv.hi[c]) ? 1u : 0u;
+        const float x = kvq_h2f(k_new[(int64_t)t * D + c]), lo = pv.lo[c], hi = pv.hi[c];
+        mine += ((x < lo) | (x > hi)) ? 1u : 0u;
     }
     for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mine;
@@ -167,18 +167,27 @@ __global__ __launch_bounds__(NT) void kvq_k_quant(const void *__restrict__ param
     for (int cb = 0; cb < D; cb += NT * IT) {
         bool is_out[IT];
         uint16_t resid[IT];
+        // every load of the pass first (no short-circuit evaluation below: a conditional load would
+        // wait for the ones before it), then the arithmetic
+        uint16_t xb[IT];
+        float zc[IT], sc[IT], ri[IT], lo[IT], hi[IT];
 #pragma unroll
         for (int j = 0; j < IT; ++j) {
             const int c = cb + j * NT + tid;
             const int cc = (c < D) ? c : D - 1;                      // clamped: straight-line loads
-            const float x = kvq_h2f(k_new[(int64_t)t * D + cc]);
-            const float z = pv.z[cc], sc = pv.s[cc];
-            const float diff = x - z;
-            const float xn = diff * pv.rinv[cc];
+            xb[j] = k_new[(int64_t)t * D + cc];
+            zc[j] = pv.z[cc]; sc[j] = pv.s[cc]; ri[j] = pv.rinv[cc]; lo[j] = pv.lo[cc]; hi[j] = pv.hi[cc];
+        }
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int c = cb + j * NT + tid;
+            const float x = kvq_h2f(xb[j]);
+            const float diff = x - zc[j];
+            const float xn = diff * ri[j];
             float sp;
             const int code = kvq_nearest<NE>(lut, xn, sp);
-            const float deq = __builtin_fmaf(sc, sp, z);
-            is_out[j] = (c < D) && ((x < pv.lo[cc]) || (x > pv.hi[cc]));
+            const float deq = __builtin_fmaf(sc[j], sp, zc[j]);
+            is_out[j] = (c < D) & ((x < lo[j]) | (x > hi[j]));
             resid[j] = kvq_f2h_rn(x - deq);
             codes_s[j][tid] = (uint8_t)code;
         }
@@ -525,12 +534,12 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *__restrict__ param
                 const int ch0 = c0 + q * 64;
                 const int64_t off = kvq_v_piece0(BITS, cap, n >> 1, ch0 / KVQ_HEAD_DIM, (ch0 >> 6) & 1) + (wd >> 2) * 1024 + (wd & 3) * 4;
                 uint32_t *p = (uint32_t *)(v_codes + off);
-                const uint32_t m = mask_s[j][q][wd], b = bits_s[j][q][wd];
-                uint32_t old = *p, assumed;
-                do {                               // the partner token of the pair may be written concurrently
-                    assumed = old;
-                    old = atomicCAS(p, assumed, (assumed & ~m) | b);
-                } while (old != assumed);
+                // The partner token of the pair owns the other bits of this dword and may be written
+                // concurrently by another workgroup: clear this token's bits, then set them, with two
+                // atomics that return nothing (no round trip; the same thread's atomics on one address
+                // are applied in order, and the partner's touch disjoint bits).
+                __hip_atomic_fetch_and(p, ~mask_s[j][q][wd], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_or(p, bits_s[j][q][wd], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         if (cb + NT * IT < D) __syncthreads();     // the next pass reuses the shared arrays
