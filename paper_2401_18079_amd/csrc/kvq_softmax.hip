@@ -29,6 +29,43 @@ __device__ inline void block_max_sum(float &m, float &s, float *sh_m, float *sh_
     __syncthreads();
 }
 
+// The SM_CHUNK elements a workgroup owns, SM_CHUNK / SM_NT per thread, read once into registers.
+// VEC: rows are 16-byte aligned, so a thread takes groups of four consecutive elements with one
+// 16-byte load each; otherwise element by element.  Elements past `n` read as `pad`.
+template <bool VEC>
+__device__ __forceinline__ void load_chunk(const float *__restrict__ xr, int64_t b, int64_t n, float pad,
+                                           float (&v)[SM_CHUNK / SM_NT])
+{
+    constexpr int PER = SM_CHUNK / SM_NT;
+    if (VEC) {
+#pragma unroll
+        for (int k = 0; k < PER / 4; ++k) {
+            const int64_t i = b + ((int64_t)k * SM_NT + threadIdx.x) * 4;
+            if (i + 3 < n) {
+                const float4 q = *(const float4 *)(xr + i);
+                v[4 * k + 0] = q.x; v[4 * k + 1] = q.y; v[4 * k + 2] = q.z; v[4 * k + 3] = q.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[4 * k + j] = (i + j < n) ? xr[i + j] : pad;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int64_t i = b + threadIdx.x + (int64_t)k * SM_NT;
+            v[k] = (i < n) ? xr[i] : pad;
+        }
+    }
+}
+
+// index of register element k of load_chunk
+template <bool VEC>
+__device__ __forceinline__ int64_t chunk_index(int64_t b, int k)
+{
+    return VEC ? b + ((int64_t)(k / 4) * SM_NT + threadIdx.x) * 4 + (k & 3) : b + threadIdx.x + (int64_t)k * SM_NT;
+}
+
+template <bool VEC>
 __global__ __launch_bounds__(SM_NT) void kvq_softmax_partial(const float *__restrict__ x, int64_t ld, int64_t n,
                                                              float2_t *__restrict__ ws, int chunks)
 {
@@ -38,11 +75,7 @@ __global__ __launch_bounds__(SM_NT) void kvq_softmax_partial(const float *__rest
     const int64_t b = (int64_t)chunk * SM_CHUNK;
     constexpr int PER = SM_CHUNK / SM_NT;          // elements per thread, read once and kept in registers
     float v[PER];
-#pragma unroll
-    for (int k = 0; k < PER; ++k) {
-        const int64_t i = b + threadIdx.x + (int64_t)k * SM_NT;
-        v[k] = (i < n) ? xr[i] : -INFINITY;
-    }
+    load_chunk<VEC>(xr, b, n, -INFINITY, v);
     float m = -INFINITY;
 #pragma unroll
     for (int k = 0; k < PER; ++k) m = fmaxf(m, v[k]);
@@ -55,6 +88,7 @@ __global__ __launch_bounds__(SM_NT) void kvq_softmax_partial(const float *__rest
     if (threadIdx.x == 0) ws[(int64_t)row * chunks + chunk] = float2_t{m, s};
 }
 
+template <bool VEC>
 __global__ __launch_bounds__(SM_NT) void kvq_softmax_finish(const float *__restrict__ x, int64_t ld_x,
                                                             float *__restrict__ y, int64_t ld_y, int64_t n,
                                                             const float2_t *__restrict__ ws, int chunks)
@@ -78,15 +112,29 @@ __global__ __launch_bounds__(SM_NT) void kvq_softmax_finish(const float *__restr
     const int64_t b = (int64_t)chunk * SM_CHUNK;
     constexpr int PER = SM_CHUNK / SM_NT;
     float v[PER];
+    load_chunk<VEC>(xr, b, n, 0.f, v);
+    if (VEC) {
 #pragma unroll
-    for (int k = 0; k < PER; ++k) {
-        const int64_t i = b + threadIdx.x + (int64_t)k * SM_NT;
-        v[k] = (i < n) ? xr[i] : 0.f;
-    }
+        for (int k = 0; k < PER / 4; ++k) {
+            const int64_t i = chunk_index<VEC>(b, 4 * k);
+            float4 q;
+            q.x = __expf(v[4 * k + 0] - m) * inv; q.y = __expf(v[4 * k + 1] - m) * inv;
+            q.z = __expf(v[4 * k + 2] - m) * inv; q.w = __expf(v[4 * k + 3] - m) * inv;
+            if (i + 3 < n) {
+                *(float4 *)(yr + i) = q;
+            } else {
+                const float e[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-    for (int k = 0; k < PER; ++k) {
-        const int64_t i = b + threadIdx.x + (int64_t)k * SM_NT;
-        if (i < n) yr[i] = __expf(v[k] - m) * inv;
+                for (int j = 0; j < 4; ++j)
+                    if (i + j < n) yr[i + j] = e[j];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int64_t i = chunk_index<VEC>(b, k);
+            if (i < n) yr[i] = __expf(v[k] - m) * inv;
+        }
     }
 }
 
@@ -108,8 +156,17 @@ extern "C" kvq_status kvq_softmax_f32(const float *d_x, int64_t ld_x, float *d_p
     const int chunks = (int)((n_cols + SM_CHUNK - 1) / SM_CHUNK);
     hipStream_t s = (hipStream_t)stream;
     dim3 grid((unsigned)chunks, (unsigned)n_rows);
-    kvq_softmax_partial<<<grid, SM_NT, 0, s>>>(d_x, ld_x, n_cols, (float2_t *)d_workspace, chunks);
-    kvq_softmax_finish<<<grid, SM_NT, 0, s>>>(d_x, ld_x, d_probs, ld_probs, n_cols, (const float2_t *)d_workspace, chunks);
+    // 16-byte loads and stores when every row of both matrices starts on a 16-byte boundary
+    const bool vec = !(((uintptr_t)d_x | (uintptr_t)d_probs) & 15) && !((ld_x | ld_probs) & 3);
+    if (vec) {
+        kvq_softmax_partial<true><<<grid, SM_NT, 0, s>>>(d_x, ld_x, n_cols, (float2_t *)d_workspace, chunks);
+        kvq_softmax_finish<true><<<grid, SM_NT, 0, s>>>(d_x, ld_x, d_probs, ld_probs, n_cols,
+                                                        (const float2_t *)d_workspace, chunks);
+    } else {
+        kvq_softmax_partial<false><<<grid, SM_NT, 0, s>>>(d_x, ld_x, n_cols, (float2_t *)d_workspace, chunks);
+        kvq_softmax_finish<false><<<grid, SM_NT, 0, s>>>(d_x, ld_x, d_probs, ld_probs, n_cols,
+                                                         (const float2_t *)d_workspace, chunks);
+    }
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }
