@@ -104,13 +104,16 @@ __device__ __forceinline__ void pv_group(const uint32_t (&W)[4 * BITS], float (&
         const uint32_t off = pv_field_off<2 * BITS>(W, G0 * PV_FIELD_GROUP + k, lane_off);
         t[k] = *(const half2_t *)((const uint8_t *)ptab + off);
     }
+    // the two FMAs of a field depend on each other: issue the group's first halves, then its second
+    // halves, so that no instruction waits for the one right before it
 #pragma unroll
-    for (int k = 0; k < PV_FIELD_GROUP; ++k) {
-        float a = acc[G0 * PV_FIELD_GROUP + k];
-        a = __builtin_fmaf((float)t[k].x, w0, a);
-        a = __builtin_fmaf((float)t[k].y, w1, a);
-        acc[G0 * PV_FIELD_GROUP + k] = a;
-    }
+    for (int k = 0; k < PV_FIELD_GROUP; ++k)
+        acc[G0 * PV_FIELD_GROUP + k] = __builtin_fmaf((float)t[k].x, w0, acc[G0 * PV_FIELD_GROUP + k]);
+#pragma unroll
+    for (int k = 0; k < PV_FIELD_GROUP; ++k) asm volatile("" : "+v"(acc[G0 * PV_FIELD_GROUP + k]));
+#pragma unroll
+    for (int k = 0; k < PV_FIELD_GROUP; ++k)
+        acc[G0 * PV_FIELD_GROUP + k] = __builtin_fmaf((float)t[k].y, w1, acc[G0 * PV_FIELD_GROUP + k]);
     // an empty asm that "modifies" the group's accumulators and clobbers memory keeps the groups in
     // order (otherwise every gather of the tile is issued first and register pressure explodes)
 #pragma unroll
