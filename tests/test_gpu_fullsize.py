@@ -124,3 +124,80 @@ def test_c2_full_context_sampled_parity():
     oa, ob, oab = (torch.zeros((wl.n_q_heads, 128), device="cuda") for _ in range(3))
     K.kvq_pv_matvec(gc, pa, oa); K.kvq_pv_matvec(gc, pb, ob); K.kvq_pv_matvec(gc, pa + pb, oab)
     assert torch.allclose(oab, oa + ob, rtol=1e-4, atol=1e-6)
+
+
+def test_c3_million_token_context_sampled_parity():
+    """Configuration 3 at its full size (context 1,048,576 + a ragged tail, nuq4, 0.1 % outliers): every
+    wavefront of the sparse kernels walks many sub-ranges here and positions reach 2^20, where the
+    rotary angle needs its two-float reduction.  The reference is evaluated only on the sampled windows
+    (the oracle's reconstruction and rotation, token by token), so the test stays within seconds."""
+    import torch
+    import paper_2401_18079_amd as K
+    import bench
+
+    Lc = (1 << 20) + 77
+    wl = S.workload("c3")
+    st = Setup(wl)
+    cap = ((Lc + 127) // 128) * 128
+    gc, dg, _, _ = bench.build_cache(st, Lc, cap, K, torch)
+    assert gc.status() == 0 and gc.n_tokens_k == Lc and gc.n_tokens_v == Lc
+
+    H, Hq, D, bits = wl.n_kv_heads, wl.n_q_heads, wl.D, wl.bits
+    rng = np.random.default_rng(wl.seed + 3)
+    starts = sorted(set([0, (Lc // WIN) * WIN, (1 << 20) - WIN] + [int(x) * WIN for x in rng.integers(1, Lc // WIN, 5)]))
+    gkp = gc.k_ptr.cpu().numpy().view(np.uint32); gvp = gc.v_ptr.cpu().numpy().view(np.uint32)
+    gsz = gc.v_sz.cpu().numpy().view(np.uint16).reshape(cap, 2)
+    q = S.gen_q(wl, 0, 0)
+    scale = np.float32(1.0 / np.sqrt(128.0))
+    scores = torch.zeros((Hq, cap), device="cuda")
+    K.kvq_qk_matvec(gc, torch.from_numpy(q).cuda(), float(scale), scores)
+    sampled, ref_cols, vhat_rows = [], [], []
+    gk, gv = gc.k_codes.cpu().numpy(), gc.v_codes.cpu().numpy()
+    for t0 in starts:
+        T = min(WIN, Lc - t0)
+        # a small oracle cache that holds just this window, at capacity 128, for quantization ...
+        kc, kcnt, kidx, kval = O.quantize_k(st.k(t0, T), bits, st.lut_k, st.s, st.z, st.lo, st.hi)
+        sz, vc, vcnt, vidx, vval = O.quantize_v(st.v(t0, T), bits, st.lut_v, st.k_side)
+        # ... compared bit for bit with what the device stored at the true positions
+        a = np.zeros((T, D), np.uint8)
+        O._unpack_k(gk, bits, H, cap, t0, T, a)
+        assert np.array_equal(a, kc), ("k codes", t0)
+        O._unpack_v(gv, bits, H, cap, t0, T, a)
+        assert np.array_equal(a, vc), ("v codes", t0)
+        assert np.array_equal(gsz[t0:t0 + T], sz)
+        assert np.array_equal(np.diff(gkp[t0:t0 + T + 1].astype(np.int64)), kcnt)
+        assert np.array_equal(np.diff(gvp[t0:t0 + T + 1].astype(np.int64)), vcnt)
+        assert np.array_equal(gc.k_idx[int(gkp[t0]):int(gkp[t0 + T])].cpu().numpy().view(np.uint16), kidx)
+        assert np.array_equal(gc.k_val[int(gkp[t0]):int(gkp[t0 + T])].cpu().numpy().view(np.uint16), kval)
+        assert np.array_equal(gc.v_idx[int(gvp[t0]):int(gvp[t0 + T])].cpu().numpy().view(np.uint16), vidx)
+        assert np.array_equal(gc.v_val[int(gvp[t0]):int(gvp[t0 + T])].cpu().numpy().view(np.uint16), vval)
+        # reference scores of the window: the oracle's reconstruction and rotation at the true positions
+        win = O.OracleCache(bits, H, Hq, 128, st.k_side, wl.rope_base, st.lut_k, st.lut_v, st.s, st.z, st.lo, st.hi)
+        win.append_k(st.k(t0, T)); win.append_v(st.v(t0, T))
+        khat, vhat = win.reconstruct_k(0, T), win.reconstruct_v(0, T)
+        g = Hq // H
+        col = np.zeros((Hq, T))
+        for t in range(T):
+            for hk in range(H):
+                krot = O.rope(khat[t, hk * 128:(hk + 1) * 128], t0 + t, wl.rope_base)
+                for j in range(g):
+                    col[hk * g + j, t] = float(scale) * np.dot(q[hk * g + j].astype(np.float64), krot)
+        sampled += list(range(t0, t0 + T)); ref_cols.append(col); vhat_rows.append(vhat)
+    sampled = np.array(sampled)
+    ref = np.concatenate(ref_cols, axis=1)
+    got = scores.cpu().numpy()[:, sampled]
+    # the row RMS of the bound is taken over the sampled columns only
+    ok, worst = matvec_close(got, ref.astype(np.float32))
+    assert ok, f"scores: worst error / bound = {worst:.3f}"
+
+    # Value mat-vec with probabilities supported on the sampled tokens
+    vhat = np.concatenate(vhat_rows, axis=0)                       # [n_sampled][D]
+    psub = O.softmax(np.ascontiguousarray(ref.astype(np.float32)))
+    g = Hq // H
+    ref_out = np.stack([psub[h].astype(np.float64) @ vhat[:, (h // g) * 128:(h // g + 1) * 128] for h in range(Hq)])
+    pfull = torch.zeros((Hq, cap), device="cuda")
+    pfull[:, torch.from_numpy(sampled).cuda()] = torch.from_numpy(psub).cuda()
+    out = torch.zeros((Hq, 128), device="cuda")
+    K.kvq_pv_matvec(gc, pfull, out)
+    ok, worst = matvec_close(out.cpu().numpy(), ref_out.astype(np.float32))
+    assert ok, f"outputs: worst error / bound = {worst:.3f}"
