@@ -332,7 +332,7 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
 
 // Sparse Key outliers, balanced (paper App. "Kernel Implementation Details": equal non-zeros per
 // thread): lanes are outlier entries.  Every wavefront works on its own: it owns a run of consecutive
-// tokens and walks it QS_TW tokens at a time.  A sub-range's pointers sit in one register (lane j:
+// tokens and walks it TW tokens at a time (8, or 32 when outliers are few: see launch_qk_sparse).  A sub-range's pointers sit in one register (lane j:
 // token j), so the token of an entry is a wavefront-uniform cursor plus the number of token starts
 // among the 64 entries of the batch, found with scalar reads of that register.  The query is
 // rotated instead of the Key (by linearity  <q, R_n (v e_c)> = v (R_n^T q)_c ) and
@@ -340,30 +340,30 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
 // (fixed-point integer atomics: LDS floating-point atomics are an order of magnitude slower here),
 // which is then written to the score buffer; the dense kernel, launched afterwards, adds its part.
 // The only workgroup-wide barrier follows the staging of the scaled query.
-constexpr int QS_TW = 8;              // tokens per sub-range
-// row length of the LDS tile: one token's outliers hit the same column of many rows, and an odd row
-// length spreads that column over all LDS banks
-constexpr int QS_ROW = QS_TW + 1;
+// Row length of the LDS tile for sub-ranges of TW tokens: one token's outliers hit the same column of
+// many rows, and an odd row length spreads that column over all LDS banks.
+__host__ __device__ constexpr int qs_row(int tw) { return tw + 1; }
 constexpr int QS_U = 6;               // 64-entry batches in flight per wavefront
 
-__host__ __device__ constexpr int qs_wave_lds_bytes(int n_q_heads)
+__host__ __device__ constexpr int qs_wave_lds_bytes(int n_q_heads, int tw)
 {
-    return ((n_q_heads * QS_ROW * 8 + 15) & ~15) + 64 * 8;       // sums, per-pair angles
+    return ((n_q_heads * qs_row(tw) * 8 + 15) & ~15) + 64 * 8;   // sums, per-pair angles
 }
 
-template <int R>
+template <int R, int QS_TW>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_t L,
                    const uint32_t *__restrict__ k_ptr, const uint16_t *__restrict__ k_idx,
                    const uint16_t *__restrict__ k_val, uint32_t nnz_cap, const float *__restrict__ q_rot,
                    float scale, float *__restrict__ scores, int64_t ld, int64_t tokens_per_wave)
 {
+    constexpr int QS_ROW = qs_row(QS_TW);
     extern __shared__ __attribute__((aligned(16))) float dyn[];
     const KvqParamsView pv = kvq_params_view(params, D);
     const int tid = threadIdx.x, lane = tid & 63, n_waves = blockDim.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // scalar: loop bounds below are uniform
     float *qs = dyn;                                                     // [n_q_heads][128], scaled query
-    char *mine = (char *)(dyn + n_q_heads * 128) + (size_t)wave * qs_wave_lds_bytes(n_q_heads);
+    char *mine = (char *)(dyn + n_q_heads * 128) + (size_t)wave * qs_wave_lds_bytes(n_q_heads, QS_TW);
     unsigned long long *S = (unsigned long long *)mine;                  // [n_q_heads][QS_ROW] 2^32-scaled sums
     // [64] (angle of the pair at the sub-range's first token, theta / 2 pi)
     float2_t *ang = (float2_t *)(mine + ((n_q_heads * QS_ROW * 8 + 15) & ~15));
@@ -466,38 +466,53 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
     if (!staged) __syncthreads();        // a wavefront without tokens still meets the workgroup's barrier
 }
 
-template <int R>
-kvq_status launch_qk_sparse(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
+template <int R, int TW>
+kvq_status launch_qk_sparse_tw(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
 {
     const int Hq = c->n_q_heads;
     const int64_t L = c->n_tokens_k;
-    if (c->cap_nnz_k >= ((int64_t)1 << 31)) return KVQ_ERR_UNSUPPORTED;      // byte offsets are 32-bit
-    // LDS: the scaled query plus one private slice per wavefront; two workgroups of 12 wavefronts per
+    // LDS: the scaled query plus one private slice per wavefront; two workgroups of 16 wavefronts per
     // CU when they fit in 77 KiB each, fewer wavefronts otherwise
-    const int per_wave = qs_wave_lds_bytes(Hq);
+    const int per_wave = qs_wave_lds_bytes(Hq, TW);
     int waves = 16;
     while (waves > 1 && (size_t)Hq * 512 + (size_t)waves * per_wave > 78848) waves -= (waves > 4) ? 4 : waves / 2;
     if ((size_t)Hq * 512 + (size_t)waves * per_wave > 147456) return KVQ_ERR_UNSUPPORTED;
     const size_t lds = (size_t)Hq * 512 + (size_t)waves * per_wave;
     static size_t lds_attr = 0;      // per instantiation
     if (lds > lds_attr) {
-        KVQ_HIP_CHECK(hipFuncSetAttribute((const void *)kvq_qk_sparse<R>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                          (int)lds));
+        KVQ_HIP_CHECK(hipFuncSetAttribute((const void *)kvq_qk_sparse<R, TW>,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         lds_attr = lds;
     }
-    // as many wavefronts as the chip holds at once (256 CUs, 160 KiB of LDS and 24 wavefronts each),
-    // every one with the same number of tokens (a multiple of 8)
+    // as many wavefronts as the chip holds at once (256 CUs, 160 KiB of LDS and 32 wavefronts each),
+    // every one with the same number of tokens
     int wgs_per_cu = (int)(163840 / lds);
     if (wgs_per_cu * waves > 32) wgs_per_cu = 32 / waves;
     if (wgs_per_cu < 1) wgs_per_cu = 1;
     const int64_t resident = (int64_t)256 * wgs_per_cu * waves;
     int64_t tpw = (L + resident - 1) / resident;
+    if (TW > 8) tpw = (tpw + TW - 1) / TW * TW;          // whole sub-ranges: full cache lines of scores
     const int64_t n_waves = (L + tpw - 1) / tpw;
     const unsigned grid = (unsigned)((n_waves + waves - 1) / waves);
-    kvq_qk_sparse<R><<<grid, 64 * waves, lds, s>>>(c->params, c->n_kv_heads * KVQ_HEAD_DIM, Hq, L, c->k_ptr, c->k_idx,
-                                                   c->k_val, (uint32_t)c->cap_nnz_k, q, scale, scores, ld, tpw);
+    kvq_qk_sparse<R, TW><<<grid, 64 * waves, lds, s>>>(c->params, c->n_kv_heads * KVQ_HEAD_DIM, Hq, L, c->k_ptr,
+                                                       c->k_idx, c->k_val, (uint32_t)c->cap_nnz_k, q, scale, scores,
+                                                       ld, tpw);
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
+}
+
+template <int R>
+kvq_status launch_qk_sparse(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
+{
+    if (c->cap_nnz_k >= ((int64_t)1 << 31)) return KVQ_ERR_UNSUPPORTED;      // byte offsets are 32-bit
+    // Sub-ranges of 8 tokens keep a wavefront's tile small (many wavefronts per CU), which is what
+    // counts when every token brings tens of outliers.  With few outliers per token the cost is the
+    // tile itself (cleared, written out as scores, one piece per head and sub-range), and sub-ranges
+    // of 32 tokens (128-byte pieces: whole cache lines) are the better trade.  The array capacity per
+    // token is the host's only handle on the density: the entry count lives on the device.
+    const int64_t per_token = c->cap_nnz_k / (c->cap_tokens > 0 ? c->cap_tokens : 1);
+    if (per_token < 16 && c->n_q_heads <= 32) return launch_qk_sparse_tw<R, 32>(c, q, scale, scores, ld, s);
+    return launch_qk_sparse_tw<R, 8>(c, q, scale, scores, ld, s);
 }
 
 // Attention-sink tokens (paper Sec. 3.5): score of query head blockIdx.y against the fp16 Key of token
