@@ -4,7 +4,7 @@ A step is one pass of the whole path over the cached context: quantize-append th
 and Value, q.K^T against the quantized Keys (RoPE after de-quantisation, sparse outliers merged),
 softmax, p.V against the quantized Values.  Workload: LLaMA-7B attention layer shape (32 heads x 128),
 context 131072, batch 1, 3-bit NUQ with 1 % outliers, seeded synthetic activations.
-Prints one JSON line (see README for the fields).
+Prints one JSON line.
 """
 import argparse
 import json
@@ -16,7 +16,6 @@ import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0
 
@@ -25,7 +24,9 @@ def build_cache(st, L, cap, K, torch, keep_fp16=False):
     """Fill a GPU cache with L synthetic tokens generated on the device, in chunks of 4096."""
     from kvq_synth.device import DeviceGen
     dg = DeviceGen(st.wl, st.layer, st.kprof, st.vprof)
-    gc = st.gpu_cache(cap)
+    wl = st.wl
+    gc = K.KvqCache(wl.bits, wl.n_kv_heads, wl.n_q_heads, cap, st.k_side, wl.rope_base, st.cap_nnz_k(cap))
+    K.kvq_lut_load(gc, st.lut_k, st.lut_v, st.s, st.z, st.lo, st.hi)
     k16 = torch.empty((L, st.wl.D), dtype=torch.float16, device="cuda") if keep_fp16 else None
     v16 = torch.empty((L, st.wl.D), dtype=torch.float16, device="cuda") if keep_fp16 else None
     t0 = 0
@@ -54,7 +55,8 @@ def cpu_baseline(st, sample_tokens):
     from oracle import kvq_oracle as O
     wl = st.wl
     cap = ((sample_tokens + 127) // 128) * 128
-    oc = st.oracle_cache(cap)
+    oc = O.OracleCache(wl.bits, wl.n_kv_heads, wl.n_q_heads, cap, st.k_side, wl.rope_base, st.lut_k, st.lut_v,
+                       st.s, st.z, st.lo, st.hi, cap_nnz_k=st.cap_nnz_k(cap))
     t0 = 0
     tq = 0.0
     while t0 < sample_tokens:                       # cache construction is not timed, except one token
@@ -98,12 +100,11 @@ def main():
     import torch
     import kvq_synth as S
     import paper_2401_18079_amd as K
-    from kvq_testlib import Setup
 
     wl = S.workload(args.workload)
     if args.context:
         wl = S.workload(args.workload, context=args.context)
-    st = Setup(wl)
+    st = S.LayerInputs(wl)
     L = wl.context
     steps, warmup = args.steps, args.warmup
     bsteps = min(steps, 50)                        # extra steps timed call by call for the breakdown
@@ -251,7 +252,7 @@ def main():
             if ln.startswith("dense_kernel_traffic_bytes_per_launch:"):
                 traffic = float(ln.split(":")[1])
 
-    # instruction-issue side of the same kernel (it is bound by VALU issue): issue slots per
+    # instruction-issue side of the same kernel (VALU issue is what bounds it): issue slots per
     # launch from the rocprofv3 SQ_INSTS_VALU run of this command, kept under profiles/
     valu = None
     vpath = os.path.join(ROOT, "profiles", f"bench_{wl.name}_valu_issue.txt")

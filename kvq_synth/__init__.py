@@ -8,5 +8,5 @@ can both be fed from it without sharing any code with each other.
 from .gen import (  # noqa: F401
     SEED_BASE, Workload, WORKLOADS, workload, splitmix64, hash_grid, normalish,
     key_channel_profile, value_channel_profile, value_token_scale,
-    gen_k, gen_v, gen_q, gen_probs_logits, make_lut, calibrate_k, k_side_from_fraction,
+    gen_k, gen_v, gen_q, gen_probs_logits, make_lut, calibrate_k, k_side_from_fraction, LayerInputs,
 )

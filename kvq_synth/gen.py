@@ -218,3 +218,29 @@ def calibrate_k(w: Workload, layer: int = 0, n_cal: int = 4096, profile=None):
     s = ((inner_max - inner_min) * np.float32(0.5)).astype(np.float16)
     s = np.where(s.astype(np.float32) <= 0, np.float16(1.0), s)
     return s, z, lo.astype(np.float16), hi.astype(np.float16)
+
+
+class LayerInputs:
+    """Everything one synthetic attention layer feeds the method with: look-up tables, per-channel Key
+    calibration constants, the Value outlier count per side, and the token generators."""
+
+    def __init__(self, wl: Workload, layer=0):
+        self.wl = wl
+        self.bits = wl.bits
+        self.layer = layer
+        self.lut_k = make_lut(wl.bits, wl.seed, layer, 0)
+        self.lut_v = make_lut(wl.bits, wl.seed, layer, 1)
+        self.kprof = key_channel_profile(wl, layer)
+        self.vprof = value_channel_profile(wl, layer)
+        self.s, self.z, self.lo, self.hi = calibrate_k(wl, layer, profile=self.kprof)
+        self.k_side = k_side_from_fraction(wl.outlier_fraction, wl.D)
+
+    def cap_nnz_k(self, cap):
+        """Entries to provide for Key outliers in a cache of `cap` tokens (twice the expected count)."""
+        return int(max(1024, 2.0 * max(self.wl.outlier_fraction, 1e-4) * self.wl.D * cap))
+
+    def k(self, t0, T, seq=0):
+        return gen_k(self.wl, self.layer, seq, t0, T, profile=self.kprof)
+
+    def v(self, t0, T, seq=0):
+        return gen_v(self.wl, self.layer, seq, t0, T, profile=self.vprof)

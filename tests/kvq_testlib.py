@@ -20,28 +20,8 @@ def matvec_close(got, ref, rel=REL_TOL):
     return bool(np.all(err <= bound)), worst
 
 
-class Setup:
-    """Synthetic layer: look-up tables, Key calibration constants, outlier counts."""
-
-    def __init__(self, wl: S.Workload, layer=0):
-        self.wl = wl
-        self.bits = wl.bits
-        self.lut_k = S.make_lut(wl.bits, wl.seed, layer, 0)
-        self.lut_v = S.make_lut(wl.bits, wl.seed, layer, 1)
-        self.kprof = S.key_channel_profile(wl, layer)
-        self.vprof = S.value_channel_profile(wl, layer)
-        self.s, self.z, self.lo, self.hi = S.calibrate_k(wl, layer, profile=self.kprof)
-        self.k_side = S.k_side_from_fraction(wl.outlier_fraction, wl.D)
-        self.layer = layer
-
-    def cap_nnz_k(self, cap):
-        return int(max(1024, 2.0 * max(self.wl.outlier_fraction, 1e-4) * self.wl.D * cap))
-
-    def k(self, t0, T, seq=0):
-        return S.gen_k(self.wl, self.layer, seq, t0, T, profile=self.kprof)
-
-    def v(self, t0, T, seq=0):
-        return S.gen_v(self.wl, self.layer, seq, t0, T, profile=self.vprof)
+class Setup(S.LayerInputs):
+    """A synthetic layer's inputs plus the two caches under comparison."""
 
     def oracle_cache(self, cap):
         wl = self.wl
