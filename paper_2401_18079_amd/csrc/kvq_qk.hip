@@ -71,7 +71,7 @@ __device__ inline float rope_rev(float nf, float vh, float vl)
 // that a group's LDS gathers are all in flight before the arithmetic that consumes them:
 //   1. per KV head one field extraction per pair, per query head one gather,
 //   2. the group's angles -> (cos, sin), shared by all query heads,
-//   3. two mixed-precision FMAs per (pair, query head).
+//   3. two fp32 FMAs per (pair, query head) and table part.
 // G0 is a compile-time constant so that all register-array indices fold.
 template <int BITS, int KVH, int RQ, int PAIR_GROUP, int G0>
 __device__ __forceinline__ void qk_group(uint32_t (&W)[KVH][8], float (&acc)[KVH * RQ],
@@ -89,7 +89,6 @@ __device__ __forceinline__ void qk_group(uint32_t (&W)[KVH][8], float (&acc)[KVH
     float2_t t[PAIR_GROUP][QH][NG];
 #pragma unroll
     for (int p = 0; p < PAIR_GROUP; ++p) {
-        constexpr int dummy = 0; (void)dummy;
         const int I = G0 * PAIR_GROUP + p;
 #pragma unroll
         for (int g = 0; g < KVH; ++g) {
