@@ -456,7 +456,20 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *__restrict__ param
     const uint16_t *x16 = v_new + (int64_t)t * D;
     const uint32_t base = v_ptr[n0] + (uint32_t)t * 2u * (uint32_t)k_side;
 
-    for (int c = tid; c < D; c += NT) { keys[c] = (uint16_t)order_key(x16[c]); state[c] = 0; }
+    // The thread's first IT elements (channels tid, tid + NT, ...) stay in registers for the later
+    // passes; wider vectors re-read the rest from memory.
+    uint16_t xc[IT];
+#pragma unroll
+    for (int j = 0; j < IT; ++j) {
+        const int c = tid + j * NT;
+        xc[j] = x16[c < D ? c : D - 1];
+    }
+#pragma unroll
+    for (int j = 0; j < IT; ++j) {
+        const int c = tid + j * NT;
+        if (c < D) { keys[c] = (uint16_t)order_key(xc[j]); state[c] = 0; }
+    }
+    for (int c = tid + IT * NT; c < D; c += NT) { keys[c] = (uint16_t)order_key(x16[c]); state[c] = 0; }
     __syncthreads();
     if (k_side > 0) {
         if (!select_both<NT>(keys, state, D, k_side, hist, sh, wave_tot)) {
@@ -466,7 +479,12 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *__restrict__ param
     }
     // range of the remaining elements
     float mx = -INFINITY, mn = INFINITY;
-    for (int c = tid; c < D; c += NT)
+#pragma unroll
+    for (int j = 0; j < IT; ++j) {
+        const int c = tid + j * NT;
+        if (c < D && state[c] == 0) { float x = kvq_h2f(xc[j]); mx = fmaxf(mx, x); mn = fminf(mn, x); }
+    }
+    for (int c = tid + IT * NT; c < D; c += NT)
         if (state[c] == 0) { float x = kvq_h2f(x16[c]); mx = fmaxf(mx, x); mn = fminf(mn, x); }
     for (int o = 32; o > 0; o >>= 1) { mx = fmaxf(mx, __shfl_xor(mx, o)); mn = fminf(mn, __shfl_xor(mn, o)); }
     if ((tid & 63) == 0) { redmx[tid >> 6] = mx; redmn[tid >> 6] = mn; }
@@ -491,7 +509,7 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *__restrict__ param
         for (int j = 0; j < IT; ++j) {
             const int c = cb + j * NT + tid;
             const int cc = (c < D) ? c : D - 1;
-            const float x = kvq_h2f(x16[cc]);
+            const float x = kvq_h2f(cb == 0 ? xc[j] : x16[cc]);      // the first pass has its elements in registers
             const float diff = x - zf;
             const float xn = diff * rinv;
             float sp;
