@@ -352,15 +352,14 @@ __device__ inline void bins_above2(uint32_t mine_a, uint32_t mine_b, uint32_t *w
 // selected bins).  Because 2k < D the k-th largest key is >= the k-th smallest; when they differ the
 // two selections cannot interact and this routine is exact; when they coincide (heavy ties) it
 // leaves state[] untouched and returns false, and the caller runs the two selections one after the
-// other.  hist: 512 words, sh: 24 words, wave_tot: 2*NT/64 words.
+// other.  hist: 768 words that the caller has cleared (and made visible with a barrier), sh: 24
+// words, wave_tot: 2*NT/64 words.
 template <int NT>
 __device__ bool select_both(const uint16_t *keys, uint8_t *state, int D, int k, uint32_t *hist, uint32_t *sh,
                             uint32_t *wave_tot)
 {
     const int tid = threadIdx.x;
     const uint32_t K = (uint32_t)k;
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
     for (int c = tid; c < D; c += NT) atomicAdd(&hist[keys[c] >> 8], 1u);
     __syncthreads();
     {
@@ -372,16 +371,14 @@ __device__ bool select_both(const uint16_t *keys, uint8_t *state, int D, int k, 
     }
     __syncthreads();
     const uint32_t bin_top = sh[0], above_top = sh[1], bin_bot = sh[2], below_bot = sh[3], in_bot = sh[4];
-    if (tid < 256) { hist[tid] = 0; hist[256 + tid] = 0; }
-    __syncthreads();
     for (int c = tid; c < D; c += NT) {
         const uint32_t key = keys[c];
-        if ((key >> 8) == bin_top) atomicAdd(&hist[key & 255u], 1u);
-        if ((key >> 8) == bin_bot) atomicAdd(&hist[256 + (key & 255u)], 1u);
+        if ((key >> 8) == bin_top) atomicAdd(&hist[256 + (key & 255u)], 1u);
+        if ((key >> 8) == bin_bot) atomicAdd(&hist[512 + (key & 255u)], 1u);
     }
     __syncthreads();
     {
-        const uint32_t mt = (tid < 256) ? hist[tid] : 0u, mb = (tid < 256) ? hist[256 + tid] : 0u;
+        const uint32_t mt = (tid < 256) ? hist[256 + tid] : 0u, mb = (tid < 256) ? hist[512 + tid] : 0u;
         uint32_t at, ab;
         bins_above2(mt, mb, sh + 16, at, ab);
         const uint32_t above = above_top + at;                   // keys strictly greater than this one
@@ -440,7 +437,7 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *__restrict__ param
     uint8_t *state = dyn + 2 * (size_t)D;
     constexpr int NW = NT / 64;
     constexpr int CB = NT / 64;                   // (head, half) chunks covered by one block of NT channels
-    __shared__ uint32_t hist[512];
+    __shared__ uint32_t hist[768];
     __shared__ uint32_t sh[24];
     __shared__ uint32_t wave_tot[IT * NW];
     __shared__ float redmx[NW], redmn[NW];
@@ -470,6 +467,7 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *__restrict__ param
         if (c < D) { keys[c] = (uint16_t)order_key(xc[j]); state[c] = 0; }
     }
     for (int c = tid + IT * NT; c < D; c += NT) { keys[c] = (uint16_t)order_key(x16[c]); state[c] = 0; }
+    for (int i = tid; i < 768; i += NT) hist[i] = 0;   // the three histograms of select_both
     __syncthreads();
     if (k_side > 0) {
         if (!select_both<NT>(keys, state, D, k_side, hist, sh, wave_tot)) {
