@@ -107,8 +107,9 @@ def main():
     st = S.LayerInputs(wl)
     L = wl.context
     steps, warmup = args.steps, args.warmup
-    bsteps = min(steps, 50)                        # extra steps timed call by call for the breakdown
-    n_new = steps + warmup + bsteps
+    bsteps = min(steps, 50)                        # extra steps timed call by call for the breakdowns
+    steps3 = min(steps, 100)                       # extra steps with the attention as three separate calls
+    n_new = steps + warmup + 2 * bsteps + steps3 + 5
     cap = ((L + n_new + 8 + 127) // 128) * 128
     Hq, D = wl.n_q_heads, wl.D
     scale = 1.0 / np.sqrt(128.0)
@@ -123,11 +124,16 @@ def main():
     out = torch.zeros((Hq, 128), device="cuda")
     sm_ws = torch.zeros(K.binding.kvq_softmax_workspace_bytes(Hq, cap), dtype=torch.uint8, device="cuda")
 
-    def step(i, ev=None):
+    def step(i, ev=None, fused=True):
+        """One decode step of one attention layer.  fused: scores, softmax and output in one library
+        call (the softmax folded into the mat-vec kernels); otherwise the same work as three calls."""
         K.kvq_quantize_append_k(gc, new_k[i:i + 1])
         if ev: ev[1].start()  # noqa: E701
         K.kvq_quantize_append_v(gc, new_v[i:i + 1])
         if ev: ev[2].start()  # noqa: E701
+        if fused:
+            K.kvq_attention_decode(gc, qs[i], scale, scores, out)
+            return
         K.kvq_qk_matvec(gc, qs[i], scale, scores)
         if ev: ev[3].start()  # noqa: E701
         K.kvq_softmax_f32(scores, probs, gc.n_tokens_k, sm_ws)
@@ -145,15 +151,33 @@ def main():
     wall = time.perf_counter() - t_begin
     ms_per_step = wall * 1e3 / steps
 
-    # per-call breakdown from further steps, with an event recorded on the launch stream between the
+    # the same steps with the attention as three separate calls (qk, softmax, pv)
+    base = warmup + steps
+    for i in range(5):
+        step(base + i, fused=False)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for i in range(steps3):
+        step(base + 5 + i, fused=False)
+    torch.cuda.synchronize()
+    ms_per_step_three_calls = (time.perf_counter() - t_begin) * 1e3 / steps3
+    base += 5 + steps3
+
+    # per-call breakdowns from further steps, with an event recorded on the launch stream between the
     # calls (start() records one event); the events themselves cost a few microseconds per step, which
-    # is why they stay out of the timed region above
+    # is why they stay out of the timed regions above
     evs = [[K.HipEventTimer() for _ in range(6)] for _ in range(bsteps)]
     for i in range(bsteps):
         ev = evs[i]
         ev[0].start()
-        step(warmup + steps + i, ev)
+        step(base + i, ev, fused=False)
         ev[5].start()
+    fevs = [[K.HipEventTimer() for _ in range(4)] for _ in range(bsteps)]
+    for i in range(bsteps):
+        ev = fevs[i]
+        ev[0].start()
+        step(base + bsteps + i, ev, fused=True)
+        ev[3].start()
     torch.cuda.synchronize()
 
     import ctypes
@@ -171,6 +195,8 @@ def main():
             per[n].append(gap_ms(ev[j], ev[j + 1]) * 1e3)
     breakdown = {n: float(np.mean(v)) for n, v in per.items()}
     breakdown_min = {n: float(np.min(v)) for n, v in per.items()}
+    fnames = ["append_k", "append_v", "attention_decode"]
+    fused_breakdown = {n: float(np.mean([gap_ms(ev[j], ev[j + 1]) * 1e3 for ev in fevs])) for j, n in enumerate(fnames)}
 
     Lend = gc.n_tokens_k
     nnz_k = int(gc.k_ptr[Lend].item()) & 0xFFFFFFFF
@@ -179,13 +205,12 @@ def main():
     qk_gbps = qk_bytes / (breakdown["qk_matvec"] * 1e-6) / 1e9
     pv_gbps = pv_bytes / (breakdown["pv_matvec"] * 1e-6) / 1e9
 
-    # the dominant kernel on its own: the dense Key kernel inside kvq_qk_matvec, bracketed by HIP events
-    # on the launch stream (same workload, same launch configuration as the timed steps)
+    # the dominant kernel on its own: the dense Key kernel inside the attention call, bracketed by HIP
+    # events on the launch stream (same workload, same launch configuration as the timed steps)
     K.kvq_profile_enable(True)
     dense_qk, dense_pv = [], []
     for i in range(bsteps):
-        K.kvq_qk_matvec(gc, qs[warmup + i], scale, scores)
-        K.kvq_pv_matvec(gc, probs, out)
+        K.kvq_attention_decode(gc, qs[warmup + i], scale, scores, out)
         dense_qk.append(K.kvq_profile_last_ms(0) * 1e3)
         dense_pv.append(K.kvq_profile_last_ms(1) * 1e3)
     K.kvq_profile_enable(False)
@@ -197,6 +222,7 @@ def main():
     fp16 = None
     if not args.no_fp16:
         fws = torch.zeros(K.binding.kvq_fp16_pv_workspace_bytes(Hq, L), dtype=torch.uint8, device="cuda")
+        K.kvq_softmax_f32(scores, probs, gc.n_tokens_k, sm_ws)
         p16 = probs[:, :L].contiguous()
         s16 = torch.zeros((Hq, L), device="cuda")
         tm = K.HipEventTimer()
@@ -269,6 +295,7 @@ def main():
 
     line = {
         "metric": "quantized-KV decode step latency (append K/V + QK^T + softmax + PV), one attention layer",
+        "step": "kvq_quantize_append_k + kvq_quantize_append_v + kvq_attention_decode",
         "value": ms_per_step * 1e3, "unit": "us", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
@@ -276,6 +303,9 @@ def main():
                                f"batch 1, nuq{wl.bits} with {wl.outlier_fraction * 100:g}% outliers, "
                                f"rope base {wl.rope_base:g}",
                    "bits": wl.bits, "context": L, "outlier_fraction": wl.outlier_fraction},
+        "three_calls": {"step": "appends + kvq_qk_matvec + kvq_softmax_f32 + kvq_pv_matvec",
+                        "ms_per_step": ms_per_step_three_calls, "steps": steps3},
+        "fused_breakdown_us": fused_breakdown,
         "breakdown_us": breakdown, "breakdown_min_us": breakdown_min,
         "qk_pv_us": breakdown["qk_matvec"] + breakdown["pv_matvec"],
         "hbm_gbps": {"qk_matvec": qk_gbps, "pv_matvec": pv_gbps},
@@ -283,7 +313,7 @@ def main():
         "speedup_vs_fp16": ({"qk": fp16["qk_us"] / breakdown["qk_matvec"], "pv": fp16["pv_us"] / breakdown["pv_matvec"]}
                             if fp16 else None),
         "dense_kernel_us": {"qk": dense_qk_us, "pv": dense_pv_us},
-        "roofline": {"bound": "hbm", "kernel": "kvq_qk_kernel (dense Key kernel of kvq_qk_matvec)",
+        "roofline": {"bound": "hbm", "kernel": "kvq_qk_kernel (dense Key kernel of the attention call)",
                      "achieved": dense_qk_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": dense_qk_gbps / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes": dense_qk_bytes, "avg_launch_us": dense_qk_us,

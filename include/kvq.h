@@ -165,7 +165,26 @@ kvq_status kvq_qk_matvec(const kvq_cache *cache, const float *d_q_rot, float sca
 kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs, int64_t ld_probs,
                          float *d_out, void *stream);
 
-/* ---- helpers beyond the five calls above -------------------------------------------------- */
+/*
+ * One decode step's attention in a single call: kvq_qk_matvec, the softmax over the scores and
+ * kvq_pv_matvec (paper Sec. 3 and App. "Kernel Implementation Details": the two mat-vecs of
+ * generation-time attention with the softmax between them), without separate softmax passes over
+ * the scores: the Key kernels leave per-workgroup score maxima in the cache's workspace, the Value
+ * kernels weight a token by exp(score - max) as they load its score, and the final reduction
+ * divides by the sum of the weights.
+ *   out[q][c] = sum_n softmax_n(scores[q][.])[n] * vhat[n][kv(q)*128 + c]
+ * with scores and vhat as defined for the two calls above.  Requires n_tokens_k == n_tokens_v
+ * (INVALID_ARG otherwise).
+ *   d_q_rot  : DEVICE fp32 [n_q_heads][128], rotated to the query's position.
+ *   d_scores : DEVICE fp32 [n_q_heads][ld_scores] scratch, ld_scores >= n_tokens_k; on return it
+ *              holds the raw scores (not the probabilities); entries n >= n_tokens_k untouched.
+ *   d_out    : DEVICE fp32 [n_q_heads][128]; all zero when the cache is empty.
+ * Uses cache->workspace (kvq_workspace_bytes covers it).  Errors as for the two mat-vecs.
+ */
+kvq_status kvq_attention_decode(const kvq_cache *cache, const float *d_q_rot, float scale,
+                                float *d_scores, int64_t ld_scores, float *d_out, void *stream);
+
+/* ---- helpers beyond the calls above ------------------------------------------------------- */
 
 /*
  * Row-wise softmax in fp32 with max subtraction: probs[q][n] = exp(x[q][n]-max_q)/sum, n < n_cols.

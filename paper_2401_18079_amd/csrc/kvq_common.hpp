@@ -184,6 +184,55 @@ __device__ __forceinline__ int kvq_sparse_token(uint32_t pw, int tc, int &tcur, 
     return t;
 }
 
+// ---- softmax hand-over from the Key kernels to the Value kernels (fused decode call) ------------
+// The Key kernels leave the maximum of the scores they wrote in per-head slots: a head owns
+// KVQ_STAT_SLOTS consecutive floats, one per workgroup of the dense Key kernel that covers the head
+// (at most 256) plus one per attention-sink token.  A Value kernel takes the maximum m over a head's
+// slots and weights token n by e_n = 2^(log2(e) (x_n - m)) = exp(x_n - m); the sum of the e_n is
+// gathered along the way and the final reduction divides by it.
+constexpr int KVQ_STAT_SLOTS = 256 + KVQ_MAX_SINK;
+constexpr float KVQ_LOG2E = 1.44269504088896340736f;
+constexpr float KVQ_STAT_FLOOR = -3.0e38f;      // "no score": finite, so that differences stay finite
+
+// v of the lane `N` places to the right inside the lane's row of 16 (rotating): a DPP operand
+// modifier, no LDS traffic and a few cycles of latency (a cross-lane shuffle costs a hundred).
+template <int N>
+__device__ __forceinline__ float kvq_row_ror(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float kvq_wave_max(float v)        // maximum over the 64 lanes, in every lane
+{
+    v = __builtin_fmaxf(v, kvq_row_ror<8>(v));                // every lane ends up with its row's maximum
+    v = __builtin_fmaxf(v, kvq_row_ror<4>(v));
+    v = __builtin_fmaxf(v, kvq_row_ror<2>(v));
+    v = __builtin_fmaxf(v, kvq_row_ror<1>(v));
+    const int b = __builtin_bit_cast(int, v);                 // the four rows' maxima as scalars
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return __builtin_fmaxf(__builtin_fmaxf(r0, r1), __builtin_fmaxf(r2, r3));
+}
+// Unnormalised softmax weight of score x given m2 = log2(e) * (maximum score of the head).
+__device__ __forceinline__ float kvq_stat_weight(float x, float m2)
+{
+    return __builtin_amdgcn_exp2f(x * KVQ_LOG2E - m2);
+}
+
+// The two halves of the fused decode call (kvq_attention_decode), defined beside the kernels they
+// launch.  kvq_qk_run: as kvq_qk_matvec; with `stat_slots` non-null the kernels also fill the slots
+// and *n_stat receives how many of each head's slots are in use.  kvq_pv_run: as kvq_pv_matvec; with
+// `stat_slots` non-null `weights` holds raw scores and the result is the softmax-weighted sum.
+__attribute__((visibility("hidden"))) kvq_status kvq_qk_run(const kvq_cache *cache, const float *d_q_rot, float scale,
+                                                            float *d_scores, int64_t ld, float *stat_slots,
+                                                            int *n_stat, hipStream_t s);
+__attribute__((visibility("hidden"))) kvq_status kvq_pv_run(const kvq_cache *cache, const float *d_weights, int64_t ld,
+                                                            float *d_out, const float *stat_slots, int n_stat,
+                                                            hipStream_t s);
+// Bytes of the workspace that kvq_pv_run uses (from its start); the statistics slots follow.
+__attribute__((visibility("hidden"))) int64_t kvq_pv_workspace_bytes(int n_q_heads);
+
 // Optional per-kernel timing (kvq_profile_enable): events bracketing the dense kernels.
 struct KvqProfile {
     int enabled;

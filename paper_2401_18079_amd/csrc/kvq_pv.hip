@@ -59,9 +59,10 @@ inline PvPlan pv_plan(int64_t L, int n_q_heads)
     // workgroups) and every wavefront gets the same number of tokens (a multiple of 8)
     int waves = 12;
     const size_t per_wave = (size_t)pvs_wave_lds_floats(n_q_heads) * 4;
-    while (waves > 1 && (size_t)n_q_heads * 1024 + waves * per_wave > 78848) waves -= (waves > 4) ? 4 : waves / 2;
+    const size_t shared = (size_t)n_q_heads * (1024 + 8);      // accumulators + per-head score maxima (8 bytes each: alignment)
+    while (waves > 1 && shared + waves * per_wave > 78848) waves -= (waves > 4) ? 4 : waves / 2;
     p.swaves = waves;
-    p.slds = (size_t)n_q_heads * 1024 + waves * per_wave;
+    p.slds = shared + waves * per_wave;
     int wgs_per_cu = (int)(163840 / p.slds);
     if (wgs_per_cu * waves > 24) wgs_per_cu = 24 / waves;      // six wavefronts per SIMD (register budget)
     if (wgs_per_cu < 1) wgs_per_cu = 1;
@@ -137,8 +138,13 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
                                                       const uint16_t *__restrict__ v_sz,
                                                       const float *__restrict__ probs, int64_t ld,
                                                       float *__restrict__ partial, float *__restrict__ zpart,
-                                                      int n_tiles, int n_sink)
+                                                      int n_tiles, int n_sink,
+                                                      const float *__restrict__ stat_slots, int n_stat,
+                                                      float *__restrict__ lpart)
 {
+    // stat_slots != null: `probs` holds raw scores x; a wavefront takes the maximum m of its head's
+    // n_stat slots once, weights every token by exp(x - m) as it loads its score, and also writes the
+    // sum of these weights over its slab to lpart[slab][q] (the reduce kernel divides by their total)
     // tokens below n_sink are attention-sink tokens kept in fp16: their quantized form gets weight 0
     // here and the reduce kernel adds their fp16 rows
     constexpr int NE2 = 1 << (2 * BITS);
@@ -159,6 +165,12 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
     const int kvh = qh / (n_q_heads / n_kv_heads);
     const uint32_t lane_off = (uint32_t)(lane & 31) << 2;
     const float *prow = probs + (int64_t)qh * ld;
+    float m2 = 0.f, lacc = 0.f;
+    if (stat_slots) {
+        float m = KVQ_STAT_FLOOR;
+        for (int i = lane; i < n_stat; i += 64) m = __builtin_fmaxf(m, stat_slots[(int64_t)qh * KVQ_STAT_SLOTS + i]);
+        m2 = kvq_wave_max(m) * KVQ_LOG2E;
+    }
 
     float acc[64];
 #pragma unroll
@@ -180,8 +192,13 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
                 W[4 * j + 0] = v.x; W[4 * j + 1] = v.y; W[4 * j + 2] = v.z; W[4 * j + 3] = v.w;
             }
             const uint2 sz = *(const uint2 *)(v_sz + n0 * 2);            // (s0, z0, s1, z1) fp16
-            const float p0 = (n0 >= n_sink) ? prow[n0] : 0.f;
-            const float p1 = (n0 + 1 < L && n0 + 1 >= n_sink) ? prow[n0 + 1] : 0.f;   // odd tail: second token absent
+            float p0 = (n0 >= n_sink) ? prow[n0] : 0.f;
+            float p1 = (n0 + 1 < L && n0 + 1 >= n_sink) ? prow[n0 + 1] : 0.f;   // odd tail: second token absent
+            if (stat_slots) {
+                p0 = (n0 >= n_sink) ? kvq_stat_weight(p0, m2) : 0.f;
+                p1 = (n0 + 1 < L && n0 + 1 >= n_sink) ? kvq_stat_weight(p1, m2) : 0.f;
+                lacc += p0 + p1;
+            }
             const float w0 = p0 * kvq_h2f((uint16_t)(sz.x & 0xFFFFu));
             const float w1 = p1 * kvq_h2f((uint16_t)(sz.y & 0xFFFFu));
             zacc = __builtin_fmaf(p0, kvq_h2f((uint16_t)(sz.x >> 16)), zacc);
@@ -206,9 +223,14 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
         __syncthreads();
     }
     for (int o = 32; o > 0; o >>= 1) zacc += __shfl_xor(zacc, o);
+    if (stat_slots)
+        for (int o = 32; o > 0; o >>= 1) lacc += __shfl_xor(lacc, o);
     if (active) {
         partial[((int64_t)blockIdx.x * n_q_heads + qh) * 128 + half * 64 + lane] = outv;
-        if (half == 0 && lane == 0) zpart[(int64_t)blockIdx.x * n_q_heads + qh] = zacc;
+        if (half == 0 && lane == 0) {
+            zpart[(int64_t)blockIdx.x * n_q_heads + qh] = zacc;
+            if (stat_slots) lpart[(int64_t)blockIdx.x * n_q_heads + qh] = lacc;
+        }
     }
 }
 
@@ -220,19 +242,23 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
 // p[q][n] * val to the workgroup's fixed-point LDS accumulators (integer atomics).  The workgroup's
 // sums go to the workspace; the reduce kernel adds them up.
 // R = query heads per KV head (0: any ratio, looked up at run time); SINK: the cache keeps its first
-// n_sink tokens in fp16 (a separate instantiation: the plain one has no register to spare)
-template <int R, bool SINK>
+// n_sink tokens in fp16; FUSED: `probs` holds raw scores, see below (separate instantiations: the
+// plain one has no register to spare)
+template <int R, bool SINK, bool FUSED>
 __global__ __launch_bounds__(768) __attribute__((amdgpu_waves_per_eu(6, 6)))
 void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__restrict__ v_ptr,
                    const uint16_t *__restrict__ v_idx, const uint16_t *__restrict__ v_val, uint32_t nnz_cap,
                    const float *__restrict__ probs, int64_t ld, float *__restrict__ spartial, int64_t tokens_per_wave,
-                   int n_sink)
+                   int n_sink, const float *__restrict__ stat_slots, int n_stat)
 {
+    // FUSED: `probs` holds raw scores x; the workgroup takes every head's maximum m over its n_stat
+    // slots once and scores become weights exp(x - m) on their way into the wavefront's LDS slice
     extern __shared__ __attribute__((aligned(16))) float dyn[];
     unsigned long long *sacc = (unsigned long long *)dyn;     // [n_q_heads][128] 2^40-scaled sums
+    float *sst = (float *)(sacc + n_q_heads * 128);           // [n_q_heads] log2(e) * maximum score (2 floats per head reserved)
     const int tid = threadIdx.x, lane = tid & 63, n_waves = blockDim.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);           // scalar: loop bounds below are uniform
-    float *ps = (float *)(sacc + n_q_heads * 128) + (size_t)wave * pvs_wave_lds_floats(n_q_heads);   // [n_q_heads][PVS_ROW]
+    float *ps = sst + 2 * n_q_heads + (size_t)wave * pvs_wave_lds_floats(n_q_heads);   // [n_q_heads][PVS_ROW]
     const int r = R ? R : n_q_heads / n_kv_heads;
     for (int j = tid; j < n_q_heads * 128; j += blockDim.x) sacc[j] = 0ull;
     bool cleared = false;      // the barrier after the clearing comes once the first loads are requested
@@ -248,6 +274,26 @@ void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__r
     int tc = sub_len;
     uint32_t pw = 0;
     if (tc > 0) pw = v_ptr[nc + (lane < tc ? lane : tc)];
+    if (FUSED) {
+        // every head's maximum over its slots, four heads per wavefront at a time with their loads
+        // requested together (and behind the pointer load above, so that the round trips overlap)
+        for (int q0 = 4 * wave; q0 < n_q_heads; q0 += 4 * n_waves) {
+            float m[4] = {KVQ_STAT_FLOOR, KVQ_STAT_FLOOR, KVQ_STAT_FLOOR, KVQ_STAT_FLOOR};
+            for (int i0 = 0; i0 < n_stat; i0 += 64) {
+                const int i = (i0 + lane < n_stat) ? i0 + lane : n_stat - 1;     // a repeated slot does not change a maximum
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int qh = (q0 + k < n_q_heads) ? q0 + k : q0;
+                    m[k] = __builtin_fmaxf(m[k], stat_slots[(int64_t)qh * KVQ_STAT_SLOTS + i]);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float w = kvq_wave_max(m[k]) * KVQ_LOG2E;
+                if (lane == 0 && q0 + k < n_q_heads) sst[q0 + k] = w;
+            }
+        }
+    }
     while (tc > 0) {
         const int64_t nc_next = nc + tc;
         const int tc_next = (int)((ne - nc_next < sub_len) ? (ne - nc_next) : sub_len);
@@ -271,19 +317,34 @@ void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__r
         }
         uint32_t pw_next = 0;
         if (tc_next > 0) pw_next = v_ptr[nc_next + (lane < tc_next ? lane : tc_next)];
+        if (!cleared) {          // the accumulators are clear and the statistics merged
+            __syncthreads();
+            cleared = true;
+        }
+        // (the cells' LDS addresses are recomputed from an opaque copy of the lane number: hoisted
+        // out of the loop they would cost eight registers that this kernel does not have)
+        int lane_o = lane;
+        asm volatile("" : "+v"(lane_o));
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-            const int j = lane + 64 * k;
-            if (j < n_cells) ps[(j / PVS_TW) * PVS_ROW + j % PVS_TW] = pr[k];
+            const int j = lane_o + 64 * k, qh = j / PVS_TW, t = j % PVS_TW;
+            if (j < n_cells) {
+                float w = pr[k];
+                if (FUSED) {
+                    const float e = kvq_stat_weight(w, sst[qh]);
+                    w = (t < tc && (!SINK || t >= t_sink)) ? e : 0.f;
+                }
+                ps[qh * PVS_ROW + t] = w;
+            }
         }
         for (int j0 = 64 * 8; j0 < n_cells; j0 += 64) {      // models with more than 32 query heads
             const int j = j0 + lane, qh = j / PVS_TW, t = j % PVS_TW;
-            if (j < n_cells)
-                ps[qh * PVS_ROW + t] = (t < tc && (!SINK || t >= t_sink)) ? probs[(int64_t)qh * ld + nc + t] : 0.f;
-        }
-        if (!cleared) {
-            __syncthreads();
-            cleared = true;
+            if (j < n_cells) {
+                const bool ok = t < tc && (!SINK || t >= t_sink);
+                float w = ok ? probs[(int64_t)qh * ld + nc + t] : 0.f;
+                if (FUSED && ok) w = kvq_stat_weight(w, sst[qh]);
+                ps[qh * PVS_ROW + t] = w;
+            }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -329,12 +390,23 @@ __global__ __launch_bounds__(1024) void kvq_pv_reduce(int n_q_heads, int slabs, 
                                                       const float *__restrict__ zpart,
                                                       const float *__restrict__ spartial, float *__restrict__ out,
                                                       int n_sink, int n_kv_heads, const uint16_t *__restrict__ sink_v,
-                                                      const float *__restrict__ probs, int64_t ld)
+                                                      const float *__restrict__ probs, int64_t ld,
+                                                      const float *__restrict__ stat_slots, int n_stat,
+                                                      const float *__restrict__ lpart)
 {
-    // n_sink: attention-sink tokens (already clipped to the tokens present), added from their fp16 rows
+    // n_sink: attention-sink tokens (already clipped to the tokens present), added from their fp16 rows;
+    // stat_slots != null: `probs` holds raw scores, the partial sums are weighted by exp(x - m) (see
+    // kvq_pv_dense) and the result is divided by the sum of all weights (lpart, plus the sink tokens')
     __shared__ float red[32][33];
-    __shared__ float zred[32];
+    __shared__ float zred[32], lred[32];
+    __shared__ float sm2;
     const int qh = blockIdx.x >> 2, c = (blockIdx.x & 3) * 32 + (threadIdx.x & 31), j = threadIdx.x >> 5;
+    if (stat_slots && n_sink > 0 && threadIdx.x < 64) {
+        float m = KVQ_STAT_FLOOR;
+        for (int i = threadIdx.x; i < n_stat; i += 64) m = __builtin_fmaxf(m, stat_slots[(int64_t)qh * KVQ_STAT_SLOTS + i]);
+        m = kvq_wave_max(m) * KVQ_LOG2E;
+        if (threadIdx.x == 0) sm2 = m;
+    }
     float s = 0.f;
     for (int k0 = j; k0 < slabs; k0 += 256) {          // eight loads in flight per thread
         float v[8];
@@ -361,41 +433,59 @@ __global__ __launch_bounds__(1024) void kvq_pv_reduce(int n_q_heads, int slabs, 
         float z = 0.f;
         for (int k = j; k < slabs; k += 32) z += zpart[(int64_t)k * n_q_heads + qh];
         zred[j] = z;
+        float l = 0.f;
+        if (stat_slots)
+            for (int k = j; k < slabs; k += 32) l += lpart[(int64_t)k * n_q_heads + qh];
+        lred[j] = l;
     }
     __syncthreads();
     if (j == 0) {
-        float t = 0.f, z = 0.f;
+        float t = 0.f, z = 0.f, l = 0.f;
 #pragma unroll
-        for (int i = 0; i < 32; ++i) { t += red[i][threadIdx.x & 31]; z += zred[i]; }
+        for (int i = 0; i < 32; ++i) { t += red[i][threadIdx.x & 31]; z += zred[i]; l += lred[i]; }
         float sink = 0.f;
         const int kvh = qh / (n_q_heads / n_kv_heads);
-        for (int n = 0; n < n_sink; ++n)
-            sink = __builtin_fmaf(probs[(int64_t)qh * ld + n], kvq_h2f(sink_v[(int64_t)n * n_kv_heads * 128 + kvh * 128 + c]), sink);
-        out[qh * 128 + c] = t + z + sink;
+        for (int n = 0; n < n_sink; ++n) {
+            float w = probs[(int64_t)qh * ld + n];
+            if (stat_slots) {
+                w = kvq_stat_weight(w, sm2);
+                l += w;
+            }
+            sink = __builtin_fmaf(w, kvq_h2f(sink_v[(int64_t)n * n_kv_heads * 128 + kvh * 128 + c]), sink);
+        }
+        const float r = t + z + sink;
+        out[qh * 128 + c] = stat_slots ? r / l : r;
     }
 }
 
-int64_t pv_workspace_bytes(int64_t cap, int n_q_heads)
-{
-    const PvPlan p = pv_plan(cap, n_q_heads);
-    // the plan for any L <= cap never needs more slabs than 512 dense + 512 sparse
-    (void)p;
-    return ((int64_t)512 * n_q_heads * 128 + (int64_t)512 * n_q_heads + (int64_t)512 * n_q_heads * 128) * 4;
-}
-
 }  // namespace
+
+int64_t kvq_pv_workspace_bytes(int n_q_heads)
+{
+    // no plan needs more than 512 dense + 512 sparse slabs
+    // dense partials, zero-point sums, sparse partials, weight sums (fused call)
+    return ((int64_t)512 * n_q_heads * 128 + (int64_t)512 * n_q_heads + (int64_t)512 * n_q_heads * 128 +
+            (int64_t)512 * n_q_heads) * 4;
+}
 
 extern "C" int64_t kvq_workspace_bytes(const kvq_cache *cache, int32_t max_append)
 {
     if (!cache) return 0;
     int64_t a = (int64_t)(max_append > 0 ? max_append : 1) * 4;
-    int64_t b = pv_workspace_bytes(cache->cap_tokens, cache->n_q_heads);
+    // slab partials of the Value kernels, then the softmax statistics of the fused decode call
+    int64_t b = kvq_pv_workspace_bytes(cache->n_q_heads) + (int64_t)cache->n_q_heads * KVQ_STAT_SLOTS * 4;
     int64_t w = a > b ? a : b;
     return (w + 255) & ~(int64_t)255;
 }
 
 extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs, int64_t ld_probs, float *d_out,
                                     void *stream)
+{
+    return kvq_pv_run(cache, d_probs, ld_probs, d_out, nullptr, 0, (hipStream_t)stream);
+}
+
+kvq_status kvq_pv_run(const kvq_cache *cache, const float *d_probs, int64_t ld_probs, float *d_out,
+                      const float *stat_slots, int n_stat, hipStream_t s)
 {
     kvq_status st = kvq_check_cache(cache);
     if (st != KVQ_OK) return st;
@@ -404,26 +494,27 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
     const int64_t L = cache->n_tokens_v;
     if (ld_probs < L) return KVQ_ERR_INVALID_ARG;
     const int Hq = cache->n_q_heads, D = cache->n_kv_heads * KVQ_HEAD_DIM;
-    hipStream_t s = (hipStream_t)stream;
-    if (!cache->workspace || cache->workspace_bytes < pv_workspace_bytes(cache->cap_tokens, Hq)) return KVQ_ERR_CAPACITY;
+    if (!cache->workspace || cache->workspace_bytes < kvq_pv_workspace_bytes(Hq)) return KVQ_ERR_CAPACITY;
     const PvPlan plan = (L > 0) ? pv_plan(L, Hq) : PvPlan{0, 0, 0, 0, 0, 0};
     float *partial = (float *)cache->workspace;
     float *zpart = partial + (int64_t)512 * Hq * 128;
     float *spartial = zpart + (int64_t)512 * Hq;
+    float *lpart = spartial + (int64_t)512 * Hq * 128;
     if (L > 0) {
         const int r = Hq / cache->n_kv_heads;
         const bool sink = cache->n_sink > 0;
         const int ri = (r == 1) ? 1 : (r == 2) ? 2 : (r == 4) ? 3 : (r == 8) ? 4 : 0;
-        using SparseKernel = decltype(&kvq_pv_sparse<0, false>);
-        static const SparseKernel kernels[5][2] = {{kvq_pv_sparse<0, false>, kvq_pv_sparse<0, true>},
-                                                   {kvq_pv_sparse<1, false>, kvq_pv_sparse<1, true>},
-                                                   {kvq_pv_sparse<2, false>, kvq_pv_sparse<2, true>},
-                                                   {kvq_pv_sparse<4, false>, kvq_pv_sparse<4, true>},
-                                                   {kvq_pv_sparse<8, false>, kvq_pv_sparse<8, true>}};
-        const SparseKernel sparse = kernels[ri][sink];
+        const bool fused = stat_slots != nullptr;
+        using SparseKernel = decltype(&kvq_pv_sparse<0, false, false>);
+#define KVQ_PVS_ROW(R) {{kvq_pv_sparse<R, false, false>, kvq_pv_sparse<R, false, true>},       \
+                        {kvq_pv_sparse<R, true, false>, kvq_pv_sparse<R, true, true>}}
+        static const SparseKernel kernels[5][2][2] = {KVQ_PVS_ROW(0), KVQ_PVS_ROW(1), KVQ_PVS_ROW(2), KVQ_PVS_ROW(4),
+                                                      KVQ_PVS_ROW(8)};
+#undef KVQ_PVS_ROW
+        const SparseKernel sparse = kernels[ri][sink][fused];
         // one dynamic-LDS limit per instantiation, raised on demand
-        static size_t lds_attr[5][2] = {};
-        size_t &attr = lds_attr[ri][sink];
+        static size_t lds_attr[5][2][2] = {};
+        size_t &attr = lds_attr[ri][sink][fused];
         if (plan.slds > attr) {
             KVQ_HIP_CHECK(hipFuncSetAttribute((const void *)sparse, hipFuncAttributeMaxDynamicSharedMemorySize,
                                               (int)plan.slds));
@@ -435,13 +526,13 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
         sparse<<<plan.sslabs, 64 * plan.swaves, plan.slds, s>>>(cache->n_kv_heads, Hq, L, cache->v_ptr, cache->v_idx,
                                                                 cache->v_val, (uint32_t)cache->cap_nnz_v, d_probs,
                                                                 ld_probs, spartial, plan.tokens_per_swave,
-                                                                cache->n_sink);
+                                                                cache->n_sink, stat_slots, n_stat);
 
         dim3 grid((unsigned)plan.slabs, (unsigned)((2 * Hq + PV_WAVES - 1) / PV_WAVES));
 #define LAUNCH_PV(B)                                                                                          \
     kvq_pv_dense<B><<<grid, PV_NT, 0, s>>>(cache->params, D, cache->n_kv_heads, Hq, cache->cap_tokens, L,      \
                                            cache->v_codes, cache->v_sz, d_probs, ld_probs, partial, zpart,    \
-                                           plan.tiles, cache->n_sink)
+                                           plan.tiles, cache->n_sink, stat_slots, n_stat, lpart)
         KvqProfile &prof = kvq_profile_state();
         if (prof.enabled) KVQ_HIP_CHECK(hipEventRecord(prof.ev[1][0], s));
         if (cache->bits == 2) LAUNCH_PV(2);
@@ -452,7 +543,7 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
     }
     const int ns = (int)(cache->n_sink < L ? cache->n_sink : L);
     kvq_pv_reduce<<<4 * Hq, 1024, 0, s>>>(Hq, plan.slabs, plan.sslabs, partial, zpart, spartial, d_out, ns,
-                                          cache->n_kv_heads, cache->sink_v, d_probs, ld_probs);
+                                          cache->n_kv_heads, cache->sink_v, d_probs, ld_probs, stat_slots, n_stat, lpart);
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }

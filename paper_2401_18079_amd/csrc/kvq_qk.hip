@@ -198,14 +198,17 @@ __device__ __forceinline__ void qk_all_pairs(std::integer_sequence<int, G...>,
 
 // KVH KV heads per workgroup, RQ query heads per KV head handled here (RQ divides the model's GQA
 // ratio `r`; when RQ < r several workgroups share a KV head), PG channel pairs per gather group.
-template <int BITS, int KVH, int RQ, int NT, int PG>
+template <int BITS, int KVH, int RQ, int NT, int PG, bool STATS>
 __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ params, int D, int r,
                                                     int64_t cap, int64_t L, const uint8_t *__restrict__ k_codes,
                                                     const float *__restrict__ q_rot, float scale,
                                                     float *__restrict__ scores, int64_t ld, int n_tiles,
-                                                    int add_prev)
+                                                    int add_prev, float *__restrict__ stat_slots, int n_sink)
 {
-    // add_prev != 0: the score buffer already holds the sparse part; add to it instead of overwriting
+    // add_prev != 0: the score buffer already holds the sparse part; add to it instead of overwriting.
+    // STATS: the workgroup also leaves the maximum of the scores it wrote (tokens below n_sink
+    // excepted: the attention-sink kernel replaces their scores) in slot blockIdx.x of each of its
+    // query heads.  A separate instantiation: the running maxima cost a register per head.
     using C = QkCfg<BITS>;
     constexpr int QH = KVH * RQ, R = RQ;
     constexpr int NE = C::NE;
@@ -283,6 +286,11 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
                 W[g][4 * j + 0] = v.x; W[g][4 * j + 1] = v.y; W[g][4 * j + 2] = v.z; W[g][4 * j + 3] = v.w;
             }
     }
+    float stat_m[STATS ? QH : 1];
+    if (STATS) {
+#pragma unroll
+        for (int qh = 0; qh < QH; ++qh) stat_m[qh] = KVQ_STAT_FLOOR;
+    }
     for (int tile = 0; tile < tiles_per_wg; ++tile) {
         const int64_t nn = n + NT;
         const bool next_valid = (tile + 1 < tiles_per_wg) && (nn < L);
@@ -320,12 +328,32 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
         }
         if (valid) {
 #pragma unroll
-            for (int qh = 0; qh < QH; ++qh)
-                scores[(int64_t)(q0 + qh) * ld + n] = acc[qh] + prev[qh];
+            for (int qh = 0; qh < QH; ++qh) {
+                const float x = acc[qh] + prev[qh];
+                scores[(int64_t)(q0 + qh) * ld + n] = x;
+                if (STATS && n >= n_sink) stat_m[STATS ? qh : 0] = __builtin_fmaxf(stat_m[STATS ? qh : 0], x);
+            }
         }
         n = nn;
         valid = next_valid;
         cur_chunk = next_chunk;
+    }
+    if (STATS) {
+        // workgroup-wide maximum per query head: wavefronts first, then one thread per head over the
+        // wavefronts' values (the staged query is dead by now: its array holds them)
+        float *wst = qs;                                      // [NT / 64][QH]
+#pragma unroll
+        for (int qh = 0; qh < QH; ++qh) {
+            const float w = kvq_wave_max(stat_m[STATS ? qh : 0]);
+            if ((tid & 63) == 0) wst[(tid >> 6) * QH + qh] = w;
+        }
+        __syncthreads();
+        if (tid < QH) {
+            float m = KVQ_STAT_FLOOR;
+#pragma unroll
+            for (int w = 0; w < NT / 64; ++w) m = __builtin_fmaxf(m, wst[w * QH + tid]);
+            stat_slots[(int64_t)(q0 + tid) * KVQ_STAT_SLOTS + blockIdx.x] = m;
+        }
     }
 }
 
@@ -520,8 +548,10 @@ kvq_status launch_qk_sparse(const kvq_cache *c, const float *q, float scale, flo
 __global__ __launch_bounds__(64) void kvq_qk_sink(const void *__restrict__ params, int D, int r,
                                                    const uint16_t *__restrict__ sink_k,
                                                    const float *__restrict__ q_rot, float scale,
-                                                   float *__restrict__ scores, int64_t ld)
+                                                   float *__restrict__ scores, int64_t ld,
+                                                   float *__restrict__ stat_slots, int first_slot)
 {
+    // stat_slots != null: the token's score also goes into a slot of its own (first_slot + token)
     const KvqParamsView pv = kvq_params_view(params, D);
     const int n = blockIdx.x, qh = blockIdx.y, i = threadIdx.x, kvh = qh / r;
     const float k_lo = kvq_h2f(sink_k[(int64_t)n * D + kvh * 128 + i]);
@@ -531,16 +561,20 @@ __global__ __launch_bounds__(64) void kvq_qk_sink(const void *__restrict__ param
     const float cs = __builtin_amdgcn_cosf(rev), sn = __builtin_amdgcn_sinf(rev);
     float t = (qa * k_lo + qb * k_hi) * cs + (qb * k_lo - qa * k_hi) * sn;
     for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o);
-    if (i == 0) scores[(int64_t)qh * ld + n] = t;
+    if (i == 0) {
+        scores[(int64_t)qh * ld + n] = t;
+        if (stat_slots) stat_slots[(int64_t)qh * KVQ_STAT_SLOTS + first_slot + n] = t;
+    }
 }
 
 template <int BITS, int KVH, int RQ, int NT, int PG, int R>
-kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
+kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, float *stat_slots,
+                     int *n_stat, hipStream_t s)
 {
     constexpr int QH = KVH * RQ;
     const int D = c->n_kv_heads * KVQ_HEAD_DIM;
     const int64_t L = c->n_tokens_k;
-    auto kern = kvq_qk_kernel<BITS, KVH, RQ, NT, PG>;
+    auto kern = stat_slots ? kvq_qk_kernel<BITS, KVH, RQ, NT, PG, true> : kvq_qk_kernel<BITS, KVH, RQ, NT, PG, false>;
     const int groups = c->n_q_heads / QH;
     const int64_t tiles = (L + NT - 1) / NT;
     // about one workgroup per compute unit in total (the tables fill most of a CU's LDS); each
@@ -557,13 +591,15 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     }
     KvqProfile &prof = kvq_profile_state();
     if (prof.enabled) KVQ_HIP_CHECK(hipEventRecord(prof.ev[0][0], s));
+    static_assert(KVQ_STAT_SLOTS >= 256 + KVQ_MAX_SINK, "a slot per workgroup of a head plus the sink tokens");
+    const unsigned ns = (unsigned)(c->n_sink < L ? c->n_sink : L);
     kern<<<grid, NT, 0, s>>>(c->params, D, R, c->cap_tokens, L, c->k_codes, q, scale, scores, ld, (int)tiles,
-                             sparse_first);
+                             sparse_first, stat_slots, (int)ns);
     if (prof.enabled) { KVQ_HIP_CHECK(hipEventRecord(prof.ev[0][1], s)); prof.have[0] = 1; }
-    if (c->n_sink > 0) {
-        const unsigned ns = (unsigned)(c->n_sink < L ? c->n_sink : L);
-        kvq_qk_sink<<<dim3(ns, (unsigned)c->n_q_heads), 64, 0, s>>>(c->params, D, R, c->sink_k, q, scale, scores, ld);
-    }
+    if (ns > 0)
+        kvq_qk_sink<<<dim3(ns, (unsigned)c->n_q_heads), 64, 0, s>>>(c->params, D, R, c->sink_k, q, scale, scores, ld,
+                                                                    stat_slots, (int)gx);
+    if (n_stat) *n_stat = (int)gx + (int)ns;
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }
@@ -571,49 +607,57 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
 // Query heads per workgroup: as many as fit the LDS budget (fp32 (A,B) tables: 64 pairs x entries x
 // 8 bytes per query head = 8 / 32 / 16 KiB for 2 / 3 / 4 bits).
 template <int BITS, int R>
-kvq_status dispatch_qk(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
+kvq_status dispatch_qk(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, float *st,
+                       int *n_stat, hipStream_t s)
 {
     constexpr int QHMAX = (BITS == 3) ? 4 : 8;
     constexpr int PGD = (BITS == 4) ? 1 : (BITS == 3 ? 4 : 2);
     constexpr int PG = PGD;
     if constexpr (R >= QHMAX) {
         // one KV head per workgroup, QHMAX of its query heads (R / QHMAX workgroups share the KV head)
-        return launch_qk<BITS, 1, QHMAX, 1024, PG, R>(c, q, scale, scores, ld, s);
+        return launch_qk<BITS, 1, QHMAX, 1024, PG, R>(c, q, scale, scores, ld, st, n_stat, s);
     } else {
         constexpr int KVH = QHMAX / R;
-        if (c->n_kv_heads % KVH == 0) return launch_qk<BITS, KVH, R, 1024, PG, R>(c, q, scale, scores, ld, s);
+        if (c->n_kv_heads % KVH == 0) return launch_qk<BITS, KVH, R, 1024, PG, R>(c, q, scale, scores, ld, st, n_stat, s);
         // few KV heads: one per workgroup
-        return launch_qk<BITS, 1, R, 512, PG, R>(c, q, scale, scores, ld, s);
+        return launch_qk<BITS, 1, R, 512, PG, R>(c, q, scale, scores, ld, st, n_stat, s);
     }
 }
 
 template <int BITS>
-kvq_status dispatch_qk_r(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
+kvq_status dispatch_qk_r(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, float *st,
+                         int *n_stat, hipStream_t s)
 {
     switch (c->n_q_heads / c->n_kv_heads) {
-    case 1: return dispatch_qk<BITS, 1>(c, q, scale, scores, ld, s);
-    case 2: return dispatch_qk<BITS, 2>(c, q, scale, scores, ld, s);
-    case 4: return dispatch_qk<BITS, 4>(c, q, scale, scores, ld, s);
-    case 8: return dispatch_qk<BITS, 8>(c, q, scale, scores, ld, s);
+    case 1: return dispatch_qk<BITS, 1>(c, q, scale, scores, ld, st, n_stat, s);
+    case 2: return dispatch_qk<BITS, 2>(c, q, scale, scores, ld, st, n_stat, s);
+    case 4: return dispatch_qk<BITS, 4>(c, q, scale, scores, ld, st, n_stat, s);
+    case 8: return dispatch_qk<BITS, 8>(c, q, scale, scores, ld, st, n_stat, s);
     default: return KVQ_ERR_UNSUPPORTED;
     }
 }
 
 }  // namespace
 
-extern "C" kvq_status kvq_qk_matvec(const kvq_cache *cache, const float *d_q_rot, float scale, float *d_scores,
-                                    int64_t ld_scores, void *stream)
+kvq_status kvq_qk_run(const kvq_cache *cache, const float *d_q_rot, float scale, float *d_scores, int64_t ld_scores,
+                      float *stat_slots, int *n_stat, hipStream_t s)
 {
     kvq_status st = kvq_check_cache(cache);
     if (st != KVQ_OK) return st;
     if (!cache->loaded) return KVQ_ERR_NOT_LOADED;
     if (!d_q_rot || !d_scores || ((uintptr_t)d_q_rot & 3) || ((uintptr_t)d_scores & 3)) return KVQ_ERR_INVALID_ARG;
     if (ld_scores < cache->n_tokens_k) return KVQ_ERR_INVALID_ARG;
+    if (n_stat) *n_stat = 0;
     if (cache->n_tokens_k == 0) return KVQ_OK;
-    hipStream_t s = (hipStream_t)stream;
     switch (cache->bits) {
-    case 2: return dispatch_qk_r<2>(cache, d_q_rot, scale, d_scores, ld_scores, s);
-    case 3: return dispatch_qk_r<3>(cache, d_q_rot, scale, d_scores, ld_scores, s);
-    default: return dispatch_qk_r<4>(cache, d_q_rot, scale, d_scores, ld_scores, s);
+    case 2: return dispatch_qk_r<2>(cache, d_q_rot, scale, d_scores, ld_scores, stat_slots, n_stat, s);
+    case 3: return dispatch_qk_r<3>(cache, d_q_rot, scale, d_scores, ld_scores, stat_slots, n_stat, s);
+    default: return dispatch_qk_r<4>(cache, d_q_rot, scale, d_scores, ld_scores, stat_slots, n_stat, s);
     }
+}
+
+extern "C" kvq_status kvq_qk_matvec(const kvq_cache *cache, const float *d_q_rot, float scale, float *d_scores,
+                                    int64_t ld_scores, void *stream)
+{
+    return kvq_qk_run(cache, d_q_rot, scale, d_scores, ld_scores, nullptr, nullptr, (hipStream_t)stream);
 }

@@ -20,6 +20,26 @@ N_WINDOWS = 12
 WIN = 128
 
 
+def _check_fused_against_separate_calls(gc, q, scale, scores, Ln, cap):
+    """The fused decode call at full size: the same scores bit for bit and the same output as softmax
+    and Value mat-vec run as separate calls on those scores (whose parts the caller has tied to the
+    oracle; at small sizes the fused call is compared with the oracle itself)."""
+    import torch
+    import paper_2401_18079_amd as K
+    Hq = gc.c.n_q_heads
+    probs = torch.zeros((Hq, cap), device="cuda")
+    out = torch.zeros((Hq, 128), device="cuda")
+    ws = torch.zeros(K.binding.kvq_softmax_workspace_bytes(Hq, cap), dtype=torch.uint8, device="cuda")
+    K.kvq_softmax_f32(scores, probs, Ln, ws)
+    K.kvq_pv_matvec(gc, probs, out)
+    fscores = torch.zeros((Hq, cap), device="cuda")
+    fout = torch.zeros((Hq, 128), device="cuda")
+    K.kvq_attention_decode(gc, torch.from_numpy(q).cuda(), scale, fscores, fout)
+    assert torch.equal(fscores[:, :Ln], scores[:, :Ln])
+    ok, worst = matvec_close(fout.cpu().numpy(), out.cpu().numpy(), rel=2e-5)
+    assert ok, f"fused against separate calls: worst error / bound = {worst:.3f}"
+
+
 def test_c2_full_context_sampled_parity():
     import torch
     import paper_2401_18079_amd as K
@@ -125,6 +145,8 @@ def test_c2_full_context_sampled_parity():
     K.kvq_pv_matvec(gc, pa, oa); K.kvq_pv_matvec(gc, pb, ob); K.kvq_pv_matvec(gc, pa + pb, oab)
     assert torch.allclose(oab, oa + ob, rtol=1e-4, atol=1e-6)
 
+    _check_fused_against_separate_calls(gc, q, float(scale), scores, Ln=L, cap=cap)
+
 
 def test_c3_million_token_context_sampled_parity():
     """Configuration 3 at its full size (context 1,048,576 + a ragged tail, nuq4, 0.1 % outliers): every
@@ -201,3 +223,4 @@ def test_c3_million_token_context_sampled_parity():
     K.kvq_pv_matvec(gc, pfull, out)
     ok, worst = matvec_close(out.cpu().numpy(), ref_out.astype(np.float32))
     assert ok, f"outputs: worst error / bound = {worst:.3f}"
+    _check_fused_against_separate_calls(gc, q, float(scale), scores, Ln=Lc, cap=cap)
