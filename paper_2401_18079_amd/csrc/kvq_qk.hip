@@ -300,12 +300,15 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
         const int lane_id = tid & 63;
         const float nf = (float)lane_id;
         const float wave_base = rope_rev((float)(n - lane_id), my_vh, my_vl);
+        // the sparse part of the scores: requested before the tile's arithmetic and consumed after it
+        // when the registers allow; with eight query heads per thread they do not, and the loads wait
+        // until the arithmetic is done (other wavefronts cover the latency)
+        constexpr bool PREV_EARLY = QH < 8;
         float acc[QH], prev[QH];
 #pragma unroll
         for (int qh = 0; qh < QH; ++qh) {
             acc[qh] = 0.f;
-            // requested now, consumed after the tile's arithmetic
-            prev[qh] = (add_prev && valid) ? scores[(int64_t)(q0 + qh) * ld + n] : 0.f;
+            if (PREV_EARLY) prev[qh] = (add_prev && valid) ? scores[(int64_t)(q0 + qh) * ld + n] : 0.f;
         }
         // lanes past the end run the arithmetic on whatever their registers hold (table offsets are
         // masked, so every gather stays inside the table) and simply skip loads and stores
@@ -324,6 +327,13 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
                     const uint4 v = *(const uint4 *)(next_chunk + g * plane + 1024);
                     W[g][4] = v.x; W[g][5] = v.y; W[g][6] = v.z; W[g][7] = v.w;
                 }
+            }
+        }
+        if (!PREV_EARLY) {
+#pragma unroll
+            for (int qh = 0; qh < QH; ++qh) {
+                asm volatile("" : "+v"(acc[qh]));      // keeps the loads below the arithmetic
+                prev[qh] = (add_prev && valid) ? scores[(int64_t)(q0 + qh) * ld + n] : 0.f;
             }
         }
         if (valid) {
