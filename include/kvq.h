@@ -139,6 +139,16 @@ kvq_status kvq_quantize_append_k(kvq_cache *cache, const uint16_t *d_k_new, int3
 kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_v_new, int32_t T, void *stream);
 
 /*
+ * Both appends of a decode step in one call and, for the quantization itself, one kernel launch:
+ * exactly kvq_quantize_append_k(cache, d_k_new, T) followed by kvq_quantize_append_v(cache, d_v_new, T)
+ * (paper Sec. 3.1-3.4, 3.6 as above), with the workgroups of the two running side by side: a
+ * single-token append is latency-bound and the two do not depend on each other.  The checks of both
+ * calls are made before anything is launched; n_tokens_k and n_tokens_v both advance by T.
+ */
+kvq_status kvq_quantize_append_kv(kvq_cache *cache, const uint16_t *d_k_new, const uint16_t *d_v_new,
+                                  int32_t T, void *stream);
+
+/*
  * Attention scores against the quantized Keys, dense and sparse parts merged in one result
  * (paper Sec. 3.2 and App. "RoPE Equation": the rotation of position n is applied to the
  * de-quantised Key; App. "Kernel Implementation Details": LUT mat-vec plus sparse mat-vec):

@@ -56,6 +56,7 @@ def load_library():
         "kvq_lut_load": (C.c_int, [P, V, V, V, V, V, V, V]),
         "kvq_quantize_append_k": (C.c_int, [P, V, I32, V]),
         "kvq_quantize_append_v": (C.c_int, [P, V, I32, V]),
+        "kvq_quantize_append_kv": (C.c_int, [P, V, V, I32, V]),
         "kvq_qk_matvec": (C.c_int, [P, V, F, V, I64, V]),
         "kvq_pv_matvec": (C.c_int, [P, V, I64, V, V]),
         "kvq_attention_decode": (C.c_int, [P, V, F, V, I64, V, V]),
@@ -80,7 +81,8 @@ def load_library():
 
 EXPORTED_SYMBOLS = [
     "kvq_codes_bytes", "kvq_params_bytes", "kvq_workspace_bytes", "kvq_status_string", "kvq_version",
-    "kvq_lut_load", "kvq_quantize_append_k", "kvq_quantize_append_v", "kvq_qk_matvec", "kvq_pv_matvec",
+    "kvq_lut_load", "kvq_quantize_append_k", "kvq_quantize_append_v", "kvq_quantize_append_kv",
+    "kvq_qk_matvec", "kvq_pv_matvec",
     "kvq_attention_decode", "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
     "kvq_fp16_pv_matvec", "kvq_event_create", "kvq_event_record", "kvq_event_elapsed_ms", "kvq_event_destroy",
     "kvq_profile_enable", "kvq_profile_last_ms",
@@ -209,6 +211,13 @@ def kvq_quantize_append_v(cache: KvqCache, v_new: torch.Tensor, stream=None):
     x = _fp16_rows(cache, v_new)
     _check(load_library().kvq_quantize_append_v(C.byref(cache.c), x.data_ptr(), x.shape[0], _stream_ptr(stream)),
            "kvq_quantize_append_v")
+
+
+def kvq_quantize_append_kv(cache: KvqCache, k_new: torch.Tensor, v_new: torch.Tensor, stream=None):
+    xk, xv = _fp16_rows(cache, k_new), _fp16_rows(cache, v_new)
+    assert xk.shape[0] == xv.shape[0]
+    _check(load_library().kvq_quantize_append_kv(C.byref(cache.c), xk.data_ptr(), xv.data_ptr(), xk.shape[0],
+                                                 _stream_ptr(stream)), "kvq_quantize_append_kv")
 
 
 def kvq_qk_matvec(cache: KvqCache, q_rot: torch.Tensor, scale: float, scores: torch.Tensor, stream=None):

@@ -139,12 +139,13 @@ __device__ inline uint32_t block_rank_multi(const bool (&flag)[IT], uint32_t (&r
 // filled by kvq_ptr_scan and is only read.
 // A pass handles IT blocks of NT channels: all its loads are issued up front, and ranks, packing and
 // stores of the IT blocks share one set of barriers (a single-token decode append is pure latency).
+// (The body of the kernels below: `t` is the token's index within the call.)
 template <int BITS, int NT>
-__global__ __launch_bounds__(NT) void kvq_k_quant(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
-                                                  const uint16_t *__restrict__ k_new, uint8_t *__restrict__ k_codes,
-                                                  uint32_t *__restrict__ k_ptr, uint16_t *__restrict__ k_idx,
-                                                  uint16_t *__restrict__ k_val, int64_t cap_nnz, int single,
-                                                  int32_t *d_status)
+__device__ __forceinline__ void k_quant_token(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
+                                              const uint16_t *__restrict__ k_new, uint8_t *__restrict__ k_codes,
+                                              uint32_t *__restrict__ k_ptr, uint16_t *__restrict__ k_idx,
+                                              uint16_t *__restrict__ k_val, int64_t cap_nnz, int single,
+                                              int32_t *d_status, const int t)
 {
     constexpr int NE = 1 << BITS;
     constexpr int CW = 4 * BITS;                 // dwords per chunk
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(NT) void kvq_k_quant(const void *__restrict__ param
 #pragma unroll
     for (int j = 0; j < NE; ++j) lut[j] = pv.hdr->lut_k[j];
 
-    const int t = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const int64_t n = n0 + t;
     const uint32_t base = k_ptr[n];
     uint32_t running = 0;
@@ -421,13 +422,15 @@ __device__ bool select_both(const uint16_t *keys, uint8_t *state, int D, int k, 
     return true;
 }
 
-// A pass of the main loop handles IT blocks of NT channels (see kvq_k_quant).
+// Quantize, pack and append the Values of one new token per workgroup (`t`: the token's index within
+// the call).  A pass of the main loop handles IT blocks of NT channels (see k_quant_token).
 template <int BITS, int NT>
-__global__ __launch_bounds__(NT) void kvq_v_quant(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
-                                                  int k_side, const uint16_t *__restrict__ v_new,
-                                                  uint8_t *__restrict__ v_codes, uint16_t *__restrict__ v_sz,
-                                                  uint32_t *__restrict__ v_ptr, uint16_t *__restrict__ v_idx,
-                                                  uint16_t *__restrict__ v_val, int64_t cap_nnz, int32_t *d_status)
+__device__ __forceinline__ void v_quant_token(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
+                                              int k_side, const uint16_t *__restrict__ v_new,
+                                              uint8_t *__restrict__ v_codes, uint16_t *__restrict__ v_sz,
+                                              uint32_t *__restrict__ v_ptr, uint16_t *__restrict__ v_idx,
+                                              uint16_t *__restrict__ v_val, int64_t cap_nnz, int32_t *d_status,
+                                              const int t)
 {
     constexpr int NE = 1 << BITS;
     constexpr int CW = 4 * BITS;
@@ -448,7 +451,7 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *__restrict__ param
     float lut[NE];
 #pragma unroll
     for (int j = 0; j < NE; ++j) lut[j] = pv.hdr->lut_v[j];
-    const int t = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const int64_t n = n0 + t;
     const uint16_t *x16 = v_new + (int64_t)t * D;
     const uint32_t base = v_ptr[n0] + (uint32_t)t * 2u * (uint32_t)k_side;
@@ -568,6 +571,53 @@ __global__ __launch_bounds__(NT) void kvq_v_quant(const void *__restrict__ param
     if (overflow) atomicExch(d_status, (int32_t)KVQ_ERR_NNZ_OVERFLOW);
 }
 
+template <int BITS, int NT>
+__global__ __launch_bounds__(NT) void kvq_k_quant(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
+                                                  const uint16_t *__restrict__ k_new, uint8_t *__restrict__ k_codes,
+                                                  uint32_t *__restrict__ k_ptr, uint16_t *__restrict__ k_idx,
+                                                  uint16_t *__restrict__ k_val, int64_t cap_nnz, int single,
+                                                  int32_t *d_status)
+{
+    k_quant_token<BITS, NT>(params, D, cap, n0, k_new, k_codes, k_ptr, k_idx, k_val, cap_nnz, single, d_status,
+                            (int)blockIdx.x);
+}
+
+template <int BITS, int NT>
+__global__ __launch_bounds__(NT) void kvq_v_quant(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
+                                                  int k_side, const uint16_t *__restrict__ v_new,
+                                                  uint8_t *__restrict__ v_codes, uint16_t *__restrict__ v_sz,
+                                                  uint32_t *__restrict__ v_ptr, uint16_t *__restrict__ v_idx,
+                                                  uint16_t *__restrict__ v_val, int64_t cap_nnz, int32_t *d_status)
+{
+    v_quant_token<BITS, NT>(params, D, cap, n0, k_side, v_new, v_codes, v_sz, v_ptr, v_idx, v_val, cap_nnz, d_status,
+                            (int)blockIdx.x);
+}
+
+// Keys and Values of the same tokens in one launch: even workgroups take a token's Keys, odd ones its
+// Values (a single-token append is pure latency, and the two do not depend on each other).
+struct KvAppendArgs {
+    const void *params;
+    int D, k_side, single;
+    int64_t cap, n0_k, n0_v, cap_nnz_k, cap_nnz_v;
+    const uint16_t *k_new, *v_new;
+    uint8_t *k_codes, *v_codes;
+    uint16_t *v_sz;
+    uint32_t *k_ptr, *v_ptr;
+    uint16_t *k_idx, *k_val, *v_idx, *v_val;
+    int32_t *d_status;
+};
+template <int BITS, int NT>
+__global__ __launch_bounds__(NT) void kvq_kv_quant(const KvAppendArgs a)
+{
+    const int t = (int)(blockIdx.x >> 1);
+    if ((blockIdx.x & 1) == 0)
+        k_quant_token<BITS, NT>(a.params, a.D, a.cap, a.n0_k, a.k_new, a.k_codes, a.k_ptr, a.k_idx, a.k_val, a.cap_nnz_k,
+                                a.single, a.d_status, t);
+    else
+        v_quant_token<BITS, NT>(a.params, a.D, a.cap, a.n0_v, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, a.v_idx,
+                                a.v_val, a.cap_nnz_v, a.d_status, t);
+}
+
 }  // namespace
 
 // The first n_sink tokens are also kept as they came (paper Sec. 3.5): copy their rows.
@@ -656,6 +706,54 @@ extern "C" kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_
     KVQ_HIP_CHECK(hipGetLastError());
     st = copy_sink_rows(cache, cache->sink_v, d_v_new, cache->n_tokens_v, T, s);
     if (st != KVQ_OK) return st;
+    cache->n_tokens_v += T;
+    return KVQ_OK;
+}
+
+extern "C" kvq_status kvq_quantize_append_kv(kvq_cache *cache, const uint16_t *d_k_new, const uint16_t *d_v_new,
+                                             int32_t T, void *stream)
+{
+    kvq_status st = append_checks(cache, d_k_new, T, cache ? cache->n_tokens_k : 0);
+    if (st != KVQ_OK) return st;
+    st = append_checks(cache, d_v_new, T, cache->n_tokens_v);
+    if (st != KVQ_OK) return st;
+    const int D = cache->n_kv_heads * KVQ_HEAD_DIM;
+    if (cache->k_side_v < 0 || 2 * (int64_t)cache->k_side_v >= D) return KVQ_ERR_INVALID_ARG;
+    if (D > 16384) return KVQ_ERR_UNSUPPORTED;       // the per-token Value selection keeps the vector in LDS
+    hipStream_t s = (hipStream_t)stream;
+    const int single = (T == 1);
+    if (!single) {
+        if (!cache->workspace || cache->workspace_bytes < (int64_t)T * 4) return KVQ_ERR_CAPACITY;
+        uint32_t *cnt = (uint32_t *)cache->workspace;
+        if (D >= 2048) kvq_k_count<1024><<<T, 1024, 0, s>>>(cache->params, D, d_k_new, cnt);
+        else kvq_k_count<256><<<T, 256, 0, s>>>(cache->params, D, d_k_new, cnt);
+        kvq_ptr_scan<<<1, 1024, 0, s>>>(cache->k_ptr, cache->n_tokens_k, T, cnt, cache->cap_nnz_k, cache->d_status);
+    }
+    KvAppendArgs a;
+    a.params = cache->params; a.D = D; a.k_side = cache->k_side_v; a.single = single;
+    a.cap = cache->cap_tokens; a.n0_k = cache->n_tokens_k; a.n0_v = cache->n_tokens_v;
+    a.cap_nnz_k = cache->cap_nnz_k; a.cap_nnz_v = cache->cap_nnz_v;
+    a.k_new = d_k_new; a.v_new = d_v_new;
+    a.k_codes = cache->k_codes; a.v_codes = cache->v_codes; a.v_sz = cache->v_sz;
+    a.k_ptr = cache->k_ptr; a.v_ptr = cache->v_ptr;
+    a.k_idx = cache->k_idx; a.k_val = cache->k_val; a.v_idx = cache->v_idx; a.v_val = cache->v_val;
+    a.d_status = cache->d_status;
+    const size_t dyn = 3 * (size_t)D;
+#define LAUNCH_KV(B)                                                                     \
+    do {                                                                                 \
+        if (D >= 2048) kvq_kv_quant<B, 1024><<<2 * T, 1024, dyn, s>>>(a);                \
+        else kvq_kv_quant<B, 256><<<2 * T, 256, dyn, s>>>(a);                            \
+    } while (0)
+    if (cache->bits == 2) LAUNCH_KV(2);
+    else if (cache->bits == 3) LAUNCH_KV(3);
+    else LAUNCH_KV(4);
+#undef LAUNCH_KV
+    KVQ_HIP_CHECK(hipGetLastError());
+    st = copy_sink_rows(cache, cache->sink_k, d_k_new, cache->n_tokens_k, T, s);
+    if (st != KVQ_OK) return st;
+    st = copy_sink_rows(cache, cache->sink_v, d_v_new, cache->n_tokens_v, T, s);
+    if (st != KVQ_OK) return st;
+    cache->n_tokens_k += T;
     cache->n_tokens_v += T;
     return KVQ_OK;
 }
