@@ -220,6 +220,34 @@ def calibrate_k(w: Workload, layer: int = 0, n_cal: int = 4096, profile=None):
     return s, z, lo.astype(np.float16), hi.astype(np.float16)
 
 
+T_CALX, T_CALW = 9, 10
+
+
+def gen_calibration(seed: int, n: int, layer: int = 0):
+    """Stand-in for the inputs of the offline datatype derivation: n normalised calibration
+    activations in [-1, 1] and their sensitivity weights (Fisher information times squared scale).
+
+    Values: bell-shaped, with a width that depends on the element's channel (i mod 128), clipped to
+    [-1, 1]; one element in 257 sits exactly on an end of the range (every normalised vector touches
+    both ends).  Weights: log-normal times a per-channel factor, one in 64 exactly zero (elements
+    the loss does not depend on).  Both fp32; element i depends on (seed, layer, i) only."""
+    i = np.arange(n, dtype=_U64)
+    key = _U64(seed) ^ (_U64(layer) << _U64(48))
+    hx = splitmix64(key ^ (_U64(T_CALX) << _U64(56)) ^ i)
+    hw = splitmix64(key ^ (_U64(T_CALW) << _U64(56)) ^ i)
+    ch = (i % _U64(128)).astype(np.int64)
+    width = (np.float32(0.18) + np.float32(0.30) * ((ch * 37) % 128).astype(np.float32) / np.float32(128.0))
+    x = np.clip(normalish(hx).reshape(-1) * width, -1.0, 1.0).astype(np.float32)
+    h2 = splitmix64(hx)
+    end = (h2 % _U64(257)) == 0
+    x = np.where(end, np.where((h2 >> _U64(20)) & _U64(1), np.float32(1.0), np.float32(-1.0)), x).astype(np.float32)
+    g = normalish(hw).reshape(-1)
+    chan = (np.float32(0.25) + ((ch * 53) % 128).astype(np.float32) / np.float32(64.0)) ** 2
+    w = (np.exp(np.float32(1.5) * g).astype(np.float32) * chan.astype(np.float32)).astype(np.float32)
+    w = np.where((splitmix64(hw) % _U64(64)) == 0, np.float32(0.0), w).astype(np.float32)
+    return x, w
+
+
 class LayerInputs:
     """Everything one synthetic attention layer feeds the method with: look-up tables, per-channel Key
     calibration constants, the Value outlier count per side, and the token generators."""
