@@ -206,6 +206,25 @@ kvq_status kvq_softmax_f32(const float *d_x, int64_t ld_x, float *d_probs, int64
                            void *stream);
 
 /*
+ * Offline derivation of the non-uniform datatype of one Key or Value layer (paper Sec. 3.3, Eq. (1),
+ * with the weighting of the appendix on per-channel scaling): Lloyd's k-means iteration in one
+ * dimension for the 2^bits signposts c that minimise  sum_i w[i] * (x[i] - nearest_c(x[i]))^2.
+ *   d_x_norm   : DEVICE fp32 [n], calibration activations normalised per vector to [-1, 1].
+ *   d_w        : DEVICE fp32 [n], w[i] = F_ii * s_i^2 >= 0 (Fisher information times squared scale).
+ *   h_signposts: HOST fp32 [2^bits]; in: initial signposts, out: the signposts after `iters`
+ *                iterations, sorted ascending.  The call synchronizes the stream before returning.
+ *   d_workspace: DEVICE, 256-byte aligned, at least kvq_calibrate_workspace_bytes() bytes.
+ * An iteration assigns every element to its nearest signpost (fp32 distances, ties to the smaller
+ * index) and moves every signpost to the weighted mean of its elements (fp64 sums in a fixed order,
+ * rounded to fp32); a signpost whose elements have total weight zero stays.  Both arrays 16-byte
+ * aligned, n >= 1, iters >= 0.  Errors: INVALID_ARG, UNSUPPORTED (bits), CAPACITY (workspace), HIP.
+ */
+int64_t kvq_calibrate_workspace_bytes(void);
+kvq_status kvq_calibrate_nuq(const float *d_x_norm, const float *d_w, int64_t n, int32_t bits,
+                             int32_t iters, float *h_signposts, void *d_workspace,
+                             int64_t workspace_bytes, void *stream);
+
+/*
  * Same-GPU fp16-cache baselines (what the quantized path is compared against):
  *   scores[q][n] = scale * sum_c q[q][c] * K16[n][kv(q)*128+c]   (K16 fp16 [L][D], already rotated)
  *   out[q][c]    = sum_n probs[q][n] * V16[n][kv(q)*128+c]

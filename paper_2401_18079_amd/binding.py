@@ -62,6 +62,8 @@ def load_library():
         "kvq_attention_decode": (C.c_int, [P, V, F, V, I64, V, V]),
         "kvq_softmax_workspace_bytes": (I64, [I32, I64]),
         "kvq_softmax_f32": (C.c_int, [V, I64, V, I64, I32, I64, V, I64, V]),
+        "kvq_calibrate_workspace_bytes": (I64, []),
+        "kvq_calibrate_nuq": (C.c_int, [V, V, I64, I32, I32, V, V, I64, V]),
         "kvq_fp16_qk_matvec": (C.c_int, [V, I64, I32, I32, V, F, V, I64, V]),
         "kvq_fp16_pv_workspace_bytes": (I64, [I32, I64]),
         "kvq_fp16_pv_matvec": (C.c_int, [V, I64, I32, I32, V, I64, V, V, I64, V]),
@@ -85,7 +87,7 @@ EXPORTED_SYMBOLS = [
     "kvq_qk_matvec", "kvq_pv_matvec",
     "kvq_attention_decode", "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
     "kvq_fp16_pv_matvec", "kvq_event_create", "kvq_event_record", "kvq_event_elapsed_ms", "kvq_event_destroy",
-    "kvq_profile_enable", "kvq_profile_last_ms",
+    "kvq_profile_enable", "kvq_profile_last_ms", "kvq_calibrate_workspace_bytes", "kvq_calibrate_nuq",
 ]
 
 
@@ -253,6 +255,20 @@ def kvq_softmax_f32(x: torch.Tensor, probs: torch.Tensor, n_cols: int, workspace
     _check(load_library().kvq_softmax_f32(x.data_ptr(), x.stride(0), probs.data_ptr(), probs.stride(0), x.shape[0],
                                           int(n_cols), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                           _stream_ptr(stream)), "kvq_softmax_f32")
+
+
+def kvq_calibrate_nuq(x_norm: torch.Tensor, w: torch.Tensor, bits: int, iters: int, init, stream=None) -> np.ndarray:
+    """Signposts of the non-uniform datatype from normalised calibration values and their weights."""
+    assert x_norm.is_cuda and w.is_cuda and x_norm.dtype == torch.float32 and w.dtype == torch.float32
+    assert x_norm.dim() == 1 and x_norm.is_contiguous() and w.is_contiguous() and w.shape == x_norm.shape
+    lib = load_library()
+    c = np.ascontiguousarray(np.asarray(init, dtype=np.float32).copy())
+    assert c.shape == (1 << bits,)
+    ws = torch.empty(int(lib.kvq_calibrate_workspace_bytes()), dtype=torch.uint8, device=x_norm.device)
+    _check(lib.kvq_calibrate_nuq(x_norm.data_ptr(), w.data_ptr(), x_norm.numel(), int(bits), int(iters),
+                                 c.ctypes.data_as(C.c_void_p), ws.data_ptr(), ws.numel(), _stream_ptr(stream)),
+           "kvq_calibrate_nuq")
+    return c
 
 
 def kvq_softmax_workspace_bytes(n_rows: int, n_cols: int) -> int:

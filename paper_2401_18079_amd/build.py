@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvq.so")
-SOURCES = ["kvq_params.hip", "kvq_append.hip", "kvq_qk.hip", "kvq_pv.hip", "kvq_attention.hip", "kvq_softmax.hip",
+SOURCES = ["kvq_params.hip", "kvq_append.hip", "kvq_qk.hip", "kvq_pv.hip", "kvq_attention.hip", "kvq_softmax.hip", "kvq_calib.hip",
            "kvq_fp16_baseline.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-ffp-contract=off",
