@@ -64,6 +64,20 @@ def bulk_append_rate(st, dg, K, torch, T=4096, calls=4):
             "input_gbps": 2 * T * wl.D * 2 / (best * 1e-6) / 1e9}
 
 
+def calibration_rate(bits, K, torch, n=1 << 26, iters=10):
+    """Offline datatype derivation (weighted k-means over n normalised values and weights resident in
+    HBM): time per iteration and the rate at which an iteration streams its 8 bytes per element."""
+    x = torch.empty(n, device="cuda").normal_(0, 0.3).clamp_(-1, 1)
+    w = torch.empty(n, device="cuda").log_normal_(0, 1.5)
+    c0 = np.linspace(-1, 1, 1 << bits).astype(np.float32)
+    K.kvq_calibrate_nuq(x, w, bits, 1, c0)                 # warm-up
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    K.kvq_calibrate_nuq(x, w, bits, iters, c0)             # synchronizes before it returns
+    dt = (time.perf_counter() - t) / iters
+    return {"elements": n, "bits": bits, "us_per_iteration": dt * 1e6, "gbps": 8 * n / dt / 1e9}
+
+
 def algorithmic_bytes(wl, L, nnz_k, nnz_v):
     """Bytes the method must move per launch (compressed cache + outputs), not the fp16 bytes it avoids."""
     D, Hq, b = wl.D, wl.n_q_heads, wl.bits
@@ -285,6 +299,7 @@ def main():
         del src, dst
 
     bulk = bulk_append_rate(st, dg, K, torch)
+    calib = calibration_rate(wl.bits, K, torch)
 
     cpu = None
     if args.cpu_sample > 0:
@@ -339,6 +354,7 @@ def main():
         "qk_pv_us": breakdown["qk_matvec"] + breakdown["pv_matvec"],
         "hbm_gbps": {"qk_matvec": qk_gbps, "pv_matvec": pv_gbps},
         "bulk_append": bulk,
+        "calibration": calib,
         "fp16_cache_baseline": fp16,
         "speedup_vs_fp16": ({"qk": fp16["qk_us"] / breakdown["qk_matvec"], "pv": fp16["pv_us"] / breakdown["pv_matvec"]}
                             if fp16 else None),
