@@ -107,6 +107,17 @@ def test_fused_decode_matches_oracle_chain(name, ov, n_sink, L, chunks):
     _check_fused(st, oc, gc, L)
 
 
+@pytest.mark.parametrize("n_sink", [0, 3])
+def test_fused_decode_with_more_than_64_maxima_per_head(n_sink):
+    """Four heads in one head group and 69 tiles of 1024 tokens: the dense Key kernel runs 69 workgroups
+    per head, so every consumer merges more score maxima than a wavefront has lanes."""
+    wl = S.workload("c2", n_kv_heads=4, n_q_heads=4)
+    st = Setup(wl)
+    L = 69 * 1024 + 77
+    oc, gc = _pair(st, 70 * 1024, n_sink, L, [4096])
+    _check_fused(st, oc, gc, L, steps=1)
+
+
 @pytest.mark.parametrize("n_sink", [0, 2])
 def test_fused_decode_with_large_scores(n_sink):
     """Scores of magnitude in the hundreds: exp overflows fp32 unless the maximum is subtracted, and
