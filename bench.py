@@ -125,6 +125,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--context", type=int, default=0, help="override the context length")
+    ap.add_argument("--bits", type=int, default=0, help="override the code width (2, 3 or 4)")
+    ap.add_argument("--outliers", type=float, default=-1.0, help="override the outlier fraction (e.g. 0.01)")
     ap.add_argument("--cpu-sample", type=int, default=4096, help="tokens of context for the CPU-oracle timing (0 = skip)")
     ap.add_argument("--no-fp16", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -138,9 +140,14 @@ def main():
     import kvq_synth as S
     import paper_2401_18079_amd as K
 
-    wl = S.workload(args.workload)
+    over = {}
     if args.context:
-        wl = S.workload(args.workload, context=args.context)
+        over["context"] = args.context
+    if args.bits:
+        over["bits"] = args.bits
+    if args.outliers >= 0:
+        over["outlier_fraction"] = args.outliers
+    wl = S.workload(args.workload, **over)
     st = S.LayerInputs(wl)
     L = wl.context
     steps, warmup = args.steps, args.warmup
@@ -316,7 +323,7 @@ def main():
     # (FETCH_SIZE / WRITE_SIZE scaled by a known-size copy), kept as a text summary under profiles/
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"kvq_qk_kernel_{wl.name}_hbm_traffic.txt")
-    if os.path.exists(tpath) and not args.context:
+    if os.path.exists(tpath) and not over:
         for ln in open(tpath):
             if ln.startswith("dense_kernel_traffic_bytes_per_launch:"):
                 traffic = float(ln.split(":")[1])
@@ -325,7 +332,7 @@ def main():
     # launch from the rocprofv3 SQ_INSTS_VALU run of this command, kept under profiles/
     valu = None
     vpath = os.path.join(ROOT, "profiles", f"bench_{wl.name}_valu_issue.txt")
-    if os.path.exists(vpath) and not args.context:
+    if os.path.exists(vpath) and not over:
         kv = {}
         for ln in open(vpath):
             if ":" in ln and ln.split(":")[0] in ("qk_valu_issue_slots_per_launch", "valu_issue_peak_slots_per_s"):

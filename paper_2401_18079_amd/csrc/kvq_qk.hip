@@ -628,8 +628,27 @@ kvq_status dispatch_qk(const kvq_cache *c, const float *q, float scale, float *s
         return launch_qk<BITS, 1, QHMAX, 1024, PG, R>(c, q, scale, scores, ld, st, n_stat, s);
     } else {
         constexpr int KVH = QHMAX / R;
-        if (c->n_kv_heads % KVH == 0) return launch_qk<BITS, KVH, R, 1024, PG, R>(c, q, scale, scores, ld, st, n_stat, s);
-        // few KV heads: one per workgroup
+        // Many heads per workgroup share the rotary sines and cosines but need a long context to keep
+        // the chip busy (a workgroup builds its tables once, then takes tiles of 1024 tokens).  With a
+        // shorter context that leaves most compute units idle: half as many heads per workgroup and
+        // tiles of 512 tokens give four times as many workgroups (two fit a compute unit), one KV head
+        // per workgroup 2 * KVH times as many.  The largest grouping that still yields 160 workgroups
+        // is taken.
+        const int64_t L = c->n_tokens_k;
+        auto workgroups = [&](int kvh, int nt) {
+            const int64_t groups = c->n_kv_heads / kvh, tiles = (L + nt - 1) / nt;
+            int64_t gx = 256 / groups;
+            if (gx < 1) gx = 1;
+            if (gx > tiles) gx = tiles;
+            return gx * groups;
+        };
+        if (c->n_kv_heads % KVH == 0 && workgroups(KVH, 1024) >= 160)
+            return launch_qk<BITS, KVH, R, 1024, PG, R>(c, q, scale, scores, ld, st, n_stat, s);
+        if constexpr (KVH >= 4) {
+            if (c->n_kv_heads % (KVH / 2) == 0 && workgroups(KVH / 2, 512) >= 160)
+                return launch_qk<BITS, KVH / 2, R, 512, PG, R>(c, q, scale, scores, ld, st, n_stat, s);
+        }
+        // few KV heads or a short context: one KV head per workgroup
         return launch_qk<BITS, 1, R, 512, PG, R>(c, q, scale, scores, ld, st, n_stat, s);
     }
 }

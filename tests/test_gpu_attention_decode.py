@@ -118,6 +118,18 @@ def test_fused_decode_with_more_than_64_maxima_per_head(n_sink):
     _check_fused(st, oc, gc, L, steps=1)
 
 
+@pytest.mark.parametrize("name,L", [("c2", 6000), ("c3", 10500)])
+def test_mid_context_uses_the_half_size_head_groups(name, L):
+    """Full-width layers (32 heads) at contexts of a few thousand tokens: too short for the widest
+    head grouping of the dense Key kernel, long enough for the one with half as many heads per
+    workgroup and tiles of 512 tokens (3-bit from 5K tokens, 4-bit from 10K)."""
+    wl = S.workload(name)
+    st = Setup(wl)
+    cap = (L + 127) // 128 * 128 + 128
+    oc, gc = _pair(st, cap, 0, L, [4096])
+    _check_fused(st, oc, gc, L, steps=1)
+
+
 @pytest.mark.parametrize("n_sink", [0, 2])
 def test_fused_decode_with_large_scores(n_sink):
     """Scores of magnitude in the hundreds: exp overflows fp32 unless the maximum is subtracted, and
