@@ -118,6 +118,67 @@ def cpu_baseline(st, sample_tokens):
     return tq, float(np.median(times)), O.max_threads(), float(out[0, 0])
 
 
+def model_step(args, wl, S, K, torch):
+    """`--layers N`: one decode step of N attention layers, each with its own cache, look-up tables and
+    per-channel constants (the full-model configuration: 32 layers at a context of 2^20 tokens keep
+    ~110 GB of compressed cache resident).  Per layer: kvq_quantize_append_kv + kvq_attention_decode."""
+    L, steps, warmup, n_layers = wl.context, args.steps, args.warmup, args.layers
+    n_new = steps + warmup
+    cap = ((L + n_new + 8 + 127) // 128) * 128
+    Hq = wl.n_q_heads
+    scale = 1.0 / np.sqrt(128.0)
+    caches, new_k, new_v = [], [], []
+    t0 = time.perf_counter()
+    for layer in range(n_layers):
+        st = S.LayerInputs(wl, layer)
+        gc, dg, _, _ = build_cache(st, L, cap, K, torch)
+        assert gc.status() == 0
+        caches.append(gc)
+        new_k.append(dg.k(L, n_new))
+        new_v.append(dg.v(L, n_new))
+    torch.cuda.synchronize()
+    build_s = time.perf_counter() - t0
+    qs = torch.from_numpy(np.stack([S.gen_q(wl, 0, 0, step=i) for i in range(n_new)])).cuda()
+    scores = torch.zeros((Hq, cap), device="cuda")           # scratch shared by the layers
+    out = torch.zeros((n_layers, Hq, 128), device="cuda")
+
+    def step(i):
+        for layer, gc in enumerate(caches):
+            K.kvq_quantize_append_kv(gc, new_k[layer][i:i + 1], new_v[layer][i:i + 1])
+            K.kvq_attention_decode(gc, qs[i], scale, scores, out[layer])
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for i in range(steps):
+        step(warmup + i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t_begin) * 1e3 / steps
+    for gc in caches:
+        assert gc.status() == 0
+    tensors = ("params", "k_codes", "v_codes", "v_sz", "k_ptr", "v_ptr", "k_idx", "k_val", "v_idx", "v_val", "workspace")
+    resident = sum(getattr(gc, t).numel() * getattr(gc, t).element_size() for gc in caches for t in tensors)
+    gc = caches[0]
+    Lend = gc.n_tokens_k
+    nnz_k = int(gc.k_ptr[Lend].item()) & 0xFFFFFFFF
+    nnz_v = int(gc.v_ptr[Lend].item()) & 0xFFFFFFFF
+    qk_bytes, pv_bytes = algorithmic_bytes(wl, Lend, nnz_k, nnz_v)
+    line = {
+        "metric": "quantized-KV decode step latency over all layers (per layer: append K/V + QK^T + softmax + PV)",
+        "value": ms, "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {n_layers} layers x {wl.n_q_heads} q-heads x {wl.n_kv_heads} kv-heads x 128, "
+                               f"context {L}, batch 1, nuq{wl.bits} with {wl.outlier_fraction * 100:g}% outliers",
+                   "layers": n_layers, "bits": wl.bits, "context": L, "outlier_fraction": wl.outlier_fraction},
+        "us_per_layer": ms * 1e3 / n_layers,
+        "resident_cache_gb": resident / 1e9,
+        "cache_build_s": build_s,
+        "hbm_gbps_algorithmic": n_layers * (qk_bytes + pv_bytes) / (ms * 1e-3) / 1e9,
+    }
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -128,6 +189,8 @@ def main():
     ap.add_argument("--bits", type=int, default=0, help="override the code width (2, 3 or 4)")
     ap.add_argument("--outliers", type=float, default=-1.0, help="override the outlier fraction (e.g. 0.01)")
     ap.add_argument("--cpu-sample", type=int, default=4096, help="tokens of context for the CPU-oracle timing (0 = skip)")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="more than 1: time a decode step over that many layers (each its own cache), nothing else")
     ap.add_argument("--no-fp16", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy (known traffic) so profiler byte counters can be scaled")
@@ -148,6 +211,9 @@ def main():
     if args.outliers >= 0:
         over["outlier_fraction"] = args.outliers
     wl = S.workload(args.workload, **over)
+    if args.layers > 1:
+        model_step(args, wl, S, K, torch)
+        return
     st = S.LayerInputs(wl)
     L = wl.context
     steps, warmup = args.steps, args.warmup
