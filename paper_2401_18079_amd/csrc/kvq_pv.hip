@@ -95,10 +95,14 @@ __device__ inline uint32_t pv_field_off(const uint32_t *W, int i, uint32_t lane_
     return kvq_and_or(x, M, lane_off);
 }
 
-template <int BITS, int G0>
-__device__ __forceinline__ void pv_group(const uint32_t (&W)[4 * BITS], float (&acc)[64], const half2_t *ptab,
-                                         uint32_t lane_off, float w0, float w1)
+// One group of PV_FIELD_GROUP fields of a lane's slice.  RG query heads share the fields (grouped-query
+// attention): one extraction and one gather per field, two multiply-adds per field and head.
+// Accumulator of (head h, field i): acc[h * (64 / RG) + i].
+template <int BITS, int RG, int G0>
+__device__ __forceinline__ void pv_group(const uint32_t (&W)[4 * BITS / RG], float (&acc)[64], const half2_t *ptab,
+                                         uint32_t lane_off, const float (&w0)[RG], const float (&w1)[RG])
 {
+    constexpr int NF = 64 / RG;
     half2_t t[PV_FIELD_GROUP];
 #pragma unroll
     for (int k = 0; k < PV_FIELD_GROUP; ++k) {
@@ -108,30 +112,47 @@ __device__ __forceinline__ void pv_group(const uint32_t (&W)[4 * BITS], float (&
     // the two FMAs of a field depend on each other: issue the group's first halves, then its second
     // halves, so that no instruction waits for the one right before it
 #pragma unroll
-    for (int k = 0; k < PV_FIELD_GROUP; ++k)
-        acc[G0 * PV_FIELD_GROUP + k] = __builtin_fmaf((float)t[k].x, w0, acc[G0 * PV_FIELD_GROUP + k]);
+    for (int h = 0; h < RG; ++h)
 #pragma unroll
-    for (int k = 0; k < PV_FIELD_GROUP; ++k) asm volatile("" : "+v"(acc[G0 * PV_FIELD_GROUP + k]));
+        for (int k = 0; k < PV_FIELD_GROUP; ++k) {
+            float &a = acc[h * NF + G0 * PV_FIELD_GROUP + k];
+            a = __builtin_fmaf((float)t[k].x, w0[h], a);
+        }
 #pragma unroll
-    for (int k = 0; k < PV_FIELD_GROUP; ++k)
-        acc[G0 * PV_FIELD_GROUP + k] = __builtin_fmaf((float)t[k].y, w1, acc[G0 * PV_FIELD_GROUP + k]);
+    for (int h = 0; h < RG; ++h)
+#pragma unroll
+        for (int k = 0; k < PV_FIELD_GROUP; ++k) asm volatile("" : "+v"(acc[h * NF + G0 * PV_FIELD_GROUP + k]));
+#pragma unroll
+    for (int h = 0; h < RG; ++h)
+#pragma unroll
+        for (int k = 0; k < PV_FIELD_GROUP; ++k) {
+            float &a = acc[h * NF + G0 * PV_FIELD_GROUP + k];
+            a = __builtin_fmaf((float)t[k].y, w1[h], a);
+        }
     // an empty asm that "modifies" the group's accumulators and clobbers memory keeps the groups in
     // order (otherwise every gather of the tile is issued first and register pressure explodes)
 #pragma unroll
-    for (int k = 0; k < PV_FIELD_GROUP; ++k) asm volatile("" : "+v"(acc[G0 * PV_FIELD_GROUP + k]) : : "memory");
+    for (int h = 0; h < RG; ++h)
+#pragma unroll
+        for (int k = 0; k < PV_FIELD_GROUP; ++k)
+            asm volatile("" : "+v"(acc[h * NF + G0 * PV_FIELD_GROUP + k]) : : "memory");
 }
 
-template <int BITS, int... G>
-__device__ __forceinline__ void pv_all_fields(std::integer_sequence<int, G...>, const uint32_t (&W)[4 * BITS],
-                                              float (&acc)[64], const half2_t *ptab, uint32_t lane_off, float w0,
-                                              float w1)
+template <int BITS, int RG, int... G>
+__device__ __forceinline__ void pv_all_fields(std::integer_sequence<int, G...>, const uint32_t (&W)[4 * BITS / RG],
+                                              float (&acc)[64], const half2_t *ptab, uint32_t lane_off,
+                                              const float (&w0)[RG], const float (&w1)[RG])
 {
-    (pv_group<BITS, G>(W, acc, ptab, lane_off, w0, w1), ...);
+    (pv_group<BITS, RG, G>(W, acc, ptab, lane_off, w0, w1), ...);
 }
 
-// Dense part.  grid = (slabs, 2*Hq / 4); wavefront w of a workgroup owns combination blockIdx.y*4 + w
-// = query head * 2 + channel half.  Writes partial[slab][q][128] and zpart[slab][q].
-template <int BITS>
+// Dense part.  A wavefront owns one combination of (group of RG query heads that share a KV head,
+// 64-channel half, slice of 64/RG channels of that half): its lanes are token pairs and keep the
+// RG x 64/RG = 64 accumulators of their pair's fields.  RG = 1: one query head, the whole half.  With
+// grouped-query attention RG > 1 heads share every extraction and gather.  grid = (slabs, 2*Hq / 4):
+// wavefront w of a workgroup owns combination blockIdx.y*4 + w.  Writes partial[slab][q][128] and
+// zpart[slab][q].
+template <int BITS, int RG>
 __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ params, int D, int n_kv_heads,
                                                       int n_q_heads, int64_t cap, int64_t L,
                                                       const uint8_t *__restrict__ v_codes,
@@ -142,13 +163,15 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
                                                       const float *__restrict__ stat_slots, int n_stat,
                                                       float *__restrict__ lpart)
 {
-    // stat_slots != null: `probs` holds raw scores x; a wavefront takes the maximum m of its head's
-    // n_stat slots once, weights every token by exp(x - m) as it loads its score, and also writes the
-    // sum of these weights over its slab to lpart[slab][q] (the reduce kernel divides by their total)
     // tokens below n_sink are attention-sink tokens kept in fp16: their quantized form gets weight 0
-    // here and the reduce kernel adds their fp16 rows
+    // here and the reduce kernel adds their fp16 rows.
+    // stat_slots != null: `probs` holds raw scores x; a wavefront takes the maximum m of each of its
+    // heads' n_stat slots once, weights every token by exp(x - m) as it loads its score, and also writes
+    // the sum of these weights over its slab to lpart[slab][q] (the reduce kernel divides by their total)
     constexpr int NE2 = 1 << (2 * BITS);
-    constexpr int CW = 4 * BITS;
+    constexpr int NF = 64 / RG;                    // fields (channels) per lane and head
+    constexpr int ND = 4 * BITS / RG;              // dwords of a chunk that hold them
+    static_assert((4 * BITS) % RG == 0 && NF % PV_FIELD_GROUP == 0, "a slice is whole dwords and whole field groups");
     __shared__ __attribute__((aligned(16))) half2_t ptab[NE2 * 32];      // replicated pair table
     __shared__ float red[PV_WAVES][64][17];
     const KvqParamsView pv = kvq_params_view(params, D);
@@ -161,21 +184,24 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
 
     const int combo = blockIdx.y * PV_WAVES + wave;
     const bool active = combo < 2 * n_q_heads;
-    const int qh = active ? (combo >> 1) : 0, half = combo & 1;
-    const int kvh = qh / (n_q_heads / n_kv_heads);
+    const int slice = combo % RG, half = (combo / RG) & 1;
+    const int q0 = active ? (combo / (2 * RG)) * RG : 0;          // first query head of the group
+    const int kvh = q0 / (n_q_heads / n_kv_heads);
     const uint32_t lane_off = (uint32_t)(lane & 31) << 2;
-    const float *prow = probs + (int64_t)qh * ld;
-    float m2 = 0.f, lacc = 0.f;
-    if (stat_slots) {
-        float m = KVQ_STAT_FLOOR;
-        for (int i = lane; i < n_stat; i += 64) m = __builtin_fmaxf(m, stat_slots[(int64_t)qh * KVQ_STAT_SLOTS + i]);
-        m2 = kvq_wave_max(m) * KVQ_LOG2E;
+    float m2[RG], lacc[RG], zacc[RG];
+#pragma unroll
+    for (int h = 0; h < RG; ++h) {
+        m2[h] = 0.f; lacc[h] = 0.f; zacc[h] = 0.f;
+        if (stat_slots) {
+            float m = KVQ_STAT_FLOOR;
+            for (int i = lane; i < n_stat; i += 64) m = __builtin_fmaxf(m, stat_slots[(int64_t)(q0 + h) * KVQ_STAT_SLOTS + i]);
+            m2[h] = kvq_wave_max(m) * KVQ_LOG2E;
+        }
     }
 
     float acc[64];
 #pragma unroll
     for (int j = 0; j < 64; ++j) acc[j] = 0.f;
-    float zacc = 0.f;
 
     const int64_t tile0 = ((int64_t)blockIdx.x * n_tiles) / gridDim.x;
     const int64_t tile1 = ((int64_t)(blockIdx.x + 1) * n_tiles) / gridDim.x;
@@ -184,30 +210,48 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
             const int64_t m = t * 64 + lane;                // token pair
             const int64_t n0 = 2 * m;
             if (n0 >= L) continue;
-            uint32_t W[CW];
+            uint32_t W[ND];
             const uint8_t *p = v_codes + kvq_v_piece0(BITS, cap, m, kvh, half);
+            if constexpr (RG == 1) {
 #pragma unroll
-            for (int j = 0; j < BITS; ++j) {
-                const uint4 v = *(const uint4 *)(p + j * 1024);
-                W[4 * j + 0] = v.x; W[4 * j + 1] = v.y; W[4 * j + 2] = v.z; W[4 * j + 3] = v.w;
+                for (int j = 0; j < BITS; ++j) {
+                    const uint4 v = *(const uint4 *)(p + j * 1024);
+                    W[4 * j + 0] = v.x; W[4 * j + 1] = v.y; W[4 * j + 2] = v.z; W[4 * j + 3] = v.w;
+                }
+            } else {
+                // dword d of the chunk sits in 16-byte piece d / 4 (pieces are 1024 bytes apart)
+#pragma unroll
+                for (int j = 0; j < ND; ++j) {
+                    const int d = slice * ND + j;
+                    W[j] = *(const uint32_t *)(p + (d >> 2) * 1024 + (d & 3) * 4);
+                }
             }
             const uint2 sz = *(const uint2 *)(v_sz + n0 * 2);            // (s0, z0, s1, z1) fp16
-            float p0 = (n0 >= n_sink) ? prow[n0] : 0.f;
-            float p1 = (n0 + 1 < L && n0 + 1 >= n_sink) ? prow[n0 + 1] : 0.f;   // odd tail: second token absent
-            if (stat_slots) {
-                p0 = (n0 >= n_sink) ? kvq_stat_weight(p0, m2) : 0.f;
-                p1 = (n0 + 1 < L && n0 + 1 >= n_sink) ? kvq_stat_weight(p1, m2) : 0.f;
-                lacc += p0 + p1;
+            const bool ok0 = n0 >= n_sink, ok1 = n0 + 1 < L && n0 + 1 >= n_sink;   // odd tail: second token absent
+            const float s0 = kvq_h2f((uint16_t)(sz.x & 0xFFFFu)), z0 = kvq_h2f((uint16_t)(sz.x >> 16));
+            // (scale, zero-point) of an absent second token may be anything, NaN included
+            const float s1 = ok1 ? kvq_h2f((uint16_t)(sz.y & 0xFFFFu)) : 0.f, z1 = ok1 ? kvq_h2f((uint16_t)(sz.y >> 16)) : 0.f;
+            float w0[RG], w1[RG];
+#pragma unroll
+            for (int h = 0; h < RG; ++h) {
+                const float *prow = probs + (int64_t)(q0 + h) * ld;
+                float p0 = ok0 ? prow[n0] : 0.f;
+                float p1 = ok1 ? prow[n0 + 1] : 0.f;
+                if (stat_slots) {
+                    p0 = ok0 ? kvq_stat_weight(p0, m2[h]) : 0.f;
+                    p1 = ok1 ? kvq_stat_weight(p1, m2[h]) : 0.f;
+                    lacc[h] += p0 + p1;
+                }
+                w0[h] = p0 * s0;
+                w1[h] = p1 * s1;
+                zacc[h] = __builtin_fmaf(p0, z0, zacc[h]);
+                zacc[h] = __builtin_fmaf(p1, z1, zacc[h]);
             }
-            const float w0 = p0 * kvq_h2f((uint16_t)(sz.x & 0xFFFFu));
-            const float w1 = p1 * kvq_h2f((uint16_t)(sz.y & 0xFFFFu));
-            zacc = __builtin_fmaf(p0, kvq_h2f((uint16_t)(sz.x >> 16)), zacc);
-            zacc = __builtin_fmaf(p1, kvq_h2f((uint16_t)(sz.y >> 16)), zacc);
-            pv_all_fields<BITS>(std::make_integer_sequence<int, 64 / PV_FIELD_GROUP>{}, W, acc, ptab, lane_off, w0, w1);
+            pv_all_fields<BITS, RG>(std::make_integer_sequence<int, NF / PV_FIELD_GROUP>{}, W, acc, ptab, lane_off, w0, w1);
         }
     }
     // sum the 64 lanes: four rounds of 16 accumulators through LDS
-    float outv = 0.f;      // lane l (< 64) ends up with channel l of this half
+    float outv = 0.f;      // lane l (< 64) ends up with the sum of accumulator l
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
 #pragma unroll
@@ -219,17 +263,25 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
         for (int j = 0; j < 16; ++j) s += red[wave][quarter * 16 + j][col];
         s += __shfl_xor(s, 16);
         s += __shfl_xor(s, 32);
-        if ((lane >> 4) == r) outv = s;          // lanes 16r..16r+15 keep channels 16r..16r+15
+        if ((lane >> 4) == r) outv = s;          // lanes 16r..16r+15 keep accumulators 16r..16r+15
         __syncthreads();
     }
-    for (int o = 32; o > 0; o >>= 1) zacc += __shfl_xor(zacc, o);
-    if (stat_slots)
-        for (int o = 32; o > 0; o >>= 1) lacc += __shfl_xor(lacc, o);
+#pragma unroll
+    for (int h = 0; h < RG; ++h) {
+        for (int o = 32; o > 0; o >>= 1) zacc[h] += __shfl_xor(zacc[h], o);
+        if (stat_slots)
+            for (int o = 32; o > 0; o >>= 1) lacc[h] += __shfl_xor(lacc[h], o);
+    }
     if (active) {
-        partial[((int64_t)blockIdx.x * n_q_heads + qh) * 128 + half * 64 + lane] = outv;
-        if (half == 0 && lane == 0) {
-            zpart[(int64_t)blockIdx.x * n_q_heads + qh] = zacc;
-            if (stat_slots) lpart[(int64_t)blockIdx.x * n_q_heads + qh] = lacc;
+        // accumulator a = (head a / NF of the group, channel a % NF of the slice)
+        const int qh = q0 + lane / NF;
+        partial[((int64_t)blockIdx.x * n_q_heads + qh) * 128 + half * 64 + slice * NF + lane % NF] = outv;
+        if (half == 0 && slice == 0 && lane == 0) {
+#pragma unroll
+            for (int h = 0; h < RG; ++h) {
+                zpart[(int64_t)blockIdx.x * n_q_heads + q0 + h] = zacc[h];
+                if (stat_slots) lpart[(int64_t)blockIdx.x * n_q_heads + q0 + h] = lacc[h];
+            }
         }
     }
 }
@@ -529,15 +581,19 @@ kvq_status kvq_pv_run(const kvq_cache *cache, const float *d_probs, int64_t ld_p
                                                                 cache->n_sink, stat_slots, n_stat);
 
         dim3 grid((unsigned)plan.slabs, (unsigned)((2 * Hq + PV_WAVES - 1) / PV_WAVES));
-#define LAUNCH_PV(B)                                                                                          \
-    kvq_pv_dense<B><<<grid, PV_NT, 0, s>>>(cache->params, D, cache->n_kv_heads, Hq, cache->cap_tokens, L,      \
-                                           cache->v_codes, cache->v_sz, d_probs, ld_probs, partial, zpart,    \
-                                           plan.tiles, cache->n_sink, stat_slots, n_stat, lpart)
+#define LAUNCH_PV(B, G)                                                                                       \
+    kvq_pv_dense<B, G><<<grid, PV_NT, 0, s>>>(cache->params, D, cache->n_kv_heads, Hq, cache->cap_tokens, L,   \
+                                              cache->v_codes, cache->v_sz, d_probs, ld_probs, partial, zpart, \
+                                              plan.tiles, cache->n_sink, stat_slots, n_stat, lpart)
         KvqProfile &prof = kvq_profile_state();
         if (prof.enabled) KVQ_HIP_CHECK(hipEventRecord(prof.ev[1][0], s));
-        if (cache->bits == 2) LAUNCH_PV(2);
-        else if (cache->bits == 3) LAUNCH_PV(3);
-        else LAUNCH_PV(4);
+        // query heads of one KV head that a wavefront takes together (they share extraction and gather).
+        // Not when the kernel also turns scores into weights: every wavefront that covers a head
+        // evaluates that head's exponentials, and grouping multiplies the wavefronts per head.
+        const int rg = stat_slots ? 1 : (r % 4 == 0) ? 4 : (r % 2 == 0) ? 2 : 1;
+        if (cache->bits == 2) { if (rg == 4) LAUNCH_PV(2, 4); else if (rg == 2) LAUNCH_PV(2, 2); else LAUNCH_PV(2, 1); }
+        else if (cache->bits == 3) { if (rg == 4) LAUNCH_PV(3, 4); else if (rg == 2) LAUNCH_PV(3, 2); else LAUNCH_PV(3, 1); }
+        else { if (rg == 4) LAUNCH_PV(4, 4); else if (rg == 2) LAUNCH_PV(4, 2); else LAUNCH_PV(4, 1); }
 #undef LAUNCH_PV
         if (prof.enabled) { KVQ_HIP_CHECK(hipEventRecord(prof.ev[1][1], s)); prof.have[1] = 1; }
     }
