@@ -132,3 +132,28 @@ def test_gqa_with_crafted_tokens():
     assert gc.status() == 0
     assert not compare_caches(oc, gc)
     _check_matvecs(st, oc, gc, L)
+
+
+def test_storage_past_the_last_token_is_never_used():
+    """Odd token count: the last token shares its code words and its (scale, zero-point) pair slot
+    with a token that does not exist yet.  Whatever the buffers hold there (NaN scale, set bits in the
+    codes) must not reach the result of either mat-vec or of the fused call."""
+    import torch
+    import paper_2401_18079_amd as K
+    wl = S.workload("c2", n_kv_heads=4, n_q_heads=4)
+    st = Setup(wl)
+    L = 333
+    oc, gc = _run(st, st.k(0, L), st.v(0, L), L, 512)
+    assert not compare_caches(oc, gc)
+    gc.v_sz.view(torch.int16)[2 * L:] = 0x7E00                    # fp16 NaN in every later (scale, zero-point)
+    q = S.gen_q(wl, 0, 0)
+    ref_scores = oc.qk(q, SCALE)
+    p = O.softmax(ref_scores)
+    out = torch.empty((wl.n_q_heads, 128), device="cuda")
+    K.kvq_pv_matvec(gc, torch.from_numpy(p).cuda(), out)
+    ok, worst = matvec_close(out.cpu().numpy(), oc.pv(p))
+    assert ok, f"pv worst error / bound = {worst:.3f}"
+    scores = torch.zeros((wl.n_q_heads, L), device="cuda")
+    K.kvq_attention_decode(gc, torch.from_numpy(q).cuda(), SCALE, scores, out)
+    ok, worst = matvec_close(out.cpu().numpy(), oc.pv(p), rel=2e-3)
+    assert ok, f"fused worst error / bound = {worst:.3f}"
