@@ -224,3 +224,124 @@ def test_c3_million_token_context_sampled_parity():
     ok, worst = matvec_close(out.cpu().numpy(), ref_out.astype(np.float32))
     assert ok, f"outputs: worst error / bound = {worst:.3f}"
     _check_fused_against_separate_calls(gc, q, float(scale), scores, Ln=Lc, cap=cap)
+
+
+def test_c2_full_context_constant_value_rows_closed_form():
+    """A closed form that needs no oracle and covers every token of the full-size workload.  Every
+    Value vector is constant, v[n][:] = c_n.  Then (paper Sec. 3.4/3.6 with the tie rules of the
+    per-token selection) the first 2*k_side channels are the outliers, zero-point = c_n, scale = 1,
+    every code is the signpost l0 nearest to zero, an outlier's residual is -l0, and the de-quantised
+    row is c_n on the outlier channels and c_n + l0 elsewhere.  So for any weights w:
+        out[h][c] = sum_n w[h][n] * c_n  (+ l0 * sum_n w[h][n]  on the other channels),
+    which is checked for kvq_pv_matvec with given probabilities and for the fused call with the
+    softmax of the scores it returns (evaluated on the host in fp64)."""
+    import torch
+    import paper_2401_18079_amd as K
+    from kvq_synth.device import DeviceGen
+
+    wl = S.workload("c2")
+    st = Setup(wl)
+    Lc = 131072 + 37
+    cap = ((Lc + 127) // 128) * 128
+    gc = st.gpu_cache(cap)
+    dg = DeviceGen(wl, st.layer, st.kprof, st.vprof)
+    n_all = torch.arange(Lc, device="cuda")
+    c_all = ((n_all % 7) - 3).to(torch.float16)                     # c_n in {-3, ..., 3}
+    t0 = 0
+    while t0 < Lc:
+        T = min(4096, Lc - t0)
+        K.kvq_quantize_append_k(gc, dg.k(t0, T))
+        K.kvq_quantize_append_v(gc, c_all[t0:t0 + T, None].expand(T, wl.D).contiguous())
+        t0 += T
+    torch.cuda.synchronize()
+    assert gc.status() == 0 and gc.n_tokens_v == Lc
+
+    lut_v = np.asarray(st.lut_v, dtype=np.float32)
+    l0 = float(lut_v[int(np.argmin(np.abs(lut_v)))])                # first minimum: ties to the smaller index
+    n_out = 2 * st.k_side
+    c_host = c_all.float().cpu().numpy().astype(np.float64)
+    # what the append stored: outliers are channels 0 .. 2*k_side-1 of every token, residual -l0
+    vp = gc.v_ptr.cpu().numpy().view(np.uint32)[:Lc + 1].astype(np.int64)
+    assert np.array_equal(np.diff(vp), np.full(Lc, n_out))
+    for n in (0, 1, 4095, 4096, Lc - 1):
+        idx = gc.v_idx[int(vp[n]):int(vp[n + 1])].cpu().numpy().view(np.uint16)
+        val = gc.v_val[int(vp[n]):int(vp[n + 1])].cpu().numpy().view(np.float16)
+        assert np.array_equal(idx, np.arange(n_out, dtype=np.uint16))
+        assert np.all(val.astype(np.float32) == np.float32(-l0))
+
+    def expected(w):                                                 # w: [Hq][Lc] float64
+        base = w @ c_host                                            # [Hq]
+        out = np.repeat(base[:, None], 128, axis=1) + l0 * w.sum(axis=1)[:, None]
+        g = wl.n_q_heads // wl.n_kv_heads
+        for h in range(wl.n_q_heads):                                # outlier channels all lie in KV head 0
+            if h // g == 0:
+                out[h, :min(n_out, 128)] = base[h]
+        return out
+
+    assert n_out <= 128
+    # (1) the Value mat-vec alone, with probabilities that vary over the whole context
+    p = torch.softmax(torch.randn((wl.n_q_heads, Lc), device="cuda", generator=torch.Generator("cuda").manual_seed(5)) * 2.0, dim=1)
+    pfull = torch.zeros((wl.n_q_heads, cap), device="cuda")
+    pfull[:, :Lc] = p
+    out = torch.zeros((wl.n_q_heads, 128), device="cuda")
+    K.kvq_pv_matvec(gc, pfull, out)
+    ok, worst = matvec_close(out.cpu().numpy(), expected(p.double().cpu().numpy()))
+    assert ok, f"pv closed form: worst error / bound = {worst:.3f}"
+    # (2) the fused call: its weights are the softmax of the scores it leaves behind
+    q = S.gen_q(wl, 0, 0)
+    scores = torch.zeros((wl.n_q_heads, cap), device="cuda")
+    K.kvq_attention_decode(gc, torch.from_numpy(q).cuda(), 1.0 / np.sqrt(128.0), scores, out)
+    x = scores[:, :Lc].double().cpu().numpy()
+    w = np.exp(x - x.max(axis=1, keepdims=True))
+    w /= w.sum(axis=1, keepdims=True)
+    ok, worst = matvec_close(out.cpu().numpy(), expected(w))
+    assert ok, f"fused closed form: worst error / bound = {worst:.3f}"
+
+
+def test_c2_full_context_constant_keys_closed_form():
+    """Every Key equals its channel's zero-point, so every code is the signpost l0 nearest to zero,
+    no element is an outlier, and the de-quantised Key is the same vector k = s*l0 + z at every
+    position.  The score of token n is then the closed form of the rotary product (paper App. "RoPE
+    Equation", half-split pairs):
+        scale * sum_i (q_i k_i + q_{i+64} k_{i+64}) cos(n theta_i) + (q_{i+64} k_i - q_i k_{i+64}) sin(n theta_i),
+    evaluated here in fp64 for every token of the full context (no oracle involved)."""
+    import torch
+    import paper_2401_18079_amd as K
+
+    wl = S.workload("c2")
+    st = Setup(wl)
+    Lc = 131072 + 37
+    cap = ((Lc + 127) // 128) * 128
+    gc = st.gpu_cache(cap)
+    z16 = np.asarray(st.z, dtype=np.float16)
+    row = torch.from_numpy(z16).cuda()
+    t0 = 0
+    while t0 < Lc:
+        T = min(4096, Lc - t0)
+        K.kvq_quantize_append_k(gc, row[None, :].expand(T, wl.D).contiguous())
+        t0 += T
+    torch.cuda.synchronize()
+    assert gc.status() == 0 and int(gc.k_ptr[Lc].item()) == 0           # not a single outlier
+
+    lut_k = np.asarray(st.lut_k, dtype=np.float32)
+    l0 = np.float32(lut_k[int(np.argmin(np.abs(lut_k)))])
+    s32 = np.asarray(st.s, dtype=np.float16).astype(np.float32)
+    # fmaf(s, l0, z): the exact sum rounded once to fp32
+    khat = np.float32(s32.astype(np.float64) * np.float64(l0) + z16.astype(np.float64)).astype(np.float64)
+    q = S.gen_q(wl, 0, 0).astype(np.float64)
+    scale = 1.0 / np.sqrt(128.0)
+    n = np.arange(Lc, dtype=np.float64)
+    theta = wl.rope_base ** (-2.0 * np.arange(64) / 128.0)
+    ang = n[:, None] * theta[None, :]
+    cs, sn = np.cos(ang), np.sin(ang)                                   # [Lc][64]
+    g = wl.n_q_heads // wl.n_kv_heads
+    ref = np.zeros((wl.n_q_heads, Lc))
+    for h in range(wl.n_q_heads):
+        k = khat[(h // g) * 128:(h // g + 1) * 128]
+        A = q[h, :64] * k[:64] + q[h, 64:] * k[64:]
+        B = q[h, 64:] * k[:64] - q[h, :64] * k[64:]
+        ref[h] = scale * (cs @ A + sn @ B)
+    scores = torch.zeros((wl.n_q_heads, cap), device="cuda")
+    K.kvq_qk_matvec(gc, torch.from_numpy(q.astype(np.float32)).cuda(), scale, scores)
+    ok, worst = matvec_close(scores[:, :Lc].cpu().numpy(), ref)
+    assert ok, f"scores closed form: worst error / bound = {worst:.3f}"
