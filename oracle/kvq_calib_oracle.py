@@ -63,3 +63,37 @@ def objective(x_norm, w, c):
     c = np.asarray(c, dtype=np.float32)
     q = c[nearest(x, c)].astype(np.float64)
     return float(np.sum(np.asarray(w, dtype=np.float64) * (x.astype(np.float64) - q) ** 2))
+
+
+def key_channel_constants(x16, outlier_fraction):
+    """Offline per-channel calibration of the Keys (paper Sec. 3.6 and the appendix on offline
+    calibration: per-channel outlier thresholds, scaling factors and zero-points come from a
+    calibration set; Sec. 3.4: the thresholds isolate a fixed fraction of each channel as outliers).
+
+    x16: fp16 calibration Keys [T][D] (pre-RoPE).  Readings where the paper gives no formula:
+      * k = floor(outlier_fraction / 2 * T + 1/2) elements per side and channel;
+      * with the channel's values sorted ascending as xs: lower threshold xs[k-1], upper threshold
+        xs[T-k] (the k-th smallest / largest value), and the range that is normalised to [-1, 1] is
+        [xs[k], xs[T-k-1]], the values strictly inside; k = 0: thresholds -65504 / +65504, range
+        [xs[0], xs[T-1]];
+      * zero-point = mid-range, scale = half-range, each computed in fp32 and rounded to fp16;
+        a scale that is not positive becomes 1.
+    Returns fp16 arrays (s, z, lo, hi) of shape [D]."""
+    x = np.asarray(x16, dtype=np.float16).astype(np.float32)
+    T, D = x.shape
+    k = int(np.floor(float(outlier_fraction) / 2.0 * T + 0.5))
+    assert 2 * k < T
+    s = np.zeros(D, np.float16); z = np.zeros(D, np.float16)
+    lo = np.zeros(D, np.float16); hi = np.zeros(D, np.float16)
+    for c in range(D):
+        xs = np.sort(x[:, c], kind="stable")
+        if k > 0:
+            lo[c], hi[c] = np.float16(xs[k - 1]), np.float16(xs[T - k])
+            a, b = xs[k], xs[T - k - 1]
+        else:
+            lo[c], hi[c] = np.float16(-65504.0), np.float16(65504.0)
+            a, b = xs[0], xs[T - 1]
+        z[c] = np.float16((np.float32(b) + np.float32(a)) * np.float32(0.5))
+        sc = np.float16((np.float32(b) - np.float32(a)) * np.float32(0.5))
+        s[c] = sc if np.float32(sc) > 0 else np.float16(1.0)
+    return s, z, lo, hi

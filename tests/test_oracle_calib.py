@@ -148,3 +148,57 @@ def test_s_squared_weighting_is_the_unnormalised_error():
     lhs = float(np.sum(F * (A - QA) ** 2))
     rhs = C.objective(a_norm.reshape(-1), (F * s ** 2).astype(np.float32).reshape(-1), c)
     assert rhs == pytest.approx(lhs, rel=1e-5)
+
+
+def test_key_channel_constants_against_numpy_partition_and_counts():
+    """Order statistics by np.partition (no sort), element counts on each side of the thresholds,
+    and the mid-/half-range identities."""
+    wl = S.workload("c2", n_kv_heads=2, n_q_heads=2)
+    x = S.gen_k(wl, 0, 0, 0, 3000, tensor_id=7)
+    p = 0.01
+    s, z, lo, hi = C.key_channel_constants(x, p)
+    T, D = x.shape
+    k = 15                                                         # floor(0.005 * 3000 + 0.5)
+    xf = x.astype(np.float32)
+    part_lo = np.partition(xf, [k - 1, k], axis=0)
+    part_hi = np.partition(xf, [T - k - 1, T - k], axis=0)
+    assert np.array_equal(lo.astype(np.float32), part_lo[k - 1])
+    assert np.array_equal(hi.astype(np.float32), part_hi[T - k])
+    # at most k-1 elements lie strictly outside a threshold, at least k at or beyond it
+    assert np.all((xf < lo.astype(np.float32)).sum(0) <= k - 1) and np.all((xf <= lo.astype(np.float32)).sum(0) >= k)
+    assert np.all((xf > hi.astype(np.float32)).sum(0) <= k - 1) and np.all((xf >= hi.astype(np.float32)).sum(0) >= k)
+    a, b = part_lo[k], part_hi[T - k - 1]
+    assert np.array_equal(z, ((b + a) * np.float32(0.5)).astype(np.float16))
+    sc = ((b - a) * np.float32(0.5)).astype(np.float16)
+    assert np.array_equal(s, np.where(sc.astype(np.float32) > 0, sc, np.float16(1.0)))
+    # every inlier normalises into [-1, 1] up to the fp16 rounding of scale and zero-point
+    inl = (xf >= a) & (xf <= b)
+    xn = (xf - z.astype(np.float32)) / s.astype(np.float32)
+    assert np.max(np.abs(xn[inl])) <= 1.0 + 2e-3
+
+
+def test_key_channel_constants_equal_the_input_generators_calibration():
+    """The synthetic-input package calibrates its Key channels with code of its own (numpy, written
+    for input generation): same data, same constants."""
+    wl = S.workload("c2", n_kv_heads=4, n_q_heads=4)
+    prof = S.key_channel_profile(wl, 0)
+    from kvq_synth.gen import T_KCAL
+    x = S.gen_k(wl, 0, 0, 0, 4096, profile=prof, tensor_id=T_KCAL)
+    s, z, lo, hi = C.key_channel_constants(x, wl.outlier_fraction)
+    gs, gz, glo, ghi = S.calibrate_k(wl, 0, n_cal=4096, profile=prof)
+    for a, b in ((s, gs), (z, gz), (lo, glo), (hi, ghi)):
+        assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
+def test_key_channel_constants_degenerate_cases():
+    x = np.zeros((64, 3), np.float16)
+    x[:, 1] = np.arange(64, dtype=np.float16)                      # 0..63
+    x[:, 2] = np.float16(2.5)                                      # constant channel
+    s, z, lo, hi = C.key_channel_constants(x, 0.0)                 # no outliers: open thresholds, full range
+    assert np.all(lo == np.float16(-65504)) and np.all(hi == np.float16(65504))
+    assert z[1] == np.float16(31.5) and s[1] == np.float16(31.5)
+    assert s[0] == np.float16(1.0) and z[0] == np.float16(0.0) and s[2] == np.float16(1.0) and z[2] == np.float16(2.5)
+    s, z, lo, hi = C.key_channel_constants(x, 2.0 / 64 * 2)        # k = 2 per side
+    assert lo[1] == np.float16(1.0) and hi[1] == np.float16(62.0)
+    assert z[1] == np.float16(31.5) and s[1] == np.float16(29.5)   # range [2, 61]
+    assert lo[2] == np.float16(2.5) and hi[2] == np.float16(2.5) and s[2] == np.float16(1.0)
