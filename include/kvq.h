@@ -219,6 +219,21 @@ kvq_status kvq_softmax_f32(const float *d_x, int64_t ld_x, float *d_probs, int64
  * rounded to fp32); a signpost whose elements have total weight zero stays.  Both arrays 16-byte
  * aligned, n >= 1, iters >= 0.  Errors: INVALID_ARG, UNSUPPORTED (bits), CAPACITY (workspace), HIP.
  */
+/*
+ * Offline per-channel calibration of the Keys of one layer (paper Sec. 3.6 and the appendix on offline
+ * calibration; Sec. 3.4 for the outlier fraction): from T calibration Key vectors, per channel, the
+ * lower / upper outlier thresholds (the k-th smallest / k-th largest value, k = floor(fraction/2*T+1/2)
+ * per side), and zero-point (mid-range) and scale (half-range; not positive -> 1) of the values
+ * strictly inside, each rounded to fp16: the four arrays kvq_lut_load takes.  fraction = 0: thresholds
+ * -65504 / +65504 and the full range.
+ *   d_k_cal : DEVICE fp16 [T][D], pre-RoPE.  1 <= T <= 32768, 2k < T.
+ *   d_s, d_z, d_lo, d_hi : DEVICE fp16 bit patterns [D] (copy them to the host for kvq_lut_load).
+ * Asynchronous on `stream`.  Errors: INVALID_ARG, UNSUPPORTED (T), HIP.
+ */
+kvq_status kvq_calibrate_key_channels(const uint16_t *d_k_cal, int32_t T, int32_t D, float outlier_fraction,
+                                      uint16_t *d_s, uint16_t *d_z, uint16_t *d_lo, uint16_t *d_hi,
+                                      void *stream);
+
 int64_t kvq_calibrate_workspace_bytes(void);
 kvq_status kvq_calibrate_nuq(const float *d_x_norm, const float *d_w, int64_t n, int32_t bits,
                              int32_t iters, float *h_signposts, void *d_workspace,

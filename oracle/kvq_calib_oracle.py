@@ -77,7 +77,7 @@ def key_channel_constants(x16, outlier_fraction):
         [xs[k], xs[T-k-1]], the values strictly inside; k = 0: thresholds -65504 / +65504, range
         [xs[0], xs[T-1]];
       * zero-point = mid-range, scale = half-range, each computed in fp32 and rounded to fp16;
-        a scale that is not positive becomes 1.
+        a scale that is not positive becomes 1; zeros are returned as +0.
     Returns fp16 arrays (s, z, lo, hi) of shape [D]."""
     x = np.asarray(x16, dtype=np.float16).astype(np.float32)
     T, D = x.shape
@@ -96,4 +96,7 @@ def key_channel_constants(x16, outlier_fraction):
         z[c] = np.float16((np.float32(b) + np.float32(a)) * np.float32(0.5))
         sc = np.float16((np.float32(b) - np.float32(a)) * np.float32(0.5))
         s[c] = sc if np.float32(sc) > 0 else np.float16(1.0)
-    return s, z, lo, hi
+    # a zero is returned as +0 whatever the signs of the zeros in the data (no comparison or sum
+    # downstream can tell the two apart)
+    pz = np.float16(0.0)
+    return s, z + pz, lo + pz, hi + pz

@@ -62,6 +62,7 @@ def load_library():
         "kvq_attention_decode": (C.c_int, [P, V, F, V, I64, V, V]),
         "kvq_softmax_workspace_bytes": (I64, [I32, I64]),
         "kvq_softmax_f32": (C.c_int, [V, I64, V, I64, I32, I64, V, I64, V]),
+        "kvq_calibrate_key_channels": (C.c_int, [V, I32, I32, F, V, V, V, V, V]),
         "kvq_calibrate_workspace_bytes": (I64, []),
         "kvq_calibrate_nuq": (C.c_int, [V, V, I64, I32, I32, V, V, I64, V]),
         "kvq_fp16_qk_matvec": (C.c_int, [V, I64, I32, I32, V, F, V, I64, V]),
@@ -88,6 +89,7 @@ EXPORTED_SYMBOLS = [
     "kvq_attention_decode", "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
     "kvq_fp16_pv_matvec", "kvq_event_create", "kvq_event_record", "kvq_event_elapsed_ms", "kvq_event_destroy",
     "kvq_profile_enable", "kvq_profile_last_ms", "kvq_calibrate_workspace_bytes", "kvq_calibrate_nuq",
+    "kvq_calibrate_key_channels",
 ]
 
 
@@ -255,6 +257,17 @@ def kvq_softmax_f32(x: torch.Tensor, probs: torch.Tensor, n_cols: int, workspace
     _check(load_library().kvq_softmax_f32(x.data_ptr(), x.stride(0), probs.data_ptr(), probs.stride(0), x.shape[0],
                                           int(n_cols), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                           _stream_ptr(stream)), "kvq_softmax_f32")
+
+
+def kvq_calibrate_key_channels(k_cal: torch.Tensor, outlier_fraction: float, stream=None):
+    """Per-channel Key constants (s, z, lo, hi) as fp16 numpy arrays, from calibration Keys [T][D] on the GPU."""
+    assert k_cal.is_cuda and k_cal.dtype == torch.float16 and k_cal.dim() == 2 and k_cal.is_contiguous()
+    T, D = k_cal.shape
+    outs = [torch.empty(D, dtype=torch.int16, device=k_cal.device) for _ in range(4)]
+    _check(load_library().kvq_calibrate_key_channels(k_cal.data_ptr(), T, D, float(outlier_fraction),
+                                                     *[o.data_ptr() for o in outs], _stream_ptr(stream)),
+           "kvq_calibrate_key_channels")
+    return tuple(o.cpu().numpy().view(np.float16) for o in outs)
 
 
 def kvq_calibrate_nuq(x_norm: torch.Tensor, w: torch.Tensor, bits: int, iters: int, init, stream=None) -> np.ndarray:

@@ -599,6 +599,77 @@ void kvq_v_quant(const void *__restrict__ params, int D, int64_t cap, int64_t n0
                             (int)blockIdx.x);
 }
 
+// Offline calibration of one Key channel per workgroup (paper Sec. 3.6 and the appendix on offline
+// calibration): the k smallest and the k largest of the channel's T calibration values are its
+// outliers; thresholds are the k-th smallest / largest value, and the values strictly inside give
+// the zero-point (mid-range) and scale (half-range).  Same two-level radix selection as for the
+// per-token Value outliers, on the channel's column of the [T][D] calibration matrix.
+// dyn: keys 2*T bytes, state T bytes.
+template <int NT>
+__global__ __launch_bounds__(NT) void kvq_calib_channel(const uint16_t *__restrict__ k_cal, int T, int D, int k,
+                                                        uint16_t *__restrict__ s_out, uint16_t *__restrict__ z_out,
+                                                        uint16_t *__restrict__ lo_out, uint16_t *__restrict__ hi_out)
+{
+    extern __shared__ uint8_t dyn[];
+    uint16_t *keys = (uint16_t *)dyn;
+    uint8_t *state = dyn + 2 * (size_t)T;
+    __shared__ uint32_t hist[768];
+    __shared__ uint32_t sh[24];
+    __shared__ uint32_t wave_tot[2 * NT / 64];
+    __shared__ uint32_t red[4][NT / 64];
+    const int tid = threadIdx.x, c = blockIdx.x;
+    for (int t = tid; t < T; t += NT) {
+        keys[t] = (uint16_t)order_key(k_cal[(int64_t)t * D + c]);
+        state[t] = 0;
+    }
+    for (int i = tid; i < 768; i += NT) hist[i] = 0;
+    __syncthreads();
+    if (k > 0) {
+        if (!select_both<NT>(keys, state, T, k, hist, sh, wave_tot)) {
+            select_top<NT>(keys, state, T, k, 0u, 1, hist, sh, wave_tot);        // k largest
+            select_top<NT>(keys, state, T, k, 0xFFFFu, 2, hist, sh, wave_tot);   // k smallest of the rest
+        }
+    }
+    // largest key of the lower outliers, smallest of the upper ones, extremes of the rest
+    uint32_t lo_key = 0u, hi_key = 0xFFFFu, in_min = 0xFFFFu, in_max = 0u;
+    for (int t = tid; t < T; t += NT) {
+        const uint32_t key = keys[t];
+        const uint32_t st = state[t];
+        if (st == 2) lo_key = key > lo_key ? key : lo_key;
+        else if (st == 1) hi_key = key < hi_key ? key : hi_key;
+        else { in_min = key < in_min ? key : in_min; in_max = key > in_max ? key : in_max; }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t a = __shfl_xor(lo_key, o), b = __shfl_xor(hi_key, o), d = __shfl_xor(in_min, o), e = __shfl_xor(in_max, o);
+        lo_key = a > lo_key ? a : lo_key;
+        hi_key = b < hi_key ? b : hi_key;
+        in_min = d < in_min ? d : in_min;
+        in_max = e > in_max ? e : in_max;
+    }
+    if ((tid & 63) == 0) {
+        red[0][tid >> 6] = lo_key; red[1][tid >> 6] = hi_key; red[2][tid >> 6] = in_min; red[3][tid >> 6] = in_max;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < NT / 64; ++w) {
+            lo_key = red[0][w] > lo_key ? red[0][w] : lo_key;
+            hi_key = red[1][w] < hi_key ? red[1][w] : hi_key;
+            in_min = red[2][w] < in_min ? red[2][w] : in_min;
+            in_max = red[3][w] > in_max ? red[3][w] : in_max;
+        }
+        // back from the order-preserving key to the fp16 bit pattern
+        auto bits_of = [](uint32_t key) { return (uint16_t)((key & 0x8000u) ? (key & 0x7FFFu) : (~key & 0xFFFFu)); };
+        const float a = kvq_h2f(bits_of(in_min)), b = kvq_h2f(bits_of(in_max));
+        const uint16_t zc = kvq_f2h_rn((b + a) * 0.5f);
+        uint16_t sc = kvq_f2h_rn((b - a) * 0.5f);
+        if (!(kvq_h2f(sc) > 0.0f)) sc = 0x3C00u;                      // 1.0
+        s_out[c] = sc;
+        z_out[c] = zc;
+        lo_out[c] = (k > 0) ? bits_of(lo_key) : (uint16_t)0xFBFFu;   // -65504
+        hi_out[c] = (k > 0) ? bits_of(hi_key) : (uint16_t)0x7BFFu;   // +65504
+    }
+}
+
 // Keys and Values of the same tokens in one launch: even workgroups take a token's Keys, odd ones its
 // Values (a single-token append is pure latency, and the two do not depend on each other).
 struct KvAppendArgs {
@@ -776,5 +847,27 @@ extern "C" kvq_status kvq_quantize_append_kv(kvq_cache *cache, const uint16_t *d
     if (st != KVQ_OK) return st;
     cache->n_tokens_k += T;
     cache->n_tokens_v += T;
+    return KVQ_OK;
+}
+
+
+extern "C" kvq_status kvq_calibrate_key_channels(const uint16_t *d_k_cal, int32_t T, int32_t D, float outlier_fraction,
+                                                 uint16_t *d_s, uint16_t *d_z, uint16_t *d_lo, uint16_t *d_hi,
+                                                 void *stream)
+{
+    if (!d_k_cal || !d_s || !d_z || !d_lo || !d_hi || ((uintptr_t)d_k_cal & 1)) return KVQ_ERR_INVALID_ARG;
+    if (T < 1 || D < 1 || !(outlier_fraction >= 0.0f) || !(outlier_fraction < 1.0f)) return KVQ_ERR_INVALID_ARG;
+    if (T > 32768) return KVQ_ERR_UNSUPPORTED;        // a channel's calibration values are kept in LDS
+    const int k = (int)floorf(outlier_fraction * 0.5f * (float)T + 0.5f);
+    if (2 * k >= T) return KVQ_ERR_INVALID_ARG;
+    const size_t dyn = 3 * (size_t)T;
+    static size_t lds_attr = 0;
+    if (dyn > lds_attr) {
+        KVQ_HIP_CHECK(hipFuncSetAttribute((const void *)kvq_calib_channel<1024>,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn));
+        lds_attr = dyn;
+    }
+    kvq_calib_channel<1024><<<D, 1024, dyn, (hipStream_t)stream>>>(d_k_cal, T, D, k, d_s, d_z, d_lo, d_hi);
+    KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }

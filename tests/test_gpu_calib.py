@@ -106,3 +106,86 @@ def test_argument_errors():
     assert lib.kvq_calibrate_nuq(x.data_ptr(), w.data_ptr(), 0, 3, 1, p, ws.data_ptr(), ws.numel(), sp) != 0      # n
     assert lib.kvq_calibrate_nuq(x.data_ptr(), w.data_ptr(), 1024, 3, -1, p, ws.data_ptr(), ws.numel(), sp) != 0  # iters
     assert lib.kvq_calibrate_nuq(x.data_ptr(), w.data_ptr(), 1024, 3, 1, p, ws.data_ptr(), 1000, sp) != 0         # workspace
+
+
+# ---- per-channel Key calibration (thresholds, scale, zero-point): bit-exact against the oracle ----------
+
+def _gpu_channels(x16, p):
+    import torch
+    import paper_2401_18079_amd as K
+    return K.kvq_calibrate_key_channels(torch.from_numpy(x16).cuda(), p)
+
+
+def _same(got, ref):
+    for name, a, b in zip(("s", "z", "lo", "hi"), got, ref):
+        a, b = np.asarray(a).view(np.uint16), np.asarray(b).view(np.uint16)
+        assert np.array_equal(a, b), (name, int(np.sum(a != b)), np.nonzero(a != b)[0][:5])
+
+
+@pytest.mark.parametrize("heads,T,p", [
+    (4, 4096, 0.01),
+    (4, 3000, 0.01),          # T not a multiple of the workgroup size
+    (32, 4096, 0.01),         # the bench layer's width
+    (2, 32768, 0.001),        # the largest calibration set (16 samples of 2K tokens)
+    (2, 700, 0.0),            # no outliers: open thresholds, full range
+    (2, 65, 0.4),             # a quarter of every channel on each side
+    (1, 1, 0.0),              # a single calibration token
+])
+def test_key_channel_constants_match_oracle(heads, T, p):
+    wl = S.workload("c2", n_kv_heads=heads, n_q_heads=heads)
+    from kvq_synth.gen import T_KCAL
+    x = S.gen_k(wl, 0, 0, 0, T, tensor_id=T_KCAL)
+    _same(_gpu_channels(x, p), C.key_channel_constants(x, p))
+
+
+def test_key_channel_constants_with_heavy_ties_and_special_values():
+    rng = np.random.default_rng(3)
+    T, D = 2048, 256
+    x = rng.integers(-3, 4, size=(T, D)).astype(np.float16)            # seven distinct values: ties everywhere
+    x[:, 0] = np.float16(1.25)                                         # a constant channel
+    x[:, 1] = np.where(rng.random(T) < 0.5, np.float16(0.0), np.float16(-0.0))   # +0 and -0 only
+    x[:, 2] = rng.standard_normal(T).astype(np.float16) * np.float16(1e-6)       # subnormals
+    x[:5, 3] = np.float16(65504.0); x[5:10, 3] = np.float16(-65504.0)            # the largest finite values
+    for p in (0.01, 0.05, 0.0):
+        _same(_gpu_channels(x, p), C.key_channel_constants(x, p))
+
+
+def test_calibrated_constants_feed_the_cache():
+    """End to end: constants calibrated on the GPU load into a cache and the append matches the oracle
+    run with the oracle-calibrated constants."""
+    import torch
+    import paper_2401_18079_amd as K
+    from oracle import kvq_oracle as O
+    from kvq_synth.gen import T_KCAL
+    wl = S.workload("c2", n_kv_heads=4, n_q_heads=4)
+    prof = S.key_channel_profile(wl, 0)
+    xcal = S.gen_k(wl, 0, 0, 0, 4096, profile=prof, tensor_id=T_KCAL)
+    s, z, lo, hi = _gpu_channels(xcal, wl.outlier_fraction)
+    lut_k, lut_v = S.make_lut(wl.bits, wl.seed, 0, 0), S.make_lut(wl.bits, wl.seed, 0, 1)
+    k_side = S.k_side_from_fraction(wl.outlier_fraction, wl.D)
+    gc = K.KvqCache(wl.bits, 4, 4, 256, k_side, wl.rope_base, 64 * 256)
+    K.kvq_lut_load(gc, lut_k, lut_v, s, z, lo, hi)
+    rs, rz, rlo, rhi = C.key_channel_constants(xcal, wl.outlier_fraction)
+    oc = O.OracleCache(wl.bits, 4, 4, 256, k_side, wl.rope_base, lut_k, lut_v, rs, rz, rlo, rhi, cap_nnz_k=64 * 256)
+    k = S.gen_k(wl, 0, 0, 0, 200, profile=prof)
+    oc.append_k(k)
+    K.kvq_quantize_append_k(gc, torch.from_numpy(k).cuda())
+    torch.cuda.synchronize()
+    assert gc.status() == 0
+    assert np.array_equal(gc.k_codes.cpu().numpy(), oc.k_codes)
+    nk = int(oc.k_ptr[200])
+    assert np.array_equal(gc.k_idx.cpu().numpy().view(np.uint16)[:nk], oc.k_idx[:nk])
+    assert 0.005 < nk / (200 * wl.D) < 0.02                        # about the calibrated 1 % are outliers
+
+
+def test_key_channel_calibration_argument_errors():
+    import torch
+    import paper_2401_18079_amd as K
+    x = torch.zeros((64, 128), dtype=torch.float16, device="cuda")
+    with pytest.raises(K.KvqError):
+        K.kvq_calibrate_key_channels(x, 1.0)                           # 2k >= T
+    with pytest.raises(K.KvqError):
+        K.kvq_calibrate_key_channels(x, -0.1)
+    big = torch.zeros((32769, 2), dtype=torch.float16, device="cuda")
+    with pytest.raises(K.KvqError):
+        K.kvq_calibrate_key_channels(big, 0.01)                        # more tokens than a channel's LDS holds
