@@ -92,6 +92,9 @@ def _check_fused(st, oc, gc, L, scale=SCALE, q_gain=1.0, steps=2):
     ("c3", dict(n_kv_heads=8, n_q_heads=8, outlier_fraction=0.004), 0, 777, [777]),    # 4-bit, 8 heads per workgroup
     ("c4", dict(n_kv_heads=2, n_q_heads=8), 0, 1300, [2, 640]),                # grouped-query attention
     ("c2", dict(n_kv_heads=2, n_q_heads=16), 0, 300, [150]),                    # eight query heads per KV head
+    ("c2", dict(n_kv_heads=4, n_q_heads=8), 0, 450, [450]),                     # two per KV head (3-bit)
+    ("c3", dict(n_kv_heads=2, n_q_heads=8, outlier_fraction=0.004), 0, 390, [390]),   # four per KV head, 4-bit
+    ("c2", dict(n_kv_heads=2, n_q_heads=8, bits=2), 2, 333, [333]),             # four per KV head, 2-bit, sinks
     ("c2", dict(n_kv_heads=3, n_q_heads=3), 0, 700, [350]),                     # head count that fits no group: one head per workgroup
     ("c2", dict(n_kv_heads=4, n_q_heads=4, outlier_fraction=0.0), 0, 129, [5]), # no outliers: the sparse Key kernel is skipped
     ("c2", dict(n_kv_heads=8, n_q_heads=8), 1, 1500, [1, 2, 500]),              # one attention-sink token
