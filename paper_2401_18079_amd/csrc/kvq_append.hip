@@ -7,7 +7,12 @@
 
 namespace {
 
-constexpr int KVQ_BULK_TOKENS = 64;     // calls with at least this many tokens count as bulk appends
+// Measured on 4096-channel tokens: 1024-thread workgroups finish a call of up to 256 tokens in one
+// round (Values: 25 us against 37 us with 256 threads), break even at 512 tokens and lose beyond
+// (4096 tokens: 216 us against 105 us), where eight small workgroups per compute unit hide each
+// other's barriers.
+constexpr int KVQ_BULK_TOKENS = 512;      // calls with at least this many tokens count as bulk appends
+constexpr int KVQ_KV_SPLIT_TOKENS = 256;  // from here on the combined call runs the Key and Value kernels in turn
 
 // Workgroups have NT threads: 256 for narrow models, 1024 once a token vector has >= 2048 channels
 // (fewer passes over the vector, hence fewer barriers, for the single-token decode append).
@@ -803,10 +808,11 @@ extern "C" kvq_status kvq_quantize_append_kv(kvq_cache *cache, const uint16_t *d
     const int D = cache->n_kv_heads * KVQ_HEAD_DIM;
     if (cache->k_side_v < 0 || 2 * (int64_t)cache->k_side_v >= D) return KVQ_ERR_INVALID_ARG;
     if (D > 16384) return KVQ_ERR_UNSUPPORTED;       // the per-token Value selection keeps the vector in LDS
-    if (T >= KVQ_BULK_TOKENS) {
-        // A bulk append fills the GPU with either kernel alone, and compute units that run both bodies
-        // at once are slower than the two launches one after the other (measured: 233 us against
-        // 188 us for 4096 tokens of 4096 channels); every check of both calls has passed above.
+    if (T >= KVQ_KV_SPLIT_TOKENS) {
+        // Such an append fills the GPU with either kernel alone, and compute units that run both bodies
+        // at once are slower than the two launches one after the other (measured: 50 us against 44 us
+        // for 256 tokens of 4096 channels, 233 us against 188 us for 4096); every check of both calls
+        // has passed above.
         if (!cache->workspace || cache->workspace_bytes < (int64_t)T * 4) return KVQ_ERR_CAPACITY;
         st = kvq_quantize_append_k(cache, d_k_new, T, stream);
         if (st != KVQ_OK) return st;

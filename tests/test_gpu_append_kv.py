@@ -24,6 +24,7 @@ def _caches(st, cap, n_sink=0):
 
 @pytest.mark.parametrize("name,ov,n_sink,chunks", [
     ("c2", dict(n_kv_heads=32, n_q_heads=32), 0, [1, 1, 1, 130, 1, 64, 1]),      # the bench shape (D = 4096)
+    ("c2", dict(n_kv_heads=16, n_q_heads=16), 0, [1, 520, 1, 511]),               # D = 2048: bulk and wide-workgroup calls
     ("c2", dict(n_kv_heads=8, n_q_heads=8, bits=2), 0, [1, 5, 1, 200]),
     ("c3", dict(n_kv_heads=8, n_q_heads=8, outlier_fraction=0.004), 0, [3, 1, 1, 77]),
     ("c4", dict(n_kv_heads=2, n_q_heads=8), 0, [1, 1, 300, 1]),                  # D = 256: the 256-thread kernels
