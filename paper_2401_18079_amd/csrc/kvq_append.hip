@@ -40,27 +40,38 @@ __device__ inline uint32_t block_rank(bool flag, uint32_t *wave_tot, uint32_t &t
     return before + prefix;
 }
 
-// Number of Key outliers of each new token (threshold test only).
-template <int NT>
-__global__ __launch_bounds__(NT) void kvq_k_count(const void *params, int D, const uint16_t *k_new, uint32_t *cnt)
+// Number of Key outliers of each new token (threshold test only).  One wavefront per token, eight
+// channels per lane and pass (16-byte loads of the fp16 vector, D is a multiple of 128): no barriers.
+constexpr int KVQ_COUNT_NT = 256;
+__global__ __launch_bounds__(KVQ_COUNT_NT) void kvq_k_count(const void *params, int D, int T, const uint16_t *k_new,
+                                                            uint32_t *cnt)
 {
-    constexpr int NW = NT / 64;
-    __shared__ uint32_t red[NW];
     KvqParamsView pv = kvq_params_view(params, D);
-    const int t = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * (KVQ_COUNT_NT / 64) + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const uint4 *row = (const uint4 *)(k_new + (int64_t)t * D);
+    const float4 *lo4 = (const float4 *)pv.lo, *hi4 = (const float4 *)pv.hi;
     uint32_t mine = 0;
-    for (int c = threadIdx.x; c < D; c += NT) {
-        const float x = kvq_h2f(k_new[(int64_t)t * D + c]), lo = pv.lo[c], hi = pv.hi[c];
-        mine += ((x < lo) | (x > hi)) ? 1u : 0u;
+    if ((uintptr_t)k_new & 15) {          // input not 16-byte aligned: one channel per lane and pass
+        for (int c = lane; c < D; c += 64) {
+            const float x = kvq_h2f(k_new[(int64_t)t * D + c]);
+            mine += ((x < pv.lo[c]) | (x > pv.hi[c])) ? 1u : 0u;
+        }
+    } else for (int v = lane; v < D / 8; v += 64) {
+        const uint4 h = row[v];
+        const float4 la = lo4[2 * v], lb = lo4[2 * v + 1], ha = hi4[2 * v], hb = hi4[2 * v + 1];
+        const uint32_t w[4] = {h.x, h.y, h.z, h.w};
+        const float lo[8] = {la.x, la.y, la.z, la.w, lb.x, lb.y, lb.z, lb.w};
+        const float hi[8] = {ha.x, ha.y, ha.z, ha.w, hb.x, hb.y, hb.z, hb.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float x = kvq_h2f((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+            mine += ((x < lo[e]) | (x > hi[e])) ? 1u : 0u;
+        }
     }
     for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mine;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t s = 0;
-        for (int i = 0; i < NW; ++i) s += red[i];
-        cnt[t] = s;
-    }
+    if (lane == 0) cnt[t] = mine;
 }
 
 // ptr[n0+1+t] = min(ptr[n0] + cnt[0] + ... + cnt[t], cap_nnz); one workgroup, T <= 4096.
@@ -739,8 +750,7 @@ extern "C" kvq_status kvq_quantize_append_k(kvq_cache *cache, const uint16_t *d_
     if (!single) {
         if (!cache->workspace || cache->workspace_bytes < (int64_t)T * 4) return KVQ_ERR_CAPACITY;
         uint32_t *cnt = (uint32_t *)cache->workspace;
-        if (D >= 2048) kvq_k_count<1024><<<T, 1024, 0, s>>>(cache->params, D, d_k_new, cnt);
-        else kvq_k_count<256><<<T, 256, 0, s>>>(cache->params, D, d_k_new, cnt);
+        kvq_k_count<<<(T + KVQ_COUNT_NT / 64 - 1) / (KVQ_COUNT_NT / 64), KVQ_COUNT_NT, 0, s>>>(cache->params, D, T, d_k_new, cnt);
         kvq_ptr_scan<<<1, 1024, 0, s>>>(cache->k_ptr, cache->n_tokens_k, T, cnt, cache->cap_nnz_k, cache->d_status);
     }
 #define LAUNCH_K(B)                                                                                             \
@@ -823,8 +833,7 @@ extern "C" kvq_status kvq_quantize_append_kv(kvq_cache *cache, const uint16_t *d
     if (!single) {
         if (!cache->workspace || cache->workspace_bytes < (int64_t)T * 4) return KVQ_ERR_CAPACITY;
         uint32_t *cnt = (uint32_t *)cache->workspace;
-        if (D >= 2048) kvq_k_count<1024><<<T, 1024, 0, s>>>(cache->params, D, d_k_new, cnt);
-        else kvq_k_count<256><<<T, 256, 0, s>>>(cache->params, D, d_k_new, cnt);
+        kvq_k_count<<<(T + KVQ_COUNT_NT / 64 - 1) / (KVQ_COUNT_NT / 64), KVQ_COUNT_NT, 0, s>>>(cache->params, D, T, d_k_new, cnt);
         kvq_ptr_scan<<<1, 1024, 0, s>>>(cache->k_ptr, cache->n_tokens_k, T, cnt, cache->cap_nnz_k, cache->d_status);
     }
     KvAppendArgs a;

@@ -77,6 +77,37 @@ def test_append_kv_mixes_with_separate_appends_and_unequal_counts():
     assert not compare_caches(oc, gc)
 
 
+def test_appends_from_inputs_that_are_only_2_byte_aligned():
+    """New-token matrices that start one fp16 element into an allocation: legal for every append call
+    (the boundary asks for fp16 alignment only), so no kernel may rely on wider loads of them."""
+    import torch
+    import paper_2401_18079_amd as K
+    wl = S.workload("c2", n_kv_heads=8, n_q_heads=8)
+    st = Setup(wl)
+    oc, gc = _caches(st, 512)
+
+    def shifted(a):
+        buf = torch.zeros(a.size + 1, dtype=torch.float16, device="cuda")
+        buf[1:] = torch.from_numpy(a).cuda().reshape(-1)
+        x = buf[1:].view(a.shape)
+        assert x.data_ptr() % 16 == 2 and x.is_contiguous()
+        return x
+
+    t0 = 0
+    for T, combined in ((1, True), (37, True), (1, False), (90, False)):
+        k, v = st.k(t0, T), st.v(t0, T)
+        oc.append_k(k); oc.append_v(v)
+        if combined:
+            K.kvq_quantize_append_kv(gc, shifted(k), shifted(v))
+        else:
+            K.kvq_quantize_append_k(gc, shifted(k))
+            K.kvq_quantize_append_v(gc, shifted(v))
+        t0 += T
+    torch.cuda.synchronize()
+    assert gc.status() == 0
+    assert not compare_caches(oc, gc)
+
+
 def test_append_kv_overflow_and_argument_errors():
     import torch
     import paper_2401_18079_amd as K
