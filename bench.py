@@ -363,6 +363,21 @@ def main():
                 "qk_gbps": L * D * 2 / (res["qk"] * 1e-6) / 1e9, "pv_gbps": L * D * 2 / (res["pv"] * 1e-6) / 1e9}
         del k16, v16
 
+    # what a kernel that only reads reaches on this GPU (4 GiB: sixteen times the last-level cache)
+    sbuf = torch.ones(1 << 32, dtype=torch.uint8, device="cuda")
+    sws = torch.zeros(K.binding.kvq_stream_read_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    tm = K.HipEventTimer()
+    for _ in range(3):
+        K.binding.kvq_stream_read(sbuf, sws)
+    tm.start()
+    for _ in range(10):
+        K.binding.kvq_stream_read(sbuf, sws)
+    tm.stop()
+    stream_gbps = sbuf.numel() / (tm.elapsed_ms() * 1e-3 / 10) / 1e9
+    stream_read = {"gbps": stream_gbps, "bytes": sbuf.numel(), "frac_of_peak": stream_gbps / HBM_PEAK_GBPS,
+                   "dense_qk_frac_of_stream_read": dense_qk_gbps / stream_gbps}
+    del sbuf, sws
+
     if args.calibrate_copy:
         src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -438,6 +453,7 @@ def main():
                      "algorithmic_bytes": dense_qk_bytes, "avg_launch_us": dense_qk_us,
                      "whole_call": {"algorithmic_bytes": qk_bytes, "avg_us": breakdown["qk_matvec"],
                                     "achieved": qk_gbps, "frac": qk_gbps / HBM_PEAK_GBPS},
+                     "stream_read": stream_read,
                      "valu_issue": valu},
         "cpu_baseline": cpu,
     }

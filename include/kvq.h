@@ -254,6 +254,19 @@ kvq_status kvq_fp16_pv_matvec(const uint16_t *d_v16, int64_t L, int32_t n_kv_hea
                               void *d_workspace, int64_t workspace_bytes, void *stream);
 
 /*
+ * Streaming-read reference for the bandwidth figures (no part of the method): reads `bytes` bytes of
+ * d_buf once with 16-byte loads and leaves per-workgroup checksums (sum over the workgroup's 16-byte
+ * groups of the XOR of their four 32-bit words, as uint32) in d_workspace; the time of this call is
+ * what a kernel that only reads can reach on this GPU.
+ *   d_buf: DEVICE, 16-byte aligned, bytes a positive multiple of 16.
+ *   d_workspace: DEVICE, kvq_stream_read_workspace_bytes() bytes.
+ * Errors: INVALID_ARG, CAPACITY (workspace), HIP.
+ */
+int64_t kvq_stream_read_workspace_bytes(void);
+kvq_status kvq_stream_read(const void *d_buf, int64_t bytes, void *d_workspace, int64_t workspace_bytes,
+                           void *stream);
+
+/*
  * Timing aid: runs `fn`-independent HIP events on `stream`.  kvq_event_* wrap hipEvent so that a
  * Python caller can time work on the stream the kernels are launched on without another binding.
  */

@@ -68,6 +68,8 @@ def load_library():
         "kvq_fp16_qk_matvec": (C.c_int, [V, I64, I32, I32, V, F, V, I64, V]),
         "kvq_fp16_pv_workspace_bytes": (I64, [I32, I64]),
         "kvq_fp16_pv_matvec": (C.c_int, [V, I64, I32, I32, V, I64, V, V, I64, V]),
+        "kvq_stream_read_workspace_bytes": (I64, []),
+        "kvq_stream_read": (C.c_int, [V, I64, V, I64, V]),
         "kvq_event_create": (C.c_int, [C.POINTER(V)]),
         "kvq_event_record": (C.c_int, [V, V]),
         "kvq_event_elapsed_ms": (C.c_int, [V, V, C.POINTER(F)]),
@@ -89,7 +91,7 @@ EXPORTED_SYMBOLS = [
     "kvq_attention_decode", "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
     "kvq_fp16_pv_matvec", "kvq_event_create", "kvq_event_record", "kvq_event_elapsed_ms", "kvq_event_destroy",
     "kvq_profile_enable", "kvq_profile_last_ms", "kvq_calibrate_workspace_bytes", "kvq_calibrate_nuq",
-    "kvq_calibrate_key_channels",
+    "kvq_calibrate_key_channels", "kvq_stream_read_workspace_bytes", "kvq_stream_read",
 ]
 
 
@@ -307,6 +309,18 @@ def kvq_fp16_pv_matvec(v16: torch.Tensor, n_kv_heads: int, n_q_heads: int, probs
                                              probs.stride(0), out.data_ptr(), workspace.data_ptr(),
                                              workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
            "kvq_fp16_pv_matvec")
+
+
+def kvq_stream_read(buf: torch.Tensor, workspace: torch.Tensor, stream=None):
+    """Reads `buf` once (the streaming-read reference); per-workgroup checksums land in `workspace` (uint32)."""
+    assert buf.is_cuda and buf.is_contiguous() and workspace.is_cuda and workspace.is_contiguous()
+    _check(load_library().kvq_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), workspace.data_ptr(),
+                                          workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+           "kvq_stream_read")
+
+
+def kvq_stream_read_workspace_bytes() -> int:
+    return int(load_library().kvq_stream_read_workspace_bytes())
 
 
 class HipEventTimer:

@@ -51,6 +51,16 @@ __host__ __device__ inline KvqParamsView kvq_params_view(const void *block, int 
     return v;
 }
 
+// 16-byte load of data that is read once per launch (packed codes): the non-temporal hint keeps the
+// stream from displacing what is read again (scores, partial sums) and a plain read of a large
+// buffer is measurably faster with it.
+__device__ __forceinline__ uint4 kvq_load_stream16(const void *p)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = __builtin_nontemporal_load((const u32x4 *)p);
+    return uint4{v.x, v.y, v.z, v.w};
+}
+
 // ---- storage format addressing (bytes) -----------------------------------------------------
 // Key chunk of (token n, KV head h): `bits` pieces of 16 bytes, piece j at k_piece0 + j*1024.
 __host__ __device__ inline int64_t kvq_k_piece0(int bits, int64_t cap, int64_t n, int h)

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256) void fp16_qk(const uint16_t *__restrict__ k16,
         for (int t = 0; t < tokens_per_wg; ++t) {
             const int64_t n = n0 + t;
             if (n >= L) break;
-            const uint4 raw = *(const uint4 *)(k16 + n * D + (int64_t)v * 8);
+            const uint4 raw = kvq_load_stream16(k16 + n * D + (int64_t)v * 8);
             const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
             float acc[R];
 #pragma unroll
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(256) void fp16_pv(const uint16_t *__restrict__ v16,
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int64_t n = (n0 + u < ne) ? n0 + u : ne - 1;   // clamped: straight-line loads
-                raw[u] = *(const uint4 *)(v16 + n * D + (int64_t)v * 8);
+                raw[u] = kvq_load_stream16(v16 + n * D + (int64_t)v * 8);
 #pragma unroll
                 for (int r = 0; r < R; ++r)
                     pr[u][r] = (n0 + u < ne) ? probs[(int64_t)(kvh * R + r) * ld + n] : 0.f;
@@ -134,7 +134,58 @@ __global__ __launch_bounds__(1024) void fp16_pv_reduce(int n_q_heads, int slabs,
 
 constexpr int FP16_PV_SLABS = 1024;
 
+// Plain streaming read: every workgroup walks its share of the buffer in 16-byte loads (eight in
+// flight per lane) and leaves one partial sum, so nothing but the reads limits it.  The loads carry
+// the non-temporal hint; measured over 4 GiB: 6.4 TB/s with it, 5.9 TB/s without, and 8192 workgroups
+// of 256 threads striding through the buffer together beat both fewer workgroups and one contiguous
+// chunk per workgroup.
+constexpr int STREAM_NT = 256, STREAM_WGS = 8192, STREAM_UNROLL = 8;
+__device__ __forceinline__ uint32_t stream_fold(const uint4 *p)
+{
+    const uint4 v = kvq_load_stream16(p);
+    return v.x ^ v.y ^ v.z ^ v.w;
+}
+__global__ __launch_bounds__(STREAM_NT) void stream_read(const uint4 *__restrict__ buf, int64_t n16,
+                                                          uint32_t *__restrict__ sums)
+{
+    uint32_t acc = 0;
+    const int64_t stride = (int64_t)gridDim.x * STREAM_NT;
+    int64_t i = (int64_t)blockIdx.x * STREAM_NT + threadIdx.x;
+    for (; i + (STREAM_UNROLL - 1) * stride < n16; i += STREAM_UNROLL * stride) {
+        uint32_t v[STREAM_UNROLL];
+#pragma unroll
+        for (int u = 0; u < STREAM_UNROLL; ++u) v[u] = stream_fold(buf + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < STREAM_UNROLL; ++u) acc += v[u];
+    }
+    for (; i < n16; i += stride) acc += stream_fold(buf + i);
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    __shared__ uint32_t red[STREAM_NT / 64];
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int w = 0; w < STREAM_NT / 64; ++w) t += red[w];
+        sums[blockIdx.x] = t;
+    }
+}
+
 }  // namespace
+
+extern "C" int64_t kvq_stream_read_workspace_bytes(void) { return (int64_t)STREAM_WGS * 4; }
+
+extern "C" kvq_status kvq_stream_read(const void *d_buf, int64_t bytes, void *d_workspace, int64_t workspace_bytes,
+                                      void *stream)
+{
+    if (!d_buf || ((uintptr_t)d_buf & 15) || bytes < 16 || (bytes & 15)) return KVQ_ERR_INVALID_ARG;
+    if (!d_workspace || workspace_bytes < kvq_stream_read_workspace_bytes()) return KVQ_ERR_CAPACITY;
+    const int64_t n16 = bytes / 16;
+    int64_t wgs = (n16 + STREAM_NT - 1) / STREAM_NT;
+    if (wgs > STREAM_WGS) wgs = STREAM_WGS;
+    stream_read<<<(unsigned)wgs, STREAM_NT, 0, (hipStream_t)stream>>>((const uint4 *)d_buf, n16, (uint32_t *)d_workspace);
+    KVQ_HIP_CHECK(hipGetLastError());
+    return KVQ_OK;
+}
 
 extern "C" kvq_status kvq_fp16_qk_matvec(const uint16_t *d_k16, int64_t L, int32_t n_kv_heads, int32_t n_q_heads,
                                          const float *d_q, float scale, float *d_scores, int64_t ld_scores,

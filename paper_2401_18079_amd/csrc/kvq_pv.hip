@@ -215,7 +215,7 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
             if constexpr (RG == 1) {
 #pragma unroll
                 for (int j = 0; j < BITS; ++j) {
-                    const uint4 v = *(const uint4 *)(p + j * 1024);
+                    const uint4 v = kvq_load_stream16(p + j * 1024);
                     W[4 * j + 0] = v.x; W[4 * j + 1] = v.y; W[4 * j + 2] = v.z; W[4 * j + 3] = v.w;
                 }
             } else {

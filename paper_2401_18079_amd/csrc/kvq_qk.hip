@@ -164,7 +164,7 @@ __device__ __forceinline__ void qk_group(uint32_t (&W)[KVH][8], float (&acc)[KVH
                 if (valid) {
 #pragma unroll
                     for (int g = 0; g < KVH; ++g) {
-                        const uint4 v = *(const uint4 *)(cur_chunk + g * plane + jn * 1024);
+                        const uint4 v = kvq_load_stream16(cur_chunk + g * plane + jn * 1024);
                         W[g][(jn & 1) * 4 + 0] = v.x; W[g][(jn & 1) * 4 + 1] = v.y;
                         W[g][(jn & 1) * 4 + 2] = v.z; W[g][(jn & 1) * 4 + 3] = v.w;
                     }
@@ -175,7 +175,7 @@ __device__ __forceinline__ void qk_group(uint32_t (&W)[KVH][8], float (&acc)[KVH
                 if (next_valid) {
 #pragma unroll
                     for (int g = 0; g < KVH; ++g) {
-                        const uint4 v = *(const uint4 *)(next_chunk + g * plane + jt * 1024);
+                        const uint4 v = kvq_load_stream16(next_chunk + g * plane + jt * 1024);
                         W[g][(j & 1) * 4 + 0] = v.x; W[g][(j & 1) * 4 + 1] = v.y;
                         W[g][(j & 1) * 4 + 2] = v.z; W[g][(j & 1) * 4 + 3] = v.w;
                     }
@@ -282,7 +282,7 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
         for (int g = 0; g < KVH; ++g)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const uint4 v = *(const uint4 *)(cur_chunk + g * plane + j * 1024);
+                const uint4 v = kvq_load_stream16(cur_chunk + g * plane + j * 1024);
                 W[g][4 * j + 0] = v.x; W[g][4 * j + 1] = v.y; W[g][4 * j + 2] = v.z; W[g][4 * j + 3] = v.w;
             }
     }
@@ -324,7 +324,7 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
 #pragma unroll
                 for (int k = 0; k < 4; ++k) W[g][k] = W[g][4 + k];
                 if (next_valid) {
-                    const uint4 v = *(const uint4 *)(next_chunk + g * plane + 1024);
+                    const uint4 v = kvq_load_stream16(next_chunk + g * plane + 1024);
                     W[g][4] = v.x; W[g][5] = v.y; W[g][6] = v.z; W[g][7] = v.w;
                 }
             }
