@@ -188,7 +188,7 @@ def main():
     ap.add_argument("--context", type=int, default=0, help="override the context length")
     ap.add_argument("--bits", type=int, default=0, help="override the code width (2, 3 or 4)")
     ap.add_argument("--outliers", type=float, default=-1.0, help="override the outlier fraction (e.g. 0.01)")
-    ap.add_argument("--cpu-sample", type=int, default=4096, help="tokens of context for the CPU-oracle timing (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=16384, help="tokens of context for the CPU-oracle timing (0 = skip)")
     ap.add_argument("--layers", type=int, default=1,
                     help="more than 1: time a decode step over that many layers (each its own cache), nothing else")
     ap.add_argument("--no-fp16", action="store_true")
