@@ -119,7 +119,8 @@ kvq_status kvq_lut_load(kvq_cache *cache, const float *h_lut_k, const float *h_l
  * normalise / de-quantise equations of App. "Derivation for Quantization Error").  Per element:
  * x_norm = (x - z_c) * (1/s_c) in fp32, code = nearest signpost (ties to the smaller index),
  * outlier iff x < lo_c or x > hi_c; an outlier's sparse value is fp16(x - fmaf(s_c, lut[code], z_c)).
- *   d_k_new : DEVICE fp16 [T][D], row t is token n_tokens_k + t.  1 <= T <= 4096.
+ *   d_k_new : DEVICE fp16 [T][D], row t is token n_tokens_k + t.  1 <= T <= 4096.  Any fp16-aligned
+ *             address (16-byte alignment lets the outlier count of a multi-token call use wide loads).
  * Writes the packed codes, k_ptr[n+1..n+T], k_idx/k_val; advances cache->n_tokens_k by T.
  * Outliers that do not fit cap_nnz_k are dropped (highest channels of the overflowing token
  * first) and *d_status is set to KVQ_ERR_NNZ_OVERFLOW.  Host errors: INVALID_ARG, CAPACITY,
@@ -142,7 +143,8 @@ kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_v_new, int3
  * Both appends of a decode step in one call and, for the quantization itself, one kernel launch:
  * exactly kvq_quantize_append_k(cache, d_k_new, T) followed by kvq_quantize_append_v(cache, d_v_new, T)
  * (paper Sec. 3.1-3.4, 3.6 as above), with the workgroups of the two running side by side: a
- * single-token append is latency-bound and the two do not depend on each other.  The checks of both
+ * single-token append is latency-bound and the two do not depend on each other (from 256 tokens per
+ * call on, where either kernel fills the GPU alone, the two run one after the other).  The checks of both
  * calls are made before anything is launched; n_tokens_k and n_tokens_v both advance by T.
  */
 kvq_status kvq_quantize_append_kv(kvq_cache *cache, const uint16_t *d_k_new, const uint16_t *d_v_new,
