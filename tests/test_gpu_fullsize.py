@@ -153,12 +153,23 @@ def test_c3_million_token_context_sampled_parity():
     wavefront of the sparse kernels walks many sub-ranges here and positions reach 2^20, where the
     rotary angle needs its two-float reduction.  The reference is evaluated only on the sampled windows
     (the oracle's reconstruction and rotation, token by token), so the test stays within seconds."""
+    Lc = (1 << 20) + 77
+    _sampled_full_size_parity(S.workload("c3"), Lc, [0, (Lc // WIN) * WIN, (1 << 20) - WIN], n_random=5)
+
+
+def test_c4_half_million_token_gqa_context_sampled_parity():
+    """Configuration 4's sequence at its full size (32 query / 8 KV heads, context 524,288 + a ragged
+    tail, nuq2, 1 % outliers, rotary base 500000): four query heads share every KV head's codes in the
+    launch configuration the benchmark times for this shape."""
+    Lc = (1 << 19) + 55
+    _sampled_full_size_parity(S.workload("c4"), Lc, [0, (Lc // WIN) * WIN, (1 << 19) - WIN], n_random=4)
+
+
+def _sampled_full_size_parity(wl, Lc, fixed_starts, n_random):
     import torch
     import paper_2401_18079_amd as K
     import bench
 
-    Lc = (1 << 20) + 77
-    wl = S.workload("c3")
     st = Setup(wl)
     cap = ((Lc + 127) // 128) * 128
     gc, dg, _, _ = bench.build_cache(st, Lc, cap, K, torch)
@@ -166,7 +177,7 @@ def test_c3_million_token_context_sampled_parity():
 
     H, Hq, D, bits = wl.n_kv_heads, wl.n_q_heads, wl.D, wl.bits
     rng = np.random.default_rng(wl.seed + 3)
-    starts = sorted(set([0, (Lc // WIN) * WIN, (1 << 20) - WIN] + [int(x) * WIN for x in rng.integers(1, Lc // WIN, 5)]))
+    starts = sorted(set(list(fixed_starts) + [int(x) * WIN for x in rng.integers(1, Lc // WIN, n_random)]))
     gkp = gc.k_ptr.cpu().numpy().view(np.uint32); gvp = gc.v_ptr.cpu().numpy().view(np.uint32)
     gsz = gc.v_sz.cpu().numpy().view(np.uint16).reshape(cap, 2)
     q = S.gen_q(wl, 0, 0)
