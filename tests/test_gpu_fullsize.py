@@ -165,12 +165,20 @@ def test_c4_half_million_token_gqa_context_sampled_parity():
     _sampled_full_size_parity(S.workload("c4"), Lc, [0, (Lc // WIN) * WIN, (1 << 19) - WIN], n_random=4)
 
 
-def _sampled_full_size_parity(wl, Lc, fixed_starts, n_random):
+def test_c5_last_layer_million_token_context_sampled_parity():
+    """One layer of configuration 5 at its full size (the last of the 32: its own look-up tables and
+    per-channel constants; context 1,048,576 + a ragged tail, nuq3, 1 % outliers: eight times the
+    benchmark workload's context, 32 tiles per workgroup of the dense kernels)."""
+    Lc = (1 << 20) + 21
+    _sampled_full_size_parity(S.workload("c5"), Lc, [0, (Lc // WIN) * WIN, (1 << 20) - WIN], n_random=4, layer=31)
+
+
+def _sampled_full_size_parity(wl, Lc, fixed_starts, n_random, layer=0):
     import torch
     import paper_2401_18079_amd as K
     import bench
 
-    st = Setup(wl)
+    st = Setup(wl, layer)
     cap = ((Lc + 127) // 128) * 128
     gc, dg, _, _ = bench.build_cache(st, Lc, cap, K, torch)
     assert gc.status() == 0 and gc.n_tokens_k == Lc and gc.n_tokens_v == Lc
