@@ -183,6 +183,45 @@ class KvqCache:
     def status(self) -> int:
         return int(self.d_status[0].item())
 
+    # Blocked allocation of the sparse arrays (paper App. "Limitations": allocating the outlier
+    # storage in blocks, so that appending a token does not copy what is already stored, is what the paper plans).  The library never
+    # allocates: capacity is a field of the descriptor, so the owner of the memory grows the arrays
+    # between calls, here by whole blocks of NNZ_BLOCK entries, and nothing already stored changes.
+    NNZ_BLOCK = 1 << 20
+
+    def nnz_used(self):
+        """(Key, Value) outlier entries stored so far.  Reads two device words: synchronises."""
+        k = int(self.k_ptr[self.n_tokens_k].item()) & 0xFFFFFFFF
+        v = int(self.v_ptr[self.n_tokens_v].item()) & 0xFFFFFFFF
+        return k, v
+
+    def ensure_nnz_room(self, extra_k: int, extra_v: int, block: int = None) -> bool:
+        """Make room for `extra_k` / `extra_v` more outlier entries (worst case of the next appends: every
+        element of a Key token can be an outlier, a Value token has exactly 2 * k_side_v).  Grows the
+        arrays by whole blocks when needed, copying the entries in use.  Returns True if anything grew."""
+        block = int(block or self.NNZ_BLOCK)
+        used_k, used_v = self.nnz_used()
+        grew = False
+        for used, extra, cap_name, names in ((used_k, extra_k, "cap_nnz_k", ("k_idx", "k_val")),
+                                             (used_v, extra_v, "cap_nnz_v", ("v_idx", "v_val"))):
+            need = used + int(extra)
+            if need <= getattr(self.c, cap_name):
+                continue
+            if need >= 1 << 32:
+                raise KvqError(3, "ensure_nnz_room")            # pointers are 32-bit
+            cap = min((need + block - 1) // block * block, (1 << 32) - 1)
+            for name in names:
+                old = getattr(self, name)
+                new_t = torch.zeros(cap, dtype=old.dtype, device=old.device)
+                new_t[:used] = old[:used]
+                setattr(self, name, new_t)
+                setattr(self.c, name, new_t.data_ptr())
+            setattr(self.c, cap_name, cap)
+            grew = True
+        if grew:
+            torch.cuda.synchronize(self.device)                 # the old arrays are released after the copies
+        return grew
+
 
 def _host_u16(a):
     a = np.ascontiguousarray(a)
