@@ -6,12 +6,15 @@ benchmark.  The GPU library never imports or calls anything in this package.
 from __future__ import annotations
 
 import ctypes as C
+import os
 
 import numpy as np
 
 from . import build as _build
 
-_lib = C.CDLL(_build.build())
+# KVQ_ORACLE_LIB: load this build of the oracle instead (the test that plants mistakes in a copy of
+# the C source and checks that the pins notice uses it; nothing else sets it)
+_lib = C.CDLL(os.environ.get("KVQ_ORACLE_LIB") or _build.build())
 
 _u8p = np.ctypeslib.ndpointer(dtype=np.uint8, flags="C_CONTIGUOUS")
 _u16p = np.ctypeslib.ndpointer(dtype=np.uint16, flags="C_CONTIGUOUS")

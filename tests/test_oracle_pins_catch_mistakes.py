@@ -1,0 +1,103 @@
+"""The pins of the C oracle are only worth something if a plausible mistake in the oracle trips one of
+them.  Each case plants one mistake (a wrong sign, a dropped term, an off-by-one, a swapped tie rule, a
+transposed index) in a copy of oracle/kvq_oracle.c, builds it, and runs the oracle's pin tests against
+that build in a child process: the run must fail.  The unmodified source, built the same way, must pass.
+Everything here runs on the CPU."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "kvq_oracle.c")
+
+PINS_QUANT = ["tests/test_oracle_quant.py", "tests/test_oracle_fp16_pack.py"]
+PINS_MATVEC = ["tests/test_oracle_rope_matvec.py", "tests/test_oracle_sink.py"]
+
+# (name, text in the source, mistaken text, pin files that must notice)
+MISTAKES = [
+    ("rope: sign of the sine term of the lower channel",
+     "y[i] = x[i] * c - x[i + half] * sn;", "y[i] = x[i] * c + x[i + half] * sn;", PINS_MATVEC),
+    ("rope: sign of the sine term of the upper channel",
+     "y[i + half] = x[i + half] * c + x[i] * sn;", "y[i + half] = x[i + half] * c - x[i] * sn;", PINS_MATVEC),
+    ("rope: frequency exponent halved",
+     "pow(base, -2.0 * (double)i / (double)d)", "pow(base, -1.0 * (double)i / (double)d)", PINS_MATVEC),
+    ("rope: position off by one",
+     "double phi = (double)n * theta;", "double phi = (double)(n + 1) * theta;", PINS_MATVEC),
+    ("nearest signpost: ties to the larger index",
+     "if (dj < bestd) { bestd = dj; best = j; }", "if (dj <= bestd) { bestd = dj; best = j; }", PINS_QUANT),
+    ("dequantisation: zero-point dropped",
+     "*deq = fmaf(s, lut[code], z);", "*deq = s * lut[code];", PINS_QUANT),
+    ("normalisation: zero-point not subtracted",
+     "float diff = x - z;", "float diff = x;", PINS_QUANT),
+    ("Key outlier test: non-strict comparison",
+     "if (xv < kvqo_h2f(lo[c]) || xv > kvqo_h2f(hi[c])) {", "if (xv <= kvqo_h2f(lo[c]) || xv >= kvqo_h2f(hi[c])) {",
+     PINS_QUANT),
+    ("Value scale: full range instead of half range",
+     "uint16_t sb = kvqo_f2h(dif * 0.5f);", "uint16_t sb = kvqo_f2h(dif);", PINS_QUANT),
+    ("Value zero-point: minimum instead of mid-range",
+     "uint16_t zb = kvqo_f2h(sum * 0.5f);", "uint16_t zb = kvqo_f2h(mn);", PINS_QUANT),
+    ("Value lower outliers: off by one in the sorted rest",
+     "is_out[w[k_side + k].i] = 1;", "is_out[w[k_side + k + 1].i] = 1;", PINS_QUANT),
+    ("Value upper outliers: equal values taken from the larger index",
+     "    if (p->v < q->v) return 1;\n    return (p->i > q->i) - (p->i < q->i);      /* equal values: smaller index first */",
+     "    if (p->v < q->v) return 1;\n    return (p->i < q->i) - (p->i > q->i);", PINS_QUANT),
+    ("sparse residual: stored without subtracting the dense part",
+     "val[total] = kvqo_f2h(xv - deq);\n                }\n                ++total;\n                ++c_t;\n            }\n        }\n        cnt[t] = c_t;\n    }\n    return total;",
+     "val[total] = kvqo_f2h(xv);\n                }\n                ++total;\n                ++c_t;\n            }\n        }\n        cnt[t] = c_t;\n    }\n    return total;",
+     PINS_QUANT),
+    ("reconstruction: Key outliers not added back",
+     "khat[t * D + idx[e]] += (double)kvqo_h2f(val[e]);", "(void)val;", PINS_MATVEC),
+    ("reconstruction: Value outliers added at the neighbouring channel",
+     "vhat[t * D + idx[e]] += (double)kvqo_h2f(val[e]);", "vhat[t * D + (idx[e] ^ 1)] += (double)kvqo_h2f(val[e]);",
+     PINS_MATVEC),
+    ("scores: softmax scale dropped",
+     "scores[h * ld + n] = (float)((double)scale * acc);", "scores[h * ld + n] = (float)acc;", PINS_MATVEC),
+    ("scores: query heads of a group read the next KV head",
+     "kvqo_rope(khat + hk * d, d, n, rope_base, krot);",
+     "kvqo_rope(khat + ((hk + 1) % n_kv_heads) * d, d, n, rope_base, krot);", PINS_MATVEC),
+    ("outputs: Value channels read transposed within the head",
+     "acc[h * d + c] += p * vhat[hk * d + c];", "acc[h * d + c] += p * vhat[hk * d + (d - 1 - c)];", PINS_MATVEC),
+    ("packing: the two codes of a Key field swapped",
+     "put_bits(buf, k_chunk_base(bits, cap, n, h), 2 * bits * field + upper * bits, bits, code);",
+     "put_bits(buf, k_chunk_base(bits, cap, n, h), 2 * bits * field + (1 - upper) * bits, bits, code);", PINS_QUANT),
+    ("packing: Value pieces of a token pair at the wrong stride",
+     "return (int64_t)(h * 2 + g) * (cap / 2) * 16 * bits + (m / 64) * 64 * 16 * bits + (m % 64) * 16;",
+     "return (int64_t)(h * 2 + g) * (cap / 2) * 16 * bits + (m / 64) * 64 * 16 * bits + (m % 64) * 8;", PINS_QUANT),
+    ("fp16 rounding: truncation instead of round-to-nearest-even",
+     "double r = nearbyint(q);", "double r = floor(q);", PINS_QUANT),
+]
+
+
+def _build(src_text, out_dir, name):
+    c_path = os.path.join(out_dir, name + ".c")
+    so_path = os.path.join(out_dir, name + ".so")
+    with open(c_path, "w") as f:
+        f.write(src_text)
+    subprocess.run(["gcc", "-O1", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-o", so_path, c_path, "-lm"],
+                   check=True)
+    return so_path
+
+
+def _pins_pass(lib, files):
+    env = dict(os.environ, KVQ_ORACLE_LIB=lib, OMP_NUM_THREADS="2")
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", "-m", "not gpu", *files],
+                       cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    return r.returncode == 0, r.stdout[-1500:]
+
+
+def test_the_unmodified_oracle_built_this_way_passes_its_pins(tmp_path):
+    lib = _build(open(SRC).read(), str(tmp_path), "plain")
+    ok, tail = _pins_pass(lib, PINS_QUANT + PINS_MATVEC)
+    assert ok, tail
+
+
+@pytest.mark.parametrize("name,good,bad,files", MISTAKES, ids=[m[0] for m in MISTAKES])
+def test_a_planted_mistake_trips_a_pin(tmp_path, name, good, bad, files):
+    text = open(SRC).read()
+    assert text.count(good) >= 1, f"the source no longer contains the line this case edits: {name}"
+    mutated = text.replace(good, bad, 1)
+    lib = _build(mutated, str(tmp_path), "mutant")
+    ok, tail = _pins_pass(lib, files)
+    assert not ok, f"no pin noticed: {name}\n{tail}"
