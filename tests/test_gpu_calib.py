@@ -125,6 +125,8 @@ def _same(got, ref):
 @pytest.mark.parametrize("heads,T,p", [
     (4, 4096, 0.01),
     (4, 3000, 0.01),          # T not a multiple of the workgroup size
+    (4, 4096, 0.01006),       # fraction/2 * T = 20.6: the outlier count rounds to the nearest integer, 21
+    (4, 100, 0.05),           # fraction/2 * T = 2.5: a half rounds up, 3
     (32, 4096, 0.01),         # the bench layer's width
     (2, 32768, 0.001),        # the largest calibration set (16 samples of 2K tokens)
     (2, 700, 0.0),            # no outliers: open thresholds, full range

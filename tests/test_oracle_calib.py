@@ -177,10 +177,12 @@ def test_key_channel_constants_against_numpy_partition_and_counts():
     assert np.max(np.abs(xn[inl])) <= 1.0 + 2e-3
 
 
-def test_key_channel_constants_equal_the_input_generators_calibration():
+@pytest.mark.parametrize("fraction", [0.01, 0.01006, 0.0012])
+def test_key_channel_constants_equal_the_input_generators_calibration(fraction):
     """The synthetic-input package calibrates its Key channels with code of its own (numpy, written
-    for input generation): same data, same constants."""
-    wl = S.workload("c2", n_kv_heads=4, n_q_heads=4)
+    for input generation): same data, same constants.  The fractions put fraction/2 * 4096 at 20.48,
+    20.60 and 2.46: rounding the outlier count to the nearest integer matters for the second."""
+    wl = S.workload("c2", n_kv_heads=4, n_q_heads=4, outlier_fraction=fraction)
     prof = S.key_channel_profile(wl, 0)
     from kvq_synth.gen import T_KCAL
     x = S.gen_k(wl, 0, 0, 0, 4096, profile=prof, tensor_id=T_KCAL)

@@ -101,3 +101,62 @@ def test_a_planted_mistake_trips_a_pin(tmp_path, name, good, bad, files):
     lib = _build(mutated, str(tmp_path), "mutant")
     ok, tail = _pins_pass(lib, files)
     assert not ok, f"no pin noticed: {name}\n{tail}"
+
+
+# ---- the calibration oracle (numpy): the same exercise on a copy of the tree ------------------------
+CALIB_SRC = os.path.join(ROOT, "oracle", "kvq_calib_oracle.py")
+
+CALIB_MISTAKES = [
+    ("k-means: weights ignored in the update",
+     "c[j] = np.float32(float(np.sum(w64[m] * x64[m])) / sw)", "c[j] = np.float32(float(np.mean(x64[m])))"),
+    ("k-means: ties to the larger index", "closer = d < bestd", "closer = d <= bestd"),
+    ("k-means: a signpost without weight jumps to zero",
+     "        if sw > 0.0:\n            c[j] = np.float32(float(np.sum(w64[m] * x64[m])) / sw)",
+     "        c[j] = np.float32(float(np.sum(w64[m] * x64[m])) / sw) if sw > 0.0 else np.float32(0.0)"),
+    ("k-means: one iteration too few", "for _ in range(int(iters)):", "for _ in range(int(iters) - 1):"),
+    ("objective: weights left out",
+     "return float(np.sum(np.asarray(w, dtype=np.float64) * (x.astype(np.float64) - q) ** 2))",
+     "return float(np.sum((x.astype(np.float64) - q) ** 2))"),
+    ("thresholds: outlier count rounded down", "k = int(np.floor(float(outlier_fraction) / 2.0 * T + 0.5))",
+     "k = int(np.floor(float(outlier_fraction) / 2.0 * T))"),
+    ("thresholds: one order statistic too far out",
+     "lo[c], hi[c] = np.float16(xs[k - 1]), np.float16(xs[T - k])", "lo[c], hi[c] = np.float16(xs[max(k - 2, 0)]), np.float16(xs[min(T - k + 1, T - 1)])"),
+    ("range: includes the thresholds themselves", "a, b = xs[k], xs[T - k - 1]", "a, b = xs[k - 1], xs[T - k]"),
+    ("scale: full range", "sc = np.float16((np.float32(b) - np.float32(a)) * np.float32(0.5))",
+     "sc = np.float16(np.float32(b) - np.float32(a))"),
+    ("zero-point: lower end instead of mid-range",
+     "z[c] = np.float16((np.float32(b) + np.float32(a)) * np.float32(0.5))", "z[c] = np.float16(np.float32(a))"),
+]
+
+
+def _run_calib_pins(tree):
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", "-m", "not gpu",
+                        "tests/test_oracle_calib.py"], cwd=tree, env=dict(os.environ, OMP_NUM_THREADS="2"),
+                       stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    return r.returncode == 0, r.stdout[-1500:]
+
+
+def _copy_tree(dst, calib_text):
+    import shutil
+    for d in ("oracle", "kvq_synth"):
+        shutil.copytree(os.path.join(ROOT, d), os.path.join(dst, d), ignore=shutil.ignore_patterns("__pycache__"))
+    os.makedirs(os.path.join(dst, "tests"))
+    for f in ("conftest.py", "kvq_testlib.py", "test_oracle_calib.py"):
+        shutil.copy(os.path.join(ROOT, "tests", f), os.path.join(dst, "tests", f))
+    with open(os.path.join(dst, "oracle", "kvq_calib_oracle.py"), "w") as f:
+        f.write(calib_text)
+
+
+def test_the_unmodified_calibration_oracle_passes_its_pins_in_a_copied_tree(tmp_path):
+    _copy_tree(str(tmp_path / "t"), open(CALIB_SRC).read())
+    ok, tail = _run_calib_pins(str(tmp_path / "t"))
+    assert ok, tail
+
+
+@pytest.mark.parametrize("name,good,bad", CALIB_MISTAKES, ids=[m[0] for m in CALIB_MISTAKES])
+def test_a_planted_mistake_in_the_calibration_oracle_trips_a_pin(tmp_path, name, good, bad):
+    text = open(CALIB_SRC).read()
+    assert text.count(good) == 1, f"the source no longer contains the line this case edits: {name}"
+    _copy_tree(str(tmp_path / "t"), text.replace(good, bad, 1))
+    ok, tail = _run_calib_pins(str(tmp_path / "t"))
+    assert not ok, f"no pin noticed: {name}\n{tail}"
