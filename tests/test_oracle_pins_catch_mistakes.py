@@ -65,6 +65,42 @@ MISTAKES = [
     ("packing: Value pieces of a token pair at the wrong stride",
      "return (int64_t)(h * 2 + g) * (cap / 2) * 16 * bits + (m / 64) * 64 * 16 * bits + (m % 64) * 16;",
      "return (int64_t)(h * 2 + g) * (cap / 2) * 16 * bits + (m / 64) * 64 * 16 * bits + (m % 64) * 8;", PINS_QUANT),
+    ("fp16 decoding: subnormals scaled as normal numbers",
+     "v = ldexp((double)m, -24);", "v = ldexp((double)m, -25);", PINS_QUANT),
+    ("fp16 decoding: exponent bias off by one",
+     "v = ldexp((double)(m + 1024u), e - 25);", "v = ldexp((double)(m + 1024u), e - 24);", PINS_QUANT),
+    ("packing: Key token blocks of 32 instead of 64",
+     "return (int64_t)h * cap * 16 * bits + (n / 64) * 64 * 16 * bits + (n % 64) * 16;",
+     "return (int64_t)h * cap * 16 * bits + (n / 32) * 32 * 16 * bits + (n % 32) * 16;", PINS_QUANT),
+    ("packing: pieces 512 bytes apart",
+     "*byte = base + (int64_t)piece * 1024 + inpiece / 8;", "*byte = base + (int64_t)piece * 512 + inpiece / 8;",
+     PINS_QUANT),
+    ("packing: bits of a code written most significant first",
+     "unsigned b = (value >> k) & 1u;", "unsigned b = (value >> (nbits - 1 - k)) & 1u;", PINS_QUANT),
+    ("packing: Value token parity ignored (both tokens of a pair in the low half of a field)",
+     "int g = c / 64, field = c % 64, upper = (int)(n % 2);\n    put_bits(", "int g = c / 64, field = c % 64, upper = 0;\n    put_bits(",
+     PINS_QUANT),
+    ("Value scale: a zero range left at zero",
+     "if (sf == 0.0f) { sf = 1.0f; sb = 0x3c00u; }", "if (sf == 0.0f) { sf = 0.0f; }", PINS_QUANT),
+    ("Value outliers: guard against too many outliers dropped",
+     "if (2 * k_side >= D) return -1;", "if (2 * k_side > D) return -1;", PINS_QUANT),
+    ("softmax: maximum not subtracted",
+     "for (int64_t n = 0; n < L; ++n) sum += exp((double)scores[h * ld_in + n] - mx);\n        for (int64_t n = 0; n < L; ++n)\n            probs[h * ld_out + n] = (float)(exp((double)scores[h * ld_in + n] - mx) / sum);",
+     "mx = 0.0;\n        for (int64_t n = 0; n < L; ++n) sum += exp((double)scores[h * ld_in + n] - mx);\n        for (int64_t n = 0; n < L; ++n)\n            probs[h * ld_out + n] = (float)(exp((double)scores[h * ld_in + n] - mx) / sum);",
+     PINS_MATVEC),
+    ("softmax: normalised by the maximum term instead of the sum",
+     "probs[h * ld_out + n] = (float)(exp((double)scores[h * ld_in + n] - mx) / sum);",
+     "probs[h * ld_out + n] = (float)(exp((double)scores[h * ld_in + n] - mx));", PINS_MATVEC),
+    ("attention sink: one token too many read from the fp16 rows (scores)",
+     "            if (n < n_sink)\n                for (int c = 0; c < D; ++c) khat[c] = (double)kvqo_h2f(sink_k[n * D + c]);",
+     "            if (n < n_sink + 1 && n_sink > 0)\n                for (int c = 0; c < D; ++c) khat[c] = (double)kvqo_h2f(sink_k[(n < n_sink ? n : n_sink - 1) * D + c]);",
+     PINS_MATVEC),
+    ("attention sink: Value rows of sink tokens taken from the quantized cache",
+     "            if (n < n_sink)\n                for (int c = 0; c < D; ++c) vhat[c] = (double)kvqo_h2f(sink_v[n * D + c]);\n            else\n                kvqo_reconstruct_v(",
+     "            if (0)\n                for (int c = 0; c < D; ++c) vhat[c] = (double)kvqo_h2f(sink_v[n * D + c]);\n            else\n                kvqo_reconstruct_v(",
+     PINS_MATVEC),
+    ("outputs: grouped-query heads all read KV head 0",
+     "int hk = h / group;", "int hk = 0; (void)group;", PINS_MATVEC),
     ("fp16 rounding: truncation instead of round-to-nearest-even",
      "double r = nearbyint(q);", "double r = floor(q);", PINS_QUANT),
 ]
@@ -87,19 +123,42 @@ def _pins_pass(lib, files):
     return r.returncode == 0, r.stdout[-1500:]
 
 
-def test_the_unmodified_oracle_built_this_way_passes_its_pins(tmp_path):
-    lib = _build(open(SRC).read(), str(tmp_path), "plain")
-    ok, tail = _pins_pass(lib, PINS_QUANT + PINS_MATVEC)
+def _run_all(jobs):
+    """jobs: name -> callable returning (passed, output tail).  A few at a time: each is a child pytest."""
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=max(1, min(6, (os.cpu_count() or 2) - 1))) as pool:
+        futures = {name: pool.submit(fn) for name, fn in jobs.items()}
+        return {name: f.result() for name, f in futures.items()}
+
+
+@pytest.fixture(scope="module")
+def c_oracle_runs(tmp_path_factory):
+    text = open(SRC).read()
+    out = str(tmp_path_factory.mktemp("c_oracle"))
+
+    def job(i, good, bad, files):
+        def run():
+            if good is not None and text.count(good) < 1:
+                return None, "the source no longer contains the line this case edits"
+            lib = _build(text if good is None else text.replace(good, bad, 1), out, f"variant{i}")
+            return _pins_pass(lib, files)
+        return run
+
+    jobs = {"unmodified": job(0, None, None, PINS_QUANT + PINS_MATVEC)}
+    for i, (name, good, bad, files) in enumerate(MISTAKES, 1):
+        jobs[name] = job(i, good, bad, files)
+    return _run_all(jobs)
+
+
+def test_the_unmodified_oracle_built_this_way_passes_its_pins(c_oracle_runs):
+    ok, tail = c_oracle_runs["unmodified"]
     assert ok, tail
 
 
-@pytest.mark.parametrize("name,good,bad,files", MISTAKES, ids=[m[0] for m in MISTAKES])
-def test_a_planted_mistake_trips_a_pin(tmp_path, name, good, bad, files):
-    text = open(SRC).read()
-    assert text.count(good) >= 1, f"the source no longer contains the line this case edits: {name}"
-    mutated = text.replace(good, bad, 1)
-    lib = _build(mutated, str(tmp_path), "mutant")
-    ok, tail = _pins_pass(lib, files)
+@pytest.mark.parametrize("name", [m[0] for m in MISTAKES])
+def test_a_planted_mistake_trips_a_pin(c_oracle_runs, name):
+    ok, tail = c_oracle_runs[name]
+    assert ok is not None, f"{name}: {tail}"
     assert not ok, f"no pin noticed: {name}\n{tail}"
 
 
@@ -147,16 +206,33 @@ def _copy_tree(dst, calib_text):
         f.write(calib_text)
 
 
-def test_the_unmodified_calibration_oracle_passes_its_pins_in_a_copied_tree(tmp_path):
-    _copy_tree(str(tmp_path / "t"), open(CALIB_SRC).read())
-    ok, tail = _run_calib_pins(str(tmp_path / "t"))
+@pytest.fixture(scope="module")
+def calib_oracle_runs(tmp_path_factory):
+    text = open(CALIB_SRC).read()
+    out = tmp_path_factory.mktemp("calib_oracle")
+
+    def job(i, good, bad):
+        def run():
+            if good is not None and text.count(good) != 1:
+                return None, "the source no longer contains the line this case edits"
+            tree = str(out / f"tree{i}")
+            _copy_tree(tree, text if good is None else text.replace(good, bad, 1))
+            return _run_calib_pins(tree)
+        return run
+
+    jobs = {"unmodified": job(0, None, None)}
+    for i, (name, good, bad) in enumerate(CALIB_MISTAKES, 1):
+        jobs[name] = job(i, good, bad)
+    return _run_all(jobs)
+
+
+def test_the_unmodified_calibration_oracle_passes_its_pins_in_a_copied_tree(calib_oracle_runs):
+    ok, tail = calib_oracle_runs["unmodified"]
     assert ok, tail
 
 
-@pytest.mark.parametrize("name,good,bad", CALIB_MISTAKES, ids=[m[0] for m in CALIB_MISTAKES])
-def test_a_planted_mistake_in_the_calibration_oracle_trips_a_pin(tmp_path, name, good, bad):
-    text = open(CALIB_SRC).read()
-    assert text.count(good) == 1, f"the source no longer contains the line this case edits: {name}"
-    _copy_tree(str(tmp_path / "t"), text.replace(good, bad, 1))
-    ok, tail = _run_calib_pins(str(tmp_path / "t"))
+@pytest.mark.parametrize("name", [m[0] for m in CALIB_MISTAKES])
+def test_a_planted_mistake_in_the_calibration_oracle_trips_a_pin(calib_oracle_runs, name):
+    ok, tail = calib_oracle_runs[name]
+    assert ok is not None, f"{name}: {tail}"
     assert not ok, f"no pin noticed: {name}\n{tail}"

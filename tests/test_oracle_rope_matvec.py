@@ -100,6 +100,20 @@ def exact_cache(bits, H, Hq, L, seed):
     return oc, K, V
 
 
+def test_softmax_subtracts_the_row_maximum():
+    """Scores in the thousands: exp overflows even in double unless the maximum is subtracted first; the
+    result must still be scipy's (which subtracts it) and every row must sum to 1.  A row of equal
+    scores (uniform weights) rides along."""
+    rng = np.random.default_rng(11)
+    x = (rng.standard_normal((3, 50)) * 900.0).astype(np.float32)
+    x[1] = np.float32(-1234.5)
+    p = O.softmax(x)
+    assert np.all(np.isfinite(p))
+    assert np.allclose(p, scipy.special.softmax(x.astype(np.float64), axis=1), rtol=1e-6, atol=1e-12)
+    assert np.allclose(p.sum(1), 1.0, atol=1e-6)
+    assert np.allclose(p[1], 1.0 / 50, rtol=1e-6)
+
+
 @pytest.mark.parametrize("bits,H,Hq", [(3, 2, 2), (4, 1, 4), (2, 2, 8)])
 def test_lossless_cache_reduces_to_textbook_attention_matvecs(bits, H, Hq):
     L = 200
