@@ -588,9 +588,11 @@ kvq_status kvq_pv_run(const kvq_cache *cache, const float *d_probs, int64_t ld_p
         KvqProfile &prof = kvq_profile_state();
         if (prof.enabled) KVQ_HIP_CHECK(hipEventRecord(prof.ev[1][0], s));
         // query heads of one KV head that a wavefront takes together (they share extraction and gather).
-        // Not when the kernel also turns scores into weights: every wavefront that covers a head
-        // evaluates that head's exponentials, and grouping multiplies the wavefronts per head.
-        const int rg = stat_slots ? 1 : (r % 4 == 0) ? 4 : (r % 2 == 0) ? 2 : 1;
+        // When the kernel also turns scores into weights every wavefront that covers a head evaluates
+        // that head's exponentials, and grouping multiplies the wavefronts per head: pairs of heads
+        // still pay there, fours do not (measured, 32 / 8 heads, 2-bit, 512K tokens: 142 us with two,
+        // 155 us with one, 156 us with four heads per wavefront).
+        const int rg = stat_slots ? ((r % 2 == 0) ? 2 : 1) : (r % 4 == 0) ? 4 : (r % 2 == 0) ? 2 : 1;
         if (cache->bits == 2) { if (rg == 4) LAUNCH_PV(2, 4); else if (rg == 2) LAUNCH_PV(2, 2); else LAUNCH_PV(2, 1); }
         else if (cache->bits == 3) { if (rg == 4) LAUNCH_PV(3, 4); else if (rg == 2) LAUNCH_PV(3, 2); else LAUNCH_PV(3, 1); }
         else { if (rg == 4) LAUNCH_PV(4, 4); else if (rg == 2) LAUNCH_PV(4, 2); else LAUNCH_PV(4, 1); }
