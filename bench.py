@@ -217,9 +217,9 @@ def main():
     st = S.LayerInputs(wl)
     L = wl.context
     steps, warmup = args.steps, args.warmup
-    bsteps = min(steps, 50)                        # extra steps timed call by call for the breakdowns
-    steps3 = min(steps, 100)                       # extra steps made of five separate calls
-    n_new = steps + warmup + 2 * bsteps + steps3 + 5
+    bsteps = min(steps, 200)                       # extra steps timed call by call for the breakdowns
+    steps3 = min(steps, 200)                       # extra steps made of five separate calls
+    n_new = steps + warmup + 4 * bsteps + steps3 + 5
     cap = ((L + n_new + 8 + 127) // 128) * 128
     Hq, D = wl.n_q_heads, wl.D
     scale = 1.0 / np.sqrt(128.0)
@@ -308,8 +308,12 @@ def main():
             per[n].append(gap_ms(ev[j], ev[j + 1]) * 1e3)
     breakdown = {n: float(np.mean(v)) for n, v in per.items()}
     breakdown_min = {n: float(np.min(v)) for n, v in per.items()}
+    breakdown_median = {n: float(np.median(v)) for n, v in per.items()}
     fnames = ["append_kv", "attention_decode"]
-    fused_breakdown = {n: float(np.mean([gap_ms(ev[j], ev[j + 1]) * 1e3 for ev in fevs])) for j, n in enumerate(fnames)}
+    fper = {n: [gap_ms(ev[j], ev[j + 1]) * 1e3 for ev in fevs] for j, n in enumerate(fnames)}
+    fused_breakdown = {n: float(np.mean(v)) for n, v in fper.items()}
+    fused_breakdown_stats = {n: {"median": float(np.median(v)), "min": float(np.min(v)), "samples": len(v)}
+                             for n, v in fper.items()}
 
     Lend = gc.n_tokens_k
     nnz_k = int(gc.k_ptr[Lend].item()) & 0xFFFFFFFF
@@ -318,16 +322,27 @@ def main():
     qk_gbps = qk_bytes / (breakdown["qk_matvec"] * 1e-6) / 1e9
     pv_gbps = pv_bytes / (breakdown["pv_matvec"] * 1e-6) / 1e9
 
-    # the dominant kernel on its own: the dense Key kernel inside the attention call, bracketed by HIP
-    # events on the launch stream (same workload, same launch configuration as the timed steps)
-    K.kvq_profile_enable(True)
-    dense_qk, dense_pv = [], []
+    # the dominant kernel on its own, inside full decode steps run back to back exactly like the timed
+    # region (same workload, same launch configuration, no wait for the GPU between steps).  Its
+    # duration is the kernel's own span (first wavefront start to last wavefront end on the GPU's wall
+    # clock, which is what a kernel trace reports); the interval between HIP events recorded around the
+    # launch is taken in further steps and reported beside it: the event records stall the queue, so
+    # that interval is an upper bound (by 1 to 7 us, depending on the machine)
+    base = warmup + steps + 5 + steps3 + 2 * bsteps
+    K.kvq_profile_enable(True, spans=True, events=False)
     for i in range(bsteps):
-        K.kvq_attention_decode(gc, qs[warmup + i], scale, scores, out)
-        dense_qk.append(K.kvq_profile_last_ms(0) * 1e3)
-        dense_pv.append(K.kvq_profile_last_ms(1) * 1e3)
+        step(base + i)
+    torch.cuda.synchronize()
     K.kvq_profile_enable(False)
+    dense_qk, dense_pv = K.kvq_profile_read_all_spans_us(0), K.kvq_profile_read_all_spans_us(1)
+    assert len(dense_qk) == bsteps and len(dense_pv) == bsteps
     dense_qk_us, dense_pv_us = float(np.mean(dense_qk)), float(np.mean(dense_pv))
+    K.kvq_profile_enable(True)
+    for i in range(bsteps):
+        step(base + bsteps + i)
+    torch.cuda.synchronize()
+    K.kvq_profile_enable(False)
+    ev_qk, ev_pv = K.kvq_profile_read_all_us(0), K.kvq_profile_read_all_us(1)
     # dense kernel: packed codes in, fp32 scores out (the sparse kernel's bytes are counted with the call)
     dense_qk_bytes = Lend * (D * wl.bits // 8) + 4 * Hq * Lend
     dense_qk_gbps = dense_qk_bytes / (dense_qk_us * 1e-6) / 1e9
@@ -438,7 +453,8 @@ def main():
                                    "+ kvq_pv_matvec",
                            "ms_per_step": ms_per_step_separate, "steps": steps3},
         "fused_breakdown_us": fused_breakdown,
-        "breakdown_us": breakdown, "breakdown_min_us": breakdown_min,
+        "fused_breakdown_stats_us": fused_breakdown_stats,
+        "breakdown_us": breakdown, "breakdown_min_us": breakdown_min, "breakdown_median_us": breakdown_median,
         "qk_pv_us": breakdown["qk_matvec"] + breakdown["pv_matvec"],
         "hbm_gbps": {"qk_matvec": qk_gbps, "pv_matvec": pv_gbps},
         "bulk_append": bulk,
@@ -446,7 +462,12 @@ def main():
         "fp16_cache_baseline": fp16,
         "speedup_vs_fp16": ({"qk": fp16["qk_us"] / breakdown["qk_matvec"], "pv": fp16["pv_us"] / breakdown["pv_matvec"]}
                             if fp16 else None),
-        "dense_kernel_us": {"qk": dense_qk_us, "pv": dense_pv_us},
+        "dense_kernel_us": {"qk": dense_qk_us, "pv": dense_pv_us,
+                            "qk_median": float(np.median(dense_qk)), "qk_min": float(np.min(dense_qk)),
+                            "pv_median": float(np.median(dense_pv)), "pv_min": float(np.min(dense_pv)),
+                            "measured": "span of the kernel's wavefronts on the GPU wall clock, %d launches "
+                                        "inside back-to-back decode steps" % bsteps,
+                            "event_interval_us": {"qk": float(np.mean(ev_qk)), "pv": float(np.mean(ev_pv))}},
         "roofline": {"bound": "hbm", "kernel": "kvq_qk_kernel (dense Key kernel of the attention call)",
                      "achieved": dense_qk_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": dense_qk_gbps / HBM_PEAK_GBPS, "traffic": traffic,

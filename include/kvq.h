@@ -278,14 +278,38 @@ kvq_status kvq_event_elapsed_ms(void *start, void *stop, float *ms); /* synchron
 kvq_status kvq_event_destroy(void *event);
 
 /*
- * Per-kernel timing aid for benchmarks.  While enabled, kvq_qk_matvec and kvq_pv_matvec bracket
- * their dense kernel with HIP events on the launch stream; kvq_profile_last_ms synchronizes on the
- * events of the most recent call and returns the dense kernel's duration (`which`: 0 = QK dense
- * kernel, 1 = PV dense kernel).  The bracket adds about two microseconds to what a kernel trace
- * shows for the same launch.  Not thread-safe; leave disabled in production.
+ * Per-kernel timing aid for benchmarks, for the dense kernel of kvq_qk_matvec / kvq_pv_matvec /
+ * kvq_attention_decode (`which`: 0 = QK dense kernel, 1 = PV dense kernel).  Two measurements, each
+ * kept per call in a ring of 256, so that many calls can be timed back to back without waiting for
+ * the GPU in between:
+ *   events : a pair of HIP events recorded on the launch stream around the launch.  The interval runs
+ *            from the end of the kernel before to the end of this one, and every record stalls the
+ *            queue by a few microseconds: an upper bound on the kernel's duration.
+ *   span   : every workgroup of the kernel stores the GPU's constant-rate wall clock when it starts
+ *            and when its last wavefront's stores have been acknowledged, in a slot of its own in a
+ *            caller-provided DEVICE buffer; first start to last end over the workgroups is the span a
+ *            kernel trace reports for the launch, and nothing is inserted between kernels.  (Launches
+ *            of more than 1024 workgroups are not timed this way.)
+ *   kvq_profile_set_span_buffer(d_buf, bytes): DEVICE buffer of kvq_profile_span_buffer_bytes()
+ *     bytes, 8-byte aligned, owned by the caller and kept until spans are switched off again with a
+ *     null pointer; only while the aid is disabled.
+ *   kvq_profile_enable(on): 0 = off; 1 = events (and spans if a buffer is set); 3 = spans only, no
+ *     event records.  Enabling resets the call counts and, with a buffer, synchronizes the device and
+ *     clears the buffer.
+ *   kvq_profile_count: calls recorded since then.
+ *   kvq_profile_read_ms / kvq_profile_last_ms: event interval of call number `call` (0-based; one of
+ *     the last 256) / of the most recent call; synchronizes on that call's stop event.
+ *   kvq_profile_span_us: span of call number `call`; synchronizes the device.
+ * Not thread-safe; leave disabled in production.  Errors: INVALID_ARG (which, call out of range,
+ * measurement not being taken, buffer too small or set while enabled), HIP.
  */
 kvq_status kvq_profile_enable(int32_t on);
+int64_t kvq_profile_span_buffer_bytes(void);
+kvq_status kvq_profile_set_span_buffer(void *d_buf, int64_t bytes);
+kvq_status kvq_profile_count(int32_t which, int64_t *count);
+kvq_status kvq_profile_read_ms(int32_t which, int64_t call, float *ms);
 kvq_status kvq_profile_last_ms(int32_t which, float *ms);
+kvq_status kvq_profile_span_us(int32_t which, int64_t call, float *us);
 
 #ifdef __cplusplus
 }

@@ -76,6 +76,11 @@ def load_library():
         "kvq_event_destroy": (C.c_int, [V]),
         "kvq_profile_enable": (C.c_int, [I32]),
         "kvq_profile_last_ms": (C.c_int, [I32, C.POINTER(F)]),
+        "kvq_profile_count": (C.c_int, [I32, C.POINTER(I64)]),
+        "kvq_profile_read_ms": (C.c_int, [I32, I64, C.POINTER(F)]),
+        "kvq_profile_span_buffer_bytes": (I64, []),
+        "kvq_profile_set_span_buffer": (C.c_int, [V, I64]),
+        "kvq_profile_span_us": (C.c_int, [I32, I64, C.POINTER(F)]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -90,13 +95,53 @@ EXPORTED_SYMBOLS = [
     "kvq_qk_matvec", "kvq_pv_matvec",
     "kvq_attention_decode", "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
     "kvq_fp16_pv_matvec", "kvq_event_create", "kvq_event_record", "kvq_event_elapsed_ms", "kvq_event_destroy",
-    "kvq_profile_enable", "kvq_profile_last_ms", "kvq_calibrate_workspace_bytes", "kvq_calibrate_nuq",
+    "kvq_profile_enable", "kvq_profile_last_ms", "kvq_profile_count", "kvq_profile_read_ms",
+    "kvq_profile_span_buffer_bytes", "kvq_profile_set_span_buffer", "kvq_profile_span_us", "kvq_calibrate_workspace_bytes", "kvq_calibrate_nuq",
     "kvq_calibrate_key_channels", "kvq_stream_read_workspace_bytes", "kvq_stream_read",
 ]
 
 
-def kvq_profile_enable(on: bool):
-    _check(load_library().kvq_profile_enable(1 if on else 0), "kvq_profile_enable")
+_span_buffer = None
+
+
+def kvq_profile_enable(on: bool, spans: bool = False, events: bool = True):
+    """Switch the per-kernel timing aid on or off.  spans: also (or, with events=False, only) take each
+    dense kernel's own first-start-to-last-end span; the device buffer they land in is allocated here."""
+    global _span_buffer
+    lib = load_library()
+    if not on:
+        _check(lib.kvq_profile_enable(0), "kvq_profile_enable")
+        return
+    _check(lib.kvq_profile_enable(0), "kvq_profile_enable")
+    if spans and _span_buffer is None:
+        _span_buffer = torch.zeros(int(lib.kvq_profile_span_buffer_bytes()) // 8, dtype=torch.int64, device="cuda")
+    _check(lib.kvq_profile_set_span_buffer(_span_buffer.data_ptr() if spans else None,
+                                           _span_buffer.numel() * 8 if spans else 0), "kvq_profile_set_span_buffer")
+    _check(lib.kvq_profile_enable(1 if events else 3), "kvq_profile_enable")
+
+
+def kvq_profile_read_all_spans_us(which: int):
+    """Spans (us) of every dense-kernel launch recorded since kvq_profile_enable(True, spans=True)."""
+    lib = load_library()
+    n = C.c_int64()
+    _check(lib.kvq_profile_count(which, C.byref(n)), "kvq_profile_count")
+    out, us = [], C.c_float()
+    for call in range(max(0, n.value - 256), n.value):
+        _check(lib.kvq_profile_span_us(which, call, C.byref(us)), "kvq_profile_span_us")
+        out.append(float(us.value))
+    return out
+
+
+def kvq_profile_read_all_us(which: int):
+    """Durations (us) of every dense-kernel launch recorded since kvq_profile_enable(True) (at most the last 256)."""
+    lib = load_library()
+    n = C.c_int64()
+    _check(lib.kvq_profile_count(which, C.byref(n)), "kvq_profile_count")
+    out, ms = [], C.c_float()
+    for call in range(max(0, n.value - 256), n.value):
+        _check(lib.kvq_profile_read_ms(which, call, C.byref(ms)), "kvq_profile_read_ms")
+        out.append(float(ms.value) * 1e3)
+    return out
 
 
 def kvq_profile_last_ms(which: int) -> float:

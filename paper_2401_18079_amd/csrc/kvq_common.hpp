@@ -243,12 +243,48 @@ __attribute__((visibility("hidden"))) kvq_status kvq_pv_run(const kvq_cache *cac
 // Bytes of the workspace that kvq_pv_run uses (from its start); the statistics slots follow.
 __attribute__((visibility("hidden"))) int64_t kvq_pv_workspace_bytes(int n_q_heads);
 
-// Optional per-kernel timing (kvq_profile_enable): events bracketing the dense kernels.
+// Optional per-kernel timing (kvq_profile_enable) of the dense kernels, two ways.  (1) A ring of HIP
+// event pairs recorded around the launch: what the stream sees between the end of the kernel before
+// and the end of this one (the records themselves stall the queue by a few microseconds each).
+// (2) The kernel's own span: the first thread of every workgroup stores the GPU's constant-rate wall
+// clock when the workgroup starts and, after a barrier at the very end, when all its wavefronts are
+// done (plain stores to the workgroup's own slot of a caller-provided device buffer: atomics on one
+// address would stall the kernel they are meant to time).  First start to last end over the
+// workgroups is the span a kernel trace reports, and nothing is inserted between kernels.
+// Buffer layout: [2 kernels][RING calls][KVQ_PROFILE_MAX_WGS][start, end], 64-bit ticks, zero = unused.
+constexpr int KVQ_PROFILE_RING = 256;
+constexpr int KVQ_PROFILE_MAX_WGS = 1024;
 struct KvqProfile {
     int enabled;
-    hipEvent_t ev[2][2];     // [QK, PV][start, stop]
-    int have[2];
+    hipEvent_t ev[2][KVQ_PROFILE_RING][2];     // [QK, PV][call % ring][start, stop]
+    int64_t count[2];                          // calls recorded since the last enable
+    unsigned long long *spans;                 // device buffer or null
+    int use_events;                            // record the event pairs too
 };
+// The slots of the next call of kernel `which` (for a launch of n_wgs workgroups), or null when spans
+// are not being taken or the launch has more workgroups than a call has slots.
+inline unsigned long long *kvq_profile_span_slot(KvqProfile &p, int which, int64_t n_wgs)
+{
+    if (!p.enabled || !p.spans || n_wgs > KVQ_PROFILE_MAX_WGS) return nullptr;
+    return p.spans + ((int64_t)which * KVQ_PROFILE_RING + (p.count[which] % KVQ_PROFILE_RING)) * KVQ_PROFILE_MAX_WGS * 2;
+}
+__device__ __forceinline__ void kvq_span_start(unsigned long long *slots)
+{
+    if (slots && threadIdx.x == 0)
+        slots[2 * (blockIdx.y * gridDim.x + blockIdx.x)] = (unsigned long long)wall_clock64();
+}
+// Every thread of the workgroup must call this (it holds a barrier when spans are being taken).
+__device__ __forceinline__ void kvq_span_end(unsigned long long *slots)
+{
+    if (slots) {
+        // this wavefront's stores have been acknowledged (a wait only: a fence would also write back
+        // and invalidate caches that the workgroups still running depend on)
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0)
+            slots[2 * (blockIdx.y * gridDim.x + blockIdx.x) + 1] = (unsigned long long)wall_clock64();
+    }
+}
 KvqProfile &kvq_profile_state();
 
 #define KVQ_HIP_CHECK(expr)                         \

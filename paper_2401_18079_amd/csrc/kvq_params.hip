@@ -61,24 +61,87 @@ kvq_status kvq_event_destroy(void *event)
 kvq_status kvq_profile_enable(int32_t on)
 {
     KvqProfile &p = kvq_profile_state();
-    if (on && !p.ev[0][0]) {
+    if (on && !p.ev[0][0][0]) {
         for (int k = 0; k < 2; ++k)
-            for (int j = 0; j < 2; ++j)
-                // no system-scope fence at the record: the bracket should disturb the kernels as little as possible
-                KVQ_HIP_CHECK(hipEventCreateWithFlags(&p.ev[k][j], hipEventDisableSystemFence));
+            for (int i = 0; i < KVQ_PROFILE_RING; ++i)
+                for (int j = 0; j < 2; ++j)
+                    // no system-scope fence at the record: the bracket should disturb the kernels as little as possible
+                    KVQ_HIP_CHECK(hipEventCreateWithFlags(&p.ev[k][i][j], hipEventDisableSystemFence));
+    }
+    if (on) {
+        p.count[0] = p.count[1] = 0;
+        p.use_events = (on & 2) ? 0 : 1;                 // bit 1: spans only, nothing recorded between kernels
+        if (p.spans) {
+            KVQ_HIP_CHECK(hipDeviceSynchronize());
+            KVQ_HIP_CHECK(hipMemset(p.spans, 0, (size_t)kvq_profile_span_buffer_bytes()));
+        }
     }
     p.enabled = on ? 1 : 0;
-    p.have[0] = p.have[1] = 0;
+    return KVQ_OK;
+}
+
+int64_t kvq_profile_span_buffer_bytes(void) { return (int64_t)2 * KVQ_PROFILE_RING * KVQ_PROFILE_MAX_WGS * 2 * 8; }
+
+kvq_status kvq_profile_set_span_buffer(void *d_buf, int64_t bytes)
+{
+    KvqProfile &p = kvq_profile_state();
+    if (p.enabled) return KVQ_ERR_INVALID_ARG;
+    if (d_buf && (((uintptr_t)d_buf & 7) || bytes < kvq_profile_span_buffer_bytes())) return KVQ_ERR_INVALID_ARG;
+    p.spans = (unsigned long long *)d_buf;
+    return KVQ_OK;
+}
+
+kvq_status kvq_profile_span_us(int32_t which, int64_t call, float *us)
+{
+    KvqProfile &p = kvq_profile_state();
+    if (which < 0 || which > 1 || !us || !p.spans) return KVQ_ERR_INVALID_ARG;
+    if (call < 0 || call >= p.count[which] || call + KVQ_PROFILE_RING < p.count[which]) return KVQ_ERR_INVALID_ARG;
+    static unsigned long long host[KVQ_PROFILE_MAX_WGS * 2];
+    const unsigned long long *slots =
+        p.spans + ((int64_t)which * KVQ_PROFILE_RING + (call % KVQ_PROFILE_RING)) * KVQ_PROFILE_MAX_WGS * 2;
+    KVQ_HIP_CHECK(hipDeviceSynchronize());
+    KVQ_HIP_CHECK(hipMemcpy(host, slots, sizeof(host), hipMemcpyDeviceToHost));
+    int dev = 0, khz = 0;
+    KVQ_HIP_CHECK(hipGetDevice(&dev));
+    KVQ_HIP_CHECK(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    if (khz <= 0) return KVQ_ERR_HIP;
+    // first start to last end over the workgroups that ran (an unused slot is zero)
+    unsigned long long first = ~0ull, last = 0;
+    for (int w = 0; w < KVQ_PROFILE_MAX_WGS; ++w) {
+        if (host[2 * w] == 0 || host[2 * w + 1] == 0) continue;
+        if (host[2 * w] < first) first = host[2 * w];
+        if (host[2 * w + 1] > last) last = host[2 * w + 1];
+    }
+    if (last < first) return KVQ_ERR_INVALID_ARG;        // the launch was too large for its slots, or did not run
+    const unsigned long long best = last - first;
+    *us = (float)((double)best * 1000.0 / (double)khz);
+    return KVQ_OK;
+}
+
+kvq_status kvq_profile_count(int32_t which, int64_t *count)
+{
+    KvqProfile &p = kvq_profile_state();
+    if (which < 0 || which > 1 || !count) return KVQ_ERR_INVALID_ARG;
+    *count = p.count[which];
+    return KVQ_OK;
+}
+
+kvq_status kvq_profile_read_ms(int32_t which, int64_t call, float *ms)
+{
+    KvqProfile &p = kvq_profile_state();
+    if (which < 0 || which > 1 || !ms || !p.use_events) return KVQ_ERR_INVALID_ARG;
+    if (call < 0 || call >= p.count[which] || call + KVQ_PROFILE_RING < p.count[which]) return KVQ_ERR_INVALID_ARG;
+    hipEvent_t *e = p.ev[which][call % KVQ_PROFILE_RING];
+    KVQ_HIP_CHECK(hipEventSynchronize(e[1]));
+    KVQ_HIP_CHECK(hipEventElapsedTime(ms, e[0], e[1]));
     return KVQ_OK;
 }
 
 kvq_status kvq_profile_last_ms(int32_t which, float *ms)
 {
     KvqProfile &p = kvq_profile_state();
-    if (which < 0 || which > 1 || !ms || !p.have[which]) return KVQ_ERR_INVALID_ARG;
-    KVQ_HIP_CHECK(hipEventSynchronize(p.ev[which][1]));
-    KVQ_HIP_CHECK(hipEventElapsedTime(ms, p.ev[which][0], p.ev[which][1]));
-    return KVQ_OK;
+    if (which < 0 || which > 1) return KVQ_ERR_INVALID_ARG;
+    return kvq_profile_read_ms(which, p.count[which] - 1, ms);
 }
 
 }  // extern "C"

@@ -161,8 +161,9 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
                                                       float *__restrict__ partial, float *__restrict__ zpart,
                                                       int n_tiles, int n_sink,
                                                       const float *__restrict__ stat_slots, int n_stat,
-                                                      float *__restrict__ lpart)
+                                                      float *__restrict__ lpart, unsigned long long *span)
 {
+    kvq_span_start(span);                 // timing aid: null unless a benchmark asked for the kernel's span
     // tokens below n_sink are attention-sink tokens kept in fp16: their quantized form gets weight 0
     // here and the reduce kernel adds their fp16 rows.
     // stat_slots != null: `probs` holds raw scores x; a wavefront takes the maximum m of each of its
@@ -284,6 +285,7 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
             }
         }
     }
+    kvq_span_end(span);
 }
 
 // Sparse part, balanced (paper App. "Kernel Implementation Details": equal non-zeros per thread):
@@ -584,9 +586,11 @@ kvq_status kvq_pv_run(const kvq_cache *cache, const float *d_probs, int64_t ld_p
 #define LAUNCH_PV(B, G)                                                                                       \
     kvq_pv_dense<B, G><<<grid, PV_NT, 0, s>>>(cache->params, D, cache->n_kv_heads, Hq, cache->cap_tokens, L,   \
                                               cache->v_codes, cache->v_sz, d_probs, ld_probs, partial, zpart, \
-                                              plan.tiles, cache->n_sink, stat_slots, n_stat, lpart)
+                                              plan.tiles, cache->n_sink, stat_slots, n_stat, lpart, span)
         KvqProfile &prof = kvq_profile_state();
-        if (prof.enabled) KVQ_HIP_CHECK(hipEventRecord(prof.ev[1][0], s));
+        unsigned long long *span = kvq_profile_span_slot(prof, 1, (int64_t)grid.x * grid.y);
+        hipEvent_t *pev = (prof.enabled && prof.use_events) ? prof.ev[1][prof.count[1] % KVQ_PROFILE_RING] : nullptr;
+        if (pev) KVQ_HIP_CHECK(hipEventRecord(pev[0], s));
         // query heads of one KV head that a wavefront takes together (they share extraction and gather).
         // When the kernel also turns scores into weights every wavefront that covers a head evaluates
         // that head's exponentials, and grouping multiplies the wavefronts per head: pairs of heads
@@ -597,7 +601,8 @@ kvq_status kvq_pv_run(const kvq_cache *cache, const float *d_probs, int64_t ld_p
         else if (cache->bits == 3) { if (rg == 4) LAUNCH_PV(3, 4); else if (rg == 2) LAUNCH_PV(3, 2); else LAUNCH_PV(3, 1); }
         else { if (rg == 4) LAUNCH_PV(4, 4); else if (rg == 2) LAUNCH_PV(4, 2); else LAUNCH_PV(4, 1); }
 #undef LAUNCH_PV
-        if (prof.enabled) { KVQ_HIP_CHECK(hipEventRecord(prof.ev[1][1], s)); prof.have[1] = 1; }
+        if (pev) KVQ_HIP_CHECK(hipEventRecord(pev[1], s));
+        if (prof.enabled) ++prof.count[1];
     }
     const int ns = (int)(cache->n_sink < L ? cache->n_sink : L);
     kvq_pv_reduce<<<4 * Hq, 1024, 0, s>>>(Hq, plan.slabs, plan.sslabs, partial, zpart, spartial, d_out, ns,

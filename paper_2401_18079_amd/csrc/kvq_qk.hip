@@ -203,8 +203,10 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
                                                     int64_t cap, int64_t L, const uint8_t *__restrict__ k_codes,
                                                     const float *__restrict__ q_rot, float scale,
                                                     float *__restrict__ scores, int64_t ld, int n_tiles,
-                                                    int add_prev, float *__restrict__ stat_slots, int n_sink)
+                                                    int add_prev, float *__restrict__ stat_slots, int n_sink,
+                                                    unsigned long long *span)
 {
+    kvq_span_start(span);                 // timing aid: null unless a benchmark asked for the kernel's span
     // add_prev != 0: the score buffer already holds the sparse part; add to it instead of overwriting.
     // STATS: the workgroup also leaves the maximum of the scores it wrote (tokens below n_sink
     // excepted: the attention-sink kernel replaces their scores) in slot blockIdx.x of each of its
@@ -365,6 +367,7 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
             stat_slots[(int64_t)(q0 + tid) * KVQ_STAT_SLOTS + blockIdx.x] = m;
         }
     }
+    kvq_span_end(span);
 }
 
 // Sparse Key outliers, balanced (paper App. "Kernel Implementation Details": equal non-zeros per
@@ -600,12 +603,15 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
         if (st != KVQ_OK) return st;
     }
     KvqProfile &prof = kvq_profile_state();
-    if (prof.enabled) KVQ_HIP_CHECK(hipEventRecord(prof.ev[0][0], s));
+    unsigned long long *span = kvq_profile_span_slot(prof, 0, (int64_t)gx * groups);
+    hipEvent_t *pev = (prof.enabled && prof.use_events) ? prof.ev[0][prof.count[0] % KVQ_PROFILE_RING] : nullptr;
+    if (pev) KVQ_HIP_CHECK(hipEventRecord(pev[0], s));
     static_assert(KVQ_STAT_SLOTS >= 256 + KVQ_MAX_SINK, "a slot per workgroup of a head plus the sink tokens");
     const unsigned ns = (unsigned)(c->n_sink < L ? c->n_sink : L);
     kern<<<grid, NT, 0, s>>>(c->params, D, R, c->cap_tokens, L, c->k_codes, q, scale, scores, ld, (int)tiles,
-                             sparse_first, stat_slots, (int)ns);
-    if (prof.enabled) { KVQ_HIP_CHECK(hipEventRecord(prof.ev[0][1], s)); prof.have[0] = 1; }
+                             sparse_first, stat_slots, (int)ns, span);
+    if (pev) KVQ_HIP_CHECK(hipEventRecord(pev[1], s));
+    if (prof.enabled) ++prof.count[0];
     if (ns > 0)
         kvq_qk_sink<<<dim3(ns, (unsigned)c->n_q_heads), 64, 0, s>>>(c->params, D, R, c->sink_k, q, scale, scores, ld,
                                                                     stat_slots, (int)gx);
