@@ -152,7 +152,7 @@ __device__ __forceinline__ void pv_all_fields(std::integer_sequence<int, G...>, 
 // grouped-query attention RG > 1 heads share every extraction and gather.  grid = (slabs, 2*Hq / 4):
 // wavefront w of a workgroup owns combination blockIdx.y*4 + w.  Writes partial[slab][q][128] and
 // zpart[slab][q].
-template <int BITS, int RG>
+template <int BITS, int RG, bool SPAN = false>
 __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ params, int D, int n_kv_heads,
                                                       int n_q_heads, int64_t cap, int64_t L,
                                                       const uint8_t *__restrict__ v_codes,
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
                                                       const float *__restrict__ stat_slots, int n_stat,
                                                       float *__restrict__ lpart, unsigned long long *span)
 {
-    kvq_span_start(span);                 // timing aid: null unless a benchmark asked for the kernel's span
+    if (SPAN) kvq_span_start(span);       // timing-aid instantiation (kvq_profile_*): workgroup start and end times
     // tokens below n_sink are attention-sink tokens kept in fp16: their quantized form gets weight 0
     // here and the reduce kernel adds their fp16 rows.
     // stat_slots != null: `probs` holds raw scores x; a wavefront takes the maximum m of each of its
@@ -285,7 +285,7 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
             }
         }
     }
-    kvq_span_end(span);
+    if (SPAN) kvq_span_end(span);
 }
 
 // Sparse part, balanced (paper App. "Kernel Implementation Details": equal non-zeros per thread):
@@ -583,10 +583,13 @@ kvq_status kvq_pv_run(const kvq_cache *cache, const float *d_probs, int64_t ld_p
                                                                 cache->n_sink, stat_slots, n_stat);
 
         dim3 grid((unsigned)plan.slabs, (unsigned)((2 * Hq + PV_WAVES - 1) / PV_WAVES));
-#define LAUNCH_PV(B, G)                                                                                       \
-    kvq_pv_dense<B, G><<<grid, PV_NT, 0, s>>>(cache->params, D, cache->n_kv_heads, Hq, cache->cap_tokens, L,   \
-                                              cache->v_codes, cache->v_sz, d_probs, ld_probs, partial, zpart, \
-                                              plan.tiles, cache->n_sink, stat_slots, n_stat, lpart, span)
+#define LAUNCH_PV(B, G)                                                                                        \
+    do {                                                                                                       \
+        auto kern = span ? kvq_pv_dense<B, G, true> : kvq_pv_dense<B, G, false>;                               \
+        kern<<<grid, PV_NT, 0, s>>>(cache->params, D, cache->n_kv_heads, Hq, cache->cap_tokens, L,             \
+                                    cache->v_codes, cache->v_sz, d_probs, ld_probs, partial, zpart,            \
+                                    plan.tiles, cache->n_sink, stat_slots, n_stat, lpart, span);               \
+    } while (0)
         KvqProfile &prof = kvq_profile_state();
         unsigned long long *span = kvq_profile_span_slot(prof, 1, (int64_t)grid.x * grid.y);
         hipEvent_t *pev = (prof.enabled && prof.use_events) ? prof.ev[1][prof.count[1] % KVQ_PROFILE_RING] : nullptr;

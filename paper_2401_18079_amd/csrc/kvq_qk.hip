@@ -198,7 +198,7 @@ __device__ __forceinline__ void qk_all_pairs(std::integer_sequence<int, G...>,
 
 // KVH KV heads per workgroup, RQ query heads per KV head handled here (RQ divides the model's GQA
 // ratio `r`; when RQ < r several workgroups share a KV head), PG channel pairs per gather group.
-template <int BITS, int KVH, int RQ, int NT, int PG, bool STATS>
+template <int BITS, int KVH, int RQ, int NT, int PG, bool STATS, bool SPAN = false>
 __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ params, int D, int r,
                                                     int64_t cap, int64_t L, const uint8_t *__restrict__ k_codes,
                                                     const float *__restrict__ q_rot, float scale,
@@ -206,7 +206,10 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
                                                     int add_prev, float *__restrict__ stat_slots, int n_sink,
                                                     unsigned long long *span)
 {
-    kvq_span_start(span);                 // timing aid: null unless a benchmark asked for the kernel's span
+    // SPAN: timing-aid instantiation (kvq_profile_*): the workgroup leaves its start and end times in
+    // `span`.  A separate instantiation, and none for the eight-head variants: they have no register
+    // to spare for the pointer, and the variant that is timed should be the one that is used.
+    if (SPAN) kvq_span_start(span);
     // add_prev != 0: the score buffer already holds the sparse part; add to it instead of overwriting.
     // STATS: the workgroup also leaves the maximum of the scores it wrote (tokens below n_sink
     // excepted: the attention-sink kernel replaces their scores) in slot blockIdx.x of each of its
@@ -367,7 +370,7 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
             stat_slots[(int64_t)(q0 + tid) * KVQ_STAT_SLOTS + blockIdx.x] = m;
         }
     }
-    kvq_span_end(span);
+    if (SPAN) kvq_span_end(span);
 }
 
 // Sparse Key outliers, balanced (paper App. "Kernel Implementation Details": equal non-zeros per
@@ -588,6 +591,7 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     const int D = c->n_kv_heads * KVQ_HEAD_DIM;
     const int64_t L = c->n_tokens_k;
     auto kern = stat_slots ? kvq_qk_kernel<BITS, KVH, RQ, NT, PG, true> : kvq_qk_kernel<BITS, KVH, RQ, NT, PG, false>;
+    constexpr bool CAN_SPAN = QH < 8;
     const int groups = c->n_q_heads / QH;
     const int64_t tiles = (L + NT - 1) / NT;
     // about one workgroup per compute unit in total (the tables fill most of a CU's LDS); each
@@ -603,7 +607,12 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
         if (st != KVQ_OK) return st;
     }
     KvqProfile &prof = kvq_profile_state();
-    unsigned long long *span = kvq_profile_span_slot(prof, 0, (int64_t)gx * groups);
+    unsigned long long *span = CAN_SPAN ? kvq_profile_span_slot(prof, 0, (int64_t)gx * groups) : nullptr;
+    if constexpr (CAN_SPAN) {
+        if (span)
+            kern = stat_slots ? kvq_qk_kernel<BITS, KVH, RQ, NT, PG, true, true>
+                              : kvq_qk_kernel<BITS, KVH, RQ, NT, PG, false, true>;
+    }
     hipEvent_t *pev = (prof.enabled && prof.use_events) ? prof.ev[0][prof.count[0] % KVQ_PROFILE_RING] : nullptr;
     if (pev) KVQ_HIP_CHECK(hipEventRecord(pev[0], s));
     static_assert(KVQ_STAT_SLOTS >= 256 + KVQ_MAX_SINK, "a slot per workgroup of a head plus the sink tokens");
