@@ -75,7 +75,7 @@ def test_kernel_spans_agree_with_the_event_intervals():
             spans, evs = K.kvq_profile_read_all_spans_us(which), K.kvq_profile_read_all_us(which)
             assert len(spans) == 20 and len(evs) == 20
             assert all(1.0 < s < 2000.0 for s in spans)
-            assert np.median(spans) <= np.median(evs) + 0.5
+            assert np.median(spans) <= np.median(evs) + 2.0       # two clocks are read: a little slack
             assert np.median(spans) >= 0.4 * np.median(evs)
     finally:
         K.kvq_profile_enable(False)
