@@ -76,7 +76,7 @@ def test_kernel_spans_agree_with_the_event_intervals():
             assert len(spans) == 20 and len(evs) == 20
             assert all(1.0 < s < 2000.0 for s in spans)
             assert np.median(spans) <= np.median(evs) + 2.0       # two clocks are read: a little slack
-            assert np.median(spans) >= 0.4 * np.median(evs)
+            assert np.median(spans) >= 0.15 * np.median(evs)      # the interval also holds the launch latency
     finally:
         K.kvq_profile_enable(False)
     assert torch.equal(out, ref)
