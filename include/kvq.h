@@ -8,6 +8,12 @@
  * `stream` unless stated otherwise.  The library allocates and frees no device memory: the
  * caller owns every buffer, sized with the kvq_*_bytes helpers below.
  *
+ * Threads: calls on different caches may be made from different host threads, except for the first
+ * call of each kind in a process (a kernel's LDS limit is raised once, through an unsynchronised
+ * flag) and the timing aid at the end of this file; calls on one cache, or on caches that share a
+ * workspace, must not overlap, on the host or on the GPU (they share the workspace and the descriptor's
+ * token counts).  One GPU: the device that is current when a cache's buffers are allocated.
+ *
  * Supported shapes: head_dim = 128; bits in {2,3,4}; n_q_heads a multiple of n_kv_heads;
  * D = n_kv_heads*128 <= 65536; cap_tokens a multiple of 128.
  *
