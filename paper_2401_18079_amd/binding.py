@@ -252,9 +252,9 @@ class KvqCache:
             need = used + int(extra)
             if need <= getattr(self.c, cap_name):
                 continue
-            if need >= 1 << 32:
-                raise KvqError(3, "ensure_nnz_room")            # pointers are 32-bit
-            cap = min((need + block - 1) // block * block, (1 << 32) - 1)
+            if need >= 1 << 31:
+                raise KvqError(3, "ensure_nnz_room")            # the mat-vec kernels address entries with 32-bit byte offsets
+            cap = min((need + block - 1) // block * block, (1 << 31) - 1)
             for name in names:
                 old = getattr(self, name)
                 new_t = torch.zeros(cap, dtype=old.dtype, device=old.device)
