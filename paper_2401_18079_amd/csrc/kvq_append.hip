@@ -13,6 +13,7 @@ namespace {
 // other's barriers.
 constexpr int KVQ_BULK_TOKENS = 512;      // calls with at least this many tokens count as bulk appends
 constexpr int KVQ_KV_SPLIT_TOKENS = 256;  // from here on the combined call runs the Key and Value kernels in turn
+constexpr int KVQ_WAVE_TOKENS = 1024;     // Key appends of at least this many tokens: one wavefront per token
 
 // Workgroups have NT threads: 256 for narrow models, 1024 once a token vector has >= 2048 channels
 // (fewer passes over the vector, hence fewer barriers, for the single-token decode append).
@@ -591,6 +592,85 @@ __device__ __forceinline__ void v_quant_token(const void *__restrict__ params, i
 
 // (256-thread workgroups serve small models and bulk appends: eight wavefronts per SIMD keep more
 // tokens in flight; the 1024-thread ones are one workgroup per compute unit anyway)
+// Bulk Key append: one wavefront per token, no workgroup barrier.  Lane l takes channels l and l+64
+// of every head, the pair that shares a field of the packed chunk, so a head's 64 fields come from the
+// 64 lanes; the chunk is assembled in a slice of LDS private to the wavefront.  Outliers keep channel
+// order: within a head first the lanes' lower channels, then their upper ones, ranked by ballots.
+// Same arithmetic, same results, as k_quant_token; the per-token pointers come from kvq_ptr_scan.
+constexpr int KVQ_KW_NT = 256;
+template <int BITS>
+__global__ __launch_bounds__(KVQ_KW_NT) void kvq_k_quant_wave(const void *__restrict__ params, int D, int T,
+                                                              int64_t cap, int64_t n0,
+                                                              const uint16_t *__restrict__ k_new,
+                                                              uint8_t *__restrict__ k_codes,
+                                                              const uint32_t *__restrict__ k_ptr,
+                                                              uint16_t *__restrict__ k_idx,
+                                                              uint16_t *__restrict__ k_val, int64_t cap_nnz,
+                                                              int32_t *d_status)
+{
+    constexpr int NE = 1 << BITS;
+    constexpr int CW = 4 * BITS;                 // dwords per chunk
+    __shared__ uint32_t chunk_s[KVQ_KW_NT / 64][CW + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.x * (KVQ_KW_NT / 64) + wave;
+    if (t >= T) return;                          // whole wavefronts leave; there is no workgroup barrier below
+    KvqParamsView pv = kvq_params_view(params, D);
+    float lut[NE];
+#pragma unroll
+    for (int j = 0; j < NE; ++j) lut[j] = pv.hdr->lut_k[j];
+    const int64_t n = n0 + t;
+    const uint32_t base = k_ptr[n];
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    uint32_t *chunk = chunk_s[wave];
+    uint32_t running = 0;
+    bool overflow = false;
+    const int H = D / KVQ_HEAD_DIM;
+    for (int h = 0; h < H; ++h) {
+        const int c0 = h * KVQ_HEAD_DIM + lane, c1 = c0 + 64;
+        const uint16_t xb0 = k_new[(int64_t)t * D + c0], xb1 = k_new[(int64_t)t * D + c1];
+        const float z0 = pv.z[c0], s0 = pv.s[c0], r0 = pv.rinv[c0], lo0 = pv.lo[c0], hi0 = pv.hi[c0];
+        const float z1 = pv.z[c1], s1 = pv.s[c1], r1 = pv.rinv[c1], lo1 = pv.lo[c1], hi1 = pv.hi[c1];
+        if (lane <= CW) chunk[lane] = 0;
+        const float x0 = kvq_h2f(xb0), x1 = kvq_h2f(xb1);
+        float sp0, sp1;
+        const float d0 = x0 - z0, d1 = x1 - z1;
+        const int code0 = kvq_nearest<NE>(lut, d0 * r0, sp0);
+        const int code1 = kvq_nearest<NE>(lut, d1 * r1, sp1);
+        const float deq0 = __builtin_fmaf(s0, sp0, z0), deq1 = __builtin_fmaf(s1, sp1, z1);
+        const bool o0 = (x0 < lo0) | (x0 > hi0), o1 = (x1 < lo1) | (x1 > hi1);
+        // outliers of this head in channel order
+        const unsigned long long b0 = __ballot(o0), b1 = __ballot(o1);
+        const uint32_t rank0 = running + (uint32_t)__popcll(b0 & lt_mask);
+        running += (uint32_t)__popcll(b0);
+        const uint32_t rank1 = running + (uint32_t)__popcll(b1 & lt_mask);
+        running += (uint32_t)__popcll(b1);
+        if (o0) {
+            const uint64_t pos = (uint64_t)base + rank0;
+            if (pos < (uint64_t)cap_nnz) { k_idx[pos] = (uint16_t)c0; k_val[pos] = kvq_f2h_rn(x0 - deq0); }
+            else overflow = true;
+        }
+        if (o1) {
+            const uint64_t pos = (uint64_t)base + rank1;
+            if (pos < (uint64_t)cap_nnz) { k_idx[pos] = (uint16_t)c1; k_val[pos] = kvq_f2h_rn(x1 - deq1); }
+            else overflow = true;
+        }
+        // the head's chunk: 64 fields of 2*BITS bits, assembled in the wavefront's LDS slice (LDS
+        // operations of one wavefront execute in order; the fences keep the compiler from reordering them)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        stream_or(chunk, lane * 2 * BITS, (uint32_t)code0 | ((uint32_t)code1 << BITS), 2 * BITS);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (lane < CW) {
+            const int64_t off = kvq_k_piece0(BITS, cap, n, h) + (lane >> 2) * 1024 + (lane & 3) * 4;
+            *(uint32_t *)(k_codes + off) = chunk[lane];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (overflow) atomicExch(d_status, (int32_t)KVQ_ERR_NNZ_OVERFLOW);
+}
+
 template <int BITS, int NT>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT == 256 ? 8 : 4)))
 void kvq_k_quant(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
@@ -755,7 +835,11 @@ extern "C" kvq_status kvq_quantize_append_k(kvq_cache *cache, const uint16_t *d_
     }
 #define LAUNCH_K(B)                                                                                             \
     do {                                                                                                        \
-        if (wide_wg(D, T))                                                                                      \
+        if (T >= KVQ_WAVE_TOKENS)                                                                               \
+            kvq_k_quant_wave<B><<<(T + KVQ_KW_NT / 64 - 1) / (KVQ_KW_NT / 64), KVQ_KW_NT, 0, s>>>(               \
+                cache->params, D, T, cache->cap_tokens, cache->n_tokens_k, d_k_new, cache->k_codes,              \
+                cache->k_ptr, cache->k_idx, cache->k_val, cache->cap_nnz_k, cache->d_status);                    \
+        else if (wide_wg(D, T))                                                                                 \
             kvq_k_quant<B, 1024><<<T, 1024, 0, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_k,      \
                                                     d_k_new, cache->k_codes, cache->k_ptr, cache->k_idx,         \
                                                     cache->k_val, cache->cap_nnz_k, single, cache->d_status);    \
