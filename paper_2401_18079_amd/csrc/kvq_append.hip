@@ -671,6 +671,278 @@ __global__ __launch_bounds__(KVQ_KW_NT) void kvq_k_quant_wave(const void *__rest
     if (overflow) atomicExch(d_status, (int32_t)KVQ_ERR_NNZ_OVERFLOW);
 }
 
+// ---- bulk Value append -----------------------------------------------------------------------
+// In a histogram of 256 bins (lane l reads bins 4l..4l+3), the bin in which the K-th element counted
+// from the top (FROM_TOP) or from the bottom lies, the number of elements beyond that bin on that side,
+// and the bin's own count.  Wavefront-uniform results.  1 <= K <= number of elements.
+template <bool FROM_TOP>
+__device__ __forceinline__ void wave_find_bin(const uint32_t *h256, uint32_t K, int lane, uint32_t &bin,
+                                              uint32_t &beyond, uint32_t &in_bin)
+{
+    const uint4 v = *(const uint4 *)(h256 + 4 * lane);
+    const uint32_t hh[4] = {v.x, v.y, v.z, v.w};
+    const uint32_t s = v.x + v.y + v.z + v.w;
+    uint32_t S = s;                                // sum over this lane and the lanes on the side counted from
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = FROM_TOP ? __shfl_down(S, o) : __shfl_up(S, o);
+        if (FROM_TOP ? (lane + o < 64) : (lane >= o)) S += t;
+    }
+    uint32_t a = S - s;                            // elements in the bins of the lanes beyond this one
+    int found = -1;
+    uint32_t fa = 0, fh = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int q = FROM_TOP ? 3 - i : i;
+        if (found < 0 && a < K && a + hh[q] >= K) { found = q; fa = a; fh = hh[q]; }
+        a += hh[q];
+    }
+    const int src = __ffsll((unsigned long long)__ballot(found >= 0)) - 1;      // exactly one lane finds it
+    bin = (uint32_t)__shfl(4 * lane + found, src);
+    beyond = __shfl(fa, src);
+    in_bin = __shfl(fh, src);
+}
+
+// Bulk Value append: one workgroup of four wavefronts per token, D = 256 * JW channels (JW = 4, 8 or
+// 16).  Wavefront w takes the channel groups j = w JW .. (w + 1) JW - 1, lane l of it the channels
+// 64 j + l (half j & 1 of head j >> 1), so a wavefront packs whole chunks on its own, channel order is
+// wavefront order, and a lane keeps its JW elements in registers from the one load to the end.  The
+// selection is the two-level radix selection of select_both on histograms shared by the four
+// wavefronts (each reads the bins it needs itself); equal keys at a threshold are taken in channel
+// order, ranked with ballots and the wavefronts' counts, and when the two thresholds coincide the
+// upper outliers take the first of the equal keys and the lower ones the next, which is what taking
+// the k largest first and then the k smallest of the rest comes to.  The packed codes of all JW chunks
+// are gathered in the wavefront's LDS slice and written by all 64 lanes at the end.  Five workgroup
+// barriers per token (six when equal keys must be ranked).  Same arithmetic, same results, as
+// v_quant_token.
+constexpr int KVQ_VW_WAVES = 4;
+constexpr int KVQ_VW_NT = 64 * KVQ_VW_WAVES;
+template <int BITS, int JW>
+__global__ __launch_bounds__(KVQ_VW_NT) void kvq_v_quant_bulk(const void *__restrict__ params, int D, int64_t cap,
+                                                              int64_t n0, int k_side,
+                                                              const uint16_t *__restrict__ v_new,
+                                                              uint8_t *__restrict__ v_codes,
+                                                              uint16_t *__restrict__ v_sz,
+                                                              uint32_t *__restrict__ v_ptr,
+                                                              uint16_t *__restrict__ v_idx,
+                                                              uint16_t *__restrict__ v_val, int64_t cap_nnz,
+                                                              int32_t *d_status)
+{
+    constexpr int NE = 1 << BITS;
+    constexpr int CW = 4 * BITS;
+    constexpr int W = KVQ_VW_WAVES;
+    __shared__ __attribute__((aligned(16))) uint32_t hist[768];
+    __shared__ uint32_t bits_s[W][JW][CW + 1], mask_s[W][CW + 1];
+    __shared__ uint32_t eq_cnt[W][2], out_cnt[W];
+    __shared__ uint16_t lane_max[KVQ_VW_NT], lane_min[KVQ_VW_NT];
+    __shared__ float red_mx[W], red_mn[W];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.x;
+    uint32_t(*bits)[CW + 1] = bits_s[wave];
+    uint32_t *mask = mask_s[wave];
+    KvqParamsView pv = kvq_params_view(params, D);
+    float lut[NE];
+#pragma unroll
+    for (int j = 0; j < NE; ++j) lut[j] = pv.hdr->lut_v[j];
+    const int jb = wave * JW;                    // this wavefront's first channel group (D = 64 W JW)
+    const int64_t n = n0 + t;
+    const uint16_t *x16 = v_new + (int64_t)t * D + lane;
+    const uint32_t base = v_ptr[n0] + (uint32_t)t * 2u * (uint32_t)k_side;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    const uint32_t K = (uint32_t)k_side;
+
+    // the wavefront's packing area, cleared here and filled after the barrier that follows the ranges
+    for (int e = lane; e < JW * (CW + 1); e += 64) (&bits[0][0])[e] = 0;
+    if (lane <= CW) mask[lane] = 0;
+    uint16_t xc[JW];                             // this lane's elements, kept in registers
+#pragma unroll
+    for (int i = 0; i < JW; ++i) xc[i] = x16[64 * (jb + i)];
+
+    uint32_t top = 0, bot = 0;                   // bit i: channel 64 (jb + i) + lane is an upper / lower outlier
+    static_assert(JW <= 32, "one mask bit per element of a lane");
+    if (K > 0) {
+        for (int i = threadIdx.x; i < 768; i += KVQ_VW_NT) hist[i] = 0;
+        // Only the tails go into the histograms (shared-memory atomics on the few bins that hold the
+        // bulk of a token would serialize).  The K-th largest of the 64 W lanes' largest keys is a lower
+        // bound of the K-th largest key of the token, since that many elements are at least as large;
+        // likewise for the smallest.  Every wavefront finds both bounds by bisection over the 16 key
+        // bits, with ballots.  Histogram counts are then exact from the bounds outwards, which is all
+        // the searches below read.  More outliers per side than lanes: no bound, every key counts.
+        uint32_t kc[JW];                         // the elements' order-preserving keys
+#pragma unroll
+        for (int i = 0; i < JW; ++i) kc[i] = order_key(xc[i]);
+        uint32_t kmax = 0, kmin = 0xffffu;
+#pragma unroll
+        for (int i = 0; i < JW; ++i) {
+            const uint32_t key = kc[i];
+            kmax = key > kmax ? key : kmax;
+            kmin = key < kmin ? key : kmin;
+        }
+        lane_max[threadIdx.x] = (uint16_t)kmax;
+        lane_min[threadIdx.x] = (uint16_t)kmin;
+        __syncthreads();
+        uint32_t m_top = 0, m_bot = 0xffffu;
+        if (K <= (uint32_t)KVQ_VW_NT) {
+            uint32_t vt[W], vb[W];
+#pragma unroll
+            for (int r = 0; r < W; ++r) { vt[r] = lane_max[lane + 64 * r]; vb[r] = 0xffffu - lane_min[lane + 64 * r]; }
+            uint32_t inv_bot = 0;
+            for (int bit = 15; bit >= 0; --bit) {
+                const uint32_t ct = m_top | (1u << bit), cb = inv_bot | (1u << bit);
+                uint32_t nt = 0, nb = 0;
+#pragma unroll
+                for (int r = 0; r < W; ++r) {
+                    nt += (uint32_t)__popcll(__ballot(vt[r] >= ct));
+                    nb += (uint32_t)__popcll(__ballot(vb[r] >= cb));
+                }
+                if (nt >= K) m_top = ct;
+                if (nb >= K) inv_bot = cb;
+            }
+            m_bot = 0xffffu - inv_bot;
+        }
+        {
+#pragma unroll
+            for (int i = 0; i < JW; ++i) {
+                const uint32_t key = kc[i];
+                if (key >= m_top || key <= m_bot) atomicAdd(&hist[key >> 8], 1u);
+            }
+        }
+        __syncthreads();
+        uint32_t bin_top, above_top, in_top, bin_bot, below_bot, in_bot;
+        wave_find_bin<true>(hist, K, lane, bin_top, above_top, in_top);
+        wave_find_bin<false>(hist, K, lane, bin_bot, below_bot, in_bot);
+        {
+#pragma unroll
+            for (int i = 0; i < JW; ++i) {
+                const uint32_t key = kc[i];
+                if ((key >> 8) == bin_top && key >= m_top) atomicAdd(&hist[256 + (key & 255u)], 1u);
+                if ((key >> 8) == bin_bot && key <= m_bot) atomicAdd(&hist[512 + (key & 255u)], 1u);
+            }
+        }
+        __syncthreads();
+        uint32_t lo_top, above_in, n_eq_top, lo_bot, below_in, n_eq_bot;
+        wave_find_bin<true>(hist + 256, K - above_top, lane, lo_top, above_in, n_eq_top);
+        wave_find_bin<false>(hist + 512, K - below_bot, lane, lo_bot, below_in, n_eq_bot);
+        const uint32_t tau_top = (bin_top << 8) | lo_top, tau_bot = (bin_bot << 8) | lo_bot;
+        const uint32_t need_top = K - (above_top + above_in), need_bot = K - (below_bot + below_in);
+        const bool same = tau_top == tau_bot;
+        // ranks of equal keys are only needed when some but not all of them are taken (wavefront-uniform,
+        // and the same in all four wavefronts: the barrier inside is reached by all or none)
+        const bool ranked = same || need_top != n_eq_top || need_bot != n_eq_bot;
+        uint32_t run_top = 0, run_bot = 0;       // equal keys before this wavefront's channels, then running
+        if (ranked) {
+            uint32_t ct = 0, cb = 0;
+            {
+#pragma unroll
+                for (int i = 0; i < JW; ++i) {
+                    const uint32_t key = kc[i];
+                    ct += (uint32_t)__popcll(__ballot(key == tau_top));
+                    cb += (uint32_t)__popcll(__ballot(key == tau_bot));
+                }
+            }
+            if (lane == 0) { eq_cnt[wave][0] = ct; eq_cnt[wave][1] = cb; }
+            __syncthreads();
+            for (int w = 0; w < wave; ++w) { run_top += eq_cnt[w][0]; run_bot += eq_cnt[w][1]; }
+        }
+        {
+#pragma unroll
+            for (int i = 0; i < JW; ++i) {
+                const uint32_t key = kc[i];
+                const bool eq_t = key == tau_top, eq_b = key == tau_bot;
+                bool is_top, is_bot;
+                if (ranked) {
+                    const unsigned long long bt = __ballot(eq_t), bb = __ballot(eq_b);
+                    const uint32_t rt = run_top + (uint32_t)__popcll(bt & lt_mask);
+                    const uint32_t rb = run_bot + (uint32_t)__popcll(bb & lt_mask);
+                    run_top += (uint32_t)__popcll(bt);
+                    run_bot += (uint32_t)__popcll(bb);
+                    is_top = key > tau_top || (eq_t && rt < need_top);
+                    // thresholds coincide: the lower outliers take the equal keys that follow the upper ones'
+                    is_bot = !is_top && (key < tau_bot ||
+                                         (eq_b && (same ? (rb >= need_top && rb < need_top + need_bot) : rb < need_bot)));
+                } else {
+                    is_top = key >= tau_top;
+                    is_bot = key <= tau_bot;
+                }
+                top |= (uint32_t)is_top << i;
+                bot |= (uint32_t)is_bot << i;
+            }
+        }
+    }
+    // range of the remaining elements, and this wavefront's number of outliers
+    float mx = -INFINITY, mn = INFINITY;
+    const uint32_t outl = top | bot;
+    {
+#pragma unroll
+        for (int i = 0; i < JW; ++i)
+            if (!((outl >> i) & 1u)) { const float x = kvq_h2f(xc[i]); mx = fmaxf(mx, x); mn = fminf(mn, x); }
+    }
+    uint32_t n_out = (uint32_t)__popc(outl);
+    for (int o = 32; o > 0; o >>= 1) {
+        mx = fmaxf(mx, __shfl_xor(mx, o));
+        mn = fminf(mn, __shfl_xor(mn, o));
+        n_out += __shfl_xor(n_out, o);
+    }
+    if (lane == 0) { red_mx[wave] = mx; red_mn[wave] = mn; out_cnt[wave] = n_out; }
+    __syncthreads();
+    mx = red_mx[0]; mn = red_mn[0];
+#pragma unroll
+    for (int w = 1; w < W; ++w) { mx = fmaxf(mx, red_mx[w]); mn = fminf(mn, red_mn[w]); }
+    uint32_t running = 0;                        // outliers before this wavefront's channels, then running
+    for (int w = 0; w < wave; ++w) running += out_cnt[w];
+    const float sum = mx + mn, dif = mx - mn;
+    uint16_t zb = kvq_f2h_rn(sum * 0.5f), sb = kvq_f2h_rn(dif * 0.5f);
+    float zf = kvq_h2f(zb), sf = kvq_h2f(sb);
+    if (sf == 0.0f) { sf = 1.0f; sb = 0x3c00u; }
+    const float rinv = __fdiv_rn(1.0f, sf);
+    if (threadIdx.x == 0) { v_sz[n * 2 + 0] = sb; v_sz[n * 2 + 1] = zb; }
+
+    const int parity = (int)(n & 1);
+    bool overflow = false;
+    {
+#pragma unroll
+        for (int i = 0; i < JW; ++i) {
+            const int j = jb + i;
+            const float x = kvq_h2f(xc[i]);
+            const float diff = x - zf;
+            const float xn = diff * rinv;
+            float sp;
+            const int code = kvq_nearest<NE>(lut, xn, sp);
+            const float deq = __builtin_fmaf(sf, sp, zf);
+            const bool is_out = (outl >> i) & 1u;
+            const unsigned long long b = __ballot(is_out);
+            if (is_out) {
+                const uint64_t pos = (uint64_t)base + running + (uint32_t)__popcll(b & lt_mask);
+                if (pos < (uint64_t)cap_nnz) { v_idx[pos] = (uint16_t)(64 * j + lane); v_val[pos] = kvq_f2h_rn(x - deq); }
+                else overflow = true;
+            }
+            running += (uint32_t)__popcll(b);
+            // the chunk of (head j >> 1, half j & 1): this token's bits of 64 fields, gathered in the
+            // wavefront's own LDS slice
+            stream_or(bits[i], lane * 2 * BITS + parity * BITS, (uint32_t)code, BITS);
+        }
+    }
+    stream_or(mask, lane * 2 * BITS + parity * BITS, (uint32_t)(NE - 1), BITS);
+    // LDS operations of one wavefront execute in order; the fence keeps the compiler from moving the
+    // reads below above the atomics
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    for (int e = lane; e < JW * CW; e += 64) {
+        const int i = e / CW, d = e - i * CW, j = jb + i;
+        const int64_t off = kvq_v_piece0(BITS, cap, n >> 1, j >> 1, j & 1) + (d >> 2) * 1024 + (d & 3) * 4;
+        uint32_t *p = (uint32_t *)(v_codes + off);
+        // the partner token of the pair owns the other bits of this dword: clear this token's bits, then
+        // set them, with two atomics that return nothing (as in v_quant_token)
+        __hip_atomic_fetch_and(p, ~mask[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_or(p, bits[i][d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (threadIdx.x == 0) {
+        uint64_t p = (uint64_t)base + 2u * (uint32_t)k_side;
+        if (p > (uint64_t)cap_nnz) { p = (uint64_t)cap_nnz; overflow = true; }
+        v_ptr[n + 1] = (uint32_t)p;
+    }
+    if (overflow) atomicExch(d_status, (int32_t)KVQ_ERR_NNZ_OVERFLOW);
+}
+
 template <int BITS, int NT>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT == 256 ? 8 : 4)))
 void kvq_k_quant(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
@@ -870,7 +1142,25 @@ extern "C" kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_
     const size_t dyn = 3 * (size_t)D;
 #define LAUNCH_V(B)                                                                                             \
     do {                                                                                                        \
-        if (wide_wg(D, T))                                                                                      \
+        if (T >= KVQ_BULK_TOKENS && D == 4096)                                                                  \
+            kvq_v_quant_bulk<B, 16><<<T, KVQ_VW_NT, 0, s>>>(cache->params, D, cache->cap_tokens,                \
+                                                            cache->n_tokens_v, cache->k_side_v, d_v_new,        \
+                                                            cache->v_codes, cache->v_sz, cache->v_ptr,          \
+                                                            cache->v_idx, cache->v_val, cache->cap_nnz_v,       \
+                                                            cache->d_status);                                   \
+        else if (T >= KVQ_BULK_TOKENS && D == 2048)                                                             \
+            kvq_v_quant_bulk<B, 8><<<T, KVQ_VW_NT, 0, s>>>(cache->params, D, cache->cap_tokens,                 \
+                                                           cache->n_tokens_v, cache->k_side_v, d_v_new,         \
+                                                           cache->v_codes, cache->v_sz, cache->v_ptr,           \
+                                                           cache->v_idx, cache->v_val, cache->cap_nnz_v,        \
+                                                           cache->d_status);                                    \
+        else if (T >= KVQ_BULK_TOKENS && D == 1024)                                                             \
+            kvq_v_quant_bulk<B, 4><<<T, KVQ_VW_NT, 0, s>>>(cache->params, D, cache->cap_tokens,                 \
+                                                           cache->n_tokens_v, cache->k_side_v, d_v_new,         \
+                                                           cache->v_codes, cache->v_sz, cache->v_ptr,           \
+                                                           cache->v_idx, cache->v_val, cache->cap_nnz_v,        \
+                                                           cache->d_status);                                    \
+        else if (wide_wg(D, T))                                                                                 \
             kvq_v_quant<B, 1024><<<T, 1024, dyn, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v,    \
                                                       cache->k_side_v, d_v_new, cache->v_codes, cache->v_sz,     \
                                                       cache->v_ptr, cache->v_idx, cache->v_val,                  \

@@ -79,3 +79,31 @@ def compare_caches(oc, gc):
     chk("v_idx", oc.v_idx[:nv], g(gc.v_idx).view(np.uint16)[:nv])
     chk("v_val", oc.v_val[:nv], g(gc.v_val).view(np.uint16)[:nv])
     return bad
+
+
+def tie_vectors(D, k, rng):
+    """Value vectors full of equal elements, one row per way the top-k / bottom-k thresholds can meet ties
+    (k = outliers per side)."""
+    rows = []
+    rows.append(np.zeros(D))                                             # all equal (zero range)
+    rows.append(rng.choice([-1.0, 0.0, 1.0], size=D))                    # three values: ties on both sides
+    rows.append(np.round(rng.standard_normal(D), 1))                     # coarse grid: many ties
+    x = np.full(D, -2.0); x[rng.choice(D, D // 3, replace=False)] = rng.uniform(1, 50, D // 3)
+    rows.append(x)                                                       # distinct top, tied bottom
+    rows.append(-x)                                                      # tied top, distinct bottom
+    rows.append(np.full(D, 7.5))                                         # all equal, non-zero
+    x = np.full(D, 3.0); x[rng.choice(D, D // 2, replace=False)] = -3.0
+    rows.append(x)                                                       # two values
+    x = rng.choice([0.0, -0.0, 1e-3, -1e-3], size=D)
+    rows.append(x)                                                       # signed zeros among small values
+    x = np.full(D, 0.25); x[rng.choice(D, k, replace=False)] = rng.uniform(5, 9, k)
+    rows.append(x)                                                       # exactly k large ones
+    x = np.full(D, 0.25); x[rng.choice(D, k - 1, replace=False)] = rng.uniform(5, 9, k - 1)
+    rows.append(x)                                                       # k-1 large ones: thresholds coincide
+    rows.append(rng.standard_normal(D))                                  # ordinary
+    rows.append(np.repeat(np.arange(D // 2), 2) / 64.0)                  # every value twice, ascending
+    x = np.full(D, 1.0); x[:k] = 2.0; x[-k:] = 0.5
+    rows.append(x)                                                       # outliers exactly fill both sides
+    x = np.full(D, 1.0); x[: k + 3] = 2.0; x[-(k + 3):] = 0.5
+    rows.append(x)                                                       # three too many on both sides
+    return np.stack(rows).astype(np.float16)

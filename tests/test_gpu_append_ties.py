@@ -7,35 +7,9 @@ import pytest
 
 import kvq_synth as S
 from oracle import kvq_oracle as O
-from kvq_testlib import Setup, compare_caches, matvec_close
+from kvq_testlib import Setup, compare_caches, matvec_close, tie_vectors
 
 pytestmark = pytest.mark.gpu
-
-
-def _tie_vectors(D, k, rng):
-    rows = []
-    rows.append(np.zeros(D))                                             # all equal (zero range)
-    rows.append(rng.choice([-1.0, 0.0, 1.0], size=D))                    # three values: ties on both sides
-    rows.append(np.round(rng.standard_normal(D), 1))                     # coarse grid: many ties
-    x = np.full(D, -2.0); x[rng.choice(D, D // 3, replace=False)] = rng.uniform(1, 50, D // 3)
-    rows.append(x)                                                       # distinct top, tied bottom
-    rows.append(-x)                                                      # tied top, distinct bottom
-    rows.append(np.full(D, 7.5))                                         # all equal, non-zero
-    x = np.full(D, 3.0); x[rng.choice(D, D // 2, replace=False)] = -3.0
-    rows.append(x)                                                       # two values
-    x = rng.choice([0.0, -0.0, 1e-3, -1e-3], size=D)
-    rows.append(x)                                                       # signed zeros among small values
-    x = np.full(D, 0.25); x[rng.choice(D, k, replace=False)] = rng.uniform(5, 9, k)
-    rows.append(x)                                                       # exactly k large ones
-    x = np.full(D, 0.25); x[rng.choice(D, k - 1, replace=False)] = rng.uniform(5, 9, k - 1)
-    rows.append(x)                                                       # k-1 large ones: thresholds coincide
-    rows.append(rng.standard_normal(D))                                  # ordinary
-    rows.append(np.repeat(np.arange(D // 2), 2) / 64.0)                  # every value twice, ascending
-    x = np.full(D, 1.0); x[:k] = 2.0; x[-k:] = 0.5
-    rows.append(x)                                                       # outliers exactly fill both sides
-    x = np.full(D, 1.0); x[: k + 3] = 2.0; x[-(k + 3):] = 0.5
-    rows.append(x)                                                       # three too many on both sides
-    return np.stack(rows).astype(np.float16)
 
 
 @pytest.mark.parametrize("heads,bits", [(4, 3), (32, 3), (16, 4), (2, 2)])
@@ -46,7 +20,7 @@ def test_value_append_ties(heads, bits):
     st = Setup(wl)
     assert st.k_side >= 1
     rng = np.random.default_rng(100 + heads)
-    v = _tie_vectors(wl.D, st.k_side, rng)
+    v = tie_vectors(wl.D, st.k_side, rng)
     v = np.concatenate([v, v[::-1], v[rng.permutation(len(v))]])         # both pair parities see every row
     T = len(v)
     k = st.k(0, T)

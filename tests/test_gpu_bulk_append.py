@@ -1,5 +1,6 @@
-"""Bulk appends (calls of a thousand tokens and more take the wavefront-per-token Key kernel):
-bit-exact against the oracle for every code width, head counts that fill no workgroup evenly, calls
+"""Bulk appends (calls of a thousand tokens and more take the wavefront-per-token Key kernel, calls
+of 512 and more the four-wavefronts-per-token Value kernel where the layer is 1024, 2048 or 4096
+channels wide): bit-exact against the oracle for every code width, head counts that fill no workgroup evenly, calls
 that are not a multiple of the four tokens a workgroup takes, sink rows, and a bulk call that
 overflows the sparse arrays."""
 import numpy as np
@@ -17,6 +18,9 @@ pytestmark = pytest.mark.gpu
     ("c3", dict(n_kv_heads=4, n_q_heads=8, outlier_fraction=0.004), 0, [2049]),  # 4-bit
     ("c4", dict(n_kv_heads=1, n_q_heads=4), 1, [1100, 1100]),                    # one head: two channels per lane in all
     ("c2", dict(n_kv_heads=4, n_q_heads=4, outlier_fraction=0.0), 0, [1300]),    # thresholds admit no outlier
+    ("c2", dict(n_kv_heads=16, n_q_heads=16), 0, [513, 600]),                    # D = 2048
+    ("c3", dict(outlier_fraction=0.004), 1, [601]),                              # D = 4096, 4-bit
+    ("c2", dict(bits=2), 0, [512]),                                              # D = 4096, 2-bit
 ])
 def test_bulk_appends_bit_exact(name, ov, n_sink, chunks):
     import torch
@@ -71,3 +75,33 @@ def test_bulk_key_append_that_overflows_the_sparse_array():
     assert np.array_equal(kp, np.minimum(oc.k_ptr[:T + 1], room))
     assert np.array_equal(gc.k_idx.cpu().numpy().view(np.uint16)[:room], oc.k_idx[:room])
     assert np.array_equal(gc.k_val.cpu().numpy().view(np.uint16)[:room], oc.k_val[:room])
+
+
+@pytest.mark.parametrize("heads,bits", [(8, 3), (16, 4), (32, 3), (32, 2)])
+def test_bulk_value_append_ties(heads, bits):
+    """Bulk Value appends of vectors full of equal elements: ties at one or both thresholds, thresholds
+    that coincide, all elements equal.  The choice among equal elements must be the oracle's (lower
+    channel first, the upper side before the lower one) wherever the tied channels fall among the
+    wavefronts that share a token."""
+    import torch
+    import paper_2401_18079_amd as K
+    from kvq_testlib import tie_vectors
+    wl = S.workload("c2", n_kv_heads=heads, n_q_heads=heads, bits=bits)
+    st = Setup(wl)
+    assert st.k_side >= 1
+    rng = np.random.default_rng(300 + heads)
+    rows = tie_vectors(wl.D, st.k_side, rng)
+    T = 530                                                     # one bulk call, from an odd token on
+    v = np.stack([np.roll(rows[i % len(rows)], 37 * i) for i in range(T)])
+    v[1::3] = v[1::3, ::-1]
+    lead = st.v(0, 1)
+    k = st.k(0, T + 1)
+    oc, gc = st.oracle_cache(640), st.gpu_cache(640)
+    oc.append_k(k); oc.append_v(lead); oc.append_v(v)
+    K.kvq_quantize_append_k(gc, torch.from_numpy(k).cuda())
+    K.kvq_quantize_append_v(gc, torch.from_numpy(lead).cuda())
+    K.kvq_quantize_append_v(gc, torch.from_numpy(np.ascontiguousarray(v)).cuda())
+    torch.cuda.synchronize()
+    assert gc.status() == 0
+    bad = compare_caches(oc, gc)
+    assert not bad, bad
