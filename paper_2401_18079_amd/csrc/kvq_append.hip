@@ -717,15 +717,12 @@ __device__ __forceinline__ void wave_find_bin(const uint32_t *h256, uint32_t K, 
 constexpr int KVQ_VW_WAVES = 4;
 constexpr int KVQ_VW_NT = 64 * KVQ_VW_WAVES;
 template <int BITS, int JW>
-__global__ __launch_bounds__(KVQ_VW_NT) void kvq_v_quant_bulk(const void *__restrict__ params, int D, int64_t cap,
-                                                              int64_t n0, int k_side,
-                                                              const uint16_t *__restrict__ v_new,
-                                                              uint8_t *__restrict__ v_codes,
-                                                              uint16_t *__restrict__ v_sz,
-                                                              uint32_t *__restrict__ v_ptr,
-                                                              uint16_t *__restrict__ v_idx,
-                                                              uint16_t *__restrict__ v_val, int64_t cap_nnz,
-                                                              int32_t *d_status)
+__device__ __forceinline__ void v_quant_token4(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
+                                               int k_side, const uint16_t *__restrict__ v_new,
+                                               uint8_t *__restrict__ v_codes, uint16_t *__restrict__ v_sz,
+                                               uint32_t *__restrict__ v_ptr, uint16_t *__restrict__ v_idx,
+                                               uint16_t *__restrict__ v_val, int64_t cap_nnz, int32_t *d_status,
+                                               const int t)
 {
     constexpr int NE = 1 << BITS;
     constexpr int CW = 4 * BITS;
@@ -736,7 +733,6 @@ __global__ __launch_bounds__(KVQ_VW_NT) void kvq_v_quant_bulk(const void *__rest
     __shared__ uint16_t lane_max[KVQ_VW_NT], lane_min[KVQ_VW_NT];
     __shared__ float red_mx[W], red_mn[W];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int t = blockIdx.x;
     uint32_t(*bits)[CW + 1] = bits_s[wave];
     uint32_t *mask = mask_s[wave];
     KvqParamsView pv = kvq_params_view(params, D);
@@ -943,6 +939,18 @@ __global__ __launch_bounds__(KVQ_VW_NT) void kvq_v_quant_bulk(const void *__rest
     if (overflow) atomicExch(d_status, (int32_t)KVQ_ERR_NNZ_OVERFLOW);
 }
 
+template <int BITS, int JW>
+__global__ __launch_bounds__(KVQ_VW_NT) void kvq_v_quant4(const void *__restrict__ params, int D, int64_t cap,
+                                                          int64_t n0, int k_side, const uint16_t *__restrict__ v_new,
+                                                          uint8_t *__restrict__ v_codes, uint16_t *__restrict__ v_sz,
+                                                          uint32_t *__restrict__ v_ptr, uint16_t *__restrict__ v_idx,
+                                                          uint16_t *__restrict__ v_val, int64_t cap_nnz,
+                                                          int32_t *d_status)
+{
+    v_quant_token4<BITS, JW>(params, D, cap, n0, k_side, v_new, v_codes, v_sz, v_ptr, v_idx, v_val, cap_nnz, d_status,
+                             (int)blockIdx.x);
+}
+
 template <int BITS, int NT>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT == 256 ? 8 : 4)))
 void kvq_k_quant(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
@@ -1058,7 +1066,18 @@ __global__ __launch_bounds__(NT) void kvq_kv_quant(const KvAppendArgs a)
     if ((blockIdx.x & 1) == 0)
         k_quant_token<BITS, NT>(a.params, a.D, a.cap, a.n0_k, a.k_new, a.k_codes, a.k_ptr, a.k_idx, a.k_val, a.cap_nnz_k,
                                 a.single, a.d_status, t);
-    else
+    else if (a.D == 4096 || a.D == 2048 || a.D == 1024) {
+        // the four-wavefront routine; further wavefronts of the workgroup end here (a barrier waits
+        // only for the wavefronts that have not ended)
+        if (threadIdx.x >= KVQ_VW_NT) return;
+#define V4(J)                                                                                                    \
+    v_quant_token4<BITS, J>(a.params, a.D, a.cap, a.n0_v, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, a.v_idx, \
+                            a.v_val, a.cap_nnz_v, a.d_status, t)
+        if (a.D == 4096) V4(16);
+        else if (a.D == 2048) V4(8);
+        else V4(4);
+#undef V4
+    } else
         v_quant_token<BITS, NT>(a.params, a.D, a.cap, a.n0_v, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, a.v_idx,
                                 a.v_val, a.cap_nnz_v, a.d_status, t);
 }
@@ -1140,26 +1159,16 @@ extern "C" kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_
     if (D > 16384) return KVQ_ERR_UNSUPPORTED;       // the per-token selection keeps the vector in LDS
     hipStream_t s = (hipStream_t)stream;
     const size_t dyn = 3 * (size_t)D;
+#define LAUNCH_V4(B, J)                                                                                        \
+    kvq_v_quant4<B, J><<<T, KVQ_VW_NT, 0, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v,         \
+                                               cache->k_side_v, d_v_new, cache->v_codes, cache->v_sz,          \
+                                               cache->v_ptr, cache->v_idx, cache->v_val, cache->cap_nnz_v,     \
+                                               cache->d_status)
 #define LAUNCH_V(B)                                                                                             \
     do {                                                                                                        \
-        if (T >= KVQ_BULK_TOKENS && D == 4096)                                                                  \
-            kvq_v_quant_bulk<B, 16><<<T, KVQ_VW_NT, 0, s>>>(cache->params, D, cache->cap_tokens,                \
-                                                            cache->n_tokens_v, cache->k_side_v, d_v_new,        \
-                                                            cache->v_codes, cache->v_sz, cache->v_ptr,          \
-                                                            cache->v_idx, cache->v_val, cache->cap_nnz_v,       \
-                                                            cache->d_status);                                   \
-        else if (T >= KVQ_BULK_TOKENS && D == 2048)                                                             \
-            kvq_v_quant_bulk<B, 8><<<T, KVQ_VW_NT, 0, s>>>(cache->params, D, cache->cap_tokens,                 \
-                                                           cache->n_tokens_v, cache->k_side_v, d_v_new,         \
-                                                           cache->v_codes, cache->v_sz, cache->v_ptr,           \
-                                                           cache->v_idx, cache->v_val, cache->cap_nnz_v,        \
-                                                           cache->d_status);                                    \
-        else if (T >= KVQ_BULK_TOKENS && D == 1024)                                                             \
-            kvq_v_quant_bulk<B, 4><<<T, KVQ_VW_NT, 0, s>>>(cache->params, D, cache->cap_tokens,                 \
-                                                           cache->n_tokens_v, cache->k_side_v, d_v_new,         \
-                                                           cache->v_codes, cache->v_sz, cache->v_ptr,           \
-                                                           cache->v_idx, cache->v_val, cache->cap_nnz_v,        \
-                                                           cache->d_status);                                    \
+        if (D == 4096) LAUNCH_V4(B, 16);                                                                        \
+        else if (D == 2048) LAUNCH_V4(B, 8);                                                                    \
+        else if (D == 1024) LAUNCH_V4(B, 4);                                                                    \
         else if (wide_wg(D, T))                                                                                 \
             kvq_v_quant<B, 1024><<<T, 1024, dyn, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v,    \
                                                       cache->k_side_v, d_v_new, cache->v_codes, cache->v_sz,     \
@@ -1175,6 +1184,7 @@ extern "C" kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_
     else if (cache->bits == 3) LAUNCH_V(3);
     else LAUNCH_V(4);
 #undef LAUNCH_V
+#undef LAUNCH_V4
     KVQ_HIP_CHECK(hipGetLastError());
     st = copy_sink_rows(cache, cache->sink_v, d_v_new, cache->n_tokens_v, T, s);
     if (st != KVQ_OK) return st;
