@@ -7,10 +7,11 @@
 
 namespace {
 
-// Measured on 4096-channel tokens: 1024-thread workgroups finish a call of up to 256 tokens in one
-// round (Values: 25 us against 37 us with 256 threads), break even at 512 tokens and lose beyond
-// (4096 tokens: 216 us against 105 us), where eight small workgroups per compute unit hide each
-// other's barriers.
+// Measured on 4096-channel tokens with the workgroup-per-token bodies: 1024-thread workgroups finish
+// a call of up to 256 tokens in one round (Values: 25 us against 37 us with 256 threads), break even
+// at 512 tokens and lose beyond (4096 tokens: 216 us against 105 us), where eight small workgroups
+// per compute unit hide each other's barriers.  Values of 1024, 2048 or 4096 channels take the
+// four-wavefront body (v_quant_token4) at every call size instead.
 constexpr int KVQ_BULK_TOKENS = 512;      // calls with at least this many tokens count as bulk appends
 constexpr int KVQ_KV_SPLIT_TOKENS = 256;  // from here on the combined call runs the Key and Value kernels in turn
 constexpr int KVQ_WAVE_TOKENS = 1024;     // Key appends of at least this many tokens: one wavefront per token
