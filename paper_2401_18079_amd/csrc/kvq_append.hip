@@ -796,24 +796,20 @@ __device__ __forceinline__ void v_quant_token4(const void *__restrict__ params, 
             }
             m_bot = 0xffffu - inv_bot;
         }
-        {
 #pragma unroll
-            for (int i = 0; i < JW; ++i) {
-                const uint32_t key = kc[i];
-                if (key >= m_top || key <= m_bot) atomicAdd(&hist[key >> 8], 1u);
-            }
+        for (int i = 0; i < JW; ++i) {
+            const uint32_t key = kc[i];
+            if (key >= m_top || key <= m_bot) atomicAdd(&hist[key >> 8], 1u);
         }
         __syncthreads();
         uint32_t bin_top, above_top, in_top, bin_bot, below_bot, in_bot;
         wave_find_bin<true>(hist, K, lane, bin_top, above_top, in_top);
         wave_find_bin<false>(hist, K, lane, bin_bot, below_bot, in_bot);
-        {
 #pragma unroll
-            for (int i = 0; i < JW; ++i) {
-                const uint32_t key = kc[i];
-                if ((key >> 8) == bin_top && key >= m_top) atomicAdd(&hist[256 + (key & 255u)], 1u);
-                if ((key >> 8) == bin_bot && key <= m_bot) atomicAdd(&hist[512 + (key & 255u)], 1u);
-            }
+        for (int i = 0; i < JW; ++i) {
+            const uint32_t key = kc[i];
+            if ((key >> 8) == bin_top && key >= m_top) atomicAdd(&hist[256 + (key & 255u)], 1u);
+            if ((key >> 8) == bin_bot && key <= m_bot) atomicAdd(&hist[512 + (key & 255u)], 1u);
         }
         __syncthreads();
         uint32_t lo_top, above_in, n_eq_top, lo_bot, below_in, n_eq_bot;
@@ -828,51 +824,45 @@ __device__ __forceinline__ void v_quant_token4(const void *__restrict__ params, 
         uint32_t run_top = 0, run_bot = 0;       // equal keys before this wavefront's channels, then running
         if (ranked) {
             uint32_t ct = 0, cb = 0;
-            {
 #pragma unroll
-                for (int i = 0; i < JW; ++i) {
-                    const uint32_t key = kc[i];
-                    ct += (uint32_t)__popcll(__ballot(key == tau_top));
-                    cb += (uint32_t)__popcll(__ballot(key == tau_bot));
-                }
+            for (int i = 0; i < JW; ++i) {
+                const uint32_t key = kc[i];
+                ct += (uint32_t)__popcll(__ballot(key == tau_top));
+                cb += (uint32_t)__popcll(__ballot(key == tau_bot));
             }
             if (lane == 0) { eq_cnt[wave][0] = ct; eq_cnt[wave][1] = cb; }
             __syncthreads();
             for (int w = 0; w < wave; ++w) { run_top += eq_cnt[w][0]; run_bot += eq_cnt[w][1]; }
         }
-        {
 #pragma unroll
-            for (int i = 0; i < JW; ++i) {
-                const uint32_t key = kc[i];
-                const bool eq_t = key == tau_top, eq_b = key == tau_bot;
-                bool is_top, is_bot;
-                if (ranked) {
-                    const unsigned long long bt = __ballot(eq_t), bb = __ballot(eq_b);
-                    const uint32_t rt = run_top + (uint32_t)__popcll(bt & lt_mask);
-                    const uint32_t rb = run_bot + (uint32_t)__popcll(bb & lt_mask);
-                    run_top += (uint32_t)__popcll(bt);
-                    run_bot += (uint32_t)__popcll(bb);
-                    is_top = key > tau_top || (eq_t && rt < need_top);
-                    // thresholds coincide: the lower outliers take the equal keys that follow the upper ones'
-                    is_bot = !is_top && (key < tau_bot ||
-                                         (eq_b && (same ? (rb >= need_top && rb < need_top + need_bot) : rb < need_bot)));
-                } else {
-                    is_top = key >= tau_top;
-                    is_bot = key <= tau_bot;
-                }
-                top |= (uint32_t)is_top << i;
-                bot |= (uint32_t)is_bot << i;
+        for (int i = 0; i < JW; ++i) {
+            const uint32_t key = kc[i];
+            const bool eq_t = key == tau_top, eq_b = key == tau_bot;
+            bool is_top, is_bot;
+            if (ranked) {
+                const unsigned long long bt = __ballot(eq_t), bb = __ballot(eq_b);
+                const uint32_t rt = run_top + (uint32_t)__popcll(bt & lt_mask);
+                const uint32_t rb = run_bot + (uint32_t)__popcll(bb & lt_mask);
+                run_top += (uint32_t)__popcll(bt);
+                run_bot += (uint32_t)__popcll(bb);
+                is_top = key > tau_top || (eq_t && rt < need_top);
+                // thresholds coincide: the lower outliers take the equal keys that follow the upper ones'
+                is_bot = !is_top && (key < tau_bot ||
+                                     (eq_b && (same ? (rb >= need_top && rb < need_top + need_bot) : rb < need_bot)));
+            } else {
+                is_top = key >= tau_top;
+                is_bot = key <= tau_bot;
             }
+            top |= (uint32_t)is_top << i;
+            bot |= (uint32_t)is_bot << i;
         }
     }
     // range of the remaining elements, and this wavefront's number of outliers
     float mx = -INFINITY, mn = INFINITY;
     const uint32_t outl = top | bot;
-    {
 #pragma unroll
-        for (int i = 0; i < JW; ++i)
-            if (!((outl >> i) & 1u)) { const float x = kvq_h2f(xc[i]); mx = fmaxf(mx, x); mn = fminf(mn, x); }
-    }
+    for (int i = 0; i < JW; ++i)
+        if (!((outl >> i) & 1u)) { const float x = kvq_h2f(xc[i]); mx = fmaxf(mx, x); mn = fminf(mn, x); }
     uint32_t n_out = (uint32_t)__popc(outl);
     for (int o = 32; o > 0; o >>= 1) {
         mx = fmaxf(mx, __shfl_xor(mx, o));
@@ -895,28 +885,26 @@ __device__ __forceinline__ void v_quant_token4(const void *__restrict__ params, 
 
     const int parity = (int)(n & 1);
     bool overflow = false;
-    {
 #pragma unroll
-        for (int i = 0; i < JW; ++i) {
-            const int j = jb + i;
-            const float x = kvq_h2f(xc[i]);
-            const float diff = x - zf;
-            const float xn = diff * rinv;
-            float sp;
-            const int code = kvq_nearest<NE>(lut, xn, sp);
-            const float deq = __builtin_fmaf(sf, sp, zf);
-            const bool is_out = (outl >> i) & 1u;
-            const unsigned long long b = __ballot(is_out);
-            if (is_out) {
-                const uint64_t pos = (uint64_t)base + running + (uint32_t)__popcll(b & lt_mask);
-                if (pos < (uint64_t)cap_nnz) { v_idx[pos] = (uint16_t)(64 * j + lane); v_val[pos] = kvq_f2h_rn(x - deq); }
-                else overflow = true;
-            }
-            running += (uint32_t)__popcll(b);
-            // the chunk of (head j >> 1, half j & 1): this token's bits of 64 fields, gathered in the
-            // wavefront's own LDS slice
-            stream_or(bits[i], lane * 2 * BITS + parity * BITS, (uint32_t)code, BITS);
+    for (int i = 0; i < JW; ++i) {
+        const int j = jb + i;
+        const float x = kvq_h2f(xc[i]);
+        const float diff = x - zf;
+        const float xn = diff * rinv;
+        float sp;
+        const int code = kvq_nearest<NE>(lut, xn, sp);
+        const float deq = __builtin_fmaf(sf, sp, zf);
+        const bool is_out = (outl >> i) & 1u;
+        const unsigned long long b = __ballot(is_out);
+        if (is_out) {
+            const uint64_t pos = (uint64_t)base + running + (uint32_t)__popcll(b & lt_mask);
+            if (pos < (uint64_t)cap_nnz) { v_idx[pos] = (uint16_t)(64 * j + lane); v_val[pos] = kvq_f2h_rn(x - deq); }
+            else overflow = true;
         }
+        running += (uint32_t)__popcll(b);
+        // the chunk of (head j >> 1, half j & 1): this token's bits of 64 fields, gathered in the
+        // wavefront's own LDS slice
+        stream_or(bits[i], lane * 2 * BITS + parity * BITS, (uint32_t)code, BITS);
     }
     stream_or(mask, lane * 2 * BITS + parity * BITS, (uint32_t)(NE - 1), BITS);
     // LDS operations of one wavefront execute in order; the fence keeps the compiler from moving the
