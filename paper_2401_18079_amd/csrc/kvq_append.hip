@@ -11,7 +11,8 @@ namespace {
 // a call of up to 256 tokens in one round (Values: 25 us against 37 us with 256 threads), break even
 // at 512 tokens and lose beyond (4096 tokens: 216 us against 105 us), where eight small workgroups
 // per compute unit hide each other's barriers.  Values of 1024, 2048 or 4096 channels take the
-// four-wavefront body (v_quant_token4) at every call size instead.
+// four-wavefront body (v_quant_token4) at every call size instead, those of 5120, 6656 or 8192
+// channels (40, 52, 64 heads) in bulk appends.
 constexpr int KVQ_BULK_TOKENS = 512;      // calls with at least this many tokens count as bulk appends
 constexpr int KVQ_KV_SPLIT_TOKENS = 256;  // from here on the combined call runs the Key and Value kernels in turn
 constexpr int KVQ_WAVE_TOKENS = 1024;     // Key appends of at least this many tokens: one wavefront per token
@@ -703,8 +704,8 @@ __device__ __forceinline__ void wave_find_bin(const uint32_t *h256, uint32_t K, 
     in_bin = __shfl(fh, src);
 }
 
-// Bulk Value append: one workgroup of four wavefronts per token, D = 256 * JW channels (JW = 4, 8 or
-// 16).  Wavefront w takes the channel groups j = w JW .. (w + 1) JW - 1, lane l of it the channels
+// Value append: one workgroup of four wavefronts per token, D = 256 * JW channels (JW = 4, 8, 16,
+// 20, 26 or 32).  Wavefront w takes the channel groups j = w JW .. (w + 1) JW - 1, lane l of it the channels
 // 64 j + l (half j & 1 of head j >> 1), so a wavefront packs whole chunks on its own, channel order is
 // wavefront order, and a lane keeps its JW elements in registers from the one load to the end.  The
 // selection is the two-level radix selection of select_both on histograms shared by the four
@@ -1158,6 +1159,9 @@ extern "C" kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_
         if (D == 4096) LAUNCH_V4(B, 16);                                                                        \
         else if (D == 2048) LAUNCH_V4(B, 8);                                                                    \
         else if (D == 1024) LAUNCH_V4(B, 4);                                                                    \
+        else if (D == 5120 && T >= KVQ_BULK_TOKENS) LAUNCH_V4(B, 20);                                           \
+        else if (D == 6656 && T >= KVQ_BULK_TOKENS) LAUNCH_V4(B, 26);                                           \
+        else if (D == 8192 && T >= KVQ_BULK_TOKENS) LAUNCH_V4(B, 32);                                           \
         else if (wide_wg(D, T))                                                                                 \
             kvq_v_quant<B, 1024><<<T, 1024, dyn, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v,    \
                                                       cache->k_side_v, d_v_new, cache->v_codes, cache->v_sz,     \

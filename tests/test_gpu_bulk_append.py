@@ -1,6 +1,6 @@
 """Bulk appends (calls of a thousand tokens and more take the wavefront-per-token Key kernel, calls
-of 512 and more the four-wavefronts-per-token Value kernel where the layer is 1024, 2048 or 4096
-channels wide): bit-exact against the oracle for every code width, head counts that fill no workgroup evenly, calls
+of 512 and more the four-wavefronts-per-token Value kernel where the layer is 1024 to 8192
+channels wide in one of the supported widths): bit-exact against the oracle for every code width, head counts that fill no workgroup evenly, calls
 that are not a multiple of the four tokens a workgroup takes, sink rows, and a bulk call that
 overflows the sparse arrays."""
 import numpy as np
@@ -21,6 +21,9 @@ pytestmark = pytest.mark.gpu
     ("c2", dict(n_kv_heads=16, n_q_heads=16), 0, [513, 600]),                    # D = 2048
     ("c3", dict(outlier_fraction=0.004), 1, [601]),                              # D = 4096, 4-bit
     ("c2", dict(bits=2), 0, [512]),                                              # D = 4096, 2-bit
+    ("c2", dict(n_kv_heads=40, n_q_heads=40), 1, [513]),                         # D = 5120
+    ("c3", dict(n_kv_heads=52, n_q_heads=52, outlier_fraction=0.004), 0, [1, 512]),   # D = 6656, 4-bit, odd start
+    ("c2", dict(n_kv_heads=64, n_q_heads=64, bits=2), 0, [600]),                 # D = 8192
 ])
 def test_bulk_appends_bit_exact(name, ov, n_sink, chunks):
     import torch
@@ -77,7 +80,7 @@ def test_bulk_key_append_that_overflows_the_sparse_array():
     assert np.array_equal(gc.k_val.cpu().numpy().view(np.uint16)[:room], oc.k_val[:room])
 
 
-@pytest.mark.parametrize("heads,bits", [(8, 3), (16, 4), (32, 3), (32, 2)])
+@pytest.mark.parametrize("heads,bits", [(8, 3), (16, 4), (32, 3), (32, 2), (40, 3), (64, 4)])
 def test_bulk_value_append_ties(heads, bits):
     """Bulk Value appends of vectors full of equal elements: ties at one or both thresholds, thresholds
     that coincide, all elements equal.  The choice among equal elements must be the oracle's (lower
