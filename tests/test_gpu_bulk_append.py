@@ -1,8 +1,8 @@
 """Bulk appends (calls of a thousand tokens and more take the wavefront-per-token Key kernel, calls
-of 512 and more the four-wavefronts-per-token Value kernel where the layer is 1024 to 8192
-channels wide in one of the supported widths): bit-exact against the oracle for every code width, head counts that fill no workgroup evenly, calls
-that are not a multiple of the four tokens a workgroup takes, sink rows, and a bulk call that
-overflows the sparse arrays."""
+of 512 and more the four-wavefronts-per-token Value kernel where the layer has one of the widths it
+is built for, 1024 to 8192 channels): bit-exact against the oracle for every code width, head counts
+that fill no workgroup evenly, calls that are not a multiple of the four tokens a workgroup takes,
+sink rows, tokens full of equal elements, and a bulk call that overflows the sparse arrays."""
 import numpy as np
 import pytest
 
