@@ -110,8 +110,12 @@ const char *kvq_version(void);
  * Stage one layer's quantization constants on the device (paper Sec. 3.3: one sorted 2^bits-entry
  * signpost table per layer for Keys and one for Values, in [-1,1]; Sec. 3.1/3.4/3.6: per-channel
  * Key scale, zero-point and lower/upper outlier thresholds calibrated offline).
- *   h_lut_k, h_lut_v : HOST fp32 [2^bits], ascending.  Values are used as fp16 inside the mat-vec
- *                      kernels (signposts should be fp16-representable; others are rounded there).
+ *   h_lut_k, h_lut_v : HOST fp32 [2^bits], ascending.  The signposts of the datatype are fp16 numbers
+ *                      (the paper's look-up tables hold fp16 entries, App. "Kernel Implementation
+ *                      Details"): each entry is rounded to the nearest fp16 number, ties to even, as
+ *                      it is stored, and the appends and both mat-vecs all use the stored values
+ *                      (as fp32 in the arithmetic).  Entries may become equal by the rounding; the
+ *                      nearest-signpost rule then picks the smaller index.
  *   h_s_k, h_z_k, h_lo_k, h_hi_k : HOST fp16 bit patterns [D].
  * Copies synchronously from the host arrays (they may be freed on return), then runs a small
  * kernel on `stream`.  Sets cache->loaded.  Errors: INVALID_ARG, UNSUPPORTED, HIP.
@@ -119,6 +123,9 @@ const char *kvq_version(void);
 kvq_status kvq_lut_load(kvq_cache *cache, const float *h_lut_k, const float *h_lut_v,
                         const uint16_t *h_s_k, const uint16_t *h_z_k,
                         const uint16_t *h_lo_k, const uint16_t *h_hi_k, void *stream);
+/* The value kvq_lut_load stores for a signpost x (host-only arithmetic, no GPU needed): the nearest
+ * fp16 number, ties to even, as fp32; NaN if |x| >= 65520 or x is NaN (kvq_lut_load rejects those). */
+float kvq_stored_signpost(float x);
 
 /*
  * Quantize T new pre-RoPE Key vectors and append them (paper Sec. 3.1, 3.2, 3.4, 3.7; the
@@ -166,8 +173,8 @@ kvq_status kvq_quantize_append_kv(kvq_cache *cache, const uint16_t *d_k_new, con
  *   d_q_rot  : DEVICE fp32 [n_q_heads][128], already rotated to the query's own position.
  *   d_scores : DEVICE fp32 [n_q_heads][ld_scores], ld_scores >= n_tokens_k; entries n >= n_tokens_k
  *              are not touched.
- * fp32 accumulation; table entries are held in fp16 (relative 2^-11).  Errors: INVALID_ARG,
- * NOT_LOADED, CAPACITY (workspace), HIP.
+ * fp32 tables and fp32 accumulation throughout.  Errors: INVALID_ARG, NOT_LOADED, UNSUPPORTED
+ * (n_q_heads / n_kv_heads not in {1, 2, 4, 8}), HIP.
  */
 kvq_status kvq_qk_matvec(const kvq_cache *cache, const float *d_q_rot, float scale,
                          float *d_scores, int64_t ld_scores, void *stream);

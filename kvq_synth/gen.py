@@ -175,12 +175,18 @@ def gen_probs_logits(w: Workload, layer: int, seq: int, L: int, temperature: flo
     return (normalish(h) * np.float32(temperature)).astype(np.float32)
 
 
-def make_lut(bits: int, seed: int, layer: int, which: int):
-    """2^bits sorted signposts in [-1, 1], fp16-representable fp32, adjacent gaps >= 2^-7.
+def make_lut(bits: int, seed: int, layer: int, which: int, fp16_exact=None):
+    """2^bits sorted signposts in [-1, 1] as fp32, adjacent gaps >= 2^-7 (also after rounding to fp16).
 
     The outermost signposts are pinned to -1 and +1 (a normalised vector always touches both
-    ends of its range); the interior ones are seeded uniform draws."""
+    ends of its range); the interior ones are seeded uniform draws.  A k-means solver returns
+    fp32 signposts that are not fp16 numbers, and a cache stores fp16 signposts, so about one
+    table in three (chosen by the seed; `fp16_exact` overrides) keeps its fp32 draws and the rest
+    are fp16 numbers already."""
     n = 1 << bits
+    if fp16_exact is None:
+        pick = splitmix64(np.array([(seed & 0xFFFFFF) * 8 + layer * 2 + which + 0x5151], dtype=_U64))[0]
+        fp16_exact = bool(int(pick) % 3 != 0)
     salt = 0
     while True:
         h = splitmix64(np.arange(n, dtype=_U64) ^ (_U64(seed & 0xFFFFFF) << _U64(8)) ^ (_U64(layer * 4 + which) << _U64(32))
@@ -190,7 +196,7 @@ def make_lut(bits: int, seed: int, layer: int, which: int):
         u[0], u[-1] = -1.0, 1.0
         lut = u.astype(np.float16).astype(np.float32)
         if np.all(np.diff(lut) >= 2.0 ** -7):
-            return lut
+            return lut if fp16_exact else u.astype(np.float32)
         salt += 1
 
 

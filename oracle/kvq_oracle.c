@@ -23,6 +23,11 @@
  *                                                                      Experimental Details"
  *
  * Readings taken where the paper is silent (each is listed in the design document):
+ *   - the signposts of a layer's datatype are fp16 numbers, like every other stored constant of the
+ *     method (App. "Kernel Implementation Details": the look-up table entries and all arithmetic of
+ *     the paper's kernels are fp16; App. "Additional Experimental Details": 16-bit scale and
+ *     zero-point): a table handed over in fp32 is rounded to fp16, to nearest-even, once, when it is
+ *     stored (kvqo_store_lut), and every later step sees only the stored values;
  *   - nearest signpost: brute-force argmin of |x_norm - lut[j]| in fp32, ties to the smaller j;
  *   - (scale, zero) = (half-range, mid-range) of the non-outliers, each rounded to fp16;
  *   - every element gets a dense code; an outlier's sparse value is the fp16-rounded residual
@@ -215,6 +220,17 @@ void kvqo_unpack_v(const uint8_t *buf, int bits, int n_kv_heads, int64_t cap, in
 }
 
 /* ------------------------------------------------------------------ quantisation */
+
+/*
+ * Store a layer's signpost table (Sec. 3.3; App. "Kernel Implementation Details": fp16 table
+ * entries): each of the n_entries fp32 signposts is rounded to the nearest fp16 number (ties to
+ * even) and kept as that number's fp32 value.  Rounding is monotone, so a sorted table stays sorted
+ * (neighbours may become equal; the tie rule of kvqo_nearest then picks the smaller index).
+ */
+void kvqo_store_lut(const float *lut_in, int n_entries, float *lut_stored)
+{
+    for (int j = 0; j < n_entries; ++j) lut_stored[j] = kvqo_h2f(kvqo_f2h(lut_in[j]));
+}
 
 /* Nearest signpost by brute force in fp32; ties go to the smaller index. */
 int kvqo_nearest(const float *lut, int n_entries, float xn)

@@ -41,6 +41,7 @@ _unpack_k = _sig("kvqo_unpack_k", None, _u8p, _i32, _i32, _i64, _i64, _i64, _u8p
 _pack_v = _sig("kvqo_pack_v", None, _u8p, _i32, _i32, _i64, _i64, _i64, _u8p)
 _unpack_v = _sig("kvqo_unpack_v", None, _u8p, _i32, _i32, _i64, _i64, _i64, _u8p)
 _nearest = _sig("kvqo_nearest", _i32, _f32p, _i32, _f32)
+_store_lut = _sig("kvqo_store_lut", None, _f32p, _i32, _f32p)
 _quantize_k = _sig("kvqo_quantize_k", _i64, _u16p, _i64, _i32, _i32, _f32p, _u16p, _u16p, _u16p, _u16p,
                    _u8p, _u32p, _u16p, _u16p, _i64)
 _quantize_v = _sig("kvqo_quantize_v", _i64, _u16p, _i64, _i32, _i32, _f32p, _i32, _u16p, _u8p, _u32p,
@@ -88,6 +89,14 @@ def _as_bits(x) -> np.ndarray:
         return np.ascontiguousarray(x).view(np.uint16)
     assert x.dtype == np.uint16
     return np.ascontiguousarray(x)
+
+
+def store_lut(lut) -> np.ndarray:
+    """The signpost table as a cache stores it: every entry rounded to the nearest fp16 number."""
+    lut = np.ascontiguousarray(lut, dtype=np.float32)
+    out = np.empty_like(lut)
+    _store_lut(lut, lut.size, out)
+    return out
 
 
 def nearest(lut: np.ndarray, xn: float) -> int:
@@ -149,8 +158,9 @@ class OracleCache:
         self.D = n_kv_heads * HEAD_DIM
         self.k_side_v = k_side_v
         self.rope_base = float(rope_base)
-        self.lut_k = np.ascontiguousarray(lut_k, dtype=np.float32)
-        self.lut_v = np.ascontiguousarray(lut_v, dtype=np.float32)
+        # the cache stores fp16 signposts (see kvqo_store_lut); everything below uses the stored values
+        self.lut_k = store_lut(lut_k)
+        self.lut_v = store_lut(lut_v)
         self.s_k, self.z_k, self.lo_k, self.hi_k = (_as_bits(a).copy() for a in (s_k, z_k, lo_k, hi_k))
         nbytes = codes_bytes(bits, n_kv_heads, cap_tokens)
         self.k_codes = np.zeros(nbytes, dtype=np.uint8)

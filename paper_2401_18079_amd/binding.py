@@ -53,6 +53,7 @@ def load_library():
         "kvq_workspace_bytes": (I64, [P, I32]),
         "kvq_status_string": (C.c_char_p, [C.c_int]),
         "kvq_version": (C.c_char_p, []),
+        "kvq_stored_signpost": (C.c_float, [C.c_float]),
         "kvq_lut_load": (C.c_int, [P, V, V, V, V, V, V, V]),
         "kvq_quantize_append_k": (C.c_int, [P, V, I32, V]),
         "kvq_quantize_append_v": (C.c_int, [P, V, I32, V]),
@@ -91,7 +92,7 @@ def load_library():
 
 EXPORTED_SYMBOLS = [
     "kvq_codes_bytes", "kvq_params_bytes", "kvq_workspace_bytes", "kvq_status_string", "kvq_version",
-    "kvq_lut_load", "kvq_quantize_append_k", "kvq_quantize_append_v", "kvq_quantize_append_kv",
+    "kvq_lut_load", "kvq_stored_signpost", "kvq_quantize_append_k", "kvq_quantize_append_v", "kvq_quantize_append_kv",
     "kvq_qk_matvec", "kvq_pv_matvec",
     "kvq_attention_decode", "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
     "kvq_fp16_pv_matvec", "kvq_event_create", "kvq_event_record", "kvq_event_elapsed_ms", "kvq_event_destroy",
@@ -166,6 +167,10 @@ def kvq_status_string(status: int) -> str:
 
 def kvq_version() -> str:
     return load_library().kvq_version().decode()
+
+
+def kvq_stored_signpost(x: float) -> float:
+    return float(load_library().kvq_stored_signpost(float(x)))
 
 
 def kvq_codes_bytes(bits: int, n_kv_heads: int, cap_tokens: int) -> int:

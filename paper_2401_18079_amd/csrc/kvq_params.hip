@@ -30,7 +30,10 @@ const char *kvq_status_string(kvq_status s)
     return "unknown";
 }
 
-const char *kvq_version(void) { return "kvq 0.1 (gfx950)"; }
+const char *kvq_version(void) { return "kvq 0.2 (gfx950)"; }
+
+static float kvq_signpost_fp16(float x);
+float kvq_stored_signpost(float x) { return (fabsf(x) < 65520.0f) ? kvq_signpost_fp16(x) : NAN; }
 
 kvq_status kvq_event_create(void **event)
 {
@@ -152,6 +155,28 @@ KvqProfile &kvq_profile_state()
     return p;
 }
 
+// A signpost as the library stores it: the fp32 value of the nearest fp16 number (ties to even).  The
+// paper's look-up tables hold fp16 entries (App. "Kernel Implementation Details"), and with signposts
+// that are fp16 numbers the fp16 pair table of the dense Value kernel is exact, so append, scores and
+// outputs all see one and the same table.  Signposts lie in [-1, 1]: the mantissa is rounded in the
+// fp32 bit pattern (normal range of fp16) or on the 2^-24 grid (below 2^-14).  |x| < 65520 (checked
+// by the caller: beyond that fp16 has no finite neighbour).
+static float kvq_signpost_fp16(float x)
+{
+    if (fabsf(x) < 6.103515625e-05f) {                       // subnormal range of fp16: multiples of 2^-24
+        const float q = nearbyintf(x * 16777216.0f);         // exact product, ties to even
+        return q * (1.0f / 16777216.0f);
+    }
+    uint32_t b;
+    memcpy(&b, &x, 4);
+    const uint32_t keep = b & ~0x1FFFu, rest = b & 0x1FFFu;  // 13 mantissa bits go
+    uint32_t r = keep;
+    if (rest > 0x1000u || (rest == 0x1000u && (keep & 0x2000u))) r += 0x2000u;   // may carry into the exponent
+    float y;
+    memcpy(&y, &r, 4);
+    return y;
+}
+
 // Expand the fp16 per-channel constants to fp32 and form the reciprocal scale with one IEEE division,
 // so every later kernel normalises with exactly (x - z) * (1/s).
 __global__ void kvq_params_expand(void *block, int D)
@@ -179,10 +204,12 @@ extern "C" kvq_status kvq_lut_load(kvq_cache *cache, const float *h_lut_k, const
     const int ne = 1 << cache->bits;
     for (int j = 1; j < ne; ++j)
         if (!(h_lut_k[j] >= h_lut_k[j - 1]) || !(h_lut_v[j] >= h_lut_v[j - 1])) return KVQ_ERR_INVALID_ARG;
+    for (int j = 0; j < ne; ++j)        // finite and within the range of fp16 (also rejects NaN)
+        if (!(fabsf(h_lut_k[j]) < 65520.0f) || !(fabsf(h_lut_v[j]) < 65520.0f)) return KVQ_ERR_INVALID_ARG;
 
     KvqParamsHeader hdr;
     memset(&hdr, 0, sizeof(hdr));
-    for (int j = 0; j < ne; ++j) { hdr.lut_k[j] = h_lut_k[j]; hdr.lut_v[j] = h_lut_v[j]; }
+    for (int j = 0; j < ne; ++j) { hdr.lut_k[j] = kvq_signpost_fp16(h_lut_k[j]); hdr.lut_v[j] = kvq_signpost_fp16(h_lut_v[j]); }
     for (int i = 0; i < 64; ++i) {
         // rotation frequency of channel pair (i, i+64) in revolutions per position, split in two floats
         double rev = pow((double)cache->rope_base, -2.0 * (double)i / (double)KVQ_HEAD_DIM) / (2.0 * M_PI);

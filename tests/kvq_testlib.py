@@ -23,6 +23,12 @@ def matvec_close(got, ref, rel=REL_TOL):
 class Setup(S.LayerInputs):
     """A synthetic layer's inputs plus the two caches under comparison."""
 
+    def __init__(self, wl, layer=0):
+        super().__init__(wl, layer)
+        # the signposts as a cache stores them (fp16 numbers), for tests that call the oracle's
+        # element-level functions directly; the caches below are handed the tables as drawn
+        self.lut_k_stored, self.lut_v_stored = O.store_lut(self.lut_k), O.store_lut(self.lut_v)
+
     def oracle_cache(self, cap):
         wl = self.wl
         return O.OracleCache(wl.bits, wl.n_kv_heads, wl.n_q_heads, cap, self.k_side, wl.rope_base, self.lut_k,

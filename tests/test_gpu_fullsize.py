@@ -65,10 +65,10 @@ def test_c2_full_context_sampled_parity():
     for t0 in starts:
         T = min(WIN, L - t0)
         sampled += list(range(t0, t0 + T))
-        kc, cnt, idx, val = O.quantize_k(st.k(t0, T), bits, st.lut_k, st.s, st.z, st.lo, st.hi)
+        kc, cnt, idx, val = O.quantize_k(st.k(t0, T), bits, st.lut_k_stored, st.s, st.z, st.lo, st.hi)
         O._pack_k(ok_codes, bits, H, cap, t0, T, kc)
         kcnt[t0:t0 + T] = cnt; kidx.append(idx); kval.append(val)
-        sz, vc, cnt, idx, val = O.quantize_v(st.v(t0, T), bits, st.lut_v, st.k_side)
+        sz, vc, cnt, idx, val = O.quantize_v(st.v(t0, T), bits, st.lut_v_stored, st.k_side)
         O._pack_v(ov_codes, bits, H, cap, t0, T, vc)
         o_sz[t0:t0 + T] = sz
         vcnt[t0:t0 + T] = cnt; vidx.append(idx); vval.append(val)
@@ -117,7 +117,7 @@ def test_c2_full_context_sampled_parity():
     q = S.gen_q(wl, 0, 0)
     scale = np.float32(1.0 / np.sqrt(128.0))
     ref = np.zeros((wl.n_q_heads, L), np.float32)
-    O._qk(ok_codes, bits, H, wl.n_q_heads, cap, L, st.lut_k, O._as_bits(st.s), O._as_bits(st.z), okp,
+    O._qk(ok_codes, bits, H, wl.n_q_heads, cap, L, st.lut_k_stored, O._as_bits(st.s), O._as_bits(st.z), okp,
           oki if oki.size else np.zeros(1, np.uint16), okv if okv.size else np.zeros(1, np.uint16),
           np.ascontiguousarray(q), float(scale), float(wl.rope_base), ref, L, 0, np.zeros(1, np.uint16))
     scores = torch.zeros((wl.n_q_heads, cap), device="cuda")
@@ -130,7 +130,7 @@ def test_c2_full_context_sampled_parity():
     p = np.zeros((wl.n_q_heads, L), np.float32)
     p[:, sampled] = O.softmax(np.ascontiguousarray(ref[:, sampled]))
     ref_out = np.zeros((wl.n_q_heads, 128), np.float32)
-    O._pv(ov_codes, bits, H, wl.n_q_heads, cap, L, st.lut_v, o_sz, ovp, ovi, ovv, p, L, ref_out, 0, np.zeros(1, np.uint16))
+    O._pv(ov_codes, bits, H, wl.n_q_heads, cap, L, st.lut_v_stored, o_sz, ovp, ovi, ovv, p, L, ref_out, 0, np.zeros(1, np.uint16))
     pfull = torch.zeros((wl.n_q_heads, cap), device="cuda")
     pfull[:, :L] = torch.from_numpy(p).cuda()
     out = torch.zeros((wl.n_q_heads, 128), device="cuda")
@@ -197,8 +197,8 @@ def _sampled_full_size_parity(wl, Lc, fixed_starts, n_random, layer=0):
     for t0 in starts:
         T = min(WIN, Lc - t0)
         # a small oracle cache that holds just this window, at capacity 128, for quantization ...
-        kc, kcnt, kidx, kval = O.quantize_k(st.k(t0, T), bits, st.lut_k, st.s, st.z, st.lo, st.hi)
-        sz, vc, vcnt, vidx, vval = O.quantize_v(st.v(t0, T), bits, st.lut_v, st.k_side)
+        kc, kcnt, kidx, kval = O.quantize_k(st.k(t0, T), bits, st.lut_k_stored, st.s, st.z, st.lo, st.hi)
+        sz, vc, vcnt, vidx, vval = O.quantize_v(st.v(t0, T), bits, st.lut_v_stored, st.k_side)
         # ... compared bit for bit with what the device stored at the true positions
         a = np.zeros((T, D), np.uint8)
         O._unpack_k(gk, bits, H, cap, t0, T, a)
@@ -213,7 +213,7 @@ def _sampled_full_size_parity(wl, Lc, fixed_starts, n_random, layer=0):
         assert np.array_equal(gc.v_idx[int(gvp[t0]):int(gvp[t0 + T])].cpu().numpy().view(np.uint16), vidx)
         assert np.array_equal(gc.v_val[int(gvp[t0]):int(gvp[t0 + T])].cpu().numpy().view(np.uint16), vval)
         # reference scores of the window: the oracle's reconstruction and rotation at the true positions
-        win = O.OracleCache(bits, H, Hq, 128, st.k_side, wl.rope_base, st.lut_k, st.lut_v, st.s, st.z, st.lo, st.hi)
+        win = O.OracleCache(bits, H, Hq, 128, st.k_side, wl.rope_base, st.lut_k_stored, st.lut_v_stored, st.s, st.z, st.lo, st.hi)
         win.append_k(st.k(t0, T)); win.append_v(st.v(t0, T))
         khat, vhat = win.reconstruct_k(0, T), win.reconstruct_v(0, T)
         g = Hq // H
@@ -275,7 +275,7 @@ def test_c2_full_context_constant_value_rows_closed_form():
     torch.cuda.synchronize()
     assert gc.status() == 0 and gc.n_tokens_v == Lc
 
-    lut_v = np.asarray(st.lut_v, dtype=np.float32)
+    lut_v = np.asarray(st.lut_v_stored, dtype=np.float32)
     l0 = float(lut_v[int(np.argmin(np.abs(lut_v)))])                # first minimum: ties to the smaller index
     n_out = 2 * st.k_side
     c_host = c_all.float().cpu().numpy().astype(np.float64)
@@ -342,7 +342,7 @@ def test_c2_full_context_constant_keys_closed_form():
     torch.cuda.synchronize()
     assert gc.status() == 0 and int(gc.k_ptr[Lc].item()) == 0           # not a single outlier
 
-    lut_k = np.asarray(st.lut_k, dtype=np.float32)
+    lut_k = np.asarray(st.lut_k_stored, dtype=np.float32)
     l0 = np.float32(lut_k[int(np.argmin(np.abs(lut_k)))])
     s32 = np.asarray(st.s, dtype=np.float16).astype(np.float32)
     # fmaf(s, l0, z): the exact sum rounded once to fp32

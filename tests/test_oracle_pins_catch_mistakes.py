@@ -12,7 +12,7 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "kvq_oracle.c")
 
-PINS_QUANT = ["tests/test_oracle_quant.py", "tests/test_oracle_fp16_pack.py"]
+PINS_QUANT = ["tests/test_oracle_quant.py", "tests/test_oracle_fp16_pack.py", "tests/test_oracle_signposts.py"]
 PINS_MATVEC = ["tests/test_oracle_rope_matvec.py", "tests/test_oracle_sink.py"]
 
 # (name, text in the source, mistaken text, pin files that must notice)
@@ -101,6 +101,8 @@ MISTAKES = [
      PINS_MATVEC),
     ("outputs: grouped-query heads all read KV head 0",
      "int hk = h / group;", "int hk = 0; (void)group;", PINS_MATVEC),
+    ("signposts: stored as handed over instead of as fp16 numbers",
+     "lut_stored[j] = kvqo_h2f(kvqo_f2h(lut_in[j]));", "lut_stored[j] = lut_in[j];", PINS_QUANT),
     ("fp16 rounding: truncation instead of round-to-nearest-even",
      "double r = nearbyint(q);", "double r = floor(q);", PINS_QUANT),
 ]

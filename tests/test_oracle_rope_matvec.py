@@ -145,6 +145,9 @@ def test_sparse_part_equals_densified_outliers_and_rope_is_linear():
     oc = O.OracleCache(bits, 2, 4, L, ks, w.rope_base, lut_k, lut_v, s, z, lo, hi)
     ck = oc.append_k(S.gen_k(w, 0, 0, 0, L)); cv = oc.append_v(S.gen_v(w, 0, 0, 0, L))
     assert oc.k_ptr[L] > 0 and oc.v_ptr[L] == L * 2 * ks
+    # a cache stores its signposts as fp16 numbers: the restatement below rounds them with numpy
+    assert not np.array_equal(lut_k, lut_k.astype(np.float16).astype(np.float32))
+    lut_k, lut_v = (a.astype(np.float16).astype(np.float32) for a in (lut_k, lut_v))
     sf, zf = s.astype(np.float32), z.astype(np.float32)
     Kd = (sf * lut_k[ck] + zf).astype(np.float64)
     Ksp = np.zeros_like(Kd)
