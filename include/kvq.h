@@ -8,14 +8,19 @@
  * `stream` unless stated otherwise.  The library allocates and frees no device memory: the
  * caller owns every buffer, sized with the kvq_*_bytes helpers below.
  *
- * Threads: calls on different caches may be made from different host threads, except for the first
- * call of each kind in a process (a kernel's LDS limit is raised once, through an unsynchronised
- * flag) and the timing aid at the end of this file; calls on one cache, or on caches that share a
- * workspace, must not overlap, on the host or on the GPU (they share the workspace and the descriptor's
- * token counts).  One GPU: the device that is current when a cache's buffers are allocated.
+ * Threads: calls on different caches may be made from different host threads, except for the timing
+ * aid at the end of this file; calls on one cache, or on caches that share a workspace, must not
+ * overlap, on the host or on the GPU (they share the workspace and the descriptor's token counts).
+ * One GPU: the device that is current when a cache's buffers are allocated.
  *
  * Supported shapes: head_dim = 128; bits in {2,3,4}; n_q_heads a multiple of n_kv_heads;
- * D = n_kv_heads*128 <= 65536; cap_tokens a multiple of 128.
+ * D = n_kv_heads*128 <= 65536; cap_tokens a multiple of 128, below 2^24.  Narrower limits of single
+ * calls (they return KVQ_ERR_UNSUPPORTED beyond them): kvq_qk_matvec and kvq_attention_decode take
+ * n_q_heads / n_kv_heads in {1, 2, 4, 8}; kvq_quantize_append_v and kvq_quantize_append_kv take
+ * D <= 16384 (a token's vector is selected from in LDS); kvq_pv_matvec takes any ratio.
+ * Inputs are finite fp16 / fp32 numbers: NaN and infinities are undefined behaviour of the method
+ * (no error is raised; a cache whose Key thresholds are all -65504 / +65504 skips the sparse Key
+ * kernel although an infinite Key would have been recorded as an outlier).
  *
  * Storage format (owned by this library, bit-exact and documented so that a reference
  * implementation can check it):
@@ -186,6 +191,10 @@ kvq_status kvq_qk_matvec(const kvq_cache *cache, const float *d_q_rot, float sca
  *   vhat[n][c] = s_n*lut_v[code] + z_n + (sparse residual at (n,c)).
  *   d_probs : DEVICE fp32 [n_q_heads][ld_probs];  d_out : DEVICE fp32 [n_q_heads][128].
  * fp32 accumulation in a fixed order (results are run-to-run identical).  Uses cache->workspace.
+ * Range: the sparse part is summed per workgroup in 64-bit fixed point with 40 fractional bits, so
+ * |sum over a workgroup's tokens of probs[q][n] * residual(n, c)| must stay below 2^23 for every
+ * (q, c); with softmax weights (sum <= 1) and fp16 residuals (|r| <= 65504) it always does, with
+ * arbitrary caller-made weights it is the caller's to ensure (no error is raised; the sum wraps).
  */
 kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs, int64_t ld_probs,
                          float *d_out, void *stream);

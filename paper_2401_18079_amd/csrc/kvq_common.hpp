@@ -287,6 +287,19 @@ __device__ __forceinline__ void kvq_span_end(unsigned long long *slots)
 }
 KvqProfile &kvq_profile_state();
 
+// Compute units of the current device (MI355X: 256), asked once per process; launch plans size their
+// grids from it.  A failed query falls back to 256.
+inline int kvq_cu_count()
+{
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return 256;
+        return cus;
+    }();
+    return n;
+}
+
 #define KVQ_HIP_CHECK(expr)                         \
     do {                                            \
         hipError_t _e = (expr);                     \

@@ -46,8 +46,8 @@ inline PvPlan pv_plan(int64_t L, int n_q_heads)
 {
     PvPlan p;
     const int64_t tiles = (L + 127) / 128;
-    // aim at ~16 wavefronts per compute unit: 256 CUs * 16 / (2 * Hq) slabs
-    int64_t want = (256 * 16) / (2 * (int64_t)n_q_heads);
+    // aim at ~16 wavefronts per compute unit: CUs * 16 / (2 * Hq) slabs
+    int64_t want = ((int64_t)kvq_cu_count() * 16) / (2 * (int64_t)n_q_heads);
     if (want < 1) want = 1;
     if (want > 512) want = 512;
     if (want > tiles) want = tiles;
@@ -66,7 +66,7 @@ inline PvPlan pv_plan(int64_t L, int n_q_heads)
     int wgs_per_cu = (int)(163840 / p.slds);
     if (wgs_per_cu * waves > 24) wgs_per_cu = 24 / waves;      // six wavefronts per SIMD (register budget)
     if (wgs_per_cu < 1) wgs_per_cu = 1;
-    int64_t max_wgs = (int64_t)256 * wgs_per_cu;
+    int64_t max_wgs = (int64_t)kvq_cu_count() * wgs_per_cu;
     if (max_wgs > PVS_MAX_SLABS) max_wgs = PVS_MAX_SLABS;
     const int64_t resident = max_wgs * waves;
     int64_t tpw = (L + resident - 1) / resident;
@@ -566,14 +566,19 @@ kvq_status kvq_pv_run(const kvq_cache *cache, const float *d_probs, int64_t ld_p
                                                       KVQ_PVS_ROW(8)};
 #undef KVQ_PVS_ROW
         const SparseKernel sparse = kernels[ri][sink][fused];
-        // one dynamic-LDS limit per instantiation, raised on demand
-        static size_t lds_attr[5][2][2] = {};
-        size_t &attr = lds_attr[ri][sink][fused];
-        if (plan.slds > attr) {
-            KVQ_HIP_CHECK(hipFuncSetAttribute((const void *)sparse, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                              (int)plan.slds));
-            attr = plan.slds;
-        }
+        // every instantiation's dynamic-LDS limit is raised once, to the most a plan asks for
+        // (initialisation of a function-local static is thread-safe)
+        static const hipError_t lds_attr = [] {
+            for (auto &a : kernels)
+                for (auto &b : a)
+                    for (SparseKernel k : b) {
+                        const hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, 147456);
+                        if (e != hipSuccess) return e;
+                    }
+            return hipSuccess;
+        }();
+        KVQ_HIP_CHECK(lds_attr);
+        if (plan.slds > 147456) return KVQ_ERR_UNSUPPORTED;
         // (Running this kernel on a second stream beside the dense one was tried: its LDS footprint
         // evicts dense workgroups from the CUs and the pair gets slower.)
         if (cache->cap_nnz_v >= ((int64_t)1 << 31)) return KVQ_ERR_UNSUPPORTED;      // byte offsets are 32-bit

@@ -521,18 +521,17 @@ kvq_status launch_qk_sparse_tw(const kvq_cache *c, const float *q, float scale, 
     while (waves > 1 && (size_t)Hq * 512 + (size_t)waves * per_wave > 78848) waves -= (waves > 4) ? 4 : waves / 2;
     if ((size_t)Hq * 512 + (size_t)waves * per_wave > 147456) return KVQ_ERR_UNSUPPORTED;
     const size_t lds = (size_t)Hq * 512 + (size_t)waves * per_wave;
-    static size_t lds_attr = 0;      // per instantiation
-    if (lds > lds_attr) {
-        KVQ_HIP_CHECK(hipFuncSetAttribute((const void *)kvq_qk_sparse<R, TW>,
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        lds_attr = lds;
-    }
-    // as many wavefronts as the chip holds at once (256 CUs, 160 KiB of LDS and 32 wavefronts each),
+    // the kernel's dynamic-LDS limit is raised once per instantiation, to the most any launch asks for
+    // (initialisation of a function-local static is thread-safe)
+    static const hipError_t lds_attr = hipFuncSetAttribute((const void *)kvq_qk_sparse<R, TW>,
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 147456);
+    KVQ_HIP_CHECK(lds_attr);
+    // as many wavefronts as the chip holds at once (160 KiB of LDS and 32 wavefronts per compute unit),
     // every one with the same number of tokens
     int wgs_per_cu = (int)(163840 / lds);
     if (wgs_per_cu * waves > 32) wgs_per_cu = 32 / waves;
     if (wgs_per_cu < 1) wgs_per_cu = 1;
-    const int64_t resident = (int64_t)256 * wgs_per_cu * waves;
+    const int64_t resident = (int64_t)kvq_cu_count() * wgs_per_cu * waves;
     int64_t tpw = (L + resident - 1) / resident;
     if (TW > 8) tpw = (tpw + TW - 1) / TW * TW;          // whole sub-ranges: full cache lines of scores
     const int64_t n_waves = (L + tpw - 1) / tpw;
@@ -596,8 +595,9 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     const int64_t tiles = (L + NT - 1) / NT;
     // about one workgroup per compute unit in total (the tables fill most of a CU's LDS); each
     // workgroup builds its tables once and then streams its share of the tiles
-    int64_t gx = 256 / groups;
+    int64_t gx = kvq_cu_count() / groups;
     if (gx < 1) gx = 1;
+    if (gx > 256) gx = 256;          // a head owns 256 statistics slots
     if (gx > tiles) gx = tiles;
     dim3 grid((unsigned)gx, (unsigned)groups);
     // the sparse kernel goes first and writes its part of every score; the dense kernel adds its own
@@ -647,20 +647,22 @@ kvq_status dispatch_qk(const kvq_cache *c, const float *q, float scale, float *s
         // the chip busy (a workgroup builds its tables once, then takes tiles of 1024 tokens).  With a
         // shorter context that leaves most compute units idle: half as many heads per workgroup and
         // tiles of 512 tokens give four times as many workgroups (two fit a compute unit), one KV head
-        // per workgroup 2 * KVH times as many.  The largest grouping that still yields 160 workgroups
-        // is taken.
+        // per workgroup 2 * KVH times as many.  The largest grouping that still yields workgroups for
+        // five eighths of the compute units is taken.
         const int64_t L = c->n_tokens_k;
         auto workgroups = [&](int kvh, int nt) {
             const int64_t groups = c->n_kv_heads / kvh, tiles = (L + nt - 1) / nt;
-            int64_t gx = 256 / groups;
+            int64_t gx = kvq_cu_count() / groups;
             if (gx < 1) gx = 1;
+            if (gx > 256) gx = 256;
             if (gx > tiles) gx = tiles;
             return gx * groups;
         };
-        if (c->n_kv_heads % KVH == 0 && workgroups(KVH, 1024) >= 160)
+        const int64_t enough = (int64_t)kvq_cu_count() * 5 / 8;      // workgroups that keep most of the chip busy
+        if (c->n_kv_heads % KVH == 0 && workgroups(KVH, 1024) >= enough)
             return launch_qk<BITS, KVH, R, 1024, PG, R>(c, q, scale, scores, ld, st, n_stat, s);
         if constexpr (KVH >= 4) {
-            if (c->n_kv_heads % (KVH / 2) == 0 && workgroups(KVH / 2, 512) >= 160)
+            if (c->n_kv_heads % (KVH / 2) == 0 && workgroups(KVH / 2, 512) >= enough)
                 return launch_qk<BITS, KVH / 2, R, 512, PG, R>(c, q, scale, scores, ld, st, n_stat, s);
         }
         // few KV heads or a short context: one KV head per workgroup
