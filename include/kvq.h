@@ -218,6 +218,21 @@ kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs, int64_t l
 kvq_status kvq_attention_decode(const kvq_cache *cache, const float *d_q_rot, float scale,
                                 float *d_scores, int64_t ld_scores, float *d_out, void *stream);
 
+/*
+ * kvq_attention_decode for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and
+ * the same result, bit for bit, but the scratch (slab partials of the Value kernels, softmax
+ * statistics) is a static array in the library's device image instead of cache->workspace, which is
+ * ignored and may be NULL.  The array (16.2 MiB) exists once per GPU from the moment the library is
+ * loaded there until the process ends; its address is looked up on the first call on each device
+ * (no allocation then either).  Limit: n_q_heads <= 32 (KVQ_ERR_CAPACITY beyond; nothing is launched).
+ * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two
+ * threads) race and must be serialised by the caller.  Nothing needs clearing between calls: the
+ * kernels write every slot they later read.  Arguments and other errors as kvq_attention_decode.
+ */
+kvq_status kvq_attention_decode_noalloc(const kvq_cache *cache, const float *d_q_rot, float scale,
+                                        float *d_scores, int64_t ld_scores, float *d_out, void *stream);
+
 /* ---- helpers beyond the calls above ------------------------------------------------------- */
 
 /*

@@ -61,6 +61,7 @@ def load_library():
         "kvq_qk_matvec": (C.c_int, [P, V, F, V, I64, V]),
         "kvq_pv_matvec": (C.c_int, [P, V, I64, V, V]),
         "kvq_attention_decode": (C.c_int, [P, V, F, V, I64, V, V]),
+        "kvq_attention_decode_noalloc": (C.c_int, [P, V, F, V, I64, V, V]),
         "kvq_softmax_workspace_bytes": (I64, [I32, I64]),
         "kvq_softmax_f32": (C.c_int, [V, I64, V, I64, I32, I64, V, I64, V]),
         "kvq_calibrate_key_channels": (C.c_int, [V, I32, I32, F, V, V, V, V, V]),
@@ -94,7 +95,7 @@ EXPORTED_SYMBOLS = [
     "kvq_codes_bytes", "kvq_params_bytes", "kvq_workspace_bytes", "kvq_status_string", "kvq_version",
     "kvq_lut_load", "kvq_stored_signpost", "kvq_quantize_append_k", "kvq_quantize_append_v", "kvq_quantize_append_kv",
     "kvq_qk_matvec", "kvq_pv_matvec",
-    "kvq_attention_decode", "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
+    "kvq_attention_decode", "kvq_attention_decode_noalloc", "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
     "kvq_fp16_pv_matvec", "kvq_event_create", "kvq_event_record", "kvq_event_elapsed_ms", "kvq_event_destroy",
     "kvq_profile_enable", "kvq_profile_last_ms", "kvq_profile_count", "kvq_profile_read_ms",
     "kvq_profile_span_buffer_bytes", "kvq_profile_set_span_buffer", "kvq_profile_span_us", "kvq_calibrate_workspace_bytes", "kvq_calibrate_nuq",
@@ -341,6 +342,19 @@ def kvq_attention_decode(cache: KvqCache, q_rot: torch.Tensor, scale: float, sco
     _check(load_library().kvq_attention_decode(C.byref(cache.c), q_rot.data_ptr(), float(scale), scores.data_ptr(),
                                                scores.stride(0), out.data_ptr(), _stream_ptr(stream)),
            "kvq_attention_decode")
+
+
+def kvq_attention_decode_noalloc(cache: KvqCache, q_rot: torch.Tensor, scale: float, scores: torch.Tensor,
+                                 out: torch.Tensor, stream=None):
+    """kvq_attention_decode on the library's static scratch: cache.workspace is not used."""
+    assert q_rot.is_cuda and q_rot.dtype == torch.float32 and q_rot.is_contiguous()
+    assert q_rot.shape == (cache.c.n_q_heads, 128)
+    assert scores.is_cuda and scores.dtype == torch.float32 and scores.dim() == 2 and scores.stride(1) == 1
+    assert scores.shape[0] == cache.c.n_q_heads
+    assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.shape == (cache.c.n_q_heads, 128)
+    _check(load_library().kvq_attention_decode_noalloc(C.byref(cache.c), q_rot.data_ptr(), float(scale),
+                                                       scores.data_ptr(), scores.stride(0), out.data_ptr(),
+                                                       _stream_ptr(stream)), "kvq_attention_decode_noalloc")
 
 
 def kvq_softmax_f32(x: torch.Tensor, probs: torch.Tensor, n_cols: int, workspace: torch.Tensor, stream=None):

@@ -3,7 +3,38 @@
 // as passes of its own: the Key kernels leave per-workgroup score maxima next to the scores, the
 // Value kernels weight token n by exp(x_n - max) as they load its score and sum the weights on the
 // way, and the final reduction divides by that sum.
+#include <mutex>
 #include "kvq_common.hpp"
+
+// Scratch of kvq_attention_decode_noalloc: the slab partials of the Value kernels and the softmax
+// statistics of the Key kernels, for up to KVQ_NOALLOC_MAX_Q_HEADS query heads.  One copy per GPU,
+// held until the process ends.  In host code this name is only a handle for hipGetSymbolAddress: the
+// address kernels may use is the one that call returns, per device.
+static constexpr int KVQ_NOALLOC_MAX_DEVICES = 64;
+static constexpr int64_t KVQ_NOALLOC_PV_BYTES =
+    ((int64_t)512 * KVQ_NOALLOC_MAX_Q_HEADS * 128 * 2 + (int64_t)512 * KVQ_NOALLOC_MAX_Q_HEADS * 2) * 4;
+static constexpr int64_t KVQ_NOALLOC_BYTES =
+    KVQ_NOALLOC_PV_BYTES + (int64_t)KVQ_NOALLOC_MAX_Q_HEADS * KVQ_STAT_SLOTS * (int64_t)sizeof(float);
+static __device__ __align__(256) unsigned char kvq_noalloc_scratch[KVQ_NOALLOC_BYTES];
+
+// Device address of the scratch array on the current device (looked up once per device).
+static kvq_status kvq_noalloc_scratch_ptr(void **out)
+{
+    static std::mutex mu;
+    static void *ptrs[KVQ_NOALLOC_MAX_DEVICES] = {};
+    int dev = 0;
+    KVQ_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= KVQ_NOALLOC_MAX_DEVICES) return KVQ_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        KVQ_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(kvq_noalloc_scratch)));
+        if (!p) return KVQ_ERR_HIP;
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return KVQ_OK;
+}
 
 extern "C" kvq_status kvq_attention_decode(const kvq_cache *cache, const float *d_q_rot, float scale, float *d_scores,
                                            int64_t ld_scores, float *d_out, void *stream)
@@ -21,4 +52,23 @@ extern "C" kvq_status kvq_attention_decode(const kvq_cache *cache, const float *
     if (st != KVQ_OK) return st;
     // an empty cache has no statistics: the Value half then sums nothing and writes zeros
     return kvq_pv_run(cache, d_scores, ld_scores, d_out, n_stat > 0 ? slots : nullptr, n_stat, s);
+}
+
+extern "C" kvq_status kvq_attention_decode_noalloc(const kvq_cache *cache, const float *d_q_rot, float scale,
+                                                   float *d_scores, int64_t ld_scores, float *d_out, void *stream)
+{
+    kvq_status st = kvq_check_cache(cache);
+    if (st != KVQ_OK) return st;
+    if (cache->n_q_heads > KVQ_NOALLOC_MAX_Q_HEADS) return KVQ_ERR_CAPACITY;
+    static_assert(KVQ_NOALLOC_MAX_Q_HEADS == 32, "the header states the limit");
+    if (kvq_pv_workspace_bytes(cache->n_q_heads) > KVQ_NOALLOC_PV_BYTES) return KVQ_ERR_CAPACITY;
+    void *scratch = nullptr;
+    st = kvq_noalloc_scratch_ptr(&scratch);
+    if (st != KVQ_OK) return st;
+    // the same kernels as kvq_attention_decode, on a copy of the descriptor whose workspace is the
+    // static array (every slot that is read is written first by the kernels: nothing to clear)
+    kvq_cache view = *cache;
+    view.workspace = scratch;
+    view.workspace_bytes = KVQ_NOALLOC_BYTES;
+    return kvq_attention_decode(&view, d_q_rot, scale, d_scores, ld_scores, d_out, stream);
 }

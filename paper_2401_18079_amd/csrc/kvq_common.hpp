@@ -7,6 +7,7 @@
 
 #define KVQ_HEAD_DIM 128
 #define KVQ_MAX_APPEND 4096
+#define KVQ_NOALLOC_MAX_Q_HEADS 32
 
 typedef _Float16 half_t;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
