@@ -23,8 +23,12 @@ struct KvqParamsHeader {
     int32_t D;
     int32_t bits;
     int32_t pad[30];
+    float rope_cd[64];    // cos(KVQ_ROPE_STEP * theta_i): the rotation that advances a token's (cos, sin)
+    float rope_sd[64];    // sin(KVQ_ROPE_STEP * theta_i)   of pair i by KVQ_ROPE_STEP positions
 };
-static_assert(sizeof(KvqParamsHeader) == 768, "header layout");
+constexpr int KVQ_ROPE_STEP = 1024;
+constexpr int KVQ_PARAMS_HEADER_BYTES = 1280;
+static_assert(sizeof(KvqParamsHeader) == KVQ_PARAMS_HEADER_BYTES, "header layout");
 
 struct KvqParamsView {          // device pointers into the block
     const KvqParamsHeader *hdr;
@@ -32,14 +36,14 @@ struct KvqParamsView {          // device pointers into the block
     const float *s, *z, *rinv, *lo, *hi;       // fp32 expansions [D]; rinv = 1.0f / s (IEEE)
 };
 
-__host__ __device__ inline int64_t kvq_params_bytes_D(int D) { return 768 + (int64_t)D * (4 * 2 + 5 * 4); }
+__host__ __device__ inline int64_t kvq_params_bytes_D(int D) { return KVQ_PARAMS_HEADER_BYTES + (int64_t)D * (4 * 2 + 5 * 4); }
 
 __host__ __device__ inline KvqParamsView kvq_params_view(const void *block, int D)
 {
     KvqParamsView v;
     const char *p = (const char *)block;
     v.hdr = (const KvqParamsHeader *)p;
-    p += 768;
+    p += KVQ_PARAMS_HEADER_BYTES;
     v.s16 = (const uint16_t *)p; p += 2 * (int64_t)D;
     v.z16 = (const uint16_t *)p; p += 2 * (int64_t)D;
     v.lo16 = (const uint16_t *)p; p += 2 * (int64_t)D;
@@ -193,6 +197,25 @@ __device__ __forceinline__ int kvq_sparse_token(uint32_t pw, int tc, int &tcur, 
         j = __builtin_amdgcn_readfirstlane(j + 1);       // keeps the loop counter in a scalar register
     }
     return t;
+}
+
+// Issue priority of the calling wavefront, 0 (lowest) to 3.  The SIMD's arbiter serves the highest
+// priority first and, among equals, the OLDEST wavefront: the four wavefronts that share a SIMD for a
+// whole kernel then finish one after the other (measured on the dense Value kernel: workgroups
+// dispatched first end at 34 us, those dispatched last at 48 us, and the tail runs with the SIMDs a
+// quarter full).  A wavefront that calls this with (its slot on the SIMD + a step counter) & 3 at every
+// step spends a quarter of its steps at each priority, so the four advance at the same average rate.
+// The instruction takes an immediate operand, hence the switch.
+__device__ __forceinline__ void kvq_set_wave_priority(int p)
+{
+    // `p` must be wavefront-uniform; the read below also tells the compiler so (a divergent switch
+    // would run every case, one after the other, under execution masks)
+    switch (__builtin_amdgcn_readfirstlane(p) & 3) {
+    case 0: __builtin_amdgcn_s_setprio(0); break;
+    case 1: __builtin_amdgcn_s_setprio(1); break;
+    case 2: __builtin_amdgcn_s_setprio(2); break;
+    default: __builtin_amdgcn_s_setprio(3); break;
+    }
 }
 
 // ---- softmax hand-over from the Key kernels to the Value kernels (fused decode call) ------------

@@ -216,6 +216,10 @@ extern "C" kvq_status kvq_lut_load(kvq_cache *cache, const float *h_lut_k, const
         float hi = (float)rev;
         hdr.rope_vh[i] = hi;
         hdr.rope_vl[i] = (float)(rev - (double)hi);
+        // rotation by KVQ_ROPE_STEP positions: the angle is reduced in double before cos / sin
+        const double step = fmod((double)KVQ_ROPE_STEP * rev, 1.0) * (2.0 * M_PI);
+        hdr.rope_cd[i] = (float)cos(step);
+        hdr.rope_sd[i] = (float)sin(step);
     }
     hdr.D = D;
     hdr.bits = cache->bits;
@@ -223,10 +227,10 @@ extern "C" kvq_status kvq_lut_load(kvq_cache *cache, const float *h_lut_k, const
     KVQ_HIP_CHECK(hipStreamSynchronize(s));
     char *blk = (char *)cache->params;
     KVQ_HIP_CHECK(hipMemcpy(blk, &hdr, sizeof(hdr), hipMemcpyHostToDevice));
-    KVQ_HIP_CHECK(hipMemcpy(blk + 768, h_s_k, 2 * (size_t)D, hipMemcpyHostToDevice));
-    KVQ_HIP_CHECK(hipMemcpy(blk + 768 + 2 * (size_t)D, h_z_k, 2 * (size_t)D, hipMemcpyHostToDevice));
-    KVQ_HIP_CHECK(hipMemcpy(blk + 768 + 4 * (size_t)D, h_lo_k, 2 * (size_t)D, hipMemcpyHostToDevice));
-    KVQ_HIP_CHECK(hipMemcpy(blk + 768 + 6 * (size_t)D, h_hi_k, 2 * (size_t)D, hipMemcpyHostToDevice));
+    KVQ_HIP_CHECK(hipMemcpy(blk + KVQ_PARAMS_HEADER_BYTES, h_s_k, 2 * (size_t)D, hipMemcpyHostToDevice));
+    KVQ_HIP_CHECK(hipMemcpy(blk + KVQ_PARAMS_HEADER_BYTES + 2 * (size_t)D, h_z_k, 2 * (size_t)D, hipMemcpyHostToDevice));
+    KVQ_HIP_CHECK(hipMemcpy(blk + KVQ_PARAMS_HEADER_BYTES + 4 * (size_t)D, h_lo_k, 2 * (size_t)D, hipMemcpyHostToDevice));
+    KVQ_HIP_CHECK(hipMemcpy(blk + KVQ_PARAMS_HEADER_BYTES + 6 * (size_t)D, h_hi_k, 2 * (size_t)D, hipMemcpyHostToDevice));
     kvq_params_expand<<<(D + 255) / 256, 256, 0, s>>>(cache->params, D);
     KVQ_HIP_CHECK(hipGetLastError());
     // bit 0: loaded; bit 1: the thresholds admit no Key outlier at all (every finite fp16 passes), so

@@ -15,6 +15,10 @@
 #include <utility>
 #include "kvq_common.hpp"
 
+#ifndef KVQ_ROTATE_PRIORITY
+#define KVQ_ROTATE_PRIORITY 1
+#endif
+
 namespace {
 
 constexpr int PV_NT = 256;                 // 4 wavefronts = 4 (query head, half) combinations
@@ -161,7 +165,7 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
                                                       float *__restrict__ partial, float *__restrict__ zpart,
                                                       int n_tiles, int n_sink,
                                                       const float *__restrict__ stat_slots, int n_stat,
-                                                      float *__restrict__ lpart, unsigned long long *span)
+                                                      float *__restrict__ lpart, unsigned long long *span, int n_cu)
 {
     if (SPAN) kvq_span_start(span);       // timing-aid instantiation (kvq_profile_*): workgroup start and end times
     // tokens below n_sink are attention-sink tokens kept in fp16: their quantized form gets weight 0
@@ -206,8 +210,11 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
 
     const int64_t tile0 = ((int64_t)blockIdx.x * n_tiles) / gridDim.x;
     const int64_t tile1 = ((int64_t)(blockIdx.x + 1) * n_tiles) / gridDim.x;
+    // the workgroups that share a compute unit were dispatched n_cu apart; see kvq_set_wave_priority
+    const int prio_slot = (int)((blockIdx.y * gridDim.x + blockIdx.x) / (unsigned)n_cu);
     if (active) {
         for (int64_t t = tile0; t < tile1; ++t) {
+            if (KVQ_ROTATE_PRIORITY) kvq_set_wave_priority(prio_slot + (int)(t - tile0));
             const int64_t m = t * 64 + lane;                // token pair
             const int64_t n0 = 2 * m;
             if (n0 >= L) continue;
@@ -251,6 +258,7 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
             pv_all_fields<BITS, RG>(std::make_integer_sequence<int, NF / PV_FIELD_GROUP>{}, W, acc, ptab, lane_off, w0, w1);
         }
     }
+    if (KVQ_ROTATE_PRIORITY) __builtin_amdgcn_s_setprio(0);
     // sum the 64 lanes: four rounds of 16 accumulators through LDS
     float outv = 0.f;      // lane l (< 64) ends up with the sum of accumulator l
 #pragma unroll
@@ -593,7 +601,7 @@ kvq_status kvq_pv_run(const kvq_cache *cache, const float *d_probs, int64_t ld_p
         auto kern = span ? kvq_pv_dense<B, G, true> : kvq_pv_dense<B, G, false>;                               \
         kern<<<grid, PV_NT, 0, s>>>(cache->params, D, cache->n_kv_heads, Hq, cache->cap_tokens, L,             \
                                     cache->v_codes, cache->v_sz, d_probs, ld_probs, partial, zpart,            \
-                                    plan.tiles, cache->n_sink, stat_slots, n_stat, lpart, span);               \
+                                    plan.tiles, cache->n_sink, stat_slots, n_stat, lpart, span, kvq_cu_count()); \
     } while (0)
         KvqProfile &prof = kvq_profile_state();
         unsigned long long *span = kvq_profile_span_slot(prof, 1, (int64_t)grid.x * grid.y);

@@ -26,6 +26,21 @@
 #include <utility>
 #include "kvq_common.hpp"
 
+// Tuning knobs of the piece-major 3-bit kernel (kvq_qk3_kernel): tiles per block, fields per gather group.
+#ifndef KVQ_QK3_ENABLE
+#define KVQ_QK3_ENABLE 1
+#endif
+#ifndef KVQ_QK3_TT
+#define KVQ_QK3_TT 4
+#endif
+#ifndef KVQ_QK3_PG
+#define KVQ_QK3_PG 4
+#endif
+#ifndef KVQ_ROTATE_PRIORITY
+#define KVQ_ROTATE_PRIORITY 1
+#endif
+
+
 namespace {
 
 template <int BITS>
@@ -196,6 +211,55 @@ __device__ __forceinline__ void qk_all_pairs(std::integer_sequence<int, G...>,
     (qk_group<BITS, KVH, RQ, PG, G>(W, acc, tab, nf, wave_base, hdr, cur_chunk, next_chunk, plane, valid, next_valid), ...);
 }
 
+// Stage the scaled query and the per-channel (scale, zero-point) of the workgroup's heads in LDS and
+// build the (A,B) tables from them.  A table (one query head, one channel pair) has ENT entries; ENT
+// lanes of a wavefront fill it, one entry each, so a lane's signposts are loop constants and LDS
+// writes are conflict-free.  Ends with a workgroup barrier.
+template <int BITS, int KVH, int RQ, int NT>
+__device__ __forceinline__ void qk_build_tables(float2_t *tab, float *qs, float2_t *szs, const KvqParamsView &pv,
+                                                const float *__restrict__ q_rot, float scale, int q0, int kv0)
+{
+    using C = QkCfg<BITS>;
+    constexpr int QH = KVH * RQ, R = RQ;
+    constexpr int NE = C::NE;
+    constexpr int ENT = C::ENTRIES;
+    const int tid = threadIdx.x;
+    for (int j = tid; j < QH * 128; j += NT) qs[j] = q_rot[(int64_t)q0 * 128 + j] * scale;
+    for (int j = tid; j < KVH * 128; j += NT) szs[j] = float2_t{pv.s[kv0 * 128 + j], pv.z[kv0 * 128 + j]};
+    __syncthreads();
+    constexpr int TW = 64 / ENT;                     // tables per wavefront step
+    constexpr int NWAVES = NT / 64;
+    constexpr int STEP = NWAVES * TW;                // tables per workgroup step
+    static_assert(64 % STEP == 0 || STEP % 64 == 0, "table build assumes the step divides the pair count");
+    const int lane = tid & 63, wave = tid >> 6;
+    const int f = lane % ENT, sub = lane / ENT;
+    float lut_a = 0.f, lut_b = 0.f;                  // joint: signposts of the two codes; split: lut_a only
+#pragma unroll
+    for (int j = 0; j < NE; ++j) {
+        const float v = pv.hdr->lut_k[j];
+        if ((f & (NE - 1)) == j) lut_a = v;
+        if (C::JOINT && (f >> BITS) == j) lut_b = v;
+    }
+    const bool upper = !C::JOINT && f >= NE;         // split tables: second half belongs to channel i+64
+    for (int tb = wave * TW + sub; tb < QH * 64; tb += STEP) {
+        const int qh = tb >> 6, i = tb & 63;
+        const float2_t lo = szs[(qh / R) * 128 + i], hi = szs[(qh / R) * 128 + i + 64];
+        const float qa = qs[qh * 128 + i], qb = qs[qh * 128 + i + 64];
+        float a, b;
+        if (C::JOINT) {
+            const float klo = __builtin_fmaf(lo.x, lut_a, lo.y), khi = __builtin_fmaf(hi.x, lut_b, hi.y);
+            a = qa * klo + qb * khi;
+            b = qb * klo - qa * khi;
+        } else {
+            const float k = upper ? __builtin_fmaf(hi.x, lut_a, hi.y) : __builtin_fmaf(lo.x, lut_a, lo.y);
+            a = upper ? qb * k : qa * k;
+            b = upper ? -qa * k : qb * k;
+        }
+        tab[tb * ENT + f] = float2_t{a, b};
+    }
+    __syncthreads();
+}
+
 // KVH KV heads per workgroup, RQ query heads per KV head handled here (RQ divides the model's GQA
 // ratio `r`; when RQ < r several workgroups share a KV head), PG channel pairs per gather group.
 template <int BITS, int KVH, int RQ, int NT, int PG, bool STATS, bool SPAN = false>
@@ -229,47 +293,7 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
     const int q0 = blockIdx.y * QH;
     const int kv0 = q0 / r;
 
-    // ---- stage query, rope constants, per-channel (scale, zero-point) -------------------------
-    for (int j = tid; j < QH * 128; j += NT) qs[j] = q_rot[(int64_t)q0 * 128 + j] * scale;
-    for (int j = tid; j < KVH * 128; j += NT) szs[j] = float2_t{pv.s[kv0 * 128 + j], pv.z[kv0 * 128 + j]};
-    __syncthreads();
-
-    // ---- build the (A,B) tables -----------------------------------------------------------
-    // A table (one query head, one channel pair) has ENT entries; ENT lanes of a wavefront fill it,
-    // one entry each, so a lane's signposts are loop constants and LDS writes are conflict-free.
-    {
-        constexpr int TW = 64 / ENT;                     // tables per wavefront step
-        constexpr int NWAVES = NT / 64;
-        constexpr int STEP = NWAVES * TW;                // tables per workgroup step
-        static_assert(64 % STEP == 0 || STEP % 64 == 0, "table build assumes the step divides the pair count");
-        const int lane = tid & 63, wave = tid >> 6;
-        const int f = lane % ENT, sub = lane / ENT;
-        float lut_a = 0.f, lut_b = 0.f;                  // joint: signposts of the two codes; split: lut_a only
-#pragma unroll
-        for (int j = 0; j < NE; ++j) {
-            const float v = pv.hdr->lut_k[j];
-            if ((f & (NE - 1)) == j) lut_a = v;
-            if (C::JOINT && (f >> BITS) == j) lut_b = v;
-        }
-        const bool upper = !C::JOINT && f >= NE;         // split tables: second half belongs to channel i+64
-        for (int tb = wave * TW + sub; tb < QH * 64; tb += STEP) {
-            const int qh = tb >> 6, i = tb & 63;
-            const float2_t lo = szs[(qh / R) * 128 + i], hi = szs[(qh / R) * 128 + i + 64];
-            const float qa = qs[qh * 128 + i], qb = qs[qh * 128 + i + 64];
-            float a, b;
-            if (C::JOINT) {
-                const float klo = __builtin_fmaf(lo.x, lut_a, lo.y), khi = __builtin_fmaf(hi.x, lut_b, hi.y);
-                a = qa * klo + qb * khi;
-                b = qb * klo - qa * khi;
-            } else {
-                const float k = upper ? __builtin_fmaf(hi.x, lut_a, hi.y) : __builtin_fmaf(lo.x, lut_a, lo.y);
-                a = upper ? qb * k : qa * k;
-                b = upper ? -qa * k : qb * k;
-            }
-            tab[tb * ENT + f] = float2_t{a, b};
-        }
-        __syncthreads();
-    }
+    qk_build_tables<BITS, KVH, RQ, NT>(tab, qs, szs, pv, q_rot, scale, q0, kv0);
 
     // ---- token tiles (software-pipelined over the workgroup's tiles) -------------------------
     const int64_t plane = cap * 16 * BITS;                 // bytes between consecutive KV heads
@@ -297,6 +321,8 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
         for (int qh = 0; qh < QH; ++qh) stat_m[qh] = KVQ_STAT_FLOOR;
     }
     for (int tile = 0; tile < tiles_per_wg; ++tile) {
+        // wavefronts w, w + 4, ... of the workgroup share a SIMD: each takes every priority in turn
+        if (KVQ_ROTATE_PRIORITY) kvq_set_wave_priority(__builtin_amdgcn_readfirstlane(tid >> 8) + tile);
         const int64_t nn = n + NT;
         const bool next_valid = (tile + 1 < tiles_per_wg) && (nn < L);
         const uint8_t *next_chunk = k_codes + kvq_k_piece0(BITS, cap, next_valid ? nn : n, kv0);
@@ -373,6 +399,320 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
     if (SPAN) kvq_span_end(span);
 }
 
+// ---- piece-major dense kernel for 3-bit codes ------------------------------------------------------
+// The kernel above computes cos / sin of every (token, channel pair) with the hardware's quarter-rate
+// instructions: 11 of the ~30 issue slots a lane spends on a pair for four query heads.  Here a lane
+// owns TT tokens, one in each of TT consecutive tiles (KVQ_ROPE_STEP positions apart), and only the
+// first one's (cos, sin) come from v_cos / v_sin: each further one is the previous one rotated by the
+// wavefront-uniform angle KVQ_ROPE_STEP * theta_i (two multiplies and two multiply-adds with constants
+// from scalar registers).  To keep the pairs' (cos, sin) in registers from tile to tile the loops are
+// piece-major: for each 16-byte piece of the chunk (21 or 22 fields), for each of the TT tiles, the
+// piece of that tile's token is consumed; the partial sums of the TT x QH scores stay in registers
+// until all pieces are done.  HBM is still read once, in the same 1 KiB segments.
+// A 6-bit field is consumed in the pass of the piece that holds its last bit; fields 21 and 42 start in
+// the piece before (2 and 4 bits), which are carried over packed in three registers.
+constexpr int PM_FB = 6;                                                  // field width, bits
+__host__ __device__ constexpr int pm_pass_of(int i) { return (PM_FB * i + PM_FB - 1) / 128; }
+__host__ __device__ constexpr int pm_first(int j)                         // first field of pass j (64 for j = 3)
+{
+    int i = 0;
+    while (i < 64 && pm_pass_of(i) < j) ++i;
+    return i;
+}
+constexpr int PM_MAXF = 22;                                               // most fields in a pass
+static_assert(pm_first(1) == 21 && pm_first(2) == 42 && pm_first(3) == 64, "3-bit chunk: 21 + 21 + 22 fields");
+
+// Field at bit position `bit` (>= 0) of the piece P, moved to bit 3 (unmasked).
+__device__ __forceinline__ uint32_t pm_field_shifted(const uint32_t (&P)[4], int bit)
+{
+    const int wi = bit >> 5, sh = bit & 31;
+    if (sh + PM_FB <= 32) {
+        if (sh >= 3) return P[wi] >> (sh - 3);
+        return P[wi] << (3 - sh);
+    }
+    return __builtin_amdgcn_alignbit(P[wi + 1], P[wi], sh - 3);
+}
+
+// PG consecutive fields (first one: number G0 * PG of pass J) of tile T for all heads of the workgroup.
+template <int KVH, int RQ, int TT, int PG, int J, int T, int G0>
+__device__ __forceinline__ void pm_group(const uint32_t (&P)[KVH][4], float (&acc)[TT * KVH * RQ],
+                                         float (&cs)[PM_MAXF], float (&sn)[PM_MAXF], const uint32_t (&carry)[3],
+                                         const float2_t *tab, float nf, float wave_base,
+                                         const KvqParamsHeader *hdr)
+{
+    constexpr int QH = KVH * RQ, R = RQ, ENT = 64;
+    constexpr int F0 = pm_first(J), NF = pm_first(J + 1) - F0;
+    constexpr uint32_t M = 63u << 3;
+    float2_t t[PG][QH];
+#pragma unroll
+    for (int p = 0; p < PG; ++p) {
+        const int k = G0 * PG + p;
+        if (k < NF) {
+            const int I = F0 + k, bit = PM_FB * I - 128 * J;              // bit < 0: the field starts in the piece before
+#pragma unroll
+            for (int g = 0; g < KVH; ++g) {
+                uint32_t sh;
+                if (bit >= 0) {
+                    sh = pm_field_shifted(P[g], bit);
+                } else {
+                    // low -bit bits come from the carry of (tile T, head g), the rest from this piece
+                    const int nb = -bit, idx = T * KVH + g;
+                    uint32_t c;
+                    if (J == 1) c = __builtin_amdgcn_ubfe(carry[0], 2 * idx, 2);
+                    else c = __builtin_amdgcn_ubfe(carry[1 + (idx >> 3)], 4 * (idx & 7), 4);
+                    sh = ((P[g][0] << nb) | c) << 3;
+                }
+                uint32_t off_lo = 0;
+                bool have_lo = false;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const int qh = g * R + r;
+                    const uint32_t base = (uint32_t)((qh * 64 + I) * ENT) * 8u;
+                    const uint32_t hi = base & ~0xFFFFu;
+                    const uint8_t *tb = (const uint8_t *)tab + (base - hi);
+                    if (hi == 0) {
+                        if (!have_lo) { off_lo = sh & M; have_lo = true; }
+                        t[p][qh] = *(const float2_t *)(tb + off_lo);
+                    } else {
+                        t[p][qh] = *(const float2_t *)(tb + kvq_and_or(sh, M, hi));
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < PG; ++p) {
+        const int k = G0 * PG + p;
+        if (k < NF) {
+            const int I = F0 + k;
+            if (T == 0) {
+                const float base = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wave_base), I));
+                const float rev = __builtin_fmaf(nf, hdr->rope_vh[I], base);
+                cs[k] = __builtin_amdgcn_cosf(rev);
+                sn[k] = __builtin_amdgcn_sinf(rev);
+            } else {
+                // (cos, sin) advance by KVQ_ROPE_STEP positions, in place: written as instructions so that
+                // the results stay in the registers of the operands (otherwise every tile ends with a
+                // block of register copies)
+                const float cd = hdr->rope_cd[I], sd = hdr->rope_sd[I];
+                const float t1 = sn[k] * sd, t2 = cs[k] * sd;
+                asm("v_fma_f32 %0, %0, %1, -%2" : "+v"(cs[k]) : "s"(cd), "v"(t1));
+                asm("v_fma_f32 %0, %0, %1, %2" : "+v"(sn[k]) : "s"(cd), "v"(t2));
+            }
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < PG; ++p) {
+        const int k = G0 * PG + p;
+        if (k < NF) {
+#pragma unroll
+            for (int qh = 0; qh < QH; ++qh) {
+                acc[T * QH + qh] = __builtin_fmaf(t[p][qh].x, cs[k], acc[T * QH + qh]);
+                acc[T * QH + qh] = __builtin_fmaf(t[p][qh].y, sn[k], acc[T * QH + qh]);
+            }
+        }
+    }
+    // keeps the groups in order (see qk_group)
+#pragma unroll
+    for (int qh = 0; qh < QH; ++qh) asm volatile("" : "+v"(acc[T * QH + qh]) : : "memory");
+}
+
+template <int KVH, int RQ, int TT, int PG, int J, int T, int... G>
+__device__ __forceinline__ void pm_groups(std::integer_sequence<int, G...>, const uint32_t (&P)[KVH][4],
+                                          float (&acc)[TT * KVH * RQ], float (&cs)[PM_MAXF], float (&sn)[PM_MAXF],
+                                          const uint32_t (&carry)[3], const float2_t *tab, float nf, float wave_base,
+                                          const KvqParamsHeader *hdr)
+{
+    (pm_group<KVH, RQ, TT, PG, J, T, G>(P, acc, cs, sn, carry, tab, nf, wave_base, hdr), ...);
+}
+
+// Stage S = J * TT + T of a block: piece J of tile T.  The piece sits in W[S & 1]; the next stage's
+// piece (this block's, or piece 0 of the next block's first tile) is requested into the other slot
+// before the arithmetic starts.  Addresses are a wavefront-uniform base plus 32-bit offsets (the
+// launcher checks that the codes are smaller than 4 GiB).
+template <int KVH, int RQ, int TT, int PG, int S>
+__device__ __forceinline__ void pm_stage(uint32_t (&W)[2][KVH][4], float (&acc)[TT * KVH * RQ], float (&cs)[PM_MAXF],
+                                         float (&sn)[PM_MAXF], uint32_t (&carry)[3], const float2_t *tab, float nf,
+                                         float wave_base, const KvqParamsHeader *hdr,
+                                         const uint8_t *__restrict__ k_codes, uint32_t off0, uint32_t plane,
+                                         uint32_t vm, uint32_t any, bool next_block_valid)
+{
+    // off0: byte offset of piece 0 of this lane's token in tile 0 of the block, KV head 0 of the
+    // workgroup; tile t is KVQ_ROPE_STEP tokens = 16 blocks of 64 tokens further on.  vm: this lane's
+    // valid tiles (bit t); any: tiles with a valid token in this wavefront (uniform).
+    constexpr int J = S / TT, T = S % TT, LAST = 3 * TT - 1;
+    constexpr uint32_t TILE_BYTES = (uint32_t)(KVQ_ROPE_STEP / 64) * 64 * 16 * 3;
+    // wavefronts w, w + 4, w + 8, w + 12 of the workgroup share a SIMD: each takes every priority in turn
+    if (KVQ_ROTATE_PRIORITY) kvq_set_wave_priority(__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8)) + S);
+    if (S < LAST) {
+        constexpr int JN = (S + 1) / TT, TN = (S + 1) % TT;
+        if ((vm >> TN) & 1u) {
+#pragma unroll
+            for (int g = 0; g < KVH; ++g) {
+                const uint4 v = kvq_load_stream16(k_codes + (off0 + g * plane + (TN * TILE_BYTES + JN * 1024)));
+                W[(S + 1) & 1][g][0] = v.x; W[(S + 1) & 1][g][1] = v.y; W[(S + 1) & 1][g][2] = v.z; W[(S + 1) & 1][g][3] = v.w;
+            }
+        }
+    } else if (next_block_valid) {
+#pragma unroll
+        for (int g = 0; g < KVH; ++g) {
+            const uint4 v = kvq_load_stream16(k_codes + (off0 + g * plane + TT * TILE_BYTES));
+            W[(S + 1) & 1][g][0] = v.x; W[(S + 1) & 1][g][1] = v.y; W[(S + 1) & 1][g][2] = v.z; W[(S + 1) & 1][g][3] = v.w;
+        }
+    }
+    if ((any >> T) & 1u) {
+        if (J < 2) {
+            // the top bits of this piece open the first field of the next pass
+#pragma unroll
+            for (int g = 0; g < KVH; ++g) {
+                const int idx = T * KVH + g;
+                if (J == 0) carry[0] |= (W[S & 1][g][3] >> 30) << (2 * idx);
+                else carry[1 + (idx >> 3)] |= (W[S & 1][g][3] >> 28) << (4 * (idx & 7));
+            }
+        }
+        constexpr int NF = pm_first(J + 1) - pm_first(J);
+        pm_groups<KVH, RQ, TT, PG, J, T>(std::make_integer_sequence<int, (NF + PG - 1) / PG>{}, W[S & 1], acc, cs, sn,
+                                         carry, tab, nf, wave_base, hdr);
+    }
+}
+
+// Pass J of a block: piece J of each of the block's TT tiles.  The (cos, sin) of the pass's fields live
+// here, from the first tile (computed) to the last (rotated).
+template <int KVH, int RQ, int TT, int PG, int J, int... T>
+__device__ __forceinline__ void pm_pass(std::integer_sequence<int, T...>, uint32_t (&W)[2][KVH][4],
+                                        float (&acc)[TT * KVH * RQ], uint32_t (&carry)[3], const float2_t *tab,
+                                        float nf, float wave_base, const KvqParamsHeader *hdr,
+                                        const uint8_t *__restrict__ k_codes, uint32_t off0, uint32_t plane,
+                                        uint32_t vm, uint32_t any, bool next_block_valid)
+{
+    float cs[PM_MAXF], sn[PM_MAXF];
+    (pm_stage<KVH, RQ, TT, PG, J * TT + T>(W, acc, cs, sn, carry, tab, nf, wave_base, hdr, k_codes, off0, plane, vm,
+                                           any, next_block_valid), ...);
+}
+
+// Same arguments, grid and results as kvq_qk_kernel<3, KVH, RQ, 1024, ...>; tiles are KVQ_ROPE_STEP tokens.
+template <int KVH, int RQ, int TT, int PG, bool STATS, bool SPAN = false>
+__global__ __launch_bounds__(KVQ_ROPE_STEP) void kvq_qk3_kernel(const void *__restrict__ params, int D, int r,
+                                                               int64_t cap, int64_t L,
+                                                               const uint8_t *__restrict__ k_codes,
+                                                               const float *__restrict__ q_rot, float scale,
+                                                               float *__restrict__ scores, int64_t ld, int n_tiles,
+                                                               int add_prev, float *__restrict__ stat_slots,
+                                                               int n_sink, unsigned long long *span)
+{
+    if (SPAN) kvq_span_start(span);
+    constexpr int BITS = 3, NT = KVQ_ROPE_STEP;
+    static_assert(KVH * TT <= 16, "the carried bits of a block are packed in 32 + 64 bits");
+    constexpr int QH = KVH * RQ, R = RQ, ENT = 64;
+    __shared__ __attribute__((aligned(16))) float2_t tab[QH * 64 * ENT];  // [QH][64][ENT]
+    __shared__ float qs[QH * 128];                                        // query * scale
+    __shared__ float2_t szs[(QH / R) * 128];                              // per-channel (scale, zero-point)
+
+    const KvqParamsView pv = kvq_params_view(params, D);
+    const int tid = threadIdx.x;
+    const int q0 = blockIdx.y * QH;
+    const int kv0 = q0 / r;
+    const uint32_t plane = (uint32_t)(cap * 16 * BITS);    // bytes between consecutive KV heads
+    const int tile_begin = (int)(((int64_t)blockIdx.x * n_tiles) / gridDim.x);
+    const int tile_end = (int)(((int64_t)(blockIdx.x + 1) * n_tiles) / gridDim.x);
+    const int lane_id = tid & 63;
+    const float nf = (float)lane_id;
+    // the first piece of the first tile is requested before anything else
+    uint32_t W[2][KVH][4];
+    int64_t n0 = (int64_t)tile_begin * NT + tid;           // this lane's token in the block's first tile
+    if (tile_begin < tile_end && n0 < L) {
+        const uint32_t off = (uint32_t)kvq_k_piece0(BITS, cap, n0, kv0);
+#pragma unroll
+        for (int g = 0; g < KVH; ++g) {
+            const uint4 v = kvq_load_stream16(k_codes + (off + g * plane));
+            W[0][g][0] = v.x; W[0][g][1] = v.y; W[0][g][2] = v.z; W[0][g][3] = v.w;
+        }
+    }
+    qk_build_tables<BITS, KVH, RQ, NT>(tab, qs, szs, pv, q_rot, scale, q0, kv0);
+    const float my_vh = pv.hdr->rope_vh[lane_id], my_vl = pv.hdr->rope_vl[lane_id];   // this lane's pair
+    // STATS: a wavefront keeps the maxima of the scores it wrote in LDS slots of its own (the staged
+    // query's array, dead by now; only lane 0 of the wavefront touches its slots: no atomics)
+    float *wst = qs + (tid >> 6) * QH;                     // [NT / 64][QH]
+    if (STATS && lane_id == 0) {
+#pragma unroll
+        for (int qh = 0; qh < QH; ++qh) wst[qh] = KVQ_STAT_FLOOR;
+    }
+    for (int tile0 = tile_begin; tile0 < tile_end; tile0 += TT) {
+        const int nt_blk = (tile_end - tile0 < TT) ? tile_end - tile0 : TT;
+        uint32_t vm = 0, any = 0;
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+            const bool v = t < nt_blk && n0 + (int64_t)t * NT < L;
+            vm |= v ? (1u << t) : 0u;
+            any |= (__ballot(v) != 0ull) ? (1u << t) : 0u;
+        }
+        const bool next_block_valid = tile0 + TT < tile_end && n0 + (int64_t)TT * NT < L;
+        // (a lane past the end of the context keeps an offset inside the array; it is never loaded from)
+        const uint32_t off0 = (uint32_t)kvq_k_piece0(BITS, cap, (vm & 1u) ? n0 : 0, kv0);
+        // lane i reduces the angle of channel pair i at the wavefront's first token of the block's first tile
+        const float wave_base = rope_rev((float)(n0 - lane_id), my_vh, my_vl);
+        float acc[TT * QH];
+        uint32_t carry[3] = {0u, 0u, 0u};
+#pragma unroll
+        for (int a = 0; a < TT * QH; ++a) acc[a] = 0.f;
+        pm_pass<KVH, RQ, TT, PG, 0>(std::make_integer_sequence<int, TT>{}, W, acc, carry, tab, nf, wave_base, pv.hdr,
+                                    k_codes, off0, plane, vm, any, next_block_valid);
+        pm_pass<KVH, RQ, TT, PG, 1>(std::make_integer_sequence<int, TT>{}, W, acc, carry, tab, nf, wave_base, pv.hdr,
+                                    k_codes, off0, plane, vm, any, next_block_valid);
+        pm_pass<KVH, RQ, TT, PG, 2>(std::make_integer_sequence<int, TT>{}, W, acc, carry, tab, nf, wave_base, pv.hdr,
+                                    k_codes, off0, plane, vm, any, next_block_valid);
+        // the next block's first piece arrived in slot (3 * TT) & 1; the block expects it in slot 0
+        if ((3 * TT) & 1) {
+#pragma unroll
+            for (int g = 0; g < KVH; ++g)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) W[0][g][k] = W[1][g][k];
+        }
+        // scores of the block: the sparse part (if any) is loaded now and added
+        float prev[TT * QH];
+#pragma unroll
+        for (int t = 0; t < TT; ++t)
+#pragma unroll
+            for (int qh = 0; qh < QH; ++qh)
+                prev[t * QH + qh] = (add_prev && ((vm >> t) & 1u)) ? scores[(int64_t)(q0 + qh) * ld + n0 + (int64_t)t * NT] : 0.f;
+        float bm[STATS ? QH : 1];                             // maxima of this block's scores
+        if (STATS) {
+#pragma unroll
+            for (int qh = 0; qh < QH; ++qh) bm[qh] = KVQ_STAT_FLOOR;
+        }
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+            if ((vm >> t) & 1u) {
+                const int64_t n = n0 + (int64_t)t * NT;
+#pragma unroll
+                for (int qh = 0; qh < QH; ++qh) {
+                    const float x = acc[t * QH + qh] + prev[t * QH + qh];
+                    scores[(int64_t)(q0 + qh) * ld + n] = x;
+                    if (STATS && n >= n_sink) bm[STATS ? qh : 0] = __builtin_fmaxf(bm[STATS ? qh : 0], x);
+                }
+            }
+        }
+        if (STATS) {
+#pragma unroll
+            for (int qh = 0; qh < QH; ++qh) {
+                const float w = kvq_wave_max(bm[STATS ? qh : 0]);
+                if (lane_id == 0) wst[qh] = __builtin_fmaxf(wst[qh], w);
+            }
+        }
+        n0 += (int64_t)TT * NT;
+    }
+    if (STATS) {
+        __syncthreads();
+        if (tid < QH) {
+            float m = KVQ_STAT_FLOOR;
+#pragma unroll
+            for (int w = 0; w < NT / 64; ++w) m = __builtin_fmaxf(m, qs[w * QH + tid]);
+            stat_slots[(int64_t)(q0 + tid) * KVQ_STAT_SLOTS + blockIdx.x] = m;
+        }
+    }
+    if (SPAN) kvq_span_end(span);
+}
+
 // Sparse Key outliers, balanced (paper App. "Kernel Implementation Details": equal non-zeros per
 // thread): lanes are outlier entries.  Every wavefront works on its own: it owns a run of consecutive
 // tokens and walks it TW tokens at a time (8, or 32 when outliers are few: see launch_qk_sparse).  A sub-range's pointers sit in one register (lane j:
@@ -400,6 +740,7 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
                    const uint16_t *__restrict__ k_val, uint32_t nnz_cap, const float *__restrict__ q_rot,
                    float scale, float *__restrict__ scores, int64_t ld, int64_t tokens_per_wave)
 {
+    const int bx = (int)blockIdx.x;
     constexpr int QS_ROW = qs_row(QS_TW);
     extern __shared__ __attribute__((aligned(16))) float dyn[];
     const KvqParamsView pv = kvq_params_view(params, D);
@@ -410,7 +751,7 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
     unsigned long long *S = (unsigned long long *)mine;                  // [n_q_heads][QS_ROW] 2^32-scaled sums
     // [64] (angle of the pair at the sub-range's first token, theta / 2 pi)
     float2_t *ang = (float2_t *)(mine + ((n_q_heads * QS_ROW * 8 + 15) & ~15));
-    const int64_t nb = ((int64_t)blockIdx.x * n_waves + wave) * tokens_per_wave;
+    const int64_t nb = ((int64_t)bx * n_waves + wave) * tokens_per_wave;
     int64_t ne = nb + tokens_per_wave;
     if (ne > L) ne = L;
     const int n_cells = n_q_heads * QS_TW;
@@ -591,6 +932,15 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     const int64_t L = c->n_tokens_k;
     auto kern = stat_slots ? kvq_qk_kernel<BITS, KVH, RQ, NT, PG, true> : kvq_qk_kernel<BITS, KVH, RQ, NT, PG, false>;
     constexpr bool CAN_SPAN = QH < 8;
+    // 3-bit codes, tiles of KVQ_ROPE_STEP tokens: the piece-major kernel (rotary recurrence over TT tiles)
+    constexpr bool PIECE_MAJOR = KVQ_QK3_ENABLE && BITS == 3 && NT == KVQ_ROPE_STEP && KVH * KVQ_QK3_TT <= 16;
+    // (it addresses the codes with 32-bit offsets)
+    const bool piece_major = PIECE_MAJOR && (int64_t)c->n_kv_heads * c->cap_tokens * 16 * BITS < ((int64_t)1 << 32);
+    if constexpr (PIECE_MAJOR) {
+        if (piece_major)
+            kern = stat_slots ? kvq_qk3_kernel<KVH, RQ, KVQ_QK3_TT, KVQ_QK3_PG, true>
+                              : kvq_qk3_kernel<KVH, RQ, KVQ_QK3_TT, KVQ_QK3_PG, false>;
+    }
     const int groups = c->n_q_heads / QH;
     const int64_t tiles = (L + NT - 1) / NT;
     // about one workgroup per compute unit in total (the tables fill most of a CU's LDS); each
@@ -608,7 +958,14 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     }
     KvqProfile &prof = kvq_profile_state();
     unsigned long long *span = CAN_SPAN ? kvq_profile_span_slot(prof, 0, (int64_t)gx * groups) : nullptr;
-    if constexpr (CAN_SPAN) {
+    if constexpr (PIECE_MAJOR) {
+        if (span && piece_major)
+            kern = stat_slots ? kvq_qk3_kernel<KVH, RQ, KVQ_QK3_TT, KVQ_QK3_PG, true, true>
+                              : kvq_qk3_kernel<KVH, RQ, KVQ_QK3_TT, KVQ_QK3_PG, false, true>;
+        else if (span)
+            kern = stat_slots ? kvq_qk_kernel<BITS, KVH, RQ, NT, PG, true, true>
+                              : kvq_qk_kernel<BITS, KVH, RQ, NT, PG, false, true>;
+    } else if constexpr (CAN_SPAN) {
         if (span)
             kern = stat_slots ? kvq_qk_kernel<BITS, KVH, RQ, NT, PG, true, true>
                               : kvq_qk_kernel<BITS, KVH, RQ, NT, PG, false, true>;
