@@ -178,6 +178,134 @@ def model_step(args, wl, S, K, torch):
     }
     print(json.dumps(line))
 
+def million_token_leg(args, K, S, torch):
+    """Configuration 3 beside the headline workload: the same layer shape at a context of 1,048,576 tokens,
+    nuq4 with 0.1 % outliers, where a step first quantize-appends 64 new tokens (Keys and Values) and then
+    runs the attention (scores, softmax, output) over the whole context.  Returns the dictionary that
+    the bench line carries under "c3"."""
+    wl = S.workload("c3")
+    st = S.LayerInputs(wl)
+    L, T = wl.context, 64
+    steps = max(4, min(args.steps, 40))
+    warmup = max(2, min(args.warmup, 5))
+    bsteps = max(4, min(steps, 20))
+    n_calls = warmup + steps + 3 * bsteps
+    cap = ((L + n_calls * T + 8 + 127) // 128) * 128
+    Hq, D = wl.n_q_heads, wl.D
+    scale = 1.0 / np.sqrt(128.0)
+    gc, dg, k16, v16 = build_cache(st, L, cap, K, torch, keep_fp16=not args.no_fp16)
+    assert gc.status() == 0
+    new_k = dg.k(L, n_calls * T)
+    new_v = dg.v(L, n_calls * T)
+    q = torch.from_numpy(S.gen_q(wl, 0, 0)).cuda()
+    scores = torch.zeros((Hq, cap), device="cuda")
+    out = torch.zeros((Hq, 128), device="cuda")
+
+    def step(i, ev=None):
+        K.kvq_quantize_append_kv(gc, new_k[i * T:(i + 1) * T], new_v[i * T:(i + 1) * T])
+        if ev: ev[1].start()  # noqa: E701
+        K.kvq_attention_decode(gc, q, scale, scores, out)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for i in range(steps):
+        step(warmup + i)
+    torch.cuda.synchronize()
+    us_per_step = (time.perf_counter() - t_begin) * 1e6 / steps
+    base = warmup + steps
+    evs = [[K.HipEventTimer() for _ in range(3)] for _ in range(bsteps)]
+    for i in range(bsteps):
+        evs[i][0].start()
+        step(base + i, evs[i])
+        evs[i][2].start()
+    torch.cuda.synchronize()
+    import ctypes
+    lib = K.load_library()
+
+    def gap_us(a, b):
+        ms = ctypes.c_float()
+        lib.kvq_event_elapsed_ms(a._a, b._a, ctypes.byref(ms))
+        return ms.value * 1e3
+
+    append_us = float(np.mean([gap_us(e[0], e[1]) for e in evs]))
+    attention_us = float(np.mean([gap_us(e[1], e[2]) for e in evs]))
+    base += bsteps
+    # the dense kernels inside back-to-back steps: the Value kernel by its workgroups' span, the Key
+    # kernel (eight query heads per thread: no span-taking variant) by the HIP-event interval around
+    # its launch, which is an upper bound on its duration
+    K.kvq_profile_enable(True, spans=True, events=False)
+    for i in range(bsteps):
+        step(base + i)
+    torch.cuda.synchronize()
+    K.kvq_profile_enable(False)
+    dense_pv = K.kvq_profile_read_all_spans_us(1)
+    try:
+        dense_qk = K.kvq_profile_read_all_spans_us(0)
+        qk_how = "span of the kernel's workgroups on the GPU wall clock"
+    except K.KvqError:
+        dense_qk = None
+    K.kvq_profile_enable(True)
+    for i in range(bsteps):
+        step(base + bsteps + i)
+    torch.cuda.synchronize()
+    K.kvq_profile_enable(False)
+    ev_qk = K.kvq_profile_read_all_us(0)
+    if dense_qk is None:
+        dense_qk = ev_qk
+        qk_how = "interval between HIP events recorded around the launch (an upper bound: no span-taking variant of this kernel)"
+    Lend = gc.n_tokens_k
+    assert gc.status() == 0 and Lend == L + n_calls * T
+    nnz_k = int(gc.k_ptr[Lend].item()) & 0xFFFFFFFF
+    nnz_v = int(gc.v_ptr[Lend].item()) & 0xFFFFFFFF
+    qk_bytes, pv_bytes = algorithmic_bytes(wl, Lend, nnz_k, nnz_v)
+    append_bytes = T * (2 * (2 * D) + 2 * (D * wl.bits // 8) + 12) + 4 * (nnz_k + nnz_v) * T // Lend
+    dense_qk_us = float(np.mean(dense_qk))
+    dense_qk_bytes = Lend * (D * wl.bits // 8) + 4 * Hq * Lend
+    dense_qk_gbps = dense_qk_bytes / (dense_qk_us * 1e-6) / 1e9
+    fp16 = None
+    if not args.no_fp16:
+        probs = torch.softmax(scores[:, :L], dim=1).contiguous()
+        s16 = torch.zeros((Hq, L), device="cuda")
+        fws = torch.zeros(K.binding.kvq_fp16_pv_workspace_bytes(Hq, L), dtype=torch.uint8, device="cuda")
+        tm = K.HipEventTimer()
+        res = {}
+        for name, fn in (("qk", lambda: K.kvq_fp16_qk_matvec(k16, wl.n_kv_heads, Hq, q, scale, s16)),
+                         ("pv", lambda: K.kvq_fp16_pv_matvec(v16, wl.n_kv_heads, Hq, probs, out, fws))):
+            for _ in range(2):
+                fn()
+            tm.start()
+            for _ in range(5):
+                fn()
+            tm.stop()
+            res[name] = tm.elapsed_ms() * 1e3 / 5
+        fp16 = {"qk_us": res["qk"], "pv_us": res["pv"], "qk_gbps": L * D * 2 / (res["qk"] * 1e-6) / 1e9,
+                "pv_gbps": L * D * 2 / (res["pv"] * 1e-6) / 1e9}
+        del k16, v16, probs, s16, fws
+    total_bytes = qk_bytes + pv_bytes + append_bytes
+    return {
+        "config": {"workload": f"c3: {Hq} q-heads x {wl.n_kv_heads} kv-heads x 128, context {L}, batch 1, "
+                               f"nuq{wl.bits} with {wl.outlier_fraction * 100:g}% outliers, a step appends {T} new tokens "
+                               f"(Keys and Values) before the mat-vecs",
+                   "bits": wl.bits, "context": L, "outlier_fraction": wl.outlier_fraction, "append_tokens": T},
+        "step": "kvq_quantize_append_kv (64 tokens) + kvq_attention_decode",
+        "value": us_per_step, "unit": "us", "steps": steps, "warmup": warmup,
+        "breakdown_us": {"append_kv_64_tokens": append_us, "attention_decode": attention_us},
+        "algorithmic_bytes": {"qk": qk_bytes, "pv": pv_bytes, "append": append_bytes},
+        "hbm_gbps_step": total_bytes / (us_per_step * 1e-6) / 1e9,
+        "hbm_gbps_attention": (qk_bytes + pv_bytes) / (attention_us * 1e-6) / 1e9,
+        "dense_kernel_us": {"qk": dense_qk_us, "qk_measured": qk_how, "pv": float(np.mean(dense_pv)),
+                            "pv_measured": "span of the kernel's workgroups on the GPU wall clock",
+                            "qk_event_interval_us": float(np.mean(ev_qk)), "launches": bsteps},
+        "roofline": {"bound": "hbm", "kernel": "kvq_qk_kernel<4 bits> (dense Key kernel of the attention call)",
+                     "achieved": dense_qk_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": dense_qk_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes": dense_qk_bytes, "avg_launch_us": dense_qk_us},
+        "fp16_cache_baseline": fp16,
+        "speedup_vs_fp16_attention": ((fp16["qk_us"] + fp16["pv_us"]) / attention_us) if fp16 else None,
+    }
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -192,6 +320,7 @@ def main():
     ap.add_argument("--layers", type=int, default=1,
                     help="more than 1: time a decode step over that many layers (each its own cache), nothing else")
     ap.add_argument("--no-fp16", action="store_true")
+    ap.add_argument("--no-c3", action="store_true", help="skip the 1M-token leg (configuration 3) of the default run")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy (known traffic) so profiler byte counters can be scaled")
     args = ap.parse_args()
@@ -487,6 +616,12 @@ def main():
                      "valu_issue": valu},
         "cpu_baseline": cpu,
     }
+    # the 1M-token half of the metric: configuration 3 timed after the headline workload (whose tensors are
+    # released first), under a key of its own
+    if wl.name == "c2" and not over and not args.no_c3:
+        del gc, dg, new_k, new_v, scores, probs
+        torch.cuda.empty_cache()
+        line["c3"] = million_token_leg(args, K, S, torch)
     print(json.dumps(line))
 
 

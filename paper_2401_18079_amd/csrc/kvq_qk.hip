@@ -315,10 +315,19 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
                 W[g][4 * j + 0] = v.x; W[g][4 * j + 1] = v.y; W[g][4 * j + 2] = v.z; W[g][4 * j + 3] = v.w;
             }
     }
-    float stat_m[STATS ? QH : 1];
-    if (STATS) {
+    // STATS: running maxima of the scores written.  With eight query heads per thread there is no
+    // register for them: the wavefront's maxima then live in LDS slots of its own (the staged query's
+    // array, dead once the tables are built; only lane 0 of the wavefront touches its slots) and are
+    // brought up to date after every tile.
+    constexpr bool STAT_LDS = STATS && QH >= 8;
+    float stat_m[(STATS && !STAT_LDS) ? QH : 1];
+    if (STATS && !STAT_LDS) {
 #pragma unroll
         for (int qh = 0; qh < QH; ++qh) stat_m[qh] = KVQ_STAT_FLOOR;
+    }
+    if (STAT_LDS && (tid & 63) == 0) {
+#pragma unroll
+        for (int qh = 0; qh < QH; ++qh) qs[(tid >> 6) * QH + qh] = KVQ_STAT_FLOOR;
     }
     for (int tile = 0; tile < tiles_per_wg; ++tile) {
         // wavefronts w, w + 4, ... of the workgroup share a SIMD: each takes every priority in turn
@@ -372,7 +381,17 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
             for (int qh = 0; qh < QH; ++qh) {
                 const float x = acc[qh] + prev[qh];
                 scores[(int64_t)(q0 + qh) * ld + n] = x;
-                if (STATS && n >= n_sink) stat_m[STATS ? qh : 0] = __builtin_fmaxf(stat_m[STATS ? qh : 0], x);
+                if (STATS && !STAT_LDS && n >= n_sink)
+                    stat_m[(STATS && !STAT_LDS) ? qh : 0] = __builtin_fmaxf(stat_m[(STATS && !STAT_LDS) ? qh : 0], x);
+                acc[qh] = x;
+            }
+        }
+        if (STAT_LDS) {
+            float *wst = qs + (tid >> 6) * QH;
+#pragma unroll
+            for (int qh = 0; qh < QH; ++qh) {
+                const float w = kvq_wave_max((valid && n >= n_sink) ? acc[qh] : KVQ_STAT_FLOOR);
+                if ((tid & 63) == 0) wst[qh] = __builtin_fmaxf(wst[qh], w);
             }
         }
         n = nn;
@@ -383,10 +402,12 @@ __global__ __launch_bounds__(NT) void kvq_qk_kernel(const void *__restrict__ par
         // workgroup-wide maximum per query head: wavefronts first, then one thread per head over the
         // wavefronts' values (the staged query is dead by now: its array holds them)
         float *wst = qs;                                      // [NT / 64][QH]
+        if (!STAT_LDS) {
 #pragma unroll
-        for (int qh = 0; qh < QH; ++qh) {
-            const float w = kvq_wave_max(stat_m[STATS ? qh : 0]);
-            if ((tid & 63) == 0) wst[(tid >> 6) * QH + qh] = w;
+            for (int qh = 0; qh < QH; ++qh) {
+                const float w = kvq_wave_max(stat_m[(STATS && !STAT_LDS) ? qh : 0]);
+                if ((tid & 63) == 0) wst[(tid >> 6) * QH + qh] = w;
+            }
         }
         __syncthreads();
         if (tid < QH) {
@@ -959,9 +980,10 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     KvqProfile &prof = kvq_profile_state();
     unsigned long long *span = CAN_SPAN ? kvq_profile_span_slot(prof, 0, (int64_t)gx * groups) : nullptr;
     if constexpr (PIECE_MAJOR) {
-        if (span && piece_major)
-            kern = stat_slots ? kvq_qk3_kernel<KVH, RQ, KVQ_QK3_TT, KVQ_QK3_PG, true, true>
-                              : kvq_qk3_kernel<KVH, RQ, KVQ_QK3_TT, KVQ_QK3_PG, false, true>;
+        // no span-taking variant of the piece-major kernel: it has no register to spare, the stamps'
+        // bookkeeping makes the compiler spill around the loops and the variant runs 15 % slower than
+        // the kernel it is meant to time; callers fall back on the HIP-event interval
+        if (piece_major) span = nullptr;
         else if (span)
             kern = stat_slots ? kvq_qk_kernel<BITS, KVH, RQ, NT, PG, true, true>
                               : kvq_qk_kernel<BITS, KVH, RQ, NT, PG, false, true>;
