@@ -92,7 +92,31 @@ typedef struct kvq_cache {
     int64_t workspace_bytes;
     uint16_t *sink_k;       /* [n_sink][D] fp16: pre-RoPE Keys of tokens 0..n_sink-1 (NULL if 0) */
     uint16_t *sink_v;       /* [n_sink][D] fp16: Values of tokens 0..n_sink-1 (NULL if n_sink=0) */
+    /* Blocked outlier storage (see below).  0: k_idx .. v_val above are flat arrays.  Otherwise they
+     * are ignored and the four tables that follow list the blocks, 2^nnz_block_shift entries each.   */
+    int32_t nnz_block_shift;
+    int32_t reserved0;      /* 0                                                                 */
+    uint16_t **k_idx_blocks, **k_val_blocks; /* DEVICE arrays [cap_nnz_k >> shift] of DEVICE pointers */
+    uint16_t **v_idx_blocks, **v_val_blocks; /* DEVICE arrays [cap_nnz_v >> shift] of DEVICE pointers */
 } kvq_cache;
+
+/*
+ * Blocked outlier storage (paper App. "Limitations": the sparse matrix allocated in blocks, so that
+ * appending a token does not copy the entries already stored).  With nnz_block_shift = s in
+ * [KVQ_NNZ_BLOCK_SHIFT_MIN, KVQ_NNZ_BLOCK_SHIFT_MAX], sparse entry e of the Keys is element
+ * e & (2^s - 1) of the block k_idx_blocks[e >> s] (its index) and k_val_blocks[e >> s] (its value),
+ * likewise for the Values; the entry numbering, k_ptr / v_ptr and every result are those of the flat
+ * layout, which is the case of one block.  cap_nnz_k and cap_nnz_v are whole numbers of blocks
+ * (at least one) and every table slot below cap_nnz >> s holds a valid block of 2^s uint16
+ * (2-byte aligned is enough).  To grow, the owner allocates one more block, stores its address in
+ * the next slot of the table (the tables are the caller's: size them for the largest capacity
+ * wanted, 8 bytes per block) and adds 2^s to cap_nnz between two calls; nothing stored moves.
+ * The library only reads the tables.  Checked on the host: shift range, capacities, table pointers
+ * non-null and 8-byte aligned (INVALID_ARG); the block addresses themselves live on the device and
+ * are not checked.
+ */
+#define KVQ_NNZ_BLOCK_SHIFT_MIN 10
+#define KVQ_NNZ_BLOCK_SHIFT_MAX 30
 
 /*
  * Attention-sink-aware quantization (paper Sec. 3.5): the first n_sink tokens of the sequence stay
@@ -217,6 +241,23 @@ kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs, int64_t l
  */
 kvq_status kvq_attention_decode(const kvq_cache *cache, const float *d_q_rot, float scale,
                                 float *d_scores, int64_t ld_scores, float *d_out, void *stream);
+
+/*
+ * One generation step of one layer for one sequence in a single call (paper Sec. 3: at every step
+ * the new token's Key and Value join the cache and the query attends over all of it): exactly
+ * kvq_quantize_append_kv(cache, d_k_new, d_v_new, 1) followed by kvq_attention_decode on the cache
+ * that now ends with the new token, same kernels, same results bit for bit.
+ *   d_k_new, d_v_new : DEVICE fp16 [D], the new token's pre-RoPE Key and its Value.
+ *   d_q_rot, scale, d_scores, ld_scores, d_out : as for kvq_attention_decode; ld_scores must cover
+ *   the new token too (>= n_tokens_k + 1 on entry).
+ * Every host-side check of both halves is made before anything is launched, so a call that returns
+ * INVALID_ARG, CAPACITY or NOT_LOADED has changed nothing; UNSUPPORTED (a shape beyond the mat-vecs'
+ * limits) and HIP can come back after the append has been launched, in which case n_tokens_k and
+ * n_tokens_v have advanced.
+ */
+kvq_status kvq_decode_step(kvq_cache *cache, const uint16_t *d_k_new, const uint16_t *d_v_new,
+                           const float *d_q_rot, float scale, float *d_scores, int64_t ld_scores,
+                           float *d_out, void *stream);
 
 /*
  * kvq_attention_decode for callers that cannot allocate device memory or hand over a workspace (code

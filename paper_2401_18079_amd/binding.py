@@ -31,6 +31,9 @@ class _CCache(C.Structure):
         ("k_idx", C.c_void_p), ("k_val", C.c_void_p), ("v_idx", C.c_void_p), ("v_val", C.c_void_p),
         ("d_status", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64),
         ("sink_k", C.c_void_p), ("sink_v", C.c_void_p),
+        ("nnz_block_shift", C.c_int32), ("reserved0", C.c_int32),
+        ("k_idx_blocks", C.c_void_p), ("k_val_blocks", C.c_void_p),
+        ("v_idx_blocks", C.c_void_p), ("v_val_blocks", C.c_void_p),
     ]
 
 
@@ -62,6 +65,7 @@ def load_library():
         "kvq_pv_matvec": (C.c_int, [P, V, I64, V, V]),
         "kvq_attention_decode": (C.c_int, [P, V, F, V, I64, V, V]),
         "kvq_attention_decode_noalloc": (C.c_int, [P, V, F, V, I64, V, V]),
+        "kvq_decode_step": (C.c_int, [P, V, V, V, F, V, I64, V, V]),
         "kvq_softmax_workspace_bytes": (I64, [I32, I64]),
         "kvq_softmax_f32": (C.c_int, [V, I64, V, I64, I32, I64, V, I64, V]),
         "kvq_calibrate_key_channels": (C.c_int, [V, I32, I32, F, V, V, V, V, V]),
@@ -95,7 +99,7 @@ EXPORTED_SYMBOLS = [
     "kvq_codes_bytes", "kvq_params_bytes", "kvq_workspace_bytes", "kvq_status_string", "kvq_version",
     "kvq_lut_load", "kvq_stored_signpost", "kvq_quantize_append_k", "kvq_quantize_append_v", "kvq_quantize_append_kv",
     "kvq_qk_matvec", "kvq_pv_matvec",
-    "kvq_attention_decode", "kvq_attention_decode_noalloc", "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
+    "kvq_attention_decode", "kvq_attention_decode_noalloc", "kvq_decode_step", "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
     "kvq_fp16_pv_matvec", "kvq_event_create", "kvq_event_record", "kvq_event_elapsed_ms", "kvq_event_destroy",
     "kvq_profile_enable", "kvq_profile_last_ms", "kvq_profile_count", "kvq_profile_read_ms",
     "kvq_profile_span_buffer_bytes", "kvq_profile_set_span_buffer", "kvq_profile_span_us", "kvq_calibrate_workspace_bytes", "kvq_calibrate_nuq",
@@ -190,7 +194,10 @@ class KvqCache:
     """Device buffers of one layer's cache for one sequence (torch tensors) plus the C descriptor."""
 
     def __init__(self, bits, n_kv_heads, n_q_heads, cap_tokens, k_side_v, rope_base, cap_nnz_k, cap_nnz_v=None,
-                 max_append=4096, device="cuda:0", n_sink=0):
+                 max_append=4096, device="cuda:0", n_sink=0, nnz_block_entries=None, nnz_table_slots=4096):
+        """nnz_block_entries: None for flat outlier arrays of cap_nnz_k / cap_nnz_v entries; a power of two
+        (1024 .. 2^30) for blocked storage, where the capacities are rounded up to whole blocks and
+        ensure_nnz_room() adds blocks without copying.  nnz_table_slots: blocks each table can list."""
         load_library()
         dev = torch.device(device)
         D = n_kv_heads * 128
@@ -203,8 +210,21 @@ class KvqCache:
         self.k_codes, self.v_codes = z(nbytes, torch.uint8), z(nbytes, torch.uint8)
         self.v_sz = z(cap_tokens * 2, torch.int16)
         self.k_ptr, self.v_ptr = z(cap_tokens + 1, torch.int32), z(cap_tokens + 1, torch.int32)
-        self.k_idx, self.k_val = z(cap_nnz_k, torch.int16), z(cap_nnz_k, torch.int16)
-        self.v_idx, self.v_val = z(cap_nnz_v, torch.int16), z(cap_nnz_v, torch.int16)
+        self.block_entries = int(nnz_block_entries or 0)
+        if self.block_entries:
+            be = self.block_entries
+            assert be & (be - 1) == 0 and 1 << 10 <= be <= 1 << 30, "block size: a power of two in [2^10, 2^30]"
+            cap_nnz_k, cap_nnz_v = -(-cap_nnz_k // be) * be, -(-int(cap_nnz_v) // be) * be
+            assert max(cap_nnz_k, cap_nnz_v) // be <= nnz_table_slots
+            self.k_idx = self.k_val = self.v_idx = self.v_val = None
+            self.blocks = {n: [z(be, torch.int16) for _ in range(cap // be)]
+                           for n, cap in (("k_idx", cap_nnz_k), ("k_val", cap_nnz_k), ("v_idx", cap_nnz_v), ("v_val", cap_nnz_v))}
+            self.tables = {n: z(nnz_table_slots, torch.int64) for n in self.blocks}
+            for n, bl in self.blocks.items():
+                self.tables[n][:len(bl)] = torch.tensor([b.data_ptr() for b in bl], dtype=torch.int64)
+        else:
+            self.k_idx, self.k_val = z(cap_nnz_k, torch.int16), z(cap_nnz_k, torch.int16)
+            self.v_idx, self.v_val = z(cap_nnz_v, torch.int16), z(cap_nnz_v, torch.int16)
         self.d_status = z(4, torch.int32)
         # attention-sink tokens: the first n_sink tokens are also kept in fp16
         self.sink_k, self.sink_v = z(max(1, n_sink) * D, torch.int16), z(max(1, n_sink) * D, torch.int16)
@@ -215,9 +235,14 @@ class KvqCache:
         c.cap_nnz_k, c.cap_nnz_v = cap_nnz_k, int(cap_nnz_v)
         c.rope_base = float(rope_base)
         c.n_sink = int(n_sink)
-        for name in ("params", "k_codes", "v_codes", "v_sz", "k_ptr", "v_ptr", "k_idx", "k_val", "v_idx", "v_val",
-                     "d_status", "sink_k", "sink_v"):
+        for name in ("params", "k_codes", "v_codes", "v_sz", "k_ptr", "v_ptr", "d_status", "sink_k", "sink_v"):
             setattr(c, name, getattr(self, name).data_ptr())
+        for name in ("k_idx", "k_val", "v_idx", "v_val"):
+            if self.block_entries:
+                setattr(c, name + "_blocks", self.tables[name].data_ptr())
+            else:
+                setattr(c, name, getattr(self, name).data_ptr())
+        c.nnz_block_shift = self.block_entries.bit_length() - 1 if self.block_entries else 0
         self.c = c
         self.D, self.device = D, dev
         self.workspace = z(int(load_library().kvq_workspace_bytes(C.byref(c), max_append)), torch.uint8)
@@ -234,10 +259,12 @@ class KvqCache:
     def status(self) -> int:
         return int(self.d_status[0].item())
 
-    # Blocked allocation of the sparse arrays (paper App. "Limitations": allocating the outlier
-    # storage in blocks, so that appending a token does not copy what is already stored, is what the paper plans).  The library never
-    # allocates: capacity is a field of the descriptor, so the owner of the memory grows the arrays
-    # between calls, here by whole blocks of NNZ_BLOCK entries, and nothing already stored changes.
+    # Growing the sparse arrays.  The library never allocates: capacity is a field of the descriptor and
+    # the owner of the memory grows it between calls.  With blocked storage (paper App. "Limitations":
+    # the outlier storage allocated in blocks, so that appending a token copies nothing already
+    # stored) growing is one new block per array and one 8-byte store into each block table; with flat
+    # arrays it is a new, larger allocation and a copy of the entries in use, by NNZ_BLOCK entries at a
+    # time so that the copies are amortised.
     NNZ_BLOCK = 1 << 20
 
     def nnz_used(self):
@@ -246,13 +273,35 @@ class KvqCache:
         v = int(self.v_ptr[self.n_tokens_v].item()) & 0xFFFFFFFF
         return k, v
 
+    def sparse_entries(self, side: str, n: int):
+        """The first n (index, value) entries of side "k" or "v" as two int16 tensors, whatever the layout."""
+        if not self.block_entries:
+            return getattr(self, side + "_idx")[:n], getattr(self, side + "_val")[:n]
+        return (torch.cat(self.blocks[side + "_idx"])[:n], torch.cat(self.blocks[side + "_val"])[:n])
+
     def ensure_nnz_room(self, extra_k: int, extra_v: int, block: int = None) -> bool:
         """Make room for `extra_k` / `extra_v` more outlier entries (worst case of the next appends: every
-        element of a Key token can be an outlier, a Value token has exactly 2 * k_side_v).  Grows the
-        arrays by whole blocks when needed, copying the entries in use.  Returns True if anything grew."""
-        block = int(block or self.NNZ_BLOCK)
+        element of a Key token can be an outlier, a Value token has exactly 2 * k_side_v).  Blocked
+        storage: adds blocks, copies nothing.  Flat arrays: reallocates in steps of `block` entries and
+        copies the entries in use.  Returns True if anything grew."""
         used_k, used_v = self.nnz_used()
         grew = False
+        if self.block_entries:
+            be = self.block_entries
+            for used, extra, cap_name, names in ((used_k, extra_k, "cap_nnz_k", ("k_idx", "k_val")),
+                                                 (used_v, extra_v, "cap_nnz_v", ("v_idx", "v_val"))):
+                while used + int(extra) > getattr(self.c, cap_name):
+                    n = getattr(self.c, cap_name) // be
+                    if n >= self.tables[names[0]].numel() or (n + 1) * be >= 1 << 31:
+                        raise KvqError(3, "ensure_nnz_room")
+                    for name in names:
+                        blk = torch.zeros(be, dtype=torch.int16, device=self.device)
+                        self.blocks[name].append(blk)
+                        self.tables[name][n] = blk.data_ptr()      # one 8-byte store, ordered on the stream
+                    setattr(self.c, cap_name, (n + 1) * be)
+                    grew = True
+            return grew
+        block = int(block or self.NNZ_BLOCK)
         for used, extra, cap_name, names in ((used_k, extra_k, "cap_nnz_k", ("k_idx", "k_val")),
                                              (used_v, extra_v, "cap_nnz_v", ("v_idx", "v_val"))):
             need = used + int(extra)
@@ -342,6 +391,21 @@ def kvq_attention_decode(cache: KvqCache, q_rot: torch.Tensor, scale: float, sco
     _check(load_library().kvq_attention_decode(C.byref(cache.c), q_rot.data_ptr(), float(scale), scores.data_ptr(),
                                                scores.stride(0), out.data_ptr(), _stream_ptr(stream)),
            "kvq_attention_decode")
+
+
+def kvq_decode_step(cache: KvqCache, k_new: torch.Tensor, v_new: torch.Tensor, q_rot: torch.Tensor, scale: float,
+                    scores: torch.Tensor, out: torch.Tensor, stream=None):
+    """Append one token's Key and Value, then the fused attention over the cache that ends with it."""
+    k, v = _fp16_rows(cache, k_new), _fp16_rows(cache, v_new)
+    assert k.shape[0] == 1 and v.shape[0] == 1
+    assert q_rot.is_cuda and q_rot.dtype == torch.float32 and q_rot.is_contiguous()
+    assert q_rot.shape == (cache.c.n_q_heads, 128)
+    assert scores.is_cuda and scores.dtype == torch.float32 and scores.dim() == 2 and scores.stride(1) == 1
+    assert scores.shape[0] == cache.c.n_q_heads
+    assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.shape == (cache.c.n_q_heads, 128)
+    _check(load_library().kvq_decode_step(C.byref(cache.c), k.data_ptr(), v.data_ptr(), q_rot.data_ptr(), float(scale),
+                                          scores.data_ptr(), scores.stride(0), out.data_ptr(), _stream_ptr(stream)),
+           "kvq_decode_step")
 
 
 def kvq_attention_decode_noalloc(cache: KvqCache, q_rot: torch.Tensor, scale: float, scores: torch.Tensor,

@@ -4,6 +4,7 @@
 // (this file is compiled with floating-point contraction off) so that codes, outlier indices
 // and fp16 residuals are reproducible bit for bit.
 #include "kvq_common.hpp"
+#include <type_traits>
 
 namespace {
 
@@ -161,11 +162,10 @@ __device__ inline uint32_t block_rank_multi(const bool (&flag)[IT], uint32_t (&r
 // A pass handles IT blocks of NT channels: all its loads are issued up front, and ranks, packing and
 // stores of the IT blocks share one set of barriers (a single-token decode append is pure latency).
 // (The body of the kernels below: `t` is the token's index within the call.)
-template <int BITS, int NT>
+template <int BITS, int NT, class SP>
 __device__ __forceinline__ void k_quant_token(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
                                               const uint16_t *__restrict__ k_new, uint8_t *__restrict__ k_codes,
-                                              uint32_t *__restrict__ k_ptr, uint16_t *__restrict__ k_idx,
-                                              uint16_t *__restrict__ k_val, int64_t cap_nnz, int single,
+                                              uint32_t *__restrict__ k_ptr, const SP ksp, int64_t cap_nnz, int single,
                                               int32_t *d_status, const int t)
 {
     constexpr int NE = 1 << BITS;
@@ -220,7 +220,7 @@ __device__ __forceinline__ void k_quant_token(const void *__restrict__ params, i
         for (int j = 0; j < IT; ++j) {
             if (is_out[j]) {
                 const uint64_t pos = (uint64_t)base + running + rank[j];
-                if (pos < (uint64_t)cap_nnz) { k_idx[pos] = (uint16_t)(cb + j * NT + tid); k_val[pos] = resid[j]; }
+                if (pos < (uint64_t)cap_nnz) ksp.put(pos, (uint16_t)(cb + j * NT + tid), resid[j]);
                 else overflow = true;
             }
         }
@@ -445,12 +445,11 @@ __device__ bool select_both(const uint16_t *keys, uint8_t *state, int D, int k, 
 
 // Quantize, pack and append the Values of one new token per workgroup (`t`: the token's index within
 // the call).  A pass of the main loop handles IT blocks of NT channels (see k_quant_token).
-template <int BITS, int NT>
+template <int BITS, int NT, class SP>
 __device__ __forceinline__ void v_quant_token(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
                                               int k_side, const uint16_t *__restrict__ v_new,
                                               uint8_t *__restrict__ v_codes, uint16_t *__restrict__ v_sz,
-                                              uint32_t *__restrict__ v_ptr, uint16_t *__restrict__ v_idx,
-                                              uint16_t *__restrict__ v_val, int64_t cap_nnz, int32_t *d_status,
+                                              uint32_t *__restrict__ v_ptr, const SP vsp, int64_t cap_nnz, int32_t *d_status,
                                               const int t)
 {
     constexpr int NE = 1 << BITS;
@@ -548,7 +547,7 @@ __device__ __forceinline__ void v_quant_token(const void *__restrict__ params, i
         for (int j = 0; j < IT; ++j) {
             if (is_out[j]) {
                 const uint64_t pos = (uint64_t)base + running + rank[j];
-                if (pos < (uint64_t)cap_nnz) { v_idx[pos] = (uint16_t)(cb + j * NT + tid); v_val[pos] = resid[j]; }
+                if (pos < (uint64_t)cap_nnz) vsp.put(pos, (uint16_t)(cb + j * NT + tid), resid[j]);
                 else overflow = true;
             }
         }
@@ -600,14 +599,13 @@ __device__ __forceinline__ void v_quant_token(const void *__restrict__ params, i
 // order: within a head first the lanes' lower channels, then their upper ones, ranked by ballots.
 // Same arithmetic, same results, as k_quant_token; the per-token pointers come from kvq_ptr_scan.
 constexpr int KVQ_KW_NT = 256;
-template <int BITS>
+template <int BITS, class SP>
 __global__ __launch_bounds__(KVQ_KW_NT) void kvq_k_quant_wave(const void *__restrict__ params, int D, int T,
                                                               int64_t cap, int64_t n0,
                                                               const uint16_t *__restrict__ k_new,
                                                               uint8_t *__restrict__ k_codes,
                                                               const uint32_t *__restrict__ k_ptr,
-                                                              uint16_t *__restrict__ k_idx,
-                                                              uint16_t *__restrict__ k_val, int64_t cap_nnz,
+                                                              const SP ksp, int64_t cap_nnz,
                                                               int32_t *d_status)
 {
     constexpr int NE = 1 << BITS;
@@ -648,12 +646,12 @@ __global__ __launch_bounds__(KVQ_KW_NT) void kvq_k_quant_wave(const void *__rest
         running += (uint32_t)__popcll(b1);
         if (o0) {
             const uint64_t pos = (uint64_t)base + rank0;
-            if (pos < (uint64_t)cap_nnz) { k_idx[pos] = (uint16_t)c0; k_val[pos] = kvq_f2h_rn(x0 - deq0); }
+            if (pos < (uint64_t)cap_nnz) ksp.put(pos, (uint16_t)c0, kvq_f2h_rn(x0 - deq0));
             else overflow = true;
         }
         if (o1) {
             const uint64_t pos = (uint64_t)base + rank1;
-            if (pos < (uint64_t)cap_nnz) { k_idx[pos] = (uint16_t)c1; k_val[pos] = kvq_f2h_rn(x1 - deq1); }
+            if (pos < (uint64_t)cap_nnz) ksp.put(pos, (uint16_t)c1, kvq_f2h_rn(x1 - deq1));
             else overflow = true;
         }
         // the head's chunk: 64 fields of 2*BITS bits, assembled in the wavefront's LDS slice (LDS
@@ -718,12 +716,11 @@ __device__ __forceinline__ void wave_find_bin(const uint32_t *h256, uint32_t K, 
 // v_quant_token.
 constexpr int KVQ_VW_WAVES = 4;
 constexpr int KVQ_VW_NT = 64 * KVQ_VW_WAVES;
-template <int BITS, int JW>
+template <int BITS, int JW, class SP>
 __device__ __forceinline__ void v_quant_token4(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
                                                int k_side, const uint16_t *__restrict__ v_new,
                                                uint8_t *__restrict__ v_codes, uint16_t *__restrict__ v_sz,
-                                               uint32_t *__restrict__ v_ptr, uint16_t *__restrict__ v_idx,
-                                               uint16_t *__restrict__ v_val, int64_t cap_nnz, int32_t *d_status,
+                                               uint32_t *__restrict__ v_ptr, const SP vsp, int64_t cap_nnz, int32_t *d_status,
                                                const int t)
 {
     constexpr int NE = 1 << BITS;
@@ -899,7 +896,7 @@ __device__ __forceinline__ void v_quant_token4(const void *__restrict__ params, 
         const unsigned long long b = __ballot(is_out);
         if (is_out) {
             const uint64_t pos = (uint64_t)base + running + (uint32_t)__popcll(b & lt_mask);
-            if (pos < (uint64_t)cap_nnz) { v_idx[pos] = (uint16_t)(64 * j + lane); v_val[pos] = kvq_f2h_rn(x - deq); }
+            if (pos < (uint64_t)cap_nnz) vsp.put(pos, (uint16_t)(64 * j + lane), kvq_f2h_rn(x - deq));
             else overflow = true;
         }
         running += (uint32_t)__popcll(b);
@@ -929,39 +926,36 @@ __device__ __forceinline__ void v_quant_token4(const void *__restrict__ params, 
     if (overflow) atomicExch(d_status, (int32_t)KVQ_ERR_NNZ_OVERFLOW);
 }
 
-template <int BITS, int JW>
+template <int BITS, int JW, class SP>
 __global__ __launch_bounds__(KVQ_VW_NT) void kvq_v_quant4(const void *__restrict__ params, int D, int64_t cap,
                                                           int64_t n0, int k_side, const uint16_t *__restrict__ v_new,
                                                           uint8_t *__restrict__ v_codes, uint16_t *__restrict__ v_sz,
-                                                          uint32_t *__restrict__ v_ptr, uint16_t *__restrict__ v_idx,
-                                                          uint16_t *__restrict__ v_val, int64_t cap_nnz,
+                                                          uint32_t *__restrict__ v_ptr, const SP vsp, int64_t cap_nnz,
                                                           int32_t *d_status)
 {
-    v_quant_token4<BITS, JW>(params, D, cap, n0, k_side, v_new, v_codes, v_sz, v_ptr, v_idx, v_val, cap_nnz, d_status,
+    v_quant_token4<BITS, JW>(params, D, cap, n0, k_side, v_new, v_codes, v_sz, v_ptr, vsp, cap_nnz, d_status,
                              (int)blockIdx.x);
 }
 
-template <int BITS, int NT>
+template <int BITS, int NT, class SP>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT == 256 ? 8 : 4)))
 void kvq_k_quant(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
                                                   const uint16_t *__restrict__ k_new, uint8_t *__restrict__ k_codes,
-                                                  uint32_t *__restrict__ k_ptr, uint16_t *__restrict__ k_idx,
-                                                  uint16_t *__restrict__ k_val, int64_t cap_nnz, int single,
+                                                  uint32_t *__restrict__ k_ptr, const SP ksp, int64_t cap_nnz, int single,
                                                   int32_t *d_status)
 {
-    k_quant_token<BITS, NT>(params, D, cap, n0, k_new, k_codes, k_ptr, k_idx, k_val, cap_nnz, single, d_status,
+    k_quant_token<BITS, NT>(params, D, cap, n0, k_new, k_codes, k_ptr, ksp, cap_nnz, single, d_status,
                             (int)blockIdx.x);
 }
 
-template <int BITS, int NT>
+template <int BITS, int NT, class SP>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT == 256 ? 8 : 4)))
 void kvq_v_quant(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
                                                   int k_side, const uint16_t *__restrict__ v_new,
                                                   uint8_t *__restrict__ v_codes, uint16_t *__restrict__ v_sz,
-                                                  uint32_t *__restrict__ v_ptr, uint16_t *__restrict__ v_idx,
-                                                  uint16_t *__restrict__ v_val, int64_t cap_nnz, int32_t *d_status)
+                                                  uint32_t *__restrict__ v_ptr, const SP vsp, int64_t cap_nnz, int32_t *d_status)
 {
-    v_quant_token<BITS, NT>(params, D, cap, n0, k_side, v_new, v_codes, v_sz, v_ptr, v_idx, v_val, cap_nnz, d_status,
+    v_quant_token<BITS, NT>(params, D, cap, n0, k_side, v_new, v_codes, v_sz, v_ptr, vsp, cap_nnz, d_status,
                             (int)blockIdx.x);
 }
 
@@ -1038,6 +1032,7 @@ __global__ __launch_bounds__(NT) void kvq_calib_channel(const uint16_t *__restri
 
 // Keys and Values of the same tokens in one launch: even workgroups take a token's Keys, odd ones its
 // Values (a single-token append is pure latency, and the two do not depend on each other).
+template <class SP>
 struct KvAppendArgs {
     const void *params;
     int D, k_side, single;
@@ -1046,30 +1041,28 @@ struct KvAppendArgs {
     uint8_t *k_codes, *v_codes;
     uint16_t *v_sz;
     uint32_t *k_ptr, *v_ptr;
-    uint16_t *k_idx, *k_val, *v_idx, *v_val;
+    SP ksp, vsp;
     int32_t *d_status;
 };
-template <int BITS, int NT>
-__global__ __launch_bounds__(NT) void kvq_kv_quant(const KvAppendArgs a)
+template <int BITS, int NT, class SP>
+__global__ __launch_bounds__(NT) void kvq_kv_quant(const KvAppendArgs<SP> a)
 {
     const int t = (int)(blockIdx.x >> 1);
     if ((blockIdx.x & 1) == 0)
-        k_quant_token<BITS, NT>(a.params, a.D, a.cap, a.n0_k, a.k_new, a.k_codes, a.k_ptr, a.k_idx, a.k_val, a.cap_nnz_k,
+        k_quant_token<BITS, NT>(a.params, a.D, a.cap, a.n0_k, a.k_new, a.k_codes, a.k_ptr, a.ksp, a.cap_nnz_k,
                                 a.single, a.d_status, t);
     else if (a.D == 4096 || a.D == 2048 || a.D == 1024) {
         // the four-wavefront routine; further wavefronts of the workgroup end here (a barrier waits
         // only for the wavefronts that have not ended)
         if (threadIdx.x >= KVQ_VW_NT) return;
 #define V4(J)                                                                                                    \
-    v_quant_token4<BITS, J>(a.params, a.D, a.cap, a.n0_v, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, a.v_idx, \
-                            a.v_val, a.cap_nnz_v, a.d_status, t)
+    v_quant_token4<BITS, J>(a.params, a.D, a.cap, a.n0_v, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, a.vsp, a.cap_nnz_v, a.d_status, t)
         if (a.D == 4096) V4(16);
         else if (a.D == 2048) V4(8);
         else V4(4);
 #undef V4
     } else
-        v_quant_token<BITS, NT>(a.params, a.D, a.cap, a.n0_v, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, a.v_idx,
-                                a.v_val, a.cap_nnz_v, a.d_status, t);
+        v_quant_token<BITS, NT>(a.params, a.D, a.cap, a.n0_v, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, a.vsp, a.cap_nnz_v, a.d_status, t);
 }
 
 }  // namespace
@@ -1119,19 +1112,24 @@ extern "C" kvq_status kvq_quantize_append_k(kvq_cache *cache, const uint16_t *d_
         if (T >= KVQ_WAVE_TOKENS)                                                                               \
             kvq_k_quant_wave<B><<<(T + KVQ_KW_NT / 64 - 1) / (KVQ_KW_NT / 64), KVQ_KW_NT, 0, s>>>(               \
                 cache->params, D, T, cache->cap_tokens, cache->n_tokens_k, d_k_new, cache->k_codes,              \
-                cache->k_ptr, cache->k_idx, cache->k_val, cache->cap_nnz_k, cache->d_status);                    \
+                cache->k_ptr, ksp, cache->cap_nnz_k, cache->d_status);                                           \
         else if (wide_wg(D, T))                                                                                 \
             kvq_k_quant<B, 1024><<<T, 1024, 0, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_k,      \
-                                                    d_k_new, cache->k_codes, cache->k_ptr, cache->k_idx,         \
-                                                    cache->k_val, cache->cap_nnz_k, single, cache->d_status);    \
+                                                    d_k_new, cache->k_codes, cache->k_ptr, ksp, cache->cap_nnz_k,    \
+                                                    single, cache->d_status);                                    \
         else                                                                                                    \
             kvq_k_quant<B, 256><<<T, 256, 0, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_k,        \
-                                                  d_k_new, cache->k_codes, cache->k_ptr, cache->k_idx,           \
-                                                  cache->k_val, cache->cap_nnz_k, single, cache->d_status);      \
+                                                  d_k_new, cache->k_codes, cache->k_ptr, ksp, cache->cap_nnz_k,      \
+                                                  single, cache->d_status);                                      \
     } while (0)
-    if (cache->bits == 2) LAUNCH_K(2);
-    else if (cache->bits == 3) LAUNCH_K(3);
-    else LAUNCH_K(4);
+    // one set of kernels per layout of the outlier entries (flat arrays or a list of blocks)
+    const auto launch = [&](const auto ksp) {
+        if (cache->bits == 2) LAUNCH_K(2);
+        else if (cache->bits == 3) LAUNCH_K(3);
+        else LAUNCH_K(4);
+    };
+    if (cache->nnz_block_shift) launch(kvq_blocked_k(cache));
+    else launch(kvq_flat_k(cache));
 #undef LAUNCH_K
     KVQ_HIP_CHECK(hipGetLastError());
     st = copy_sink_rows(cache, cache->sink_k, d_k_new, cache->n_tokens_k, T, s);
@@ -1152,7 +1150,7 @@ extern "C" kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_
 #define LAUNCH_V4(B, J)                                                                                        \
     kvq_v_quant4<B, J><<<T, KVQ_VW_NT, 0, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v,         \
                                                cache->k_side_v, d_v_new, cache->v_codes, cache->v_sz,          \
-                                               cache->v_ptr, cache->v_idx, cache->v_val, cache->cap_nnz_v,     \
+                                               cache->v_ptr, vsp, cache->cap_nnz_v,                           \
                                                cache->d_status)
 #define LAUNCH_V(B)                                                                                             \
     do {                                                                                                        \
@@ -1165,17 +1163,21 @@ extern "C" kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_
         else if (wide_wg(D, T))                                                                                 \
             kvq_v_quant<B, 1024><<<T, 1024, dyn, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v,    \
                                                       cache->k_side_v, d_v_new, cache->v_codes, cache->v_sz,     \
-                                                      cache->v_ptr, cache->v_idx, cache->v_val,                  \
+                                                      cache->v_ptr, vsp,                                         \
                                                       cache->cap_nnz_v, cache->d_status);                        \
         else                                                                                                    \
             kvq_v_quant<B, 256><<<T, 256, dyn, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v,      \
                                                     cache->k_side_v, d_v_new, cache->v_codes, cache->v_sz,       \
-                                                    cache->v_ptr, cache->v_idx, cache->v_val, cache->cap_nnz_v,  \
+                                                    cache->v_ptr, vsp, cache->cap_nnz_v,                        \
                                                     cache->d_status);                                            \
     } while (0)
-    if (cache->bits == 2) LAUNCH_V(2);
-    else if (cache->bits == 3) LAUNCH_V(3);
-    else LAUNCH_V(4);
+    const auto launch = [&](const auto vsp) {
+        if (cache->bits == 2) LAUNCH_V(2);
+        else if (cache->bits == 3) LAUNCH_V(3);
+        else LAUNCH_V(4);
+    };
+    if (cache->nnz_block_shift) launch(kvq_blocked_v(cache));
+    else launch(kvq_flat_v(cache));
 #undef LAUNCH_V
 #undef LAUNCH_V4
     KVQ_HIP_CHECK(hipGetLastError());
@@ -1213,24 +1215,28 @@ extern "C" kvq_status kvq_quantize_append_kv(kvq_cache *cache, const uint16_t *d
         kvq_k_count<<<(T + KVQ_COUNT_NT / 64 - 1) / (KVQ_COUNT_NT / 64), KVQ_COUNT_NT, 0, s>>>(cache->params, D, T, d_k_new, cnt);
         kvq_ptr_scan<<<1, 1024, 0, s>>>(cache->k_ptr, cache->n_tokens_k, T, cnt, cache->cap_nnz_k, cache->d_status);
     }
-    KvAppendArgs a;
-    a.params = cache->params; a.D = D; a.k_side = cache->k_side_v; a.single = single;
-    a.cap = cache->cap_tokens; a.n0_k = cache->n_tokens_k; a.n0_v = cache->n_tokens_v;
-    a.cap_nnz_k = cache->cap_nnz_k; a.cap_nnz_v = cache->cap_nnz_v;
-    a.k_new = d_k_new; a.v_new = d_v_new;
-    a.k_codes = cache->k_codes; a.v_codes = cache->v_codes; a.v_sz = cache->v_sz;
-    a.k_ptr = cache->k_ptr; a.v_ptr = cache->v_ptr;
-    a.k_idx = cache->k_idx; a.k_val = cache->k_val; a.v_idx = cache->v_idx; a.v_val = cache->v_val;
-    a.d_status = cache->d_status;
     const size_t dyn = 3 * (size_t)D;
 #define LAUNCH_KV(B)                                                                     \
     do {                                                                                 \
         if (wide_wg(D, T)) kvq_kv_quant<B, 1024><<<2 * T, 1024, dyn, s>>>(a);            \
         else kvq_kv_quant<B, 256><<<2 * T, 256, dyn, s>>>(a);                            \
     } while (0)
-    if (cache->bits == 2) LAUNCH_KV(2);
-    else if (cache->bits == 3) LAUNCH_KV(3);
-    else LAUNCH_KV(4);
+    const auto launch = [&](const auto ksp, const auto vsp) {
+        KvAppendArgs<std::remove_cv_t<decltype(ksp)>> a;
+        a.params = cache->params; a.D = D; a.k_side = cache->k_side_v; a.single = single;
+        a.cap = cache->cap_tokens; a.n0_k = cache->n_tokens_k; a.n0_v = cache->n_tokens_v;
+        a.cap_nnz_k = cache->cap_nnz_k; a.cap_nnz_v = cache->cap_nnz_v;
+        a.k_new = d_k_new; a.v_new = d_v_new;
+        a.k_codes = cache->k_codes; a.v_codes = cache->v_codes; a.v_sz = cache->v_sz;
+        a.k_ptr = cache->k_ptr; a.v_ptr = cache->v_ptr;
+        a.ksp = ksp; a.vsp = vsp;
+        a.d_status = cache->d_status;
+        if (cache->bits == 2) LAUNCH_KV(2);
+        else if (cache->bits == 3) LAUNCH_KV(3);
+        else LAUNCH_KV(4);
+    };
+    if (cache->nnz_block_shift) launch(kvq_blocked_k(cache), kvq_blocked_v(cache));
+    else launch(kvq_flat_k(cache), kvq_flat_v(cache));
 #undef LAUNCH_KV
     KVQ_HIP_CHECK(hipGetLastError());
     st = copy_sink_rows(cache, cache->sink_k, d_k_new, cache->n_tokens_k, T, s);

@@ -72,3 +72,26 @@ extern "C" kvq_status kvq_attention_decode_noalloc(const kvq_cache *cache, const
     view.workspace_bytes = KVQ_NOALLOC_BYTES;
     return kvq_attention_decode(&view, d_q_rot, scale, d_scores, ld_scores, d_out, stream);
 }
+
+// One generation step in one call: append the new token's Key and Value, then attend over the cache
+// that now ends with it.  Everything the host can check for the attention half is checked before
+// the append is launched, so that a rejected call leaves the cache as it was.
+extern "C" kvq_status kvq_decode_step(kvq_cache *cache, const uint16_t *d_k_new, const uint16_t *d_v_new,
+                                      const float *d_q_rot, float scale, float *d_scores, int64_t ld_scores,
+                                      float *d_out, void *stream)
+{
+    kvq_status st = kvq_check_cache(cache);
+    if (st != KVQ_OK) return st;
+    if (!cache->loaded) return KVQ_ERR_NOT_LOADED;
+    if (cache->n_tokens_k != cache->n_tokens_v) return KVQ_ERR_INVALID_ARG;
+    if (!d_q_rot || !d_scores || !d_out || ((uintptr_t)d_q_rot & 3) || ((uintptr_t)d_scores & 3) ||
+        ((uintptr_t)d_out & 3))
+        return KVQ_ERR_INVALID_ARG;
+    if (ld_scores < cache->n_tokens_k + 1) return KVQ_ERR_INVALID_ARG;
+    const int64_t need = kvq_pv_workspace_bytes(cache->n_q_heads) +
+                         (int64_t)cache->n_q_heads * KVQ_STAT_SLOTS * (int64_t)sizeof(float);
+    if (!cache->workspace || cache->workspace_bytes < need) return KVQ_ERR_CAPACITY;
+    st = kvq_quantize_append_kv(cache, d_k_new, d_v_new, 1, stream);
+    if (st != KVQ_OK) return st;
+    return kvq_attention_decode(cache, d_q_rot, scale, d_scores, ld_scores, d_out, stream);
+}

@@ -149,18 +149,43 @@ __device__ __forceinline__ void kvq_lds_add_fixed(unsigned long long *cell, floa
 
 // ---- helpers shared by the two balanced sparse kernels (lanes = outlier entries) ----------------
 
+// Where the (channel index, residual) entries of one side of the cache live: two flat arrays, or
+// lists of blocks (paper App. "Limitations": the outlier storage allocated in blocks, so that an
+// append never copies what is stored).  The kernels that touch the entries are templates over the
+// two, so the flat layout pays nothing for the other.
+struct KvqSparseFlat {
+    uint16_t *idx, *val;
+    __device__ __forceinline__ void put(uint64_t e, uint16_t i, uint16_t v) const
+    {
+        idx[e] = i;
+        val[e] = v;
+    }
+};
+// Entry e is element e & (2^shift - 1) of block e >> shift; idx_b / val_b are device arrays of device
+// pointers, one per block, every slot below the capacity valid.
+struct KvqSparseBlocked {
+    uint16_t *const *idx_b, *const *val_b;
+    int shift;
+    __device__ __forceinline__ void put(uint64_t e, uint16_t i, uint16_t v) const
+    {
+        const uint64_t b = e >> shift, o = e & ((1ull << shift) - 1);
+        idx_b[b][o] = i;
+        val_b[b][o] = v;
+    }
+};
+
 // One batch of U x 64 index/value loads starting at entry `eb` (lane l takes entries eb + l + 64 u).
 // CLAMP = false: the whole batch lies inside the arrays (possibly past the sub-range's end `e_end`,
 // where the loaded values are ignored), one address per lane plus immediate offsets; CLAMP = true:
 // lanes past the end re-read the last entry.  Groups of 64 entries that lie entirely past `e_end`
-// are skipped (a wavefront-uniform branch).
+// are skipped (a wavefront-uniform branch).  `nnz_cap` is the capacity in entries.
 template <bool CLAMP, int U>
-__device__ __forceinline__ void kvq_sparse_load_batch(const uint16_t *__restrict__ idx,
-                                                      const uint16_t *__restrict__ val, uint32_t eb,
+__device__ __forceinline__ void kvq_sparse_load_batch(const KvqSparseFlat &sp, uint32_t /*nnz_cap*/, uint32_t eb,
                                                       uint32_t e_end, int lane, uint32_t (&chv)[U],
                                                       uint32_t (&vb)[U])
 {
-    const char *ib = (const char *)idx, *vbp = (const char *)val;
+    const char *__restrict__ ib = (const char *)sp.idx;
+    const char *__restrict__ vbp = (const char *)sp.val;
     if (!CLAMP) {
         const uint32_t off0 = (eb + (uint32_t)lane) * 2u;
 #pragma unroll
@@ -178,6 +203,33 @@ __device__ __forceinline__ void kvq_sparse_load_batch(const uint16_t *__restrict
             chv[u] = *(const uint16_t *)(ib + (size_t)(e * 2u));
             vb[u] = *(const uint16_t *)(vbp + (size_t)(e * 2u));
         }
+    }
+}
+
+// Blocked storage: a block holds at least 1024 entries and a batch fewer, so a batch touches the
+// block of its first entry and at most the one after; `eb` is wavefront-uniform, which makes the
+// block pointers scalar loads.
+template <bool CLAMP, int U>
+__device__ __forceinline__ void kvq_sparse_load_batch(const KvqSparseBlocked &sp, uint32_t nnz_cap, uint32_t eb,
+                                                      uint32_t e_end, int lane, uint32_t (&chv)[U],
+                                                      uint32_t (&vb)[U])
+{
+    static_assert(64 * U <= (1 << KVQ_NNZ_BLOCK_SHIFT_MIN), "a batch must fit in the smallest block");
+    const uint32_t sh = (uint32_t)sp.shift, mask = (1u << sh) - 1u;
+    const uint32_t b0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(eb >> sh));
+    const uint32_t n_blocks = nnz_cap >> sh;
+    const uint32_t b1 = (b0 + 1u < n_blocks) ? b0 + 1u : b0;
+    const uint16_t *i0 = sp.idx_b[b0], *v0 = sp.val_b[b0];
+    const uint16_t *i1 = sp.idx_b[b1], *v1 = sp.val_b[b1];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (eb + 64u * u >= e_end) break;
+        uint32_t e = eb + (uint32_t)lane + 64u * u;
+        if (CLAMP) e = (e < e_end) ? e : e_end - 1;
+        const bool first = (e >> sh) == b0;
+        const uint32_t o = e & mask;
+        chv[u] = (first ? i0 : i1)[o];
+        vb[u] = (first ? v0 : v1)[o];
     }
 }
 
@@ -339,13 +391,38 @@ static inline kvq_status kvq_check_cache(const kvq_cache *c)
     if (c->cap_tokens <= 0 || (c->cap_tokens & 127) || c->cap_tokens >= ((int64_t)1 << 24)) return KVQ_ERR_INVALID_ARG;
     if (c->n_tokens_k < 0 || c->n_tokens_k > c->cap_tokens || c->n_tokens_v < 0 || c->n_tokens_v > c->cap_tokens)
         return KVQ_ERR_INVALID_ARG;
-    const void *ptrs[] = {c->params, c->k_codes, c->v_codes, c->v_sz, c->k_ptr, c->v_ptr,
-                          c->k_idx, c->k_val, c->v_idx, c->v_val, c->d_status};
+    const void *ptrs[] = {c->params, c->k_codes, c->v_codes, c->v_sz, c->k_ptr, c->v_ptr, c->d_status};
     for (const void *p : ptrs)
         if (!p || ((uintptr_t)p & 15)) return KVQ_ERR_INVALID_ARG;
+    if (c->nnz_block_shift == 0) {
+        const void *flat[] = {c->k_idx, c->k_val, c->v_idx, c->v_val};
+        for (const void *p : flat)
+            if (!p || ((uintptr_t)p & 15)) return KVQ_ERR_INVALID_ARG;
+    } else {
+        // blocked sparse arrays: 2^10 .. 2^30 entries per block, whole blocks, at least one
+        if (c->nnz_block_shift < KVQ_NNZ_BLOCK_SHIFT_MIN || c->nnz_block_shift > KVQ_NNZ_BLOCK_SHIFT_MAX)
+            return KVQ_ERR_INVALID_ARG;
+        const int64_t be = (int64_t)1 << c->nnz_block_shift;
+        if (c->cap_nnz_k < be || (c->cap_nnz_k & (be - 1)) || c->cap_nnz_v < be || (c->cap_nnz_v & (be - 1)))
+            return KVQ_ERR_INVALID_ARG;
+        const void *tabs[] = {c->k_idx_blocks, c->k_val_blocks, c->v_idx_blocks, c->v_val_blocks};
+        for (const void *p : tabs)
+            if (!p || ((uintptr_t)p & 7)) return KVQ_ERR_INVALID_ARG;
+    }
     if (c->workspace && ((uintptr_t)c->workspace & 15)) return KVQ_ERR_INVALID_ARG;
     if (c->n_sink < 0 || c->n_sink > KVQ_MAX_SINK) return KVQ_ERR_INVALID_ARG;
     if (c->n_sink > 0 && (!c->sink_k || !c->sink_v || ((uintptr_t)c->sink_k & 15) || ((uintptr_t)c->sink_v & 15)))
         return KVQ_ERR_INVALID_ARG;
     return KVQ_OK;
+}
+
+static inline KvqSparseFlat kvq_flat_k(const kvq_cache *c) { return KvqSparseFlat{c->k_idx, c->k_val}; }
+static inline KvqSparseFlat kvq_flat_v(const kvq_cache *c) { return KvqSparseFlat{c->v_idx, c->v_val}; }
+static inline KvqSparseBlocked kvq_blocked_k(const kvq_cache *c)
+{
+    return KvqSparseBlocked{c->k_idx_blocks, c->k_val_blocks, c->nnz_block_shift};
+}
+static inline KvqSparseBlocked kvq_blocked_v(const kvq_cache *c)
+{
+    return KvqSparseBlocked{c->v_idx_blocks, c->v_val_blocks, c->nnz_block_shift};
 }

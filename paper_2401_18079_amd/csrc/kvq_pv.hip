@@ -306,10 +306,10 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
 // R = query heads per KV head (0: any ratio, looked up at run time); SINK: the cache keeps its first
 // n_sink tokens in fp16; FUSED: `probs` holds raw scores, see below (separate instantiations: the
 // plain one has no register to spare)
-template <int R, bool SINK, bool FUSED>
+template <int R, bool SINK, bool FUSED, class SP>
 __global__ __launch_bounds__(768) __attribute__((amdgpu_waves_per_eu(6, 6)))
 void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__restrict__ v_ptr,
-                   const uint16_t *__restrict__ v_idx, const uint16_t *__restrict__ v_val, uint32_t nnz_cap,
+                   const SP vsp, uint32_t nnz_cap,
                    const float *__restrict__ probs, int64_t ld, float *__restrict__ spartial, int64_t tokens_per_wave,
                    int n_sink, const float *__restrict__ stat_slots, int n_stat)
 {
@@ -374,8 +374,8 @@ void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__r
         const uint32_t e_end = (uint32_t)__builtin_amdgcn_readlane((int)pw, 63);
         uint32_t chv[PVS_U], vb[PVS_U];
         if (e_begin < e_end) {
-            if (e_begin + 64u * PVS_U <= nnz_cap) kvq_sparse_load_batch<false, PVS_U>(v_idx, v_val, e_begin, e_end, lane, chv, vb);
-            else kvq_sparse_load_batch<true, PVS_U>(v_idx, v_val, e_begin, e_end, lane, chv, vb);
+            if (e_begin + 64u * PVS_U <= nnz_cap) kvq_sparse_load_batch<false, PVS_U>(vsp, nnz_cap, e_begin, e_end, lane, chv, vb);
+            else kvq_sparse_load_batch<true, PVS_U>(vsp, nnz_cap, e_begin, e_end, lane, chv, vb);
         }
         uint32_t pw_next = 0;
         if (tc_next > 0) pw_next = v_ptr[nc_next + (lane < tc_next ? lane : tc_next)];
@@ -413,8 +413,8 @@ void kvq_pv_sparse(int n_kv_heads, int n_q_heads, int64_t L, const uint32_t *__r
         int tcur = 0;
         for (uint32_t eb = e_begin; eb < e_end; eb += 64 * PVS_U) {
             if (eb != e_begin) {                         // (the first batch was requested above)
-                if (eb + 64u * PVS_U <= nnz_cap) kvq_sparse_load_batch<false, PVS_U>(v_idx, v_val, eb, e_end, lane, chv, vb);
-                else kvq_sparse_load_batch<true, PVS_U>(v_idx, v_val, eb, e_end, lane, chv, vb);
+                if (eb + 64u * PVS_U <= nnz_cap) kvq_sparse_load_batch<false, PVS_U>(vsp, nnz_cap, eb, e_end, lane, chv, vb);
+                else kvq_sparse_load_batch<true, PVS_U>(vsp, nnz_cap, eb, e_end, lane, chv, vb);
             }
 #pragma unroll
             for (int u = 0; u < PVS_U; ++u) {
@@ -546,6 +546,43 @@ extern "C" kvq_status kvq_pv_matvec(const kvq_cache *cache, const float *d_probs
     return kvq_pv_run(cache, d_probs, ld_probs, d_out, nullptr, 0, (hipStream_t)stream);
 }
 
+// Launch of the sparse kernel for either layout of the outlier entries.  ri: index of the head ratio
+// among {any, 1, 2, 4, 8}.
+template <class SP>
+static kvq_status pv_launch_sparse(const kvq_cache *cache, const SP vsp, int ri, bool sink, bool fused,
+                                   const PvPlan &plan, const float *d_probs, int64_t ld_probs, float *spartial,
+                                   const float *stat_slots, int n_stat, hipStream_t s)
+{
+    using SparseKernel = decltype(&kvq_pv_sparse<0, false, false, SP>);
+#define KVQ_PVS_ROW(R) {{kvq_pv_sparse<R, false, false, SP>, kvq_pv_sparse<R, false, true, SP>},       \
+                        {kvq_pv_sparse<R, true, false, SP>, kvq_pv_sparse<R, true, true, SP>}}
+    static const SparseKernel kernels[5][2][2] = {KVQ_PVS_ROW(0), KVQ_PVS_ROW(1), KVQ_PVS_ROW(2), KVQ_PVS_ROW(4),
+                                                  KVQ_PVS_ROW(8)};
+#undef KVQ_PVS_ROW
+    const SparseKernel sparse = kernels[ri][sink][fused];
+    // every instantiation's dynamic-LDS limit is raised once, to the most a plan asks for
+    // (initialisation of a function-local static is thread-safe)
+    static const hipError_t lds_attr = [] {
+        for (auto &a : kernels)
+            for (auto &b : a)
+                for (SparseKernel k : b) {
+                    const hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, 147456);
+                    if (e != hipSuccess) return e;
+                }
+        return hipSuccess;
+    }();
+    KVQ_HIP_CHECK(lds_attr);
+    if (plan.slds > 147456) return KVQ_ERR_UNSUPPORTED;
+    // (Running this kernel on a second stream beside the dense one was tried: its LDS footprint
+    // evicts dense workgroups from the CUs and the pair gets slower.)
+    if (cache->cap_nnz_v >= ((int64_t)1 << 31)) return KVQ_ERR_UNSUPPORTED;      // byte offsets are 32-bit
+    sparse<<<plan.sslabs, 64 * plan.swaves, plan.slds, s>>>(cache->n_kv_heads, cache->n_q_heads, cache->n_tokens_v,
+                                                            cache->v_ptr, vsp, (uint32_t)cache->cap_nnz_v, d_probs,
+                                                            ld_probs, spartial, plan.tokens_per_swave,
+                                                            cache->n_sink, stat_slots, n_stat);
+    return KVQ_OK;
+}
+
 kvq_status kvq_pv_run(const kvq_cache *cache, const float *d_probs, int64_t ld_probs, float *d_out,
                       const float *stat_slots, int n_stat, hipStream_t s)
 {
@@ -567,33 +604,12 @@ kvq_status kvq_pv_run(const kvq_cache *cache, const float *d_probs, int64_t ld_p
         const bool sink = cache->n_sink > 0;
         const int ri = (r == 1) ? 1 : (r == 2) ? 2 : (r == 4) ? 3 : (r == 8) ? 4 : 0;
         const bool fused = stat_slots != nullptr;
-        using SparseKernel = decltype(&kvq_pv_sparse<0, false, false>);
-#define KVQ_PVS_ROW(R) {{kvq_pv_sparse<R, false, false>, kvq_pv_sparse<R, false, true>},       \
-                        {kvq_pv_sparse<R, true, false>, kvq_pv_sparse<R, true, true>}}
-        static const SparseKernel kernels[5][2][2] = {KVQ_PVS_ROW(0), KVQ_PVS_ROW(1), KVQ_PVS_ROW(2), KVQ_PVS_ROW(4),
-                                                      KVQ_PVS_ROW(8)};
-#undef KVQ_PVS_ROW
-        const SparseKernel sparse = kernels[ri][sink][fused];
-        // every instantiation's dynamic-LDS limit is raised once, to the most a plan asks for
-        // (initialisation of a function-local static is thread-safe)
-        static const hipError_t lds_attr = [] {
-            for (auto &a : kernels)
-                for (auto &b : a)
-                    for (SparseKernel k : b) {
-                        const hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, 147456);
-                        if (e != hipSuccess) return e;
-                    }
-            return hipSuccess;
-        }();
-        KVQ_HIP_CHECK(lds_attr);
-        if (plan.slds > 147456) return KVQ_ERR_UNSUPPORTED;
-        // (Running this kernel on a second stream beside the dense one was tried: its LDS footprint
-        // evicts dense workgroups from the CUs and the pair gets slower.)
-        if (cache->cap_nnz_v >= ((int64_t)1 << 31)) return KVQ_ERR_UNSUPPORTED;      // byte offsets are 32-bit
-        sparse<<<plan.sslabs, 64 * plan.swaves, plan.slds, s>>>(cache->n_kv_heads, Hq, L, cache->v_ptr, cache->v_idx,
-                                                                cache->v_val, (uint32_t)cache->cap_nnz_v, d_probs,
-                                                                ld_probs, spartial, plan.tokens_per_swave,
-                                                                cache->n_sink, stat_slots, n_stat);
+        st = cache->nnz_block_shift
+                 ? pv_launch_sparse(cache, kvq_blocked_v(cache), ri, sink, fused, plan, d_probs, ld_probs, spartial,
+                                    stat_slots, n_stat, s)
+                 : pv_launch_sparse(cache, kvq_flat_v(cache), ri, sink, fused, plan, d_probs, ld_probs, spartial,
+                                    stat_slots, n_stat, s);
+        if (st != KVQ_OK) return st;
 
         dim3 grid((unsigned)plan.slabs, (unsigned)((2 * Hq + PV_WAVES - 1) / PV_WAVES));
 #define LAUNCH_PV(B, G)                                                                                        \

@@ -754,11 +754,11 @@ __host__ __device__ constexpr int qs_wave_lds_bytes(int n_q_heads, int tw)
     return ((n_q_heads * qs_row(tw) * 8 + 15) & ~15) + 64 * 8;   // sums, per-pair angles
 }
 
-template <int R, int QS_TW>
+template <int R, int QS_TW, class SP>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_t L,
-                   const uint32_t *__restrict__ k_ptr, const uint16_t *__restrict__ k_idx,
-                   const uint16_t *__restrict__ k_val, uint32_t nnz_cap, const float *__restrict__ q_rot,
+                   const uint32_t *__restrict__ k_ptr, const SP ksp, uint32_t nnz_cap,
+                   const float *__restrict__ q_rot,
                    float scale, float *__restrict__ scores, int64_t ld, int64_t tokens_per_wave)
 {
     const int bx = (int)blockIdx.x;
@@ -801,15 +801,15 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
 #pragma unroll
                 for (int u = 0; u < QS_U; ++u) { chv[u] = chn[u]; vb[u] = vbn[u]; }
             } else if (e_begin + 64u * QS_U <= nnz_cap) {
-                kvq_sparse_load_batch<false, QS_U>(k_idx, k_val, e_begin, e_end, lane, chv, vb);
+                kvq_sparse_load_batch<false, QS_U>(ksp, nnz_cap, e_begin, e_end, lane, chv, vb);
             } else {
-                kvq_sparse_load_batch<true, QS_U>(k_idx, k_val, e_begin, e_end, lane, chv, vb);
+                kvq_sparse_load_batch<true, QS_U>(ksp, nnz_cap, e_begin, e_end, lane, chv, vb);
             }
         }
         // the next sub-range's entries follow this one's: request its first batch now (its end is not
         // known yet, so the whole batch is requested, which must then lie inside the arrays)
         have_next = tc_next > 0 && e_end + 64u * QS_U <= nnz_cap;
-        if (have_next) kvq_sparse_load_batch<false, QS_U>(k_idx, k_val, e_end, 0xFFFFFFFFu, lane, chn, vbn);
+        if (have_next) kvq_sparse_load_batch<false, QS_U>(ksp, nnz_cap, e_end, 0xFFFFFFFFu, lane, chn, vbn);
         uint32_t pw_next = 0;
         if (tc_next > 0) pw_next = k_ptr[nc_next + (lane < tc_next ? lane : tc_next)];
         ang[lane] = float2_t{rope_rev((float)nc, my_vh, my_vl), my_vh};
@@ -823,9 +823,9 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
         for (uint32_t eb = e_begin; eb < e_end; eb += 64 * QS_U) {
             if (eb != e_begin) {                         // (the first batch was requested above)
                 if (eb + 64u * QS_U <= nnz_cap)
-                    kvq_sparse_load_batch<false, QS_U>(k_idx, k_val, eb, e_end, lane, chv, vb);
+                    kvq_sparse_load_batch<false, QS_U>(ksp, nnz_cap, eb, e_end, lane, chv, vb);
                 else
-                    kvq_sparse_load_batch<true, QS_U>(k_idx, k_val, eb, e_end, lane, chv, vb);
+                    kvq_sparse_load_batch<true, QS_U>(ksp, nnz_cap, eb, e_end, lane, chv, vb);
             }
 #pragma unroll
             for (int u = 0; u < QS_U; ++u) {
@@ -871,8 +871,8 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
     if (!staged) __syncthreads();        // a wavefront without tokens still meets the workgroup's barrier
 }
 
-template <int R, int TW>
-kvq_status launch_qk_sparse_tw(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
+template <int R, int TW, class SP>
+kvq_status launch_qk_sparse_tw(const kvq_cache *c, const SP ksp, const float *q, float scale, float *scores, int64_t ld, hipStream_t s)
 {
     const int Hq = c->n_q_heads;
     const int64_t L = c->n_tokens_k;
@@ -885,7 +885,7 @@ kvq_status launch_qk_sparse_tw(const kvq_cache *c, const float *q, float scale, 
     const size_t lds = (size_t)Hq * 512 + (size_t)waves * per_wave;
     // the kernel's dynamic-LDS limit is raised once per instantiation, to the most any launch asks for
     // (initialisation of a function-local static is thread-safe)
-    static const hipError_t lds_attr = hipFuncSetAttribute((const void *)kvq_qk_sparse<R, TW>,
+    static const hipError_t lds_attr = hipFuncSetAttribute((const void *)kvq_qk_sparse<R, TW, SP>,
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, 147456);
     KVQ_HIP_CHECK(lds_attr);
     // as many wavefronts as the chip holds at once (160 KiB of LDS and 32 wavefronts per compute unit),
@@ -898,8 +898,8 @@ kvq_status launch_qk_sparse_tw(const kvq_cache *c, const float *q, float scale, 
     if (TW > 8) tpw = (tpw + TW - 1) / TW * TW;          // whole sub-ranges: full cache lines of scores
     const int64_t n_waves = (L + tpw - 1) / tpw;
     const unsigned grid = (unsigned)((n_waves + waves - 1) / waves);
-    kvq_qk_sparse<R, TW><<<grid, 64 * waves, lds, s>>>(c->params, c->n_kv_heads * KVQ_HEAD_DIM, Hq, L, c->k_ptr,
-                                                       c->k_idx, c->k_val, (uint32_t)c->cap_nnz_k, q, scale, scores,
+    kvq_qk_sparse<R, TW, SP><<<grid, 64 * waves, lds, s>>>(c->params, c->n_kv_heads * KVQ_HEAD_DIM, Hq, L, c->k_ptr,
+                                                       ksp, (uint32_t)c->cap_nnz_k, q, scale, scores,
                                                        ld, tpw);
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
@@ -915,8 +915,15 @@ kvq_status launch_qk_sparse(const kvq_cache *c, const float *q, float scale, flo
     // of 32 tokens (128-byte pieces: whole cache lines) are the better trade.  The array capacity per
     // token is the host's only handle on the density: the entry count lives on the device.
     const int64_t per_token = c->cap_nnz_k / (c->cap_tokens > 0 ? c->cap_tokens : 1);
-    if (per_token < 16 && c->n_q_heads <= 32) return launch_qk_sparse_tw<R, 32>(c, q, scale, scores, ld, s);
-    return launch_qk_sparse_tw<R, 8>(c, q, scale, scores, ld, s);
+    const bool wide = per_token < 16 && c->n_q_heads <= 32;
+    if (c->nnz_block_shift) {
+        const KvqSparseBlocked ksp = kvq_blocked_k(c);
+        return wide ? launch_qk_sparse_tw<R, 32>(c, ksp, q, scale, scores, ld, s)
+                    : launch_qk_sparse_tw<R, 8>(c, ksp, q, scale, scores, ld, s);
+    }
+    const KvqSparseFlat ksp = kvq_flat_k(c);
+    return wide ? launch_qk_sparse_tw<R, 32>(c, ksp, q, scale, scores, ld, s)
+                : launch_qk_sparse_tw<R, 8>(c, ksp, q, scale, scores, ld, s);
 }
 
 // Attention-sink tokens (paper Sec. 3.5): score of query head blockIdx.y against the fp16 Key of token

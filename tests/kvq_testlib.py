@@ -80,10 +80,11 @@ def compare_caches(oc, gc):
     chk("k_ptr", oc.k_ptr[:L + 1], g(gc.k_ptr).view(np.uint32)[:L + 1])
     chk("v_ptr", oc.v_ptr[:L + 1], g(gc.v_ptr).view(np.uint32)[:L + 1])
     nk, nv = int(oc.k_ptr[L]), int(oc.v_ptr[L])
-    chk("k_idx", oc.k_idx[:nk], g(gc.k_idx).view(np.uint16)[:nk])
-    chk("k_val", oc.k_val[:nk], g(gc.k_val).view(np.uint16)[:nk])
-    chk("v_idx", oc.v_idx[:nv], g(gc.v_idx).view(np.uint16)[:nv])
-    chk("v_val", oc.v_val[:nv], g(gc.v_val).view(np.uint16)[:nv])
+    (k_idx, k_val), (v_idx, v_val) = gc.sparse_entries("k", nk), gc.sparse_entries("v", nv)   # flat or blocked
+    chk("k_idx", oc.k_idx[:nk], g(k_idx).view(np.uint16))
+    chk("k_val", oc.k_val[:nk], g(k_val).view(np.uint16))
+    chk("v_idx", oc.v_idx[:nv], g(v_idx).view(np.uint16))
+    chk("v_val", oc.v_val[:nv], g(v_val).view(np.uint16))
     return bad
 
 

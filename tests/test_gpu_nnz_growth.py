@@ -1,6 +1,7 @@
-"""Blocked growth of the sparse outlier arrays (the blocked allocation the paper plans in App. "Limitations"):
-a cache that starts with room for a handful of outliers and grows block by block between appends holds,
-bit for bit, what a cache with the full capacity from the start holds, and the mat-vecs read it the same."""
+"""Growth of FLAT sparse outlier arrays between appends (a larger allocation and a copy of the entries in
+use, amortised by growing in steps): a cache that starts with room for a handful of outliers holds, bit for
+bit, what a cache with the full capacity from the start holds, and the mat-vecs read it the same.  (Blocked
+storage, which grows without copying, has its own test file.)"""
 import numpy as np
 import pytest
 
@@ -12,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("bits,block", [(3, 256), (2, 1000), (4, 64)])
-def test_cache_grown_in_blocks_equals_cache_with_full_capacity(bits, block):
+def test_flat_cache_grown_in_steps_equals_cache_with_full_capacity(bits, block):
     import torch
     import paper_2401_18079_amd as K
     wl = S.workload("c2", n_kv_heads=4, n_q_heads=8, bits=bits)
