@@ -714,9 +714,13 @@ __device__ __forceinline__ void wave_find_bin(const uint32_t *h256, uint32_t K, 
 // are gathered in the wavefront's LDS slice and written by all 64 lanes at the end.  Five workgroup
 // barriers per token (six when equal keys must be ranked).  Same arithmetic, same results, as
 // v_quant_token.
+// W wavefronts per token instead of four (D = 64 W JW): the same routine with fewer elements per lane,
+// for calls of a few tokens, where the time of a token is the length of a lane's instruction stream
+// (a 4096-channel token: 16 elements per lane on four wavefronts, 4 on sixteen).
 constexpr int KVQ_VW_WAVES = 4;
 constexpr int KVQ_VW_NT = 64 * KVQ_VW_WAVES;
-template <int BITS, int JW, class SP>
+constexpr int KVQ_VW_SMALL_TOKENS = 64;      // calls below this many tokens use one lane per four elements
+template <int BITS, int JW, int W, class SP>
 __device__ __forceinline__ void v_quant_token4(const void *__restrict__ params, int D, int64_t cap, int64_t n0,
                                                int k_side, const uint16_t *__restrict__ v_new,
                                                uint8_t *__restrict__ v_codes, uint16_t *__restrict__ v_sz,
@@ -725,11 +729,12 @@ __device__ __forceinline__ void v_quant_token4(const void *__restrict__ params, 
 {
     constexpr int NE = 1 << BITS;
     constexpr int CW = 4 * BITS;
-    constexpr int W = KVQ_VW_WAVES;
+    constexpr int NTW = 64 * W;                  // threads that work on the token
+    constexpr int WB = W < 4 ? W : 4;            // wavefronts whose lane extremes bound the thresholds
     __shared__ __attribute__((aligned(16))) uint32_t hist[768];
     __shared__ uint32_t bits_s[W][JW][CW + 1], mask_s[W][CW + 1];
     __shared__ uint32_t eq_cnt[W][2], out_cnt[W];
-    __shared__ uint16_t lane_max[KVQ_VW_NT], lane_min[KVQ_VW_NT];
+    __shared__ uint16_t lane_max[NTW], lane_min[NTW];
     __shared__ float red_mx[W], red_mn[W];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t(*bits)[CW + 1] = bits_s[wave];
@@ -755,7 +760,7 @@ __device__ __forceinline__ void v_quant_token4(const void *__restrict__ params, 
     uint32_t top = 0, bot = 0;                   // bit i: channel 64 (jb + i) + lane is an upper / lower outlier
     static_assert(JW <= 32, "one mask bit per element of a lane");
     if (K > 0) {
-        for (int i = threadIdx.x; i < 768; i += KVQ_VW_NT) hist[i] = 0;
+        for (int i = threadIdx.x; i < 768; i += NTW) hist[i] = 0;
         // Only the tails go into the histograms (shared-memory atomics on the few bins that hold the
         // bulk of a token would serialize).  The K-th largest of the 64 W lanes' largest keys is a lower
         // bound of the K-th largest key of the token, since that many elements are at least as large;
@@ -776,16 +781,18 @@ __device__ __forceinline__ void v_quant_token4(const void *__restrict__ params, 
         lane_min[threadIdx.x] = (uint16_t)kmin;
         __syncthreads();
         uint32_t m_top = 0, m_bot = 0xffffu;
-        if (K <= (uint32_t)KVQ_VW_NT) {
-            uint32_t vt[W], vb[W];
+        if (K <= (uint32_t)(64 * WB)) {
+            // (the lanes of the first WB wavefronts are enough: the K-th largest of ANY 64 WB elements
+            // of the token is a lower bound of its K-th largest key)
+            uint32_t vt[WB], vb[WB];
 #pragma unroll
-            for (int r = 0; r < W; ++r) { vt[r] = lane_max[lane + 64 * r]; vb[r] = 0xffffu - lane_min[lane + 64 * r]; }
+            for (int r = 0; r < WB; ++r) { vt[r] = lane_max[lane + 64 * r]; vb[r] = 0xffffu - lane_min[lane + 64 * r]; }
             uint32_t inv_bot = 0;
             for (int bit = 15; bit >= 0; --bit) {
                 const uint32_t ct = m_top | (1u << bit), cb = inv_bot | (1u << bit);
                 uint32_t nt = 0, nb = 0;
 #pragma unroll
-                for (int r = 0; r < W; ++r) {
+                for (int r = 0; r < WB; ++r) {
                     nt += (uint32_t)__popcll(__ballot(vt[r] >= ct));
                     nb += (uint32_t)__popcll(__ballot(vb[r] >= cb));
                 }
@@ -926,15 +933,15 @@ __device__ __forceinline__ void v_quant_token4(const void *__restrict__ params, 
     if (overflow) atomicExch(d_status, (int32_t)KVQ_ERR_NNZ_OVERFLOW);
 }
 
-template <int BITS, int JW, class SP>
-__global__ __launch_bounds__(KVQ_VW_NT) void kvq_v_quant4(const void *__restrict__ params, int D, int64_t cap,
+template <int BITS, int JW, int W, class SP>
+__global__ __launch_bounds__(64 * W) void kvq_v_quant4(const void *__restrict__ params, int D, int64_t cap,
                                                           int64_t n0, int k_side, const uint16_t *__restrict__ v_new,
                                                           uint8_t *__restrict__ v_codes, uint16_t *__restrict__ v_sz,
                                                           uint32_t *__restrict__ v_ptr, const SP vsp, int64_t cap_nnz,
                                                           int32_t *d_status)
 {
-    v_quant_token4<BITS, JW>(params, D, cap, n0, k_side, v_new, v_codes, v_sz, v_ptr, vsp, cap_nnz, d_status,
-                             (int)blockIdx.x);
+    v_quant_token4<BITS, JW, W>(params, D, cap, n0, k_side, v_new, v_codes, v_sz, v_ptr, vsp, cap_nnz, d_status,
+                                (int)blockIdx.x);
 }
 
 template <int BITS, int NT, class SP>
@@ -1052,14 +1059,24 @@ __global__ __launch_bounds__(NT) void kvq_kv_quant(const KvAppendArgs<SP> a)
         k_quant_token<BITS, NT>(a.params, a.D, a.cap, a.n0_k, a.k_new, a.k_codes, a.k_ptr, a.ksp, a.cap_nnz_k,
                                 a.single, a.d_status, t);
     else if (a.D == 4096 || a.D == 2048 || a.D == 1024) {
-        // the four-wavefront routine; further wavefronts of the workgroup end here (a barrier waits
-        // only for the wavefronts that have not ended)
-        if (threadIdx.x >= KVQ_VW_NT) return;
-#define V4(J)                                                                                                    \
-    v_quant_token4<BITS, J>(a.params, a.D, a.cap, a.n0_v, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, a.vsp, a.cap_nnz_v, a.d_status, t)
-        if (a.D == 4096) V4(16);
-        else if (a.D == 2048) V4(8);
-        else V4(4);
+        // the routine with one workgroup per token; wavefronts of the workgroup it does not use end here
+        // (a barrier waits only for the wavefronts that have not ended).  A wide workgroup puts sixteen
+        // (4096 channels) or eight (2048) wavefronts on the token, a narrow one four.
+#define V4(J, WV)                                                                                                \
+    do {                                                                                                         \
+        if (threadIdx.x >= 64 * (WV)) return;                                                                    \
+        v_quant_token4<BITS, J, WV>(a.params, a.D, a.cap, a.n0_v, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, \
+                                    a.vsp, a.cap_nnz_v, a.d_status, t);                                          \
+    } while (0)
+        if (NT == 1024) {
+            if (a.D == 4096) V4(4, 16);
+            else if (a.D == 2048) V4(4, 8);
+            else V4(4, 4);
+        } else {
+            if (a.D == 4096) V4(16, 4);
+            else if (a.D == 2048) V4(8, 4);
+            else V4(4, 4);
+        }
 #undef V4
     } else
         v_quant_token<BITS, NT>(a.params, a.D, a.cap, a.n0_v, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, a.vsp, a.cap_nnz_v, a.d_status, t);
@@ -1147,14 +1164,17 @@ extern "C" kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_
     if (D > 16384) return KVQ_ERR_UNSUPPORTED;       // the per-token selection keeps the vector in LDS
     hipStream_t s = (hipStream_t)stream;
     const size_t dyn = 3 * (size_t)D;
-#define LAUNCH_V4(B, J)                                                                                        \
-    kvq_v_quant4<B, J><<<T, KVQ_VW_NT, 0, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v,         \
+#define LAUNCH_V4W(B, J, WV)                                                                                   \
+    kvq_v_quant4<B, J, WV><<<T, 64 * (WV), 0, s>>>(cache->params, D, cache->cap_tokens, cache->n_tokens_v,     \
                                                cache->k_side_v, d_v_new, cache->v_codes, cache->v_sz,          \
                                                cache->v_ptr, vsp, cache->cap_nnz_v,                           \
                                                cache->d_status)
+#define LAUNCH_V4(B, J) LAUNCH_V4W(B, J, KVQ_VW_WAVES)
 #define LAUNCH_V(B)                                                                                             \
     do {                                                                                                        \
-        if (D == 4096) LAUNCH_V4(B, 16);                                                                        \
+        if (D == 4096 && T < KVQ_VW_SMALL_TOKENS) LAUNCH_V4W(B, 4, 16);                                         \
+        else if (D == 2048 && T < KVQ_VW_SMALL_TOKENS) LAUNCH_V4W(B, 4, 8);                                     \
+        else if (D == 4096) LAUNCH_V4(B, 16);                                                                   \
         else if (D == 2048) LAUNCH_V4(B, 8);                                                                    \
         else if (D == 1024) LAUNCH_V4(B, 4);                                                                    \
         else if (D == 5120 && T >= KVQ_BULK_TOKENS) LAUNCH_V4(B, 20);                                           \
@@ -1180,6 +1200,7 @@ extern "C" kvq_status kvq_quantize_append_v(kvq_cache *cache, const uint16_t *d_
     else launch(kvq_flat_v(cache));
 #undef LAUNCH_V
 #undef LAUNCH_V4
+#undef LAUNCH_V4W
     KVQ_HIP_CHECK(hipGetLastError());
     st = copy_sink_rows(cache, cache->sink_v, d_v_new, cache->n_tokens_v, T, s);
     if (st != KVQ_OK) return st;
