@@ -78,6 +78,38 @@ def calibration_rate(bits, K, torch, n=1 << 26, iters=10):
     return {"elements": n, "bits": bits, "us_per_iteration": dt * 1e6, "gbps": 8 * n / dt / 1e9}
 
 
+KERNEL_SOURCES = ("kvq_qk.hip", "kvq_pv.hip", "kvq_common.hpp")
+
+
+def kernel_source_hash():
+    """SHA-256 over the sources of the attention kernels, as the counter summaries under profiles/ name it."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2401_18079_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def profile_constants(fname, keys):
+    """`key: value` lines of a counter summary under profiles/, or None when the file is missing, lacks a
+    key, or was taken with other kernel sources than the tree holds."""
+    path = os.path.join(ROOT, "profiles", fname)
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    for ln in open(path):
+        if ":" in ln:
+            k, v = ln.split(":", 1)
+            kv[k.strip()] = v.strip()
+    if kv.get("kernel_source_sha256") != kernel_source_hash():
+        return None
+    try:
+        return {k: float(kv[k]) for k in keys}
+    except (KeyError, ValueError):
+        return None
+
+
 def algorithmic_bytes(wl, L, nnz_k, nnz_v):
     """Bytes the method must move per launch (compressed cache + outputs), not the fp16 bytes it avoids."""
     D, Hq, b = wl.D, wl.n_q_heads, wl.bits
@@ -300,7 +332,10 @@ def million_token_leg(args, K, S, torch):
                             "qk_event_interval_us": float(np.mean(ev_qk)), "launches": bsteps},
         "roofline": {"bound": "hbm", "kernel": "kvq_qk_kernel<4 bits> (dense Key kernel of the attention call)",
                      "achieved": dense_qk_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": dense_qk_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": dense_qk_gbps / HBM_PEAK_GBPS,
+                     "traffic": (profile_constants("kvq_qk_kernel_c3_hbm_traffic.txt",
+                                                   ("dense_kernel_traffic_bytes_per_launch",))
+                                 or {}).get("dense_kernel_traffic_bytes_per_launch"),
                      "algorithmic_bytes": dense_qk_bytes, "avg_launch_us": dense_qk_us},
         "fp16_cache_baseline": fp16,
         "speedup_vs_fp16_attention": ((fp16["qk_us"] + fp16["pv_us"]) / attention_us) if fp16 else None,
@@ -321,9 +356,14 @@ def main():
                     help="more than 1: time a decode step over that many layers (each its own cache), nothing else")
     ap.add_argument("--no-fp16", action="store_true")
     ap.add_argument("--no-c3", action="store_true", help="skip the 1M-token leg (configuration 3) of the default run")
+    ap.add_argument("--print-source-hash", action="store_true",
+                    help="print the hash of the attention kernels' sources (the one a counter summary must name) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy (known traffic) so profiler byte counters can be scaled")
     args = ap.parse_args()
+    if args.print_source_hash:
+        print(kernel_source_hash())
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
@@ -364,12 +404,16 @@ def main():
     sm_ws = torch.zeros(K.binding.kvq_softmax_workspace_bytes(Hq, cap), dtype=torch.uint8, device="cuda")
 
     def step(i, ev=None, fused=True):
-        """One decode step of one attention layer.  fused: two library calls, the appends in one
-        (Keys and Values quantized by one launch) and scores, softmax and output in the other (the
-        softmax folded into the mat-vec kernels); otherwise the same work as five separate calls."""
+        """One decode step of one attention layer.  fused: one library call (kvq_decode_step: the appends
+        of Keys and Values in one launch, then scores, softmax and output with the softmax folded into
+        the mat-vec kernels), or its two halves as two calls when an event goes between them;
+        otherwise the same work as five separate calls."""
+        if fused and ev is None:
+            K.kvq_decode_step(gc, new_k[i:i + 1], new_v[i:i + 1], qs[i], scale, scores, out)   # both halves in one call
+            return
         if fused:
             K.kvq_quantize_append_kv(gc, new_k[i:i + 1], new_v[i:i + 1])
-            if ev: ev[1].start()  # noqa: E701
+            ev[1].start()
             K.kvq_attention_decode(gc, qs[i], scale, scores, out)
             return
         K.kvq_quantize_append_k(gc, new_k[i:i + 1])
@@ -554,33 +598,23 @@ def main():
                          f"(append of one token {tq * 1e3:.2f} ms, qk+softmax+pv {tmv * 1e3:.1f} ms, median of 5), "
                          f"mat-vec time scaled linearly to context {L}"}
 
-    # HBM bytes per launch of the dense Key kernel from rocprofv3 counter runs of this command
-    # (FETCH_SIZE / WRITE_SIZE scaled by a known-size copy), kept as a text summary under profiles/
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"kvq_qk_kernel_{wl.name}_hbm_traffic.txt")
-    if os.path.exists(tpath) and not over:
-        for ln in open(tpath):
-            if ln.startswith("dense_kernel_traffic_bytes_per_launch:"):
-                traffic = float(ln.split(":")[1])
-
-    # instruction-issue side of the same kernel (VALU issue is what bounds it): issue slots per
-    # launch from the rocprofv3 SQ_INSTS_VALU run of this command, kept under profiles/
+    # HBM bytes and VALU instructions per launch of the dense Key kernel come from rocprofv3 counter runs of
+    # this command (they cannot be read from inside the run), kept as text summaries under profiles/.  A
+    # summary names the hash of the kernel sources it was taken with; it is used only while that hash is
+    # the hash of the sources in the tree, so a changed kernel reports null instead of a stale figure.
+    traffic = profile_constants(f"kvq_qk_kernel_{wl.name}_hbm_traffic.txt", ("dense_kernel_traffic_bytes_per_launch",))
+    traffic = traffic["dense_kernel_traffic_bytes_per_launch"] if traffic and not over else None
     valu = None
-    vpath = os.path.join(ROOT, "profiles", f"bench_{wl.name}_valu_issue.txt")
-    if os.path.exists(vpath) and not over:
-        kv = {}
-        for ln in open(vpath):
-            if ":" in ln and ln.split(":")[0] in ("qk_valu_issue_slots_per_launch", "valu_issue_peak_slots_per_s"):
-                kv[ln.split(":")[0]] = float(ln.split(":")[1])
-        if len(kv) == 2:
-            ach = kv["qk_valu_issue_slots_per_launch"] / (dense_qk_us * 1e-6)
-            valu = {"slots_per_launch": kv["qk_valu_issue_slots_per_launch"], "achieved": ach,
-                    "peak": kv["valu_issue_peak_slots_per_s"], "unit": "wavefront VALU issue slots/s",
-                    "frac": ach / kv["valu_issue_peak_slots_per_s"]}
+    kv = profile_constants(f"bench_{wl.name}_valu_issue.txt", ("qk_valu_instructions_per_launch", "valu_issue_peak_per_s"))
+    if kv and not over:
+        ach = kv["qk_valu_instructions_per_launch"] / (dense_qk_us * 1e-6)
+        valu = {"instructions_per_launch": kv["qk_valu_instructions_per_launch"], "achieved": ach,
+                "peak": kv["valu_issue_peak_per_s"], "unit": "wavefront VALU instructions/s",
+                "frac": ach / kv["valu_issue_peak_per_s"]}
 
     line = {
         "metric": "quantized-KV decode step latency (append K/V + QK^T + softmax + PV), one attention layer",
-        "step": "kvq_quantize_append_kv + kvq_attention_decode",
+        "step": "kvq_decode_step (= kvq_quantize_append_kv + kvq_attention_decode)",
         "value": ms_per_step * 1e3, "unit": "us", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",

@@ -367,7 +367,12 @@ kvq_status kvq_event_destroy(void *event);
  *            and when its last wavefront's stores have been acknowledged, in a slot of its own in a
  *            caller-provided DEVICE buffer; first start to last end over the workgroups is the span a
  *            kernel trace reports for the launch, and nothing is inserted between kernels.  (Launches
- *            of more than 1024 workgroups are not timed this way.)
+ *            of more than 1024 workgroups are not timed this way, nor the Key kernel variants that
+ *            keep eight query heads per thread: kvq_profile_span_us then returns INVALID_ARG.  The
+ *            3-bit Key kernel for tiles of 1024 tokens keeps one shared pair of words instead of a
+ *            slot per workgroup, earliest start and latest end by atomic minimum and maximum, and
+ *            finds them through a pointer in device memory that a one-workgroup kernel sets ahead
+ *            of the call's first launch while spans are being taken.)
  *   kvq_profile_set_span_buffer(d_buf, bytes): DEVICE buffer of kvq_profile_span_buffer_bytes()
  *     bytes, 8-byte aligned, owned by the caller and kept until spans are switched off again with a
  *     null pointer; only while the aid is disabled.

@@ -23,6 +23,7 @@
 // buffer and the dense kernel adds its own part, so one call yields one merged result.  Attention-
 // sink tokens (paper Sec. 3.5), if any, are scored last from their fp16 rows.
 #include <stdlib.h>
+#include <atomic>
 #include <utility>
 #include "kvq_common.hpp"
 
@@ -611,6 +612,49 @@ __device__ __forceinline__ void pm_pass(std::integer_sequence<int, T...>, uint32
                                            any, next_block_valid), ...);
 }
 
+// Timing aid of the piece-major kernel.  The kernel has no register to carry a pointer, or a slot
+// number, through its loops (an instantiation that took the slots as an argument spilled around them
+// and ran 15 % slower than the kernel it was meant to time), so the address of the launch's span
+// slots lives in device memory and is loaded where it is used, once before the first and once after
+// the last instruction of the kernel proper, and the workgroups share one pair of words: the earliest
+// start (an atomic minimum) and the latest end (an atomic maximum).  Null (the normal state): nothing
+// is stamped.  The host stores the address, and resets the launch's slots, with a small kernel on the
+// launch stream before every launch whose span is taken, and once more when spans are switched off.
+__device__ unsigned long long *kvq_qk3_span_slots = nullptr;
+__global__ void kvq_qk3_set_span(unsigned long long *slots)
+{
+    if (threadIdx.x == 0) kvq_qk3_span_slots = slots;
+    if (slots) {                                   // pair 0: (earliest start, latest end); the rest unused
+        slots[2 * threadIdx.x] = threadIdx.x == 0 ? ~0ull : 0ull;
+        slots[2 * threadIdx.x + 1] = 0ull;
+    }
+}
+__device__ __forceinline__ unsigned long long *qk3_span_slots_now()
+{
+    unsigned long long *p = *(unsigned long long *volatile *)&kvq_qk3_span_slots;
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return (unsigned long long *)(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ void qk3_span_start()
+{
+    unsigned long long *sp = qk3_span_slots_now();
+    if (sp && threadIdx.x == 0)
+        __hip_atomic_fetch_min(sp, (unsigned long long)wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Every thread of the workgroup must call this (it holds a barrier when spans are being taken).
+__device__ __forceinline__ void qk3_span_end()
+{
+    unsigned long long *sp = qk3_span_slots_now();
+    if (sp) {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");     // this wavefront's stores are acknowledged
+        __syncthreads();
+        if (threadIdx.x == 0)
+            __hip_atomic_fetch_max(sp + 1, (unsigned long long)wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 // Same arguments, grid and results as kvq_qk_kernel<3, KVH, RQ, 1024, ...>; tiles are KVQ_ROPE_STEP tokens.
 template <int KVH, int RQ, int TT, int PG, bool STATS, bool SPAN = false>
 __global__ __launch_bounds__(KVQ_ROPE_STEP) void kvq_qk3_kernel(const void *__restrict__ params, int D, int r,
@@ -619,9 +663,9 @@ __global__ __launch_bounds__(KVQ_ROPE_STEP) void kvq_qk3_kernel(const void *__re
                                                                const float *__restrict__ q_rot, float scale,
                                                                float *__restrict__ scores, int64_t ld, int n_tiles,
                                                                int add_prev, float *__restrict__ stat_slots,
-                                                               int n_sink, unsigned long long *span)
+                                                               int n_sink, unsigned long long *)
 {
-    if (SPAN) kvq_span_start(span);
+    qk3_span_start();
     constexpr int BITS = 3, NT = KVQ_ROPE_STEP;
     static_assert(KVH * TT <= 16, "the carried bits of a block are packed in 32 + 64 bits");
     constexpr int QH = KVH * RQ, R = RQ, ENT = 64;
@@ -731,7 +775,7 @@ __global__ __launch_bounds__(KVQ_ROPE_STEP) void kvq_qk3_kernel(const void *__re
             stat_slots[(int64_t)(q0 + tid) * KVQ_STAT_SLOTS + blockIdx.x] = m;
         }
     }
-    if (SPAN) kvq_span_end(span);
+    qk3_span_end();
 }
 
 // Sparse Key outliers, balanced (paper App. "Kernel Implementation Details": equal non-zeros per
@@ -951,6 +995,24 @@ __global__ __launch_bounds__(64) void kvq_qk_sink(const void *__restrict__ param
     }
 }
 
+// Store the address of the piece-major kernel's span slots (or null) in its device word and reset the
+// slots, on the launch stream: before every launch whose span is taken, and once when the word still
+// holds an address and no span is wanted any more.  Part of the timing aid: like the rest of it, not
+// meant for calls that overlap.
+kvq_status qk3_publish_span(unsigned long long *span, hipStream_t s)
+{
+    static std::atomic<bool> holds_address[64];            // zero-initialised: the word starts out null
+    int dev = 0;
+    KVQ_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return span ? KVQ_ERR_UNSUPPORTED : KVQ_OK;
+    if (!span && !holds_address[dev].load(std::memory_order_relaxed)) return KVQ_OK;
+    static_assert(KVQ_PROFILE_MAX_WGS == 1024, "one thread of the reset kernel per slot pair");
+    kvq_qk3_set_span<<<1, KVQ_PROFILE_MAX_WGS, 0, s>>>(span);
+    KVQ_HIP_CHECK(hipGetLastError());
+    holds_address[dev].store(span != nullptr, std::memory_order_relaxed);
+    return KVQ_OK;
+}
+
 template <int BITS, int KVH, int RQ, int NT, int PG, int R>
 kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *scores, int64_t ld, float *stat_slots,
                      int *n_stat, hipStream_t s)
@@ -978,26 +1040,27 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     if (gx > 256) gx = 256;          // a head owns 256 statistics slots
     if (gx > tiles) gx = tiles;
     dim3 grid((unsigned)gx, (unsigned)groups);
-    // the sparse kernel goes first and writes its part of every score; the dense kernel adds its own
-    const int sparse_first = !(c->loaded & 2);           // bit 1: thresholds admit no Key outliers
-    if (sparse_first) {
-        kvq_status st = launch_qk_sparse<R>(c, q, scale, scores, ld, s);
-        if (st != KVQ_OK) return st;
-    }
     KvqProfile &prof = kvq_profile_state();
     unsigned long long *span = CAN_SPAN ? kvq_profile_span_slot(prof, 0, (int64_t)gx * groups) : nullptr;
     if constexpr (PIECE_MAJOR) {
-        // no span-taking variant of the piece-major kernel: it has no register to spare, the stamps'
-        // bookkeeping makes the compiler spill around the loops and the variant runs 15 % slower than
-        // the kernel it is meant to time; callers fall back on the HIP-event interval
-        if (piece_major) span = nullptr;
-        else if (span)
+        // the piece-major kernel reads the address of its span slots from device memory: bring that
+        // word up to date (null when no spans are taken) before anything of this call is launched
+        if (piece_major) {
+            kvq_status st = qk3_publish_span(span, s);
+            if (st != KVQ_OK) return st;
+        } else if (span)
             kern = stat_slots ? kvq_qk_kernel<BITS, KVH, RQ, NT, PG, true, true>
                               : kvq_qk_kernel<BITS, KVH, RQ, NT, PG, false, true>;
     } else if constexpr (CAN_SPAN) {
         if (span)
             kern = stat_slots ? kvq_qk_kernel<BITS, KVH, RQ, NT, PG, true, true>
                               : kvq_qk_kernel<BITS, KVH, RQ, NT, PG, false, true>;
+    }
+    // the sparse kernel goes first and writes its part of every score; the dense kernel adds its own
+    const int sparse_first = !(c->loaded & 2);           // bit 1: thresholds admit no Key outliers
+    if (sparse_first) {
+        kvq_status st = launch_qk_sparse<R>(c, q, scale, scores, ld, s);
+        if (st != KVQ_OK) return st;
     }
     hipEvent_t *pev = (prof.enabled && prof.use_events) ? prof.ev[0][prof.count[0] % KVQ_PROFILE_RING] : nullptr;
     if (pev) KVQ_HIP_CHECK(hipEventRecord(pev[0], s));

@@ -50,6 +50,20 @@ def _every_score(wl, L, n_sink=0):
     ok, worst_f = matvec_close(out.cpu().numpy(), ref_out, rel=2e-3)
     assert ok, f"fused call: worst error / bound = {worst_f:.3f}"
     assert np.array_equal(scores.cpu().numpy()[:, :L], got[:, :L])          # same scores from both variants
+    # the timing aid: this kernel's spans (earliest workgroup start to latest end, stamped through a
+    # pointer the kernel reads from device memory); sanity bounds only, and results do not change
+    K.kvq_profile_enable(True, spans=True)
+    try:
+        for _ in range(3):
+            K.kvq_attention_decode(gc, torch.from_numpy(q).cuda(), SCALE, scores, out)
+        K.kvq_qk_matvec(gc, torch.from_numpy(q).cuda(), SCALE, scores)
+        spans, evs = K.kvq_profile_read_all_spans_us(0), K.kvq_profile_read_all_us(0)
+        assert len(spans) == 4 and len(evs) == 4
+        assert all(0.5 < x < 20000.0 for x in spans) and all(0.5 < x < 200000.0 for x in evs)
+    finally:
+        K.kvq_profile_enable(False)
+    K.kvq_qk_matvec(gc, torch.from_numpy(q).cuda(), SCALE, scores)          # the pointer is null again
+    assert np.array_equal(scores.cpu().numpy()[:, :L], got[:, :L])
     return worst
 
 
