@@ -31,6 +31,8 @@ def _caches(st, cap, n_sink=0):
     ("c2", dict(n_kv_heads=12, n_q_heads=12), 0, [1, 65, 1]),                    # D = 1536: ragged last pass
     ("c2", dict(n_kv_heads=8, n_q_heads=8), 3, [1, 1, 2, 60]),                   # attention-sink rows copied too
     ("c2", dict(n_kv_heads=4, n_q_heads=4, outlier_fraction=0.0), 0, [1, 40, 1]),
+    ("c2", dict(n_kv_heads=96, n_q_heads=96), 0, [1, 2, 40, 1]),                 # D = 12288: three passes of 4096 channels
+    ("c2", dict(n_kv_heads=128, n_q_heads=128, bits=4), 0, [1, 30]),             # D = 16384: the widest Value append
 ])
 def test_append_kv_bit_exact(name, ov, n_sink, chunks):
     import torch
@@ -106,6 +108,27 @@ def test_appends_from_inputs_that_are_only_2_byte_aligned():
     torch.cuda.synchronize()
     assert gc.status() == 0
     assert not compare_caches(oc, gc)
+
+
+def test_value_appends_wider_than_16384_channels_are_refused():
+    import torch
+    import paper_2401_18079_amd as K
+    wl = S.workload("c2", n_kv_heads=136, n_q_heads=136)         # D = 17408
+    st = Setup(wl)
+    gc = st.gpu_cache(128)
+    k, v = torch.from_numpy(st.k(0, 2)).cuda(), torch.from_numpy(st.v(0, 2)).cuda()
+    for call in (lambda: K.kvq_quantize_append_kv(gc, k, v), lambda: K.kvq_quantize_append_v(gc, v)):
+        with pytest.raises(K.KvqError) as e:
+            call()
+        assert e.value.status == 2                               # KVQ_ERR_UNSUPPORTED, nothing launched
+    assert gc.n_tokens_k == 0 and gc.n_tokens_v == 0
+    oc = st.oracle_cache(128)
+    oc.append_k(st.k(0, 2))
+    K.kvq_quantize_append_k(gc, k)                               # Keys alone have no such limit
+    torch.cuda.synchronize()
+    assert gc.status() == 0 and np.array_equal(gc.k_codes.cpu().numpy(), oc.k_codes)
+    nk = int(oc.k_ptr[2])
+    assert np.array_equal(gc.k_idx.cpu().numpy().view(np.uint16)[:nk], oc.k_idx[:nk])
 
 
 def test_append_kv_overflow_and_argument_errors():
