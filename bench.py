@@ -78,7 +78,7 @@ def calibration_rate(bits, K, torch, n=1 << 26, iters=10):
     return {"elements": n, "bits": bits, "us_per_iteration": dt * 1e6, "gbps": 8 * n / dt / 1e9}
 
 
-KERNEL_SOURCES = ("kvq_qk.hip", "kvq_pv.hip", "kvq_common.hpp")
+KERNEL_SOURCES = ("kvq_qk.hip", "kvq_qk_sparse.hpp", "kvq_pv.hip", "kvq_common.hpp")
 
 
 def kernel_source_hash():
@@ -614,7 +614,8 @@ def main():
 
     line = {
         "metric": "quantized-KV decode step latency (append K/V + QK^T + softmax + PV), one attention layer",
-        "step": "kvq_decode_step (= kvq_quantize_append_kv + kvq_attention_decode)",
+        "step": "kvq_decode_step (append of the new token and attention over the cache that ends with it)",
+        "step_launches": K.kvq_decode_step_launches(gc),
         "value": ms_per_step * 1e3, "unit": "us", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",

@@ -244,9 +244,15 @@ kvq_status kvq_attention_decode(const kvq_cache *cache, const float *d_q_rot, fl
 
 /*
  * One generation step of one layer for one sequence in a single call (paper Sec. 3: at every step
- * the new token's Key and Value join the cache and the query attends over all of it): exactly
+ * the new token's Key and Value join the cache and the query attends over all of it):
  * kvq_quantize_append_kv(cache, d_k_new, d_v_new, 1) followed by kvq_attention_decode on the cache
- * that now ends with the new token, same kernels, same results bit for bit.
+ * that now ends with the new token.  The cache ends up bit for bit as after that append.  For flat
+ * outlier storage, D = 1024 or 4096 and caches sized for 16 or more Key outliers per token the append
+ * and the sparse Key kernel over the older tokens run as workgroups of ONE launch (the append is
+ * latency only and the sparse kernel needs the new token for the last score alone; the workgroup that
+ * quantizes the new Key also sums the sparse part of its score): the scores and outputs then agree
+ * with the two calls to rounding (sums of the same terms split at other token boundaries), not bit for
+ * bit.  Every other shape runs exactly the two calls.
  *   d_k_new, d_v_new : DEVICE fp16 [D], the new token's pre-RoPE Key and its Value.
  *   d_q_rot, scale, d_scores, ld_scores, d_out : as for kvq_attention_decode; ld_scores must cover
  *   the new token too (>= n_tokens_k + 1 on entry).
@@ -258,6 +264,11 @@ kvq_status kvq_attention_decode(const kvq_cache *cache, const float *d_q_rot, fl
 kvq_status kvq_decode_step(kvq_cache *cache, const uint16_t *d_k_new, const uint16_t *d_v_new,
                            const float *d_q_rot, float scale, float *d_scores, int64_t ld_scores,
                            float *d_out, void *stream);
+/* Kernel launches of the next kvq_decode_step on this cache (host arithmetic plus one query of kernel
+ * attributes on the current device): 5 when the append and the sparse Key kernel share a launch, 6 when
+ * the step is the two calls (5 if the thresholds admit no Key outlier: no sparse Key kernel), one more
+ * with attention-sink tokens (their score kernel); copies of sink rows not counted.  -1: the descriptor is not usable for a step (the step call says why). */
+int32_t kvq_decode_step_launches(const kvq_cache *cache);
 
 /*
  * kvq_attention_decode for callers that cannot allocate device memory or hand over a workspace (code

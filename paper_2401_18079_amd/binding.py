@@ -66,6 +66,7 @@ def load_library():
         "kvq_attention_decode": (C.c_int, [P, V, F, V, I64, V, V]),
         "kvq_attention_decode_noalloc": (C.c_int, [P, V, F, V, I64, V, V]),
         "kvq_decode_step": (C.c_int, [P, V, V, V, F, V, I64, V, V]),
+        "kvq_decode_step_launches": (I32, [P]),
         "kvq_softmax_workspace_bytes": (I64, [I32, I64]),
         "kvq_softmax_f32": (C.c_int, [V, I64, V, I64, I32, I64, V, I64, V]),
         "kvq_calibrate_key_channels": (C.c_int, [V, I32, I32, F, V, V, V, V, V]),
@@ -99,7 +100,7 @@ EXPORTED_SYMBOLS = [
     "kvq_codes_bytes", "kvq_params_bytes", "kvq_workspace_bytes", "kvq_status_string", "kvq_version",
     "kvq_lut_load", "kvq_stored_signpost", "kvq_quantize_append_k", "kvq_quantize_append_v", "kvq_quantize_append_kv",
     "kvq_qk_matvec", "kvq_pv_matvec",
-    "kvq_attention_decode", "kvq_attention_decode_noalloc", "kvq_decode_step", "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
+    "kvq_attention_decode", "kvq_attention_decode_noalloc", "kvq_decode_step", "kvq_decode_step_launches", "kvq_softmax_workspace_bytes", "kvq_softmax_f32", "kvq_fp16_qk_matvec", "kvq_fp16_pv_workspace_bytes",
     "kvq_fp16_pv_matvec", "kvq_event_create", "kvq_event_record", "kvq_event_elapsed_ms", "kvq_event_destroy",
     "kvq_profile_enable", "kvq_profile_last_ms", "kvq_profile_count", "kvq_profile_read_ms",
     "kvq_profile_span_buffer_bytes", "kvq_profile_set_span_buffer", "kvq_profile_span_us", "kvq_calibrate_workspace_bytes", "kvq_calibrate_nuq",
@@ -406,6 +407,10 @@ def kvq_decode_step(cache: KvqCache, k_new: torch.Tensor, v_new: torch.Tensor, q
     _check(load_library().kvq_decode_step(C.byref(cache.c), k.data_ptr(), v.data_ptr(), q_rot.data_ptr(), float(scale),
                                           scores.data_ptr(), scores.stride(0), out.data_ptr(), _stream_ptr(stream)),
            "kvq_decode_step")
+
+
+def kvq_decode_step_launches(cache: KvqCache) -> int:
+    return int(load_library().kvq_decode_step_launches(C.byref(cache.c)))
 
 
 def kvq_attention_decode_noalloc(cache: KvqCache, q_rot: torch.Tensor, scale: float, scores: torch.Tensor,

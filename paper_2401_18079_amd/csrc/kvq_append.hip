@@ -4,6 +4,7 @@
 // (this file is compiled with floating-point contraction off) so that codes, outlier indices
 // and fp16 residuals are reproducible bit for bit.
 #include "kvq_common.hpp"
+#include "kvq_qk_sparse.hpp"
 #include <type_traits>
 
 namespace {
@@ -1082,6 +1083,94 @@ __global__ __launch_bounds__(NT) void kvq_kv_quant(const KvAppendArgs<SP> a)
         v_quant_token<BITS, NT>(a.params, a.D, a.cap, a.n0_v, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, a.vsp, a.cap_nnz_v, a.d_status, t);
 }
 
+// ---- first launch of a generation step ---------------------------------------------------------
+// kvq_decode_step appends one token and then attends over the cache that ends with it.  The append is
+// two workgroups of pure latency (12 us), and the attention's first kernel, the sparse Key kernel, needs
+// the new token only for the last of its scores: here both run as workgroups of one launch.  Workgroup 0
+// quantizes the token's Key (the 256-thread body: 62 registers, so the kernel keeps the sparse
+// kernel's eight wavefronts per SIMD) and then adds up the sparse part of the token's own scores from
+// the entries it has just stored; workgroup 1 quantizes its Value; the others are the sparse Key
+// kernel over the tokens that were there before.
+struct StepFrontArgs {
+    const void *params;
+    int D, n_q_heads, k_side;
+    int64_t cap, n;                       // n: tokens in the cache before the step
+    int64_t cap_nnz_k, cap_nnz_v;
+    const uint16_t *k_new, *v_new;
+    uint8_t *k_codes, *v_codes;
+    uint16_t *v_sz;
+    uint32_t *k_ptr, *v_ptr;
+    KvqSparseFlat ksp, vsp;
+    int32_t *d_status;
+    const float *q_rot;
+    float scale;
+    float *scores;
+    int64_t ld, tokens_per_wave;
+};
+constexpr int KVQ_STEP_K_NT = 256;        // threads of workgroup 0 that work
+
+// Sparse part of the scores of token a.n, whose entries threads 0 .. KVQ_STEP_K_NT-1 of this workgroup
+// have just stored: scale * v * (R_n^T q)_c summed per query head, as the sparse kernel does for the
+// other tokens (same arithmetic per entry; 64-bit fixed-point sums in LDS).
+template <int R>
+__device__ __forceinline__ void qk_sparse_new_token(const StepFrontArgs &a)
+{
+    extern __shared__ __attribute__((aligned(16))) float sparse_dyn[];
+    unsigned long long *S = (unsigned long long *)sparse_dyn;            // [n_q_heads]
+    const int tid = threadIdx.x;
+    for (int j = tid; j < a.n_q_heads; j += KVQ_STEP_K_NT) S[j] = 0ull;
+    // the workgroup's stores of the token's entries and of its end pointer are complete ...
+    __threadfence_block();
+    __syncthreads();
+    // ... and are read back past the vector cache, which may hold the pointer's line from before
+    const uint32_t p0 = __hip_atomic_load(a.k_ptr + a.n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t p1 = __hip_atomic_load(a.k_ptr + a.n + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const KvqParamsView pv = kvq_params_view(a.params, a.D);
+    for (uint32_t e = p0 + (uint32_t)tid; e < p1; e += KVQ_STEP_K_NT) {
+        const uint32_t ch = __hip_atomic_load(a.ksp.idx + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float v = kvq_h2f(__hip_atomic_load(a.ksp.val + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        const uint32_t i = ch & 63u;
+        const float rev = rope_rev((float)a.n, pv.hdr->rope_vh[i], pv.hdr->rope_vl[i]);
+        const float cs = __builtin_amdgcn_cosf(rev);
+        // (R_n^T q)_c = q_c cos + s q_{c^64} sin, s = +1 for the lower channel of the pair, -1 for the upper
+        const float sn = __builtin_bit_cast(
+            float, __builtin_bit_cast(uint32_t, __builtin_amdgcn_sinf(rev)) ^ ((ch & 64u) << 25));
+        const uint32_t cl = ch & 127u, kvh = ch >> 7;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint32_t qh = kvh * R + r, qi = qh * 128u + cl;
+            const float qa = a.q_rot[qi] * a.scale, qb = a.q_rot[qi ^ 64u] * a.scale;
+            const float qp = qa * cs + qb * sn;
+            kvq_lds_add_fixed<0>(&S[qh], v * qp);
+        }
+    }
+    __syncthreads();
+    for (int j = tid; j < a.n_q_heads; j += KVQ_STEP_K_NT) a.scores[(int64_t)j * a.ld + a.n] = kvq_from_fixed_fast<0>(S[j]);
+}
+
+// W: wavefronts on the Value token (D = 256 W channels: 16 or 4).  One instantiation per width: the
+// Value routine's static LDS arrays of several widths would add up and cost the sparse role a workgroup
+// per compute unit.
+template <int BITS, int R, int W>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void kvq_step_front(const StepFrontArgs a)
+{
+    if (blockIdx.x == 0) {
+        // wavefronts that a role does not use end here (a barrier waits only for those that have not ended)
+        if (threadIdx.x >= KVQ_STEP_K_NT) return;
+        k_quant_token<BITS, KVQ_STEP_K_NT>(a.params, a.D, a.cap, a.n, a.k_new, a.k_codes, a.k_ptr, a.ksp, a.cap_nnz_k, 1,
+                                           a.d_status, 0);
+        qk_sparse_new_token<R>(a);
+    } else if (blockIdx.x == 1) {
+        if (threadIdx.x >= 64 * W) return;
+        v_quant_token4<BITS, 4, W>(a.params, a.D, a.cap, a.n, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, a.vsp,
+                                   a.cap_nnz_v, a.d_status, 0);
+    } else {
+        qk_sparse_body<R, 8, KvqSparseFlat>((int)blockIdx.x - 2, a.params, a.D, a.n_q_heads, a.n, a.k_ptr, a.ksp,
+                                            (uint32_t)a.cap_nnz_k, a.q_rot, a.scale, a.scores, a.ld, a.tokens_per_wave);
+    }
+}
+
 }  // namespace
 
 // The first n_sink tokens are also kept as they came (paper Sec. 3.5): copy their rows.
@@ -1269,6 +1358,111 @@ extern "C" kvq_status kvq_quantize_append_kv(kvq_cache *cache, const uint16_t *d
     return KVQ_OK;
 }
 
+
+template <int BITS, int R, int W>
+static kvq_status step_front_launch_brw(kvq_cache *cache, StepFrontArgs &a, hipStream_t s, bool *done, bool dry)
+{
+    // static LDS of the kernel (the append bodies' arrays) comes on top of the sparse role's dynamic LDS
+    static const int static_lds = [] {
+        hipFuncAttributes fa;
+        if (hipFuncGetAttributes(&fa, (const void *)kvq_step_front<BITS, R, W>) != hipSuccess) return -1;
+        return (int)fa.sharedSizeBytes;
+    }();
+    static const hipError_t lds_attr = hipFuncSetAttribute((const void *)kvq_step_front<BITS, R, W>,
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 147456 - 16384);
+    if (static_lds < 0 || static_lds > 16384) return KVQ_OK;             // *done stays false
+    KVQ_HIP_CHECK(lds_attr);
+    QkSparsePlan plan;
+    if (!qk_sparse_plan(cache->n_q_heads, a.n, 8, (size_t)static_lds, plan) || plan.waves != 16) return KVQ_OK;
+    if (plan.lds < (size_t)cache->n_q_heads * 8) return KVQ_OK;
+    a.tokens_per_wave = plan.tokens_per_wave;
+    if (dry) {                                    // the caller only asks whether this launch applies
+        *done = true;
+        return KVQ_OK;
+    }
+    kvq_status st = copy_sink_rows(cache, cache->sink_k, a.k_new, a.n, 1, s);
+    if (st != KVQ_OK) return st;
+    st = copy_sink_rows(cache, cache->sink_v, a.v_new, a.n, 1, s);
+    if (st != KVQ_OK) return st;
+    kvq_step_front<BITS, R, W><<<plan.grid + 2, 1024, plan.lds, s>>>(a);
+    KVQ_HIP_CHECK(hipGetLastError());
+    cache->n_tokens_k += 1;
+    cache->n_tokens_v += 1;
+    *done = true;
+    return KVQ_OK;
+}
+
+template <int BITS, int R>
+static kvq_status step_front_launch_br(kvq_cache *cache, StepFrontArgs &a, hipStream_t s, bool *done, bool dry)
+{
+    if (a.D == 4096) return step_front_launch_brw<BITS, R, 16>(cache, a, s, done, dry);
+    return step_front_launch_brw<BITS, R, 4>(cache, a, s, done, dry);
+}
+
+template <int BITS>
+static kvq_status step_front_launch_b(kvq_cache *cache, StepFrontArgs &a, hipStream_t s, bool *done, bool dry)
+{
+    switch (cache->n_q_heads / cache->n_kv_heads) {
+    case 1: return step_front_launch_br<BITS, 1>(cache, a, s, done, dry);
+    case 2: return step_front_launch_br<BITS, 2>(cache, a, s, done, dry);
+    case 4: return step_front_launch_br<BITS, 4>(cache, a, s, done, dry);
+    case 8: return step_front_launch_br<BITS, 8>(cache, a, s, done, dry);
+    default: return KVQ_OK;
+    }
+}
+
+static kvq_status step_front(kvq_cache *cache, const uint16_t *d_k_new, const uint16_t *d_v_new,
+                             const float *d_q_rot, float scale, float *d_scores, int64_t ld_scores, hipStream_t s,
+                             bool *done, bool dry)
+{
+    *done = false;
+    kvq_status st = append_checks(cache, d_k_new, 1, cache ? cache->n_tokens_k : 0);
+    if (st != KVQ_OK) return st;
+    st = append_checks(cache, d_v_new, 1, cache->n_tokens_v);
+    if (st != KVQ_OK) return st;
+    const int D = cache->n_kv_heads * KVQ_HEAD_DIM;
+    if (cache->k_side_v < 0 || 2 * (int64_t)cache->k_side_v >= D) return KVQ_ERR_INVALID_ARG;
+    // shapes this launch covers; every other one takes the two calls
+    if (D != 1024 && D != 4096) return KVQ_OK;
+    if (cache->nnz_block_shift || (cache->loaded & 2) || cache->n_tokens_k != cache->n_tokens_v) return KVQ_OK;
+    if (cache->cap_nnz_k >= ((int64_t)1 << 31)) return KVQ_OK;
+    const int64_t per_token = cache->cap_nnz_k / (cache->cap_tokens > 0 ? cache->cap_tokens : 1);
+    if (per_token < 16 && cache->n_q_heads <= 32) return KVQ_OK;         // the sparse kernel would take 32-token sub-ranges
+    StepFrontArgs a;
+    a.params = cache->params; a.D = D; a.n_q_heads = cache->n_q_heads; a.k_side = cache->k_side_v;
+    a.cap = cache->cap_tokens; a.n = cache->n_tokens_k;
+    a.cap_nnz_k = cache->cap_nnz_k; a.cap_nnz_v = cache->cap_nnz_v;
+    a.k_new = d_k_new; a.v_new = d_v_new;
+    a.k_codes = cache->k_codes; a.v_codes = cache->v_codes; a.v_sz = cache->v_sz;
+    a.k_ptr = cache->k_ptr; a.v_ptr = cache->v_ptr;
+    a.ksp = kvq_flat_k(cache); a.vsp = kvq_flat_v(cache);
+    a.d_status = cache->d_status;
+    a.q_rot = d_q_rot; a.scale = scale; a.scores = d_scores; a.ld = ld_scores; a.tokens_per_wave = 1;
+    if (cache->bits == 2) return step_front_launch_b<2>(cache, a, s, done, dry);
+    if (cache->bits == 3) return step_front_launch_b<3>(cache, a, s, done, dry);
+    return step_front_launch_b<4>(cache, a, s, done, dry);
+}
+
+kvq_status kvq_step_front_launch(kvq_cache *cache, const uint16_t *d_k_new, const uint16_t *d_v_new,
+                                 const float *d_q_rot, float scale, float *d_scores, int64_t ld_scores, hipStream_t s,
+                                 bool *done)
+{
+    return step_front(cache, d_k_new, d_v_new, d_q_rot, scale, d_scores, ld_scores, s, done, false);
+}
+
+extern "C" int32_t kvq_decode_step_launches(const kvq_cache *cache)
+{
+    if (!cache) return -1;
+    kvq_cache view = *cache;                     // a dry run: nothing is launched, nothing advances
+    bool front = false;
+    static const uint16_t dummy[2] = {0, 0};     // the checks only look at alignment
+    if (step_front(&view, dummy, dummy, nullptr, 0.f, nullptr, 0, nullptr, &front, true) != KVQ_OK) return -1;
+    const int sink = cache->n_sink > 0 ? 1 : 0;
+    // the two calls: append, sparse Key (unless the thresholds admit no outlier), dense Key, sparse Value,
+    // dense Value, reduction
+    const int two_calls = (cache->loaded & 2) ? 5 : 6;
+    return (front ? 5 : two_calls) + sink;
+}
 
 extern "C" kvq_status kvq_calibrate_key_channels(const uint16_t *d_k_cal, int32_t T, int32_t D, float outlier_fraction,
                                                  uint16_t *d_s, uint16_t *d_z, uint16_t *d_lo, uint16_t *d_hi,

@@ -91,6 +91,15 @@ extern "C" kvq_status kvq_decode_step(kvq_cache *cache, const uint16_t *d_k_new,
     const int64_t need = kvq_pv_workspace_bytes(cache->n_q_heads) +
                          (int64_t)cache->n_q_heads * KVQ_STAT_SLOTS * (int64_t)sizeof(float);
     if (!cache->workspace || cache->workspace_bytes < need) return KVQ_ERR_CAPACITY;
+    // the append and the sparse Key kernel over the tokens before it as one launch, where that is built
+    bool front = false;
+    st = kvq_step_front_launch(cache, d_k_new, d_v_new, d_q_rot, scale, d_scores, ld_scores, (hipStream_t)stream, &front);
+    if (st != KVQ_OK) return st;
+    if (front) {
+        kvq_cache view = *cache;
+        view.loaded |= KVQ_LOADED_SPARSE_SCORES_DONE;
+        return kvq_attention_decode(&view, d_q_rot, scale, d_scores, ld_scores, d_out, stream);
+    }
     st = kvq_quantize_append_kv(cache, d_k_new, d_v_new, 1, stream);
     if (st != KVQ_OK) return st;
     return kvq_attention_decode(cache, d_q_rot, scale, d_scores, ld_scores, d_out, stream);

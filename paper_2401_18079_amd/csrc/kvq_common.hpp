@@ -316,6 +316,17 @@ __attribute__((visibility("hidden"))) kvq_status kvq_qk_run(const kvq_cache *cac
 __attribute__((visibility("hidden"))) kvq_status kvq_pv_run(const kvq_cache *cache, const float *d_weights, int64_t ld,
                                                             float *d_out, const float *stat_slots, int n_stat,
                                                             hipStream_t s);
+// kvq_cache.loaded: bit 0 set by kvq_lut_load, bit 1 by it too when the thresholds admit no Key outlier.
+// Bit 2 never appears in a caller's descriptor: kvq_decode_step sets it on its own copy when its first
+// launch has already written the sparse part of the scores.
+#define KVQ_LOADED_SPARSE_SCORES_DONE 4
+// First launch of kvq_decode_step: the append of one token's Key and Value and the sparse Key kernel over
+// the tokens before it, as workgroups of one kernel (kvq_append.hip).  *done = false, nothing launched,
+// nothing changed: the shape is not covered and the caller takes the two calls instead.
+__attribute__((visibility("hidden"))) kvq_status kvq_step_front_launch(kvq_cache *cache, const uint16_t *d_k_new,
+                                                                       const uint16_t *d_v_new, const float *d_q_rot,
+                                                                       float scale, float *d_scores, int64_t ld_scores,
+                                                                       hipStream_t s, bool *done);
 // Bytes of the workspace that kvq_pv_run uses (from its start); the statistics slots follow.
 __attribute__((visibility("hidden"))) int64_t kvq_pv_workspace_bytes(int n_q_heads);
 

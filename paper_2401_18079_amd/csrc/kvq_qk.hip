@@ -26,6 +26,7 @@
 #include <atomic>
 #include <utility>
 #include "kvq_common.hpp"
+#include "kvq_qk_sparse.hpp"
 
 // Tuning knobs of the piece-major 3-bit kernel (kvq_qk3_kernel): tiles per block, fields per gather group.
 #ifndef KVQ_QK3_ENABLE
@@ -70,17 +71,6 @@ __device__ __forceinline__ uint32_t field_shifted(const uint32_t (&Wg)[8], int i
         return chunk_dword(Wg, wi) << (3 - sh);
     }
     return __builtin_amdgcn_alignbit(chunk_dword(Wg, wi + 1), chunk_dword(Wg, wi), sh - 3);
-}
-
-// Angle of channel pair i at position n, in revolutions, reduced to about [0,1): n*theta_i/(2 pi)
-// from a two-float split of theta_i/(2 pi); the product's rounding error is recovered with an FMA,
-// so the result is good to ~1e-7 revolutions for n up to 2^24.
-__device__ inline float rope_rev(float nf, float vh, float vl)
-{
-    float p = nf * vh;
-    float e = __builtin_fmaf(nf, vh, -p);
-    float t = __builtin_fmaf(nf, vl, e);
-    return __builtin_amdgcn_fractf(p) + t;
 }
 
 // PAIR_GROUP consecutive channel pairs of the dense part for one token.  Written gathers-first so
@@ -778,26 +768,6 @@ __global__ __launch_bounds__(KVQ_ROPE_STEP) void kvq_qk3_kernel(const void *__re
     qk3_span_end();
 }
 
-// Sparse Key outliers, balanced (paper App. "Kernel Implementation Details": equal non-zeros per
-// thread): lanes are outlier entries.  Every wavefront works on its own: it owns a run of consecutive
-// tokens and walks it TW tokens at a time (8, or 32 when outliers are few: see launch_qk_sparse).  A sub-range's pointers sit in one register (lane j:
-// token j), so the token of an entry is a wavefront-uniform cursor plus the number of token starts
-// among the 64 entries of the batch, found with scalar reads of that register.  The query is
-// rotated instead of the Key (by linearity  <q, R_n (v e_c)> = v (R_n^T q)_c ) and
-// scale * v * (R_n^T q)_c is accumulated into the wavefront's private LDS tile [query head][token]
-// (fixed-point integer atomics: LDS floating-point atomics are an order of magnitude slower here),
-// which is then written to the score buffer; the dense kernel, launched afterwards, adds its part.
-// The only workgroup-wide barrier follows the staging of the scaled query.
-// Row length of the LDS tile for sub-ranges of TW tokens: one token's outliers hit the same column of
-// many rows, and an odd row length spreads that column over all LDS banks.
-__host__ __device__ constexpr int qs_row(int tw) { return tw + 1; }
-constexpr int QS_U = 6;               // 64-entry batches in flight per wavefront
-
-__host__ __device__ constexpr int qs_wave_lds_bytes(int n_q_heads, int tw)
-{
-    return ((n_q_heads * qs_row(tw) * 8 + 15) & ~15) + 64 * 8;   // sums, per-pair angles
-}
-
 template <int R, int QS_TW, class SP>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_t L,
@@ -805,114 +775,8 @@ void kvq_qk_sparse(const void *__restrict__ params, int D, int n_q_heads, int64_
                    const float *__restrict__ q_rot,
                    float scale, float *__restrict__ scores, int64_t ld, int64_t tokens_per_wave)
 {
-    const int bx = (int)blockIdx.x;
-    constexpr int QS_ROW = qs_row(QS_TW);
-    extern __shared__ __attribute__((aligned(16))) float dyn[];
-    const KvqParamsView pv = kvq_params_view(params, D);
-    const int tid = threadIdx.x, lane = tid & 63, n_waves = blockDim.x >> 6;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // scalar: loop bounds below are uniform
-    float *qs = dyn;                                                     // [n_q_heads][128], scaled query
-    char *mine = (char *)(dyn + n_q_heads * 128) + (size_t)wave * qs_wave_lds_bytes(n_q_heads, QS_TW);
-    unsigned long long *S = (unsigned long long *)mine;                  // [n_q_heads][QS_ROW] 2^32-scaled sums
-    // [64] (angle of the pair at the sub-range's first token, theta / 2 pi)
-    float2_t *ang = (float2_t *)(mine + ((n_q_heads * QS_ROW * 8 + 15) & ~15));
-    const int64_t nb = ((int64_t)bx * n_waves + wave) * tokens_per_wave;
-    int64_t ne = nb + tokens_per_wave;
-    if (ne > L) ne = L;
-    const int n_cells = n_q_heads * QS_TW;
-    // the run is cut into equal sub-ranges of at most QS_TW tokens; the pointers of the next one are
-    // requested while the current one is processed
-    const int run = (nb < ne) ? (int)(ne - nb) : 0, n_sub = (run + QS_TW - 1) / QS_TW;
-    const int sub_len = n_sub ? (run + n_sub - 1) / n_sub : 0;
-    int64_t nc = nb;
-    int tc = sub_len;
-    uint32_t pw = 0;
-    if (tc > 0) pw = k_ptr[nc + (lane < tc ? lane : tc)];
-    // staging of the scaled query: its barrier comes after the first sub-range's loads are requested
-    for (int j = tid; j < n_q_heads * 128; j += blockDim.x) qs[j] = q_rot[j] * scale;
-    for (int j = lane; j < n_q_heads * QS_ROW; j += 64) S[j] = 0ull;
-    const float my_vh = pv.hdr->rope_vh[lane], my_vl = pv.hdr->rope_vl[lane];
-    bool staged = false, have_next = false;
-    uint32_t chn[QS_U], vbn[QS_U];
-    while (tc > 0) {
-        const int64_t nc_next = nc + tc;
-        const int tc_next = (int)((ne - nc_next < sub_len) ? (ne - nc_next) : sub_len);
-        const uint32_t e_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)pw);
-        const uint32_t e_end = (uint32_t)__builtin_amdgcn_readlane((int)pw, 63);
-        uint32_t chv[QS_U], vb[QS_U];
-        if (e_begin < e_end) {
-            if (have_next) {                             // requested during the previous sub-range
-#pragma unroll
-                for (int u = 0; u < QS_U; ++u) { chv[u] = chn[u]; vb[u] = vbn[u]; }
-            } else if (e_begin + 64u * QS_U <= nnz_cap) {
-                kvq_sparse_load_batch<false, QS_U>(ksp, nnz_cap, e_begin, e_end, lane, chv, vb);
-            } else {
-                kvq_sparse_load_batch<true, QS_U>(ksp, nnz_cap, e_begin, e_end, lane, chv, vb);
-            }
-        }
-        // the next sub-range's entries follow this one's: request its first batch now (its end is not
-        // known yet, so the whole batch is requested, which must then lie inside the arrays)
-        have_next = tc_next > 0 && e_end + 64u * QS_U <= nnz_cap;
-        if (have_next) kvq_sparse_load_batch<false, QS_U>(ksp, nnz_cap, e_end, 0xFFFFFFFFu, lane, chn, vbn);
-        uint32_t pw_next = 0;
-        if (tc_next > 0) pw_next = k_ptr[nc_next + (lane < tc_next ? lane : tc_next)];
-        ang[lane] = float2_t{rope_rev((float)nc, my_vh, my_vl), my_vh};
-        if (!staged) {
-            __syncthreads();
-            staged = true;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        int tcur = 0;
-        for (uint32_t eb = e_begin; eb < e_end; eb += 64 * QS_U) {
-            if (eb != e_begin) {                         // (the first batch was requested above)
-                if (eb + 64u * QS_U <= nnz_cap)
-                    kvq_sparse_load_batch<false, QS_U>(ksp, nnz_cap, eb, e_end, lane, chv, vb);
-                else
-                    kvq_sparse_load_batch<true, QS_U>(ksp, nnz_cap, eb, e_end, lane, chv, vb);
-            }
-#pragma unroll
-            for (int u = 0; u < QS_U; ++u) {
-                const uint32_t first = eb + 64u * u, e = first + (uint32_t)lane;
-                if (first >= e_end) break;
-                const int t = kvq_sparse_token(pw, tc, tcur, first, e);
-                if (e < e_end) {
-                    const uint32_t ch = chv[u];
-                    const float v = kvq_h2f((uint16_t)vb[u]);
-                    const float2_t a = ang[ch & 63];
-                    const float rev = __builtin_fmaf((float)t, a.y, a.x);
-                    const float cs = __builtin_amdgcn_cosf(rev);
-                    // (R_n^T q)_c = q_c cos + s q_{c^64} sin with s = +1 for the lower channel of the
-                    // pair and -1 for the upper: fold s into the sine
-                    const float sn = __builtin_bit_cast(
-                        float, __builtin_bit_cast(uint32_t, __builtin_amdgcn_sinf(rev)) ^ ((ch & 64u) << 25));
-                    const uint32_t cl = ch & 127u, kvh = ch >> 7;
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        const uint32_t qh = kvh * R + r;
-                        const uint32_t qi = (R == 1) ? ch : qh * 128u + cl;
-                        const float qp = qs[qi] * cs + qs[qi ^ 64u] * sn;
-                        kvq_lds_add_fixed<0>(&S[__umul24(qh, QS_ROW) + t], v * qp);     // 24-bit multiply: full rate
-                    }
-                }
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        // write the tile to the score buffer and clear it for the next sub-range
-        for (int j = lane; j < n_cells; j += 64) {
-            const int qh = j / QS_TW, t = j % QS_TW;
-            const unsigned long long x = S[qh * QS_ROW + t];
-            S[qh * QS_ROW + t] = 0ull;
-            if (t < tc) scores[(int64_t)qh * ld + nc + t] = kvq_from_fixed_fast<0>(x);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        nc = nc_next;
-        tc = tc_next;
-        pw = pw_next;
-    }
-    if (!staged) __syncthreads();        // a wavefront without tokens still meets the workgroup's barrier
+    qk_sparse_body<R, QS_TW, SP>((int)blockIdx.x, params, D, n_q_heads, L, k_ptr, ksp, nnz_cap, q_rot, scale, scores,
+                                 ld, tokens_per_wave);
 }
 
 template <int R, int TW, class SP>
@@ -920,31 +784,16 @@ kvq_status launch_qk_sparse_tw(const kvq_cache *c, const SP ksp, const float *q,
 {
     const int Hq = c->n_q_heads;
     const int64_t L = c->n_tokens_k;
-    // LDS: the scaled query plus one private slice per wavefront; two workgroups of 16 wavefronts per
-    // CU when they fit in 77 KiB each, fewer wavefronts otherwise
-    const int per_wave = qs_wave_lds_bytes(Hq, TW);
-    int waves = 16;
-    while (waves > 1 && (size_t)Hq * 512 + (size_t)waves * per_wave > 78848) waves -= (waves > 4) ? 4 : waves / 2;
-    if ((size_t)Hq * 512 + (size_t)waves * per_wave > 147456) return KVQ_ERR_UNSUPPORTED;
-    const size_t lds = (size_t)Hq * 512 + (size_t)waves * per_wave;
+    QkSparsePlan plan;
+    if (!qk_sparse_plan(Hq, L, TW, 0, plan)) return KVQ_ERR_UNSUPPORTED;
     // the kernel's dynamic-LDS limit is raised once per instantiation, to the most any launch asks for
     // (initialisation of a function-local static is thread-safe)
     static const hipError_t lds_attr = hipFuncSetAttribute((const void *)kvq_qk_sparse<R, TW, SP>,
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, 147456);
     KVQ_HIP_CHECK(lds_attr);
-    // as many wavefronts as the chip holds at once (160 KiB of LDS and 32 wavefronts per compute unit),
-    // every one with the same number of tokens
-    int wgs_per_cu = (int)(163840 / lds);
-    if (wgs_per_cu * waves > 32) wgs_per_cu = 32 / waves;
-    if (wgs_per_cu < 1) wgs_per_cu = 1;
-    const int64_t resident = (int64_t)kvq_cu_count() * wgs_per_cu * waves;
-    int64_t tpw = (L + resident - 1) / resident;
-    if (TW > 8) tpw = (tpw + TW - 1) / TW * TW;          // whole sub-ranges: full cache lines of scores
-    const int64_t n_waves = (L + tpw - 1) / tpw;
-    const unsigned grid = (unsigned)((n_waves + waves - 1) / waves);
-    kvq_qk_sparse<R, TW, SP><<<grid, 64 * waves, lds, s>>>(c->params, c->n_kv_heads * KVQ_HEAD_DIM, Hq, L, c->k_ptr,
-                                                       ksp, (uint32_t)c->cap_nnz_k, q, scale, scores,
-                                                       ld, tpw);
+    kvq_qk_sparse<R, TW, SP><<<plan.grid, 64 * plan.waves, plan.lds, s>>>(
+        c->params, c->n_kv_heads * KVQ_HEAD_DIM, Hq, L, c->k_ptr, ksp, (uint32_t)c->cap_nnz_k, q, scale, scores, ld,
+        plan.tokens_per_wave);
     KVQ_HIP_CHECK(hipGetLastError());
     return KVQ_OK;
 }
@@ -1058,7 +907,9 @@ kvq_status launch_qk(const kvq_cache *c, const float *q, float scale, float *sco
     }
     // the sparse kernel goes first and writes its part of every score; the dense kernel adds its own
     const int sparse_first = !(c->loaded & 2);           // bit 1: thresholds admit no Key outliers
-    if (sparse_first) {
+    // bit 2 (set on a copy of the descriptor by kvq_decode_step): the sparse part of every score is in
+    // the buffer already, written by the step's first launch
+    if (sparse_first && !(c->loaded & KVQ_LOADED_SPARSE_SCORES_DONE)) {
         kvq_status st = launch_qk_sparse<R>(c, q, scale, scores, ld, s);
         if (st != KVQ_OK) return st;
     }
