@@ -1153,22 +1153,36 @@ __device__ __forceinline__ void qk_sparse_new_token(const StepFrontArgs &a)
 // per compute unit.
 template <int BITS, int R, int W>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void kvq_step_front(const StepFrontArgs a)
+void kvq_step_front(const StepFrontArgs)
 {
+    // The argument block is read where a role needs it, through a pointer the compiler cannot see
+    // through.  Read as a kernel argument it is loaded whole at the kernel's entry, fifty scalar
+    // registers that stay alive through all three roles and are spilled into vector-register lanes at
+    // once; their reloads (v_readlane) then sit in the sparse role's loops, 25 % more VALU instructions
+    // in a role that is bound by them.
+#if defined(__HIP_DEVICE_COMPILE__)           // (the host pass only needs the kernel's signature)
+    typedef const StepFrontArgs __attribute__((address_space(4))) *ArgsPtr;
+    ArgsPtr pa = (ArgsPtr)__builtin_amdgcn_kernarg_segment_ptr();      // the one argument sits at offset 0
+    asm volatile("" : "+s"(pa));
     if (blockIdx.x == 0) {
         // wavefronts that a role does not use end here (a barrier waits only for those that have not ended)
         if (threadIdx.x >= KVQ_STEP_K_NT) return;
+        const StepFrontArgs a = *pa;
         k_quant_token<BITS, KVQ_STEP_K_NT>(a.params, a.D, a.cap, a.n, a.k_new, a.k_codes, a.k_ptr, a.ksp, a.cap_nnz_k, 1,
                                            a.d_status, 0);
         qk_sparse_new_token<R>(a);
     } else if (blockIdx.x == 1) {
         if (threadIdx.x >= 64 * W) return;
+        const StepFrontArgs a = *pa;
         v_quant_token4<BITS, 4, W>(a.params, a.D, a.cap, a.n, a.k_side, a.v_new, a.v_codes, a.v_sz, a.v_ptr, a.vsp,
                                    a.cap_nnz_v, a.d_status, 0);
     } else {
-        qk_sparse_body<R, 8, KvqSparseFlat>((int)blockIdx.x - 2, a.params, a.D, a.n_q_heads, a.n, a.k_ptr, a.ksp,
-                                            (uint32_t)a.cap_nnz_k, a.q_rot, a.scale, a.scores, a.ld, a.tokens_per_wave);
+        const KvqSparseFlat ksp{pa->ksp.idx, pa->ksp.val};
+        qk_sparse_body<R, 8, KvqSparseFlat>((int)blockIdx.x - 2, pa->params, pa->D, pa->n_q_heads, pa->n, pa->k_ptr, ksp,
+                                            (uint32_t)pa->cap_nnz_k, pa->q_rot, pa->scale, pa->scores, pa->ld,
+                                            pa->tokens_per_wave);
     }
+#endif
 }
 
 }  // namespace
