@@ -153,7 +153,7 @@ def cpu_baseline(st, sample_tokens):
 def model_step(args, wl, S, K, torch):
     """`--layers N`: one decode step of N attention layers, each with its own cache, look-up tables and
     per-channel constants (the full-model configuration: 32 layers at a context of 2^20 tokens keep
-    ~110 GB of compressed cache resident).  Per layer: kvq_quantize_append_kv + kvq_attention_decode."""
+    ~110 GB of compressed cache resident).  Per layer: kvq_decode_step."""
     L, steps, warmup, n_layers = wl.context, args.steps, args.warmup, args.layers
     n_new = steps + warmup
     cap = ((L + n_new + 8 + 127) // 128) * 128
@@ -176,8 +176,7 @@ def model_step(args, wl, S, K, torch):
 
     def step(i):
         for layer, gc in enumerate(caches):
-            K.kvq_quantize_append_kv(gc, new_k[layer][i:i + 1], new_v[layer][i:i + 1])
-            K.kvq_attention_decode(gc, qs[i], scale, scores, out[layer])
+            K.kvq_decode_step(gc, new_k[layer][i:i + 1], new_v[layer][i:i + 1], qs[i], scale, scores, out[layer])
 
     for i in range(warmup):
         step(i)
