@@ -12,6 +12,15 @@ import os
 import sys
 import time
 
+# Kernel arguments in device memory: by default the HIP runtime keeps the argument blocks of launches in
+# host memory, and every kernel's first scalar load then crosses the host link (measured here: 1.2 us per
+# kernel, 6 us of a 161 us decode step).  HIP_FORCE_DEV_KERNARG is the runtime's own switch for it (AMD's
+# tuning guides recommend it on MI300-class GPUs); it must be set before the runtime starts, which is why
+# it is set here and not in the library.  --host-kernarg (or the variable set to 0 by the caller) keeps
+# the default.  The line reports which one it ran with.
+if "--host-kernarg" not in sys.argv:
+    os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
+
 import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -355,6 +364,9 @@ def main():
                     help="more than 1: time a decode step over that many layers (each its own cache), nothing else")
     ap.add_argument("--no-fp16", action="store_true")
     ap.add_argument("--no-c3", action="store_true", help="skip the 1M-token leg (configuration 3) of the default run")
+    ap.add_argument("--host-kernarg", action="store_true",
+                    help="leave kernel arguments in host memory (the HIP runtime's default) instead of setting "
+                         "HIP_FORCE_DEV_KERNARG=1")
     ap.add_argument("--print-source-hash", action="store_true",
                     help="print the hash of the attention kernels' sources (the one a counter summary must name) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -615,6 +627,7 @@ def main():
         "metric": "quantized-KV decode step latency (append K/V + QK^T + softmax + PV), one attention layer",
         "step": "kvq_decode_step (append of the new token and attention over the cache that ends with it)",
         "step_launches": K.kvq_decode_step_launches(gc),
+        "env": {"HIP_FORCE_DEV_KERNARG": os.environ.get("HIP_FORCE_DEV_KERNARG", "")},
         "value": ms_per_step * 1e3, "unit": "us", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
