@@ -104,3 +104,37 @@ def test_a_rejected_step_changes_nothing():
     assert gc.n_tokens_k == 9 and gc.n_tokens_v == 9
     assert all(torch.equal(x, y) for x, y in zip(before, (gc.k_codes, gc.v_codes, gc.k_ptr, gc.v_ptr)))
     assert call() == 0 and gc.n_tokens_k == 10
+
+
+def test_step_with_full_outlier_arrays_reports_overflow_like_the_two_calls():
+    """The step's first launch on a cache whose Key outlier array fills up during the step: the sticky
+    status is set, pointers are clamped, and scores and outputs are those of the two calls on a twin
+    (which drops the same entries)."""
+    import torch
+    import paper_2401_18079_amd as K
+    wl = S.workload("c2", n_kv_heads=8, n_q_heads=8)
+    st = Setup(wl)
+    cap, L0 = 128, 100
+    a, b = (K.KvqCache(wl.bits, 8, 8, cap, st.k_side, wl.rope_base, cap_nnz_k=16 * cap) for _ in range(2))
+    for c in (a, b):
+        K.kvq_lut_load(c, st.lut_k, st.lut_v, st.s, st.z, st.lo, st.hi)
+        K.kvq_quantize_append_kv(c, torch.from_numpy(st.k(0, L0)).cuda(), torch.from_numpy(st.v(0, L0)).cuda())
+    assert K.kvq_decode_step_launches(a) == 5 and a.status() == 0
+    hi, lo = (np.asarray(x, dtype=np.float16).astype(np.float32) for x in (st.hi, st.lo))
+    full = (hi + 4.0 * (hi - lo) + 1.0).astype(np.float16)[None, :]          # every channel an outlier
+    sa, sb = (torch.zeros((8, cap), device="cuda") for _ in range(2))
+    oa, ob = (torch.zeros((8, 128), device="cuda") for _ in range(2))
+    for i in range(3):                                                     # 3 x 1024 entries: the array overflows
+        kd, vd = torch.from_numpy(full).cuda(), torch.from_numpy(st.v(L0 + i, 1)).cuda()
+        qd = torch.from_numpy(S.gen_q(wl, 0, 0, step=i)).cuda()
+        K.kvq_decode_step(a, kd, vd, qd, SCALE, sa, oa)
+        K.kvq_quantize_append_kv(b, kd, vd)
+        K.kvq_attention_decode(b, qd, SCALE, sb, ob)
+        n = L0 + i + 1
+        ok, worst = matvec_close(sa.cpu().numpy()[:, :n], sb.cpu().numpy()[:, :n], rel=2e-5)
+        assert ok, f"step {i}: scores worst error / bound = {worst:.3f}"
+        ok, worst = matvec_close(oa.cpu().numpy(), ob.cpu().numpy(), rel=2e-5)
+        assert ok, f"step {i}: outputs worst error / bound = {worst:.3f}"
+    assert a.status() == 4 and b.status() == 4
+    assert torch.equal(a.k_ptr, b.k_ptr) and int(a.k_ptr[L0 + 3].item()) == 16 * cap
+    assert torch.equal(a.k_idx, b.k_idx) and torch.equal(a.k_val, b.k_val) and torch.equal(a.k_codes, b.k_codes)
