@@ -239,12 +239,26 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
             const float s0 = kvq_h2f((uint16_t)(sz.x & 0xFFFFu)), z0 = kvq_h2f((uint16_t)(sz.x >> 16));
             // (scale, zero-point) of an absent second token may be anything, NaN included
             const float s1 = ok1 ? kvq_h2f((uint16_t)(sz.y & 0xFFFFu)) : 0.f, z1 = ok1 ? kvq_h2f((uint16_t)(sz.y >> 16)) : 0.f;
-            float w0[RG], w1[RG];
+            // The scores (probabilities) are loaded whatever ok0 / ok1 say (the second from an index that
+            // always exists), and the empty asm keeps the compiler from moving the loads back under those
+            // conditions: a load inside a conditional block is followed by a wait for every load in
+            // flight, the tile's codes included, and the tile then costs two or three memory latencies
+            // instead of one.
+            const int64_t n1 = n0 + 1 < L ? n0 + 1 : n0;
+            float pl0[RG], pl1[RG];
 #pragma unroll
             for (int h = 0; h < RG; ++h) {
                 const float *prow = probs + (int64_t)(q0 + h) * ld;
-                float p0 = ok0 ? prow[n0] : 0.f;
-                float p1 = ok1 ? prow[n0 + 1] : 0.f;
+                pl0[h] = prow[n0];
+                pl1[h] = prow[n1];
+            }
+#pragma unroll
+            for (int h = 0; h < RG; ++h) asm volatile("" : "+v"(pl0[h]), "+v"(pl1[h]));
+            float w0[RG], w1[RG];
+#pragma unroll
+            for (int h = 0; h < RG; ++h) {
+                float p0 = ok0 ? pl0[h] : 0.f;
+                float p1 = ok1 ? pl1[h] : 0.f;
                 if (stat_slots) {
                     p0 = ok0 ? kvq_stat_weight(p0, m2[h]) : 0.f;
                     p1 = ok1 ? kvq_stat_weight(p1, m2[h]) : 0.f;
