@@ -157,3 +157,45 @@ def test_storage_past_the_last_token_is_never_used():
     K.kvq_attention_decode(gc, torch.from_numpy(q).cuda(), SCALE, scores, out)
     ok, worst = matvec_close(out.cpu().numpy(), oc.pv(p), rel=2e-3)
     assert ok, f"fused worst error / bound = {worst:.3f}"
+
+
+@pytest.mark.parametrize("L_full,extra", [(100, 4), (37, 0)])
+def test_value_tokens_with_unequal_outlier_counts(L_full, extra):
+    """The Value outlier array runs full part way through token L_full: the tokens before it keep their
+    2 * k_side outliers, that token `extra` of them, the later ones none.  The sparse Value kernel
+    takes an entry's token from a division where every token of a range has the same count and from
+    the pointers otherwise: both kinds of range occur here, and a range that is even except for its
+    last token.  The oracle does not model a full array; what the format prescribes for one (pointers
+    clamped to the capacity, i.e. the excess dropped, highest channels first) is applied to the
+    oracle's cache here."""
+    import torch
+    import paper_2401_18079_amd as K
+    wl = S.workload("c2", n_kv_heads=4, n_q_heads=4)
+    st = Setup(wl)
+    L, cap = 333, 512
+    cap_nnz_v = 2 * st.k_side * L_full + extra
+    k, v = st.k(0, L), st.v(0, L)
+    oc = O.OracleCache(wl.bits, wl.n_kv_heads, wl.n_q_heads, cap, st.k_side, wl.rope_base, st.lut_k, st.lut_v,
+                       st.s, st.z, st.lo, st.hi)
+    oc.append_k(k); oc.append_v(v)
+    oc.v_ptr = np.minimum(oc.v_ptr, cap_nnz_v).astype(oc.v_ptr.dtype)
+    gc = K.KvqCache(wl.bits, wl.n_kv_heads, wl.n_q_heads, cap, st.k_side, wl.rope_base, wl.D * cap, cap_nnz_v=cap_nnz_v)
+    K.kvq_lut_load(gc, st.lut_k, st.lut_v, st.s, st.z, st.lo, st.hi)
+    for t0, T in ((0, 64), (64, 130), (194, 1), (195, L - 195)):
+        K.kvq_quantize_append_k(gc, torch.from_numpy(k[t0:t0 + T]).cuda())
+        K.kvq_quantize_append_v(gc, torch.from_numpy(v[t0:t0 + T]).cuda())
+    torch.cuda.synchronize()
+    assert gc.status() == 4                                    # KVQ_ERR_NNZ_OVERFLOW: reported, the excess dropped
+    assert np.array_equal(gc.v_ptr.cpu().numpy()[:L + 1].astype(np.int64), oc.v_ptr[:L + 1].astype(np.int64))
+    idx, val = gc.sparse_entries("v", cap_nnz_v)
+    assert np.array_equal(idx.cpu().numpy().view(np.uint16), oc.v_idx[:cap_nnz_v])
+    assert np.array_equal(val.cpu().numpy().view(np.uint16), oc.v_val[:cap_nnz_v])
+    cnt = np.diff(oc.v_ptr[:L + 1].astype(np.int64))
+    assert np.all(cnt[:L_full] == 2 * st.k_side) and cnt[L_full] == extra and np.all(cnt[L_full + 1:] == 0)
+    _check_matvecs(st, oc, gc, L)
+    q = S.gen_q(wl, 0, 0)
+    scores = torch.zeros((wl.n_q_heads, L), device="cuda")
+    out = torch.empty((wl.n_q_heads, 128), device="cuda")
+    K.kvq_attention_decode(gc, torch.from_numpy(q).cuda(), SCALE, scores, out)
+    ok, worst = matvec_close(out.cpu().numpy(), oc.pv(O.softmax(oc.qk(q, SCALE))), rel=2e-3)
+    assert ok, f"fused worst error / bound = {worst:.3f}"
