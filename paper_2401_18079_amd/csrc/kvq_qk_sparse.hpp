@@ -104,6 +104,16 @@ __device__ __forceinline__ void qk_sparse_body(const int bx, const void *__restr
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         int tcur = 0;
+        // Short sub-ranges: the pointers of tokens 1 .. QS_TW - 1 as scalars (lanes from tc on hold the
+        // sub-range's end, which no entry reaches); an entry's token is the number of them it has
+        // reached: straight-line compares instead of the walk of kvq_sparse_token, whose scalar loops
+        // cost this kernel more than the arithmetic on the entries does.
+        constexpr int NPJ = (QS_TW <= 8) ? QS_TW - 1 : 1;
+        uint32_t pj[NPJ];
+        if (QS_TW <= 8) {
+#pragma unroll
+            for (int j = 0; j < NPJ; ++j) pj[j] = (uint32_t)__builtin_amdgcn_readlane((int)pw, j + 1);
+        }
         for (uint32_t eb = e_begin; eb < e_end; eb += 64 * QS_U) {
             if (eb != e_begin) {                         // (the first batch was requested above)
                 if (eb + 64u * QS_U <= nnz_cap)
@@ -115,7 +125,14 @@ __device__ __forceinline__ void qk_sparse_body(const int bx, const void *__restr
             for (int u = 0; u < QS_U; ++u) {
                 const uint32_t first = eb + 64u * u, e = first + (uint32_t)lane;
                 if (first >= e_end) break;
-                const int t = kvq_sparse_token(pw, tc, tcur, first, e);
+                int t;
+                if (QS_TW <= 8) {
+                    t = 0;
+#pragma unroll
+                    for (int j = 0; j < NPJ; ++j) t += (e >= pj[j]) ? 1 : 0;
+                } else {
+                    t = kvq_sparse_token(pw, tc, tcur, first, e);
+                }
                 if (e < e_end) {
                     const uint32_t ch = chv[u];
                     const float v = kvq_h2f((uint16_t)vb[u]);
