@@ -251,6 +251,40 @@ __device__ __forceinline__ int kvq_sparse_token(uint32_t pw, int tc, int &tcur, 
     return t;
 }
 
+// The same without a loop, for sub-ranges of many short tokens (where kvq_sparse_token walks a dozen
+// pointers per group of 64 entries, in scalar code that nothing overlaps): the token of entry
+// first + lane is the largest j with pw_j <= first + lane.  Pointer lane j (1 <= j < tc) whose token
+// starts at or before entry first + 63 leaves j in slot max(pw_j - first, 0) of `slots` (64 words of
+// LDS private to the wavefront; equal pointers, i.e. empty tokens, meet in one slot: an atomic
+// maximum); an entry's token is the running maximum of the slots up to its own, a prefix scan over
+// the lanes with DPP moves.  All 64 lanes must be active.
+__device__ __forceinline__ uint32_t kvq_dpp_max_u32(uint32_t v, uint32_t moved)
+{
+    return v > moved ? v : moved;
+}
+__device__ __forceinline__ int kvq_sparse_token_scan(uint32_t pw, int tc, uint32_t first, int lane, uint32_t *slots)
+{
+    slots[lane] = 0u;
+    const bool before = pw <= first;
+    const uint32_t rel = before ? 0u : pw - first;
+    if (lane >= 1 && lane < tc && rel <= 63u)
+        __hip_atomic_fetch_max(&slots[rel], (uint32_t)lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    uint32_t v = slots[lane];
+    // inclusive prefix maximum: inside each row of 16 lanes (a lane without a source keeps 0), then
+    // lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3
+    v = kvq_dpp_max_u32(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false));
+    v = kvq_dpp_max_u32(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false));
+    v = kvq_dpp_max_u32(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false));
+    v = kvq_dpp_max_u32(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false));
+    v = kvq_dpp_max_u32(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false));
+    v = kvq_dpp_max_u32(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false));
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");          // the next group clears the slots
+    __builtin_amdgcn_wave_barrier();
+    return (int)v;
+}
+
 // Issue priority of the calling wavefront, 0 (lowest) to 3.  The SIMD's arbiter serves the highest
 // priority first and, among equals, the OLDEST wavefront: the four wavefronts that share a SIMD for a
 // whole kernel then finish one after the other (measured on the dense Value kernel: workgroups

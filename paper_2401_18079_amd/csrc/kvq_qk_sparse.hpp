@@ -34,7 +34,8 @@ constexpr int QS_U = 6;               // 64-entry batches in flight per wavefron
 
 __host__ __device__ constexpr int qs_wave_lds_bytes(int n_q_heads, int tw)
 {
-    return ((n_q_heads * qs_row(tw) * 8 + 15) & ~15) + 64 * 8;   // sums, per-pair angles
+    // sums, per-pair angles, and for long sub-ranges the 64 slots of kvq_sparse_token_scan
+    return ((n_q_heads * qs_row(tw) * 8 + 15) & ~15) + 64 * 8 + (tw > 8 ? 64 * 4 : 0);
 }
 
 // The work of workgroup `bx` of the sparse Key kernel (a device function: the kernel of kvq_qk_matvec
@@ -56,6 +57,7 @@ __device__ __forceinline__ void qk_sparse_body(const int bx, const void *__restr
     unsigned long long *S = (unsigned long long *)mine;                  // [n_q_heads][QS_ROW] 2^32-scaled sums
     // [64] (angle of the pair at the sub-range's first token, theta / 2 pi)
     float2_t *ang = (float2_t *)(mine + ((n_q_heads * QS_ROW * 8 + 15) & ~15));
+    uint32_t *slots = (uint32_t *)(ang + 64);                            // (QS_TW > 8 only)
     const int64_t nb = ((int64_t)bx * n_waves + wave) * tokens_per_wave;
     int64_t ne = nb + tokens_per_wave;
     if (ne > L) ne = L;
@@ -103,7 +105,6 @@ __device__ __forceinline__ void qk_sparse_body(const int bx, const void *__restr
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        int tcur = 0;
         // Short sub-ranges: the pointers of tokens 1 .. QS_TW - 1 as scalars (lanes from tc on hold the
         // sub-range's end, which no entry reaches); an entry's token is the number of them it has
         // reached: straight-line compares instead of the walk of kvq_sparse_token, whose scalar loops
@@ -131,7 +132,7 @@ __device__ __forceinline__ void qk_sparse_body(const int bx, const void *__restr
 #pragma unroll
                     for (int j = 0; j < NPJ; ++j) t += (e >= pj[j]) ? 1 : 0;
                 } else {
-                    t = kvq_sparse_token(pw, tc, tcur, first, e);
+                    t = kvq_sparse_token_scan(pw, tc, first, lane, slots);
                 }
                 if (e < e_end) {
                     const uint32_t ch = chv[u];

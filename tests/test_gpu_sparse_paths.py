@@ -199,3 +199,30 @@ def test_value_tokens_with_unequal_outlier_counts(L_full, extra):
     K.kvq_attention_decode(gc, torch.from_numpy(q).cuda(), SCALE, scores, out)
     ok, worst = matvec_close(out.cpu().numpy(), oc.pv(O.softmax(oc.qk(q, SCALE))), rel=2e-3)
     assert ok, f"fused worst error / bound = {worst:.3f}"
+
+
+@pytest.mark.parametrize("heads,L", [((4, 4), 333), ((2, 8), 150)])
+def test_long_sub_ranges_with_empty_and_full_tokens(heads, L):
+    """Key outlier arrays sized for fewer than 16 outliers per token make the sparse Key kernel walk
+    sub-ranges of 32 tokens, where an entry's token comes from a scatter of the token pointers and a
+    prefix maximum over the lanes.  Planted: runs of tokens without any outlier (equal pointers), at
+    the very start and end too, and tokens whose every channel is an outlier (several groups of 64
+    entries inside one token)."""
+    wl = S.workload("c2", n_kv_heads=heads[0], n_q_heads=heads[1])
+    st = Setup(wl)
+    rng = np.random.default_rng(23)
+    k, empty, full = _crafted_keys(st, L, rng)
+    v = st.v(0, L)
+    cap = 512
+    probe = O.OracleCache(wl.bits, wl.n_kv_heads, wl.n_q_heads, cap, st.k_side, wl.rope_base, st.lut_k, st.lut_v,
+                          st.s, st.z, st.lo, st.hi)
+    probe.append_k(k)
+    nnz_k = int(probe.k_ptr[L])
+    assert nnz_k // cap < 16                                    # the 32-token sub-ranges are taken
+    oc, gc = _run(st, k, v, L, cap, cap_nnz_k=nnz_k)
+    assert gc.status() == 0
+    assert not compare_caches(oc, gc)
+    cnt = np.diff(oc.k_ptr[:L + 1].astype(np.int64))
+    assert np.all(cnt[np.setdiff1d(empty, full)] == 0) and np.all(cnt[:3] == 0) and np.all(cnt[L - 2:] == 0)
+    assert np.all(cnt[full] == wl.D)
+    _check_matvecs(st, oc, gc, L)
