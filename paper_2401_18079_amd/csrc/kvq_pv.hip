@@ -156,8 +156,10 @@ __device__ __forceinline__ void pv_all_fields(std::integer_sequence<int, G...>, 
 // grouped-query attention RG > 1 heads share every extraction and gather.  grid = (slabs, 2*Hq / 4):
 // wavefront w of a workgroup owns combination blockIdx.y*4 + w.  Writes partial[slab][q][128] and
 // zpart[slab][q].
+// (Four wavefronts per SIMD: the register allocation is held to 128, which every instantiation but
+// the 3-bit one for four heads meets without spilling.)
 template <int BITS, int RG, bool SPAN = false>
-__global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ params, int D, int n_kv_heads,
+__global__ __launch_bounds__(PV_NT, (BITS == 3 && RG == 4) ? 3 : 4) void kvq_pv_dense(const void *__restrict__ params, int D, int n_kv_heads,
                                                       int n_q_heads, int64_t cap, int64_t L,
                                                       const uint8_t *__restrict__ v_codes,
                                                       const uint16_t *__restrict__ v_sz,
@@ -177,8 +179,12 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
     constexpr int NF = 64 / RG;                    // fields (channels) per lane and head
     constexpr int ND = 4 * BITS / RG;              // dwords of a chunk that hold them
     static_assert((4 * BITS) % RG == 0 && NF % PV_FIELD_GROUP == 0, "a slice is whole dwords and whole field groups");
-    __shared__ __attribute__((aligned(16))) half2_t ptab[NE2 * 32];      // replicated pair table
-    __shared__ float red[PV_WAVES][64][17];
+    // One array for the replicated pair table (used by the tile loop) and for the lane reduction after
+    // it: with the 4-bit table (32 KB) next to the reduction's 17 KB only three workgroups fit a CU.
+    constexpr int LDS_WORDS = (NE2 * 32 > PV_WAVES * 64 * 17) ? NE2 * 32 : PV_WAVES * 64 * 17;
+    __shared__ __attribute__((aligned(16))) uint32_t lds_words[LDS_WORDS];
+    half2_t *ptab = (half2_t *)lds_words;                                 // [NE2 * 32]
+    float (*red)[64][17] = (float (*)[64][17])lds_words;                  // [PV_WAVES][64][17]
     const KvqParamsView pv = kvq_params_view(params, D);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int e = tid; e < NE2 * 32; e += PV_NT) {
@@ -273,7 +279,9 @@ __global__ __launch_bounds__(PV_NT) void kvq_pv_dense(const void *__restrict__ p
         }
     }
     if (KVQ_ROTATE_PRIORITY) __builtin_amdgcn_s_setprio(0);
-    // sum the 64 lanes: four rounds of 16 accumulators through LDS
+    // sum the 64 lanes: four rounds of 16 accumulators through LDS (over the table, once every
+    // wavefront of the workgroup has left the tile loop)
+    __syncthreads();
     float outv = 0.f;      // lane l (< 64) ends up with the sum of accumulator l
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
